@@ -1,0 +1,145 @@
+/*
+ * ctc_mi355x.h -- batched CTC cost and gradient on one MI355X (gfx950).
+ *
+ * The library computes, for B independent utterances at once, the Connectionist
+ * Temporal Classification cost of Section 3.3, Eq. (ctc),
+ *
+ *     cost_b = -ln  sum_{pi in Align(x_b, y_b)}  prod_{t < T_b}  softmax(x[t,b,:])[pi_t]
+ *
+ * and its derivative with respect to the pre-softmax activations x, by the
+ * forward (alpha) / backward (beta) passes over the blank-interleaved label and
+ * the per-character reduction described in the appendix "GPU Implementation of
+ * CTC Loss Function".  The output softmax of Section 3.1 is fused into the path.
+ *
+ * Plain C ABI: pointers and sizes only.  Each pointer argument is marked (host)
+ * or (device).  The library allocates no device memory: every buffer, including
+ * the scratch workspace, belongs to the caller (Section 4.3 motivates keeping
+ * allocation off the training step).  All device work is enqueued on the given
+ * stream and the calls return without waiting for it; host arrays are consumed
+ * before the call returns.
+ */
+#ifndef CTC_MI355X_H
+#define CTC_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CTC_STATUS_SUCCESS = 0,
+    CTC_STATUS_INVALID_VALUE = 1,       /* null pointer, size or id out of range, overlapping buffers */
+    CTC_STATUS_WORKSPACE_TOO_SMALL = 2, /* workspace_bytes below what ctc_workspace_size reports */
+    CTC_STATUS_HIP_ERROR = 3,           /* a HIP runtime call failed; see ctc_last_hip_error */
+    CTC_STATUS_UNSUPPORTED = 4          /* a label longer than CTC_MAX_LABEL_LENGTH */
+} ctc_status_t;
+
+/* Element type of activations AND gradients.  Arithmetic is always fp32/fp64 inside. */
+typedef enum {
+    CTC_DTYPE_F32 = 0,
+    CTC_DTYPE_BF16 = 1
+} ctc_dtype_t;
+
+/* Longest label string one utterance may carry (lattice of 2*L+1 states). */
+#define CTC_MAX_LABEL_LENGTH 1023
+
+/* Kernels of one call, in launch order; index into ctc_profile_kernels' output. */
+enum {
+    CTC_KERNEL_SETUP = 0,      /* per-utterance label links, costs of degenerate utterances */
+    CTC_KERNEL_SOFTMAX = 1,    /* row-wise log-softmax statistics + emission gather */
+    CTC_KERNEL_LATTICE = 2,    /* alpha and beta recursions, one launch */
+    CTC_KERNEL_GRADIENT = 3,   /* softmax minus normalised occupancy, zero fill of padding */
+    CTC_NUM_KERNELS = 4
+};
+
+/*
+ * Bytes of device workspace that ctc_loss_and_grad needs for this batch shape.
+ * (Workspace sizing for the memory-allocation concern of Section 4.3.)
+ *
+ *   T, B, A          time steps of the tensor, utterances, alphabet size incl. blank; all >= 1
+ *   label_lengths    (host) [B], each in 0..CTC_MAX_LABEL_LENGTH
+ *   input_lengths    (host) [B], each in 0..T
+ *   bytes_out        (host) receives the size; the workspace must be 256-byte aligned
+ *
+ * Pure host computation: touches no GPU.  Returns INVALID_VALUE / UNSUPPORTED as above.
+ */
+ctc_status_t ctc_workspace_size(int T, int B, int A,
+                                const int32_t *label_lengths,
+                                const int32_t *input_lengths,
+                                ctc_dtype_t dtype,
+                                size_t *bytes_out);
+
+/*
+ * CTC cost and gradient for a minibatch (Section 3.3 Eq. (ctc); Section 3.1 softmax;
+ * appendix on the GPU CTC implementation for the alpha/beta/reduction structure).
+ *
+ *   activations   (device) [T, B, A], A fastest, pre-softmax logits of type `dtype`.
+ *                 Rows t >= input_lengths[b] are never read.
+ *   flat_labels   (host) the B label strings back to back, sum(label_lengths) ids,
+ *                 each in [0, A) and different from `blank`
+ *   label_lengths (host) [B]
+ *   input_lengths (host) [B]
+ *   blank         id of the blank symbol, in [0, A)
+ *   costs         (device) [B] float: -ln p_b in nats, per utterance, not averaged;
+ *                 +inf when no alignment exists (fewer frames than symbols plus
+ *                 adjacent repeats); 0 for an empty label with zero frames
+ *   grads         (device) [T, B, A] of type `dtype`: d cost_b / d activations.
+ *                 Rows t >= input_lengths[b], and all rows of an utterance with
+ *                 infinite cost, are written as zeros.  Must not overlap activations.
+ *   workspace     (device) 256-byte aligned scratch of at least ctc_workspace_size bytes;
+ *                 contents on entry are irrelevant, contents on exit are unspecified
+ *   stream        a hipStream_t (passed as void* so that this header needs no HIP
+ *                 include); NULL is the default stream
+ *
+ * Errors are reported by status only; nothing is printed or thrown.  On an error
+ * found during validation nothing has been enqueued.  Results are bitwise
+ * repeatable from run to run on one device.  Concurrent calls need distinct
+ * workspaces.
+ */
+ctc_status_t ctc_loss_and_grad(const void *activations,
+                               const int32_t *flat_labels,
+                               const int32_t *label_lengths,
+                               const int32_t *input_lengths,
+                               int T, int B, int A, int blank,
+                               ctc_dtype_t dtype,
+                               float *costs,
+                               void *grads,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/*
+ * Same computation as ctc_loss_and_grad, but brackets each kernel with HIP events
+ * on `stream`, waits for the stream, and reports the device time of each kernel of
+ * this call in milliseconds.  For measurement (the per-kernel timings that the
+ * paper's Table "gpucpuctc" aggregates per epoch), not for the training loop.
+ *
+ *   kernel_ms     (host) [CTC_NUM_KERNELS]
+ */
+ctc_status_t ctc_profile_kernels(const void *activations,
+                                 const int32_t *flat_labels,
+                                 const int32_t *label_lengths,
+                                 const int32_t *input_lengths,
+                                 int T, int B, int A, int blank,
+                                 ctc_dtype_t dtype,
+                                 float *costs,
+                                 void *grads,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *stream,
+                                 float *kernel_ms);
+
+/* Name of kernel `index` (0..CTC_NUM_KERNELS-1) as it appears in a profiler trace; NULL otherwise. */
+const char *ctc_kernel_name(int index);
+
+/* Static, human-readable name of a status code. */
+const char *ctc_status_string(ctc_status_t status);
+
+/* Raw hipError_t value of the most recent HIP failure seen by the calling thread (0 if none). */
+int ctc_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* CTC_MI355X_H */

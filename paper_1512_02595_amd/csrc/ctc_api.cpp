@@ -1,0 +1,261 @@
+// Host side of the CTC library: argument validation, workspace layout, the per-call plan
+// (which utterances run, in which order, how wide the lattice workgroups are) and the
+// enqueueing of the four kernels.  No device memory is allocated here or anywhere else in
+// the library (Section 4.3: allocation is kept off the training step; the caller hands in
+// one workspace and this file carves it).
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "ctc_internal.h"
+
+namespace ctc {
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+inline bool record(int err)
+{
+    if (err != 0) g_last_hip_error = err;
+    return err == 0;
+}
+
+}  // namespace
+
+ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
+                         const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay)
+{
+    if (!label_lengths || !input_lengths || !lay) return CTC_STATUS_INVALID_VALUE;
+    if (T < 1 || B < 1 || A < 1) return CTC_STATUS_INVALID_VALUE;
+    if (dtype != CTC_DTYPE_F32 && dtype != CTC_DTYPE_BF16) return CTC_STATUS_INVALID_VALUE;
+    int64_t sumL = 0, emit = 0, ab = 0;
+    bool too_long = false;
+    for (int b = 0; b < B; ++b) {
+        const int64_t L = label_lengths[b], Tb = input_lengths[b];
+        if (L < 0 || Tb < 0 || Tb > T) return CTC_STATUS_INVALID_VALUE;
+        if (L > CTC_MAX_LABEL_LENGTH) too_long = true;
+        sumL += L;
+        emit += Tb * (L + 1);
+        ab += Tb * 2 * (L + 1);
+    }
+    if (too_long) return CTC_STATUS_UNSUPPORTED;
+    if (sumL > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
+    Layout l;
+    l.sumL = sumL;
+    l.emit_floats = emit;
+    l.ab_doubles = ab;
+    size_t off = 0;
+    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 32 B each: stays 4-byte aligned
+    l.order = off;  off += static_cast<size_t>(B) * sizeof(int32_t);
+    l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
+    l.upload_bytes = off;
+    off = align_up(off);
+    l.links = off;  off = align_up(off + static_cast<size_t>(sumL) * sizeof(int32_t));
+    l.logp = off;   off = align_up(off + static_cast<size_t>(B) * sizeof(double));
+    l.lse = off;    off = align_up(off + static_cast<size_t>(B) * T * sizeof(float));
+    l.emit = off;   off = align_up(off + static_cast<size_t>(emit) * sizeof(float));
+    l.alpha = off;  off = align_up(off + static_cast<size_t>(ab) * sizeof(double));
+    l.beta = off;   off = align_up(off + static_cast<size_t>(ab) * sizeof(double));
+    l.total = off;
+    *lay = l;
+    return CTC_STATUS_SUCCESS;
+}
+
+namespace {
+
+struct Call {
+    const void* x;
+    const int32_t* flat_labels;
+    const int32_t* label_lengths;
+    const int32_t* input_lengths;
+    int T, B, A, blank;
+    ctc_dtype_t dtype;
+    float* costs;
+    void* grads;
+    void* ws;
+    size_t ws_bytes;
+    void* stream;
+};
+
+// Validates everything that can be validated on the host, builds the upload image
+// (Utt records, run order, labels) and the launch parameters.
+ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
+{
+    if (!c.x || !c.label_lengths || !c.input_lengths || !c.costs || !c.grads || !c.ws)
+        return CTC_STATUS_INVALID_VALUE;
+    if (c.T < 1 || c.B < 1 || c.A < 1 || c.blank < 0 || c.blank >= c.A) return CTC_STATUS_INVALID_VALUE;
+    Layout lay;
+    ctc_status_t st = make_layout(c.T, c.B, c.A, c.label_lengths, c.input_lengths, c.dtype, &lay);
+    if (st != CTC_STATUS_SUCCESS) return st;
+    if (lay.sumL > 0 && !c.flat_labels) return CTC_STATUS_INVALID_VALUE;
+    if (reinterpret_cast<uintptr_t>(c.ws) % kAlign != 0) return CTC_STATUS_INVALID_VALUE;
+
+    const size_t elem = (c.dtype == CTC_DTYPE_F32) ? 4 : 2;
+    const size_t tensor_bytes = static_cast<size_t>(c.T) * c.B * c.A * elem;
+    {
+        const char* xa = static_cast<const char*>(c.x);
+        const char* ga = static_cast<const char*>(c.grads);
+        if (xa < ga + tensor_bytes && ga < xa + tensor_bytes) return CTC_STATUS_INVALID_VALUE;
+    }
+    if (reinterpret_cast<uintptr_t>(c.x) % elem || reinterpret_cast<uintptr_t>(c.grads) % elem)
+        return CTC_STATUS_INVALID_VALUE;
+
+    image->resize(lay.upload_bytes);
+    Utt* meta = reinterpret_cast<Utt*>(image->data() + lay.meta);
+    int32_t* order = reinterpret_cast<int32_t*>(image->data() + lay.order);
+    int32_t* labels = reinterpret_cast<int32_t*>(image->data() + lay.labels);
+
+    int64_t lab_off = 0, e_off = 0, ab_off = 0;
+    int n_run = 0, max_waves = 1;
+    for (int b = 0; b < c.B; ++b) {
+        const int L = c.label_lengths[b], Tb = c.input_lengths[b];
+        const int32_t* lab = c.flat_labels + lab_off;
+        int repeats = 0;
+        for (int i = 0; i < L; ++i) {
+            const int32_t s = lab[i];
+            if (s < 0 || s >= c.A || s == c.blank) return CTC_STATUS_INVALID_VALUE;
+            if (i > 0 && s == lab[i - 1]) ++repeats;
+            labels[lab_off + i] = s;
+        }
+        // An alignment exists iff every symbol gets a frame and equal neighbours a blank between them.
+        const bool runs = Tb > 0 && Tb >= L + repeats;
+        Utt& m = meta[b];
+        m.Tb = Tb;
+        m.L = L;
+        m.lab_off = static_cast<int32_t>(lab_off);
+        m.flags = runs ? kUttRuns : 0;
+        m.e_off = e_off;
+        m.ab_off = ab_off;
+        lab_off += L;
+        e_off += static_cast<int64_t>(Tb) * (L + 1);
+        ab_off += static_cast<int64_t>(Tb) * 2 * (L + 1);
+        if (runs) {
+            order[n_run++] = b;
+            max_waves = std::max(max_waves, (L + 1 + 63) / 64);
+        }
+    }
+    for (int i = n_run; i < c.B; ++i) order[i] = -1;
+    // Heaviest chains first, so the longest recursion does not start last.
+    std::stable_sort(order, order + n_run, [&](int a, int b) {
+        const int64_t wa = static_cast<int64_t>(meta[a].Tb) * ((meta[a].L + 64) / 64);
+        const int64_t wb = static_cast<int64_t>(meta[b].Tb) * ((meta[b].L + 64) / 64);
+        return wa > wb;
+    });
+
+    if (c.ws_bytes < lay.total) return CTC_STATUS_WORKSPACE_TOO_SMALL;
+
+    out->T = c.T; out->B = c.B; out->A = c.A; out->blank = c.blank;
+    out->dtype = c.dtype;
+    out->n_run = n_run;
+    out->max_waves = max_waves;
+    out->x = c.x;
+    out->grads = c.grads;
+    out->costs = c.costs;
+    out->ws = static_cast<char*>(c.ws);
+    out->lay = lay;
+    return CTC_STATUS_SUCCESS;
+}
+
+ctc_status_t run(const Call& c, float* kernel_ms)
+{
+    thread_local std::vector<char> image;
+    Launch p;
+    ctc_status_t st = prepare(c, &p, &image);
+    if (st != CTC_STATUS_SUCCESS) return st;
+
+    hipStream_t s = static_cast<hipStream_t>(c.stream);
+    // Pageable source: the runtime has consumed `image` when this returns.
+    if (!record(hipMemcpyAsync(p.ws, image.data(), p.lay.upload_bytes, hipMemcpyHostToDevice, s)))
+        return CTC_STATUS_HIP_ERROR;
+
+    hipEvent_t ev[CTC_NUM_KERNELS + 1] = {};
+    if (kernel_ms) {
+        for (auto& e : ev)
+            if (!record(hipEventCreate(&e))) return CTC_STATUS_HIP_ERROR;
+        if (!record(hipEventRecord(ev[0], s))) return CTC_STATUS_HIP_ERROR;
+    }
+    int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_setup, launch_softmax,
+                                                                  launch_lattice, launch_gradient};
+    for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
+        if (!record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
+        if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
+    }
+    if (kernel_ms) {
+        if (!record(hipStreamSynchronize(s))) return CTC_STATUS_HIP_ERROR;
+        for (int i = 0; i < CTC_NUM_KERNELS; ++i)
+            if (!record(hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]))) return CTC_STATUS_HIP_ERROR;
+        for (auto& e : ev) (void)hipEventDestroy(e);
+    }
+    return CTC_STATUS_SUCCESS;
+}
+
+}  // namespace
+}  // namespace ctc
+
+extern "C" {
+
+ctc_status_t ctc_workspace_size(int T, int B, int A, const int32_t* label_lengths,
+                                const int32_t* input_lengths, ctc_dtype_t dtype, size_t* bytes_out)
+{
+    if (!bytes_out) return CTC_STATUS_INVALID_VALUE;
+    ctc::Layout lay;
+    ctc_status_t st = ctc::make_layout(T, B, A, label_lengths, input_lengths, dtype, &lay);
+    if (st == CTC_STATUS_SUCCESS) *bytes_out = lay.total;
+    return st;
+}
+
+ctc_status_t ctc_loss_and_grad(const void* activations, const int32_t* flat_labels,
+                               const int32_t* label_lengths, const int32_t* input_lengths,
+                               int T, int B, int A, int blank, ctc_dtype_t dtype, float* costs,
+                               void* grads, void* workspace, size_t workspace_bytes, void* stream)
+{
+    ctc::Call c{activations, flat_labels, label_lengths, input_lengths, T, B, A, blank, dtype,
+                costs, grads, workspace, workspace_bytes, stream};
+    return ctc::run(c, nullptr);
+}
+
+ctc_status_t ctc_profile_kernels(const void* activations, const int32_t* flat_labels,
+                                 const int32_t* label_lengths, const int32_t* input_lengths,
+                                 int T, int B, int A, int blank, ctc_dtype_t dtype, float* costs,
+                                 void* grads, void* workspace, size_t workspace_bytes, void* stream,
+                                 float* kernel_ms)
+{
+    if (!kernel_ms) return CTC_STATUS_INVALID_VALUE;
+    ctc::Call c{activations, flat_labels, label_lengths, input_lengths, T, B, A, blank, dtype,
+                costs, grads, workspace, workspace_bytes, stream};
+    return ctc::run(c, kernel_ms);
+}
+
+const char* ctc_kernel_name(int index)
+{
+    switch (index) {
+        case CTC_KERNEL_SETUP: return "ctc_setup_kernel";
+        case CTC_KERNEL_SOFTMAX: return "ctc_softmax_kernel";
+        case CTC_KERNEL_LATTICE: return "ctc_lattice_kernel";
+        case CTC_KERNEL_GRADIENT: return "ctc_gradient_kernel";
+        default: return nullptr;
+    }
+}
+
+const char* ctc_status_string(ctc_status_t status)
+{
+    switch (status) {
+        case CTC_STATUS_SUCCESS: return "success";
+        case CTC_STATUS_INVALID_VALUE: return "invalid value";
+        case CTC_STATUS_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case CTC_STATUS_HIP_ERROR: return "HIP runtime error";
+        case CTC_STATUS_UNSUPPORTED: return "unsupported size";
+        default: return "unknown status";
+    }
+}
+
+int ctc_last_hip_error(void) { return ctc::g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Internal interfaces between the host launcher and the HIP kernels of the CTC library.
+// Not part of the public ABI (that is include/ctc_mi355x.h).
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+#include "ctc_mi355x.h"
+
+namespace ctc {
+
+// Per-utterance record, identical on host and device (32 bytes).
+struct Utt {
+    int32_t Tb;        // frames of this utterance (input_lengths[b])
+    int32_t L;         // label length
+    int32_t lab_off;   // offset of its label string in the flat label array
+    int32_t flags;     // bit 0: the lattice runs (Tb > 0 and an alignment exists)
+    int64_t e_off;     // offset (floats) of its emission block  [Tb][L+1]
+    int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][2(L+1)]
+};
+static_assert(sizeof(Utt) == 32, "Utt must stay 32 bytes");
+
+constexpr int kUttRuns = 1;
+
+// Byte offsets of the workspace regions, all multiples of 256.
+struct Layout {
+    size_t meta = 0;      // Utt[B]
+    size_t order = 0;     // int32[B]     utterances whose lattice runs, heaviest first
+    size_t labels = 0;    // int32[sumL]
+    size_t links = 0;     // int32[sumL]  next-occurrence links of equal symbols
+    size_t logp = 0;      // double[B]    log2 of the alignment mass
+    size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits
+    size_t emit = 0;      // float[sum Tb*(L+1)]   log2 emissions of blank and each label position
+    size_t alpha = 0;     // double[sum Tb*2(L+1)]
+    size_t beta = 0;      // double[sum Tb*2(L+1)]
+    size_t total = 0;
+    size_t upload_bytes = 0;   // meta..labels are contiguous and sent in one copy
+    int64_t sumL = 0;
+    int64_t emit_floats = 0;
+    int64_t ab_doubles = 0;
+};
+
+// Fills `lay` from the batch shape. Returns a status (argument checks on sizes and lengths).
+ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
+                         const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay);
+
+// Kernel launch parameters shared by all stages.
+struct Launch {
+    int T, B, A, blank;
+    ctc_dtype_t dtype;
+    int n_run;          // utterances whose lattice runs
+    int max_waves;      // wavefronts per lattice block
+    const void* x;
+    void* grads;
+    float* costs;
+    char* ws;           // workspace base
+    Layout lay;
+};
+
+// Each returns a hipError_t as int (0 = success). `stream` is a hipStream_t.
+int launch_setup(const Launch& p, void* stream);
+int launch_softmax(const Launch& p, void* stream);
+int launch_lattice(const Launch& p, void* stream);
+int launch_gradient(const Launch& p, void* stream);
+
+}  // namespace ctc

@@ -1,0 +1,70 @@
+"""Torch-side plumbing around the binding: device buffers, streams, result download.
+
+PyTorch is used for device memory and streams only; every step of the CTC path runs
+in the HIP library.  Used by the GPU tests, the smoke check and the benchmark.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import ctc, workloads
+
+
+def require_gpu() -> torch.device:
+    if not torch.cuda.is_available():
+        raise RuntimeError("a HIP device is required: the CTC path has no CPU fallback")
+    return torch.device("cuda:0")
+
+
+class DeviceBatch:
+    """A CTCBatch with its activations resident in HBM plus output and workspace buffers."""
+
+    def __init__(self, batch: workloads.CTCBatch, dtype: int = ctc.DTYPE_F32, device=None,
+                 poison: bool = True):
+        self.device = device or require_gpu()
+        self.batch = batch
+        self.dtype = dtype
+        if dtype == ctc.DTYPE_F32:
+            host = torch.from_numpy(np.ascontiguousarray(batch.logits, dtype=np.float32))
+            self.x = host.to(self.device)
+        else:
+            bits = workloads.bf16_bits(batch.logits).view(np.int16)
+            self.x = torch.from_numpy(bits).to(self.device).view(torch.bfloat16)
+        self.grads = torch.empty_like(self.x)
+        self.costs = torch.empty(batch.B, dtype=torch.float32, device=self.device)
+        self.ws_bytes = ctc.workspace_size(batch.T, batch.B, batch.A, batch.label_lengths,
+                                           batch.input_lengths, dtype)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
+        if poison:
+            self.poison()
+
+    def poison(self):
+        """Fill outputs and workspace with NaN bit patterns so that stale data cannot pass."""
+        self.ws.fill_(0xFF)
+        self.grads.view(torch.uint8).fill_(0xFF)
+        self.costs.fill_(float("nan"))
+
+    def run(self, stream=None, kernel_ms=None):
+        b = self.batch
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        ctc.loss_and_grad(self.x.data_ptr(), b.flat_labels, b.label_lengths, b.input_lengths,
+                          b.T, b.B, b.A, b.blank, self.dtype, self.costs.data_ptr(),
+                          self.grads.data_ptr(), self.ws_ptr, self.ws_bytes, s, kernel_ms)
+
+    def results(self):
+        """(costs float32 [B], grads float32 [T,B,A]) on the host, after synchronising."""
+        torch.cuda.synchronize(self.device)
+        costs = self.costs.cpu().numpy()
+        if self.dtype == ctc.DTYPE_F32:
+            grads = self.grads.cpu().numpy()
+        else:
+            grads = self.grads.float().cpu().numpy()
+        return costs, grads
+
+
+def run_batch(batch: workloads.CTCBatch, dtype: int = ctc.DTYPE_F32):
+    db = DeviceBatch(batch, dtype)
+    db.run()
+    return db.results()

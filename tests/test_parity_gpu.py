@@ -1,0 +1,176 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Tolerances (fp32 activations): costs within 1e-4 relative (floored at |ref| = 1e-2),
+gradients within 1e-4 absolute.  bf16 activations: the oracle is fed the bf16-rounded
+logits; costs within 2e-2 relative, gradients within 1e-2 absolute (the output itself is
+rounded to bf16).  +inf costs must match exactly.
+"""
+import numpy as np
+import pytest
+
+from oracle import ctc_oracle as orc
+from paper_1512_02595_amd import ctc, harness
+from paper_1512_02595_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+COST_RTOL, GRAD_ATOL = 1e-4, 1e-4
+BF16_COST_RTOL, BF16_GRAD_ATOL = 2e-2, 1e-2
+
+
+def check(batch, dtype=ctc.DTYPE_F32, nthreads=0):
+    print(f"case {batch.name} seed={batch.seed} T={batch.T} B={batch.B} A={batch.A} dtype={dtype}", flush=True)
+    logits = batch.logits if dtype == ctc.DTYPE_F32 else wl.to_bf16_grid(batch.logits)
+    ref_c, ref_g = orc.ctc_loss_and_grad(logits, batch.flat_labels, batch.label_lengths,
+                                         batch.input_lengths, batch.blank, nthreads=nthreads)
+    costs, grads = harness.run_batch(batch, dtype)
+    rtol, atol = (COST_RTOL, GRAD_ATOL) if dtype == ctc.DTYPE_F32 else (BF16_COST_RTOL, BF16_GRAD_ATOL)
+    inf = np.isinf(ref_c)
+    assert np.array_equal(np.isinf(costs) & (costs > 0), inf), (costs, ref_c)
+    fin = ~inf
+    err_c = np.abs(costs[fin] - ref_c[fin]) / np.maximum(np.abs(ref_c[fin]), 1e-2)
+    assert not np.isnan(costs).any()
+    assert err_c.size == 0 or err_c.max() <= rtol, f"cost rel err {err_c.max()}"
+    assert not np.isnan(grads).any()
+    err_g = np.abs(grads - ref_g).max()
+    assert err_g <= atol, f"grad abs err {err_g}"
+    for b in range(batch.B):                       # padding rows are exact zeros
+        assert not grads[batch.input_lengths[b]:, b, :].any()
+        if inf[b]:
+            assert not grads[:, b, :].any()
+    return costs, grads, float(err_c.max()) if err_c.size else 0.0, float(err_g)
+
+
+def test_tiny_config():
+    check(wl.make_config(0))
+
+
+def test_english_config():
+    check(wl.make_config(1))
+
+
+def test_long_config():
+    check(wl.make_config(3))
+
+
+def test_mandarin_config():
+    check(wl.make_config(2))
+
+
+def test_sweep_config_fp32():
+    check(wl.make_config(4))
+
+
+def test_sweep_config_bf16():
+    check(wl.make_config(4), ctc.DTYPE_BF16)
+
+
+@pytest.mark.parametrize("seed,kw", [
+    (1, dict(T=12, B=5, A=6, max_label=4)),
+    (2, dict(T=40, B=9, A=9, max_label=30)),                       # many infeasible pairs
+    (3, dict(T=70, B=6, A=3, max_label=69, min_input=60)),         # labels spanning two wavefronts
+    (4, dict(T=300, B=7, A=5, max_label=290, min_input=250, feasible_only=True)),   # up to 5 wavefronts
+    (5, dict(T=33, B=4, A=2, max_label=20, blank=1)),              # one non-blank symbol: all repeats
+    (6, dict(T=25, B=8, A=40, max_label=12, blank=39, sigma=4.0)),
+    (7, dict(T=20, B=3, A=1030, max_label=10, blank=517)),         # alphabet not a multiple of 4
+    (8, dict(T=64, B=5, A=64, max_label=63, feasible_only=True)),
+])
+def test_random_shapes(seed, kw):
+    check(wl.make_random(seed, **kw))
+
+
+def test_random_shapes_bf16():
+    check(wl.make_random(9, T=50, B=6, A=29, max_label=20, sigma=2.0, feasible_only=True), ctc.DTYPE_BF16)
+    check(wl.make_random(10, T=30, B=3, A=1001, max_label=10), ctc.DTYPE_BF16)
+
+
+def test_degenerate_lengths():
+    """Empty labels, zero frames, single frames, the feasibility boundary."""
+    rng = np.random.default_rng(0)
+    T, A = 9, 5
+    labels = [[], [], [1], [1], [2, 2], [2, 2], [1, 2, 3, 4], [3, 3, 3], [4]]
+    in_len = [0, 9, 0, 1, 2, 3, 4, 5, 9]
+    b = wl.CTCBatch(name="degenerate", T=T, B=len(labels), A=A, blank=0,
+                    logits=rng.standard_normal((T, len(labels), A), dtype=np.float32),
+                    flat_labels=np.array([k for l in labels for k in l], dtype=np.int32),
+                    label_lengths=np.array([len(l) for l in labels], dtype=np.int32),
+                    input_lengths=np.array(in_len, dtype=np.int32))
+    costs, _, _, _ = check(b)
+    assert costs[0] == 0.0 and np.isinf(costs[2]) and np.isinf(costs[4]) and np.isfinite(costs[5])
+
+
+def test_longest_supported_label():
+    L = ctc.MAX_LABEL_LENGTH
+    rng = np.random.default_rng(1)
+    T, A = L + 40, 4
+    lab = rng.integers(1, A, size=L)
+    for i in range(1, L):                      # no adjacent repeats, so that T suffices
+        if lab[i] == lab[i - 1]:
+            lab[i] = 1 + (lab[i] % (A - 1))
+    b = wl.CTCBatch(name="maxlabel", T=T, B=2, A=A, blank=0,
+                    logits=rng.standard_normal((T, 2, A), dtype=np.float32),
+                    flat_labels=np.concatenate([lab, lab[:100]]).astype(np.int32),
+                    label_lengths=np.array([L, 100], dtype=np.int32),
+                    input_lengths=np.array([T, 300], dtype=np.int32))
+    check(b)
+
+
+def test_padding_may_hold_nan_and_results_repeat_bitwise():
+    b = wl.make_random(21, T=48, B=6, A=11, max_label=15, min_input=10, feasible_only=True)
+    clean_c, clean_g, _, _ = check(b)
+    x = b.logits.copy()
+    for i in range(b.B):
+        x[b.input_lengths[i]:, i, :] = np.nan
+    b2 = wl.CTCBatch(**{**b.__dict__, "logits": x})
+    db = harness.DeviceBatch(b2)
+    db.run()
+    c1, g1 = db.results()
+    assert np.array_equal(c1, clean_c) and np.array_equal(g1, clean_g)
+    db.poison()
+    db.run()
+    c2, g2 = db.results()
+    assert np.array_equal(c1, c2) and np.array_equal(g1, g2)
+
+
+def test_back_to_back_calls_with_different_batches():
+    """Host arrays are consumed before the call returns: a second call may follow at once."""
+    b1 = wl.make_random(31, T=60, B=8, A=7, max_label=20, feasible_only=True)
+    b2 = wl.make_random(32, T=60, B=8, A=7, max_label=20, feasible_only=True)
+    d1, d2 = harness.DeviceBatch(b1), harness.DeviceBatch(b2)
+    for _ in range(3):
+        d1.run()
+        d2.run()
+    for d, b in ((d1, b1), (d2, b2)):
+        c, g = d.results()
+        rc, rg = orc.ctc_loss_and_grad(b.logits, b.flat_labels, b.label_lengths, b.input_lengths, b.blank)
+        assert np.abs(g - rg).max() <= GRAD_ATOL
+        fin = np.isfinite(rc)
+        assert (np.abs(c[fin] - rc[fin]) <= COST_RTOL * np.maximum(np.abs(rc[fin]), 1e-2)).all()
+
+
+def test_runs_on_a_side_stream():
+    import torch
+    b = wl.make_random(41, T=30, B=4, A=8, max_label=8, feasible_only=True)
+    db = harness.DeviceBatch(b)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        db.run()
+    s.synchronize()
+    c, g = db.results()
+    rc, rg = orc.ctc_loss_and_grad(b.logits, b.flat_labels, b.label_lengths, b.input_lengths, b.blank)
+    assert np.abs(g - rg).max() <= GRAD_ATOL
+
+
+def test_device_side_errors_are_reported_as_status():
+    b = wl.make_random(51, T=10, B=2, A=5, max_label=3, feasible_only=True)
+    db = harness.DeviceBatch(b)
+    args = dict(T=b.T, B=b.B, A=b.A, blank=b.blank, dtype=ctc.DTYPE_F32)
+    st = ctc.loss_and_grad_status(db.x.data_ptr(), b.flat_labels, b.label_lengths, b.input_lengths,
+                                  costs_ptr=db.costs.data_ptr(), grads_ptr=db.grads.data_ptr(),
+                                  workspace_ptr=db.ws_ptr, workspace_bytes=db.ws_bytes - 1, **args)
+    assert st == ctc.STATUS_WORKSPACE_TOO_SMALL
+    st = ctc.loss_and_grad_status(db.x.data_ptr(), b.flat_labels, b.label_lengths, b.input_lengths,
+                                  costs_ptr=db.costs.data_ptr(), grads_ptr=db.x.data_ptr(),
+                                  workspace_ptr=db.ws_ptr, workspace_bytes=db.ws_bytes, **args)
+    assert st == ctc.STATUS_INVALID_VALUE
