@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched CTC cost + gradient on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--dtype f32|bf16]
+
+A step is one ctc_loss_and_grad call (host launcher + all kernels) over one synthetic
+minibatch whose activations already sit in HBM.  The default workload is the English-shaped
+per-GPU minibatch (config index 1: B=64, A=29, T<=750).  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+# One non-packed, non-fused VALU operation per lane per clock: 256 CUs x 64 lanes x 2.4 GHz.
+# (The published 157.3 TFLOP/s fp32 vector figure counts 2 for packing and 2 for FMA on top.)
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# Lane-operations of one step of one (blank, label) state pair in one direction:
+# 5 transcendentals at quarter rate (= 20) + 25 plain operations.
+LANE_OPS_PER_PAIR_STEP = 45
+
+
+def kernel_bytes(batch, elem):
+    """Algorithmic HBM bytes of each kernel for one launch on `batch`."""
+    frames = batch.frames
+    A = batch.A
+    pairs = int((batch.input_lengths.astype(np.int64) * (batch.label_lengths.astype(np.int64) + 1)).sum())
+    cells = batch.lattice_cells
+    return {
+        "ctc_setup_kernel": int(batch.flat_labels.size) * 8,
+        # read every valid row once; write one statistic per row
+        "ctc_softmax_kernel": frames * A * elem + frames * 4,
+        # one alpha and one beta value per lattice cell, 4 bytes each, written once
+        "ctc_lattice_kernel": cells * 8,
+        # read every valid row again, write the whole gradient tensor
+        "ctc_gradient_kernel": frames * A * elem + batch.T * batch.B * A * elem,
+    }, pairs
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="0..4, index into the workload list")
+    ap.add_argument("--dtype", choices=("f32", "bf16"), default="f32")
+    ap.add_argument("--buffers", type=int, default=4, help="distinct minibatches rotated through")
+    ap.add_argument("--profile-steps", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path needs no collective; "
+                 "utterances would simply be split across ranks). Use --gpus 1.")
+
+    import torch
+    from paper_1512_02595_amd import ctc, harness, workloads
+
+    dev = harness.require_gpu()
+    ctc.load()
+    dtype = ctc.DTYPE_F32 if args.dtype == "f32" else ctc.DTYPE_BF16
+    elem = 4 if dtype == ctc.DTYPE_F32 else 2
+
+    batches = [workloads.make_config(args.config, seed=workloads.BASE_SEED + args.config + 1000 * i)
+               for i in range(args.buffers)]
+    dbs = [harness.DeviceBatch(b, dtype, dev, poison=False) for b in batches]
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    for i in range(args.warmup):
+        dbs[i % len(dbs)].run(stream)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        dbs[i % len(dbs)].run(stream)
+    torch.cuda.synchronize(dev)
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    B = batches[0].B
+    frames = float(np.mean([b.frames for b in batches]))
+    compulsory = float(np.mean([b.compulsory_bytes(elem) for b in batches]))
+
+    # Per-kernel device time, HIP events on the launch stream (ctc_profile_kernels).
+    kms = np.zeros((args.profile_steps, ctc.NUM_KERNELS), dtype=np.float32)
+    for i in range(args.profile_steps):
+        dbs[i % len(dbs)].run(stream, kernel_ms=kms[i])
+    kavg = [float(v) for v in kms.mean(axis=0)]
+    names = [ctc.kernel_name(i) for i in range(ctc.NUM_KERNELS)]
+    kb = [kernel_bytes(b, elem) for b in batches]
+    kernels = {}
+    for i, n in enumerate(names):
+        byt = float(np.mean([k[0][n] for k in kb]))
+        kernels[n] = {"ms": round(kavg[i], 5), "algorithmic_bytes": int(byt),
+                      "GBps": round(byt / (kavg[i] * 1e-3) / 1e9, 2) if kavg[i] > 0 else None}
+    dom = int(np.argmax(kavg))
+    dom_name = names[dom]
+    if dom_name == "ctc_lattice_kernel":
+        pair_steps = 2.0 * float(np.mean([k[1] for k in kb]))       # both directions
+        achieved = pair_steps * LANE_OPS_PER_PAIR_STEP / (kavg[dom] * 1e-3) / 1e12
+        roofline = {"kernel": dom_name, "bound": "alu", "achieved": round(achieved, 4),
+                    "peak": round(ALU_PEAK_TOPS, 2), "unit": "TFLOP/s",
+                    "frac": round(achieved / ALU_PEAK_TOPS, 5), "traffic": None,
+                    "note": "flop = one non-packed VALU lane-operation; transcendental = 4"}
+    else:
+        achieved = kernels[dom_name]["GBps"]
+        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None}
+
+    out = {
+        "metric": "ctc_loss_grad_utterances_per_s",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "utterances/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64 lattice state, f32 transcendentals, %s activations" % args.dtype,
+        "data": "synthetic",
+        "config": {"workload": "config[%d] %s: B=%d A=%d T=%d, %d rotating minibatches"
+                   % (args.config, batches[0].name, B, batches[0].A, batches[0].T, len(batches))},
+        "activation_frames_per_s": round(frames / (ms_per_step * 1e-3), 1),
+        "hbm_roofline_frac_end_to_end": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+        "compulsory_bytes": int(compulsory),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import ctc_oracle as orc
+        b = batches[0]
+        x64 = b.logits.astype(np.float64) if dtype == ctc.DTYPE_F32 else workloads.to_bf16_grid(b.logits).astype(np.float64)
+        nb = b.B
+        # Bounded sample: whole minibatch if its lattice is small enough, else its first utterances.
+        budget_cells = 60e6
+        if b.lattice_cells + b.frames * b.A > budget_cells:
+            w = b.input_lengths.astype(np.int64) * (2 * b.label_lengths.astype(np.int64) + 1 + b.A)
+            nb = max(1, int(np.searchsorted(np.cumsum(w), budget_cells)))
+        nlab = int(b.label_lengths[:nb].sum())
+        xs = np.ascontiguousarray(x64[:, :nb, :])
+        reps, times = 3, []
+        for _ in range(reps):
+            c0 = time.perf_counter()
+            orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank)
+            times.append(time.perf_counter() - c0)
+        tmed = float(np.median(times))
+        out["cpu_baseline"] = {"value": round(nb / tmed, 2), "unit": "utterances/s",
+                               "cores": orc.max_threads(), "kind": "oracle",
+                               "sample": "first %d of %d utterances of minibatch 0, median of %d runs, %.3f s each"
+                                         % (nb, b.B, reps, tmed),
+                               "activation_frames_per_s": round(float(b.input_lengths[:nb].sum()) / tmed, 1)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
