@@ -94,7 +94,7 @@ def main():
     kms = np.zeros((args.profile_steps, ctc.NUM_KERNELS), dtype=np.float32)
     for i in range(args.profile_steps):
         dbs[i % len(dbs)].run(stream, kernel_ms=kms[i])
-    kavg = [float(v) for v in kms.mean(axis=0)]
+    kavg = [float(v) for v in kms.mean(axis=0)] if args.profile_steps else [1e-9] * ctc.NUM_KERNELS
     names = [ctc.kernel_name(i) for i in range(ctc.NUM_KERNELS)]
     kb = [kernel_bytes(b, elem) for b in batches]
     kernels = {}

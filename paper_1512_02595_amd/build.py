@@ -21,6 +21,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 def command(out: str = LIB) -> list[str]:
     return [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+            # no NaN ever enters the arithmetic (log 0 is a finite sentinel): lets max/min
+            # skip the quieting of their operands
+            "-fno-honor-nans",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-x", "hip",
             "-Wall", "-Wextra", "-Wno-unused-command-line-argument",

@@ -35,32 +35,41 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
     if (!label_lengths || !input_lengths || !lay) return CTC_STATUS_INVALID_VALUE;
     if (T < 1 || B < 1 || A < 1) return CTC_STATUS_INVALID_VALUE;
     if (dtype != CTC_DTYPE_F32 && dtype != CTC_DTYPE_BF16) return CTC_STATUS_INVALID_VALUE;
-    int64_t sumL = 0, emit = 0, ab = 0;
+    int64_t sumL = 0, emit = 0, ab = 0, frames = 0;
     bool too_long = false;
     for (int b = 0; b < B; ++b) {
         const int64_t L = label_lengths[b], Tb = input_lengths[b];
         if (L < 0 || Tb < 0 || Tb > T) return CTC_STATUS_INVALID_VALUE;
         if (L > CTC_MAX_LABEL_LENGTH) too_long = true;
         sumL += L;
-        emit += Tb * (L + 1);
+        emit += Tb * L;
+        frames += Tb;
+        // per-utterance byte offsets inside the kernels are 32-bit
+        if (Tb * 2 * (L + 1) * 8 > INT32_MAX) too_long = true;
         ab += Tb * 2 * (L + 1);
     }
     if (too_long) return CTC_STATUS_UNSUPPORTED;
-    if (sumL > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
+    if (sumL > INT32_MAX || frames > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
     Layout l;
     l.sumL = sumL;
     l.emit_floats = emit;
+    l.frames = frames;
     l.ab_doubles = ab;
     size_t off = 0;
-    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 32 B each: stays 4-byte aligned
+    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 40 B each: stays 8-byte aligned
     l.order = off;  off += static_cast<size_t>(B) * sizeof(int32_t);
     l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
     l.upload_bytes = off;
     off = align_up(off);
     l.links = off;  off = align_up(off + static_cast<size_t>(sumL) * sizeof(int32_t));
     l.logp = off;   off = align_up(off + static_cast<size_t>(B) * sizeof(double));
+    l.sink = off;   off = align_up(off + 256);
+    l.chain_err = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.lse = off;    off = align_up(off + static_cast<size_t>(B) * T * sizeof(float));
-    l.emit = off;   off = align_up(off + static_cast<size_t>(emit) * sizeof(float));
+    l.emit_blank = off;
+    off = align_up(off + (static_cast<size_t>(frames) + 2 * kBlankSlack) * sizeof(float));
+    l.emit_label = off;
+    off = align_up(off + (static_cast<size_t>(emit) + 2 * kLabelSlack) * sizeof(float));
     l.alpha = off;  off = align_up(off + static_cast<size_t>(ab) * sizeof(double));
     l.beta = off;   off = align_up(off + static_cast<size_t>(ab) * sizeof(double));
     l.total = off;
@@ -112,8 +121,8 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     int32_t* order = reinterpret_cast<int32_t*>(image->data() + lay.order);
     int32_t* labels = reinterpret_cast<int32_t*>(image->data() + lay.labels);
 
-    int64_t lab_off = 0, e_off = 0, ab_off = 0;
-    int n_run = 0, max_waves = 1;
+    int64_t lab_off = 0, e_off = 0, ab_off = 0, f_off = 0;
+    int n_run = 0, max_waves = 1, max_frames = 0;
     for (int b = 0; b < c.B; ++b) {
         const int L = c.label_lengths[b], Tb = c.input_lengths[b];
         const int32_t* lab = c.flat_labels + lab_off;
@@ -131,14 +140,18 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
         m.L = L;
         m.lab_off = static_cast<int32_t>(lab_off);
         m.flags = runs ? kUttRuns : 0;
+        m.f_off = static_cast<int32_t>(f_off);
+        m.reserved = 0;
         m.e_off = e_off;
         m.ab_off = ab_off;
         lab_off += L;
-        e_off += static_cast<int64_t>(Tb) * (L + 1);
+        e_off += static_cast<int64_t>(Tb) * L;
+        f_off += Tb;
         ab_off += static_cast<int64_t>(Tb) * 2 * (L + 1);
         if (runs) {
             order[n_run++] = b;
             max_waves = std::max(max_waves, (L + 1 + 63) / 64);
+            max_frames = std::max(max_frames, Tb);
         }
     }
     for (int i = n_run; i < c.B; ++i) order[i] = -1;
@@ -155,6 +168,7 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     out->dtype = c.dtype;
     out->n_run = n_run;
     out->max_waves = max_waves;
+    out->max_frames = max_frames;
     out->x = c.x;
     out->grads = c.grads;
     out->costs = c.costs;

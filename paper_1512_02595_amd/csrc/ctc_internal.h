@@ -9,18 +9,30 @@
 
 namespace ctc {
 
-// Per-utterance record, identical on host and device (32 bytes).
+// Per-utterance record, identical on host and device (40 bytes).
 struct Utt {
     int32_t Tb;        // frames of this utterance (input_lengths[b])
     int32_t L;         // label length
     int32_t lab_off;   // offset of its label string in the flat label array
     int32_t flags;     // bit 0: the lattice runs (Tb > 0 and an alignment exists)
-    int64_t e_off;     // offset (floats) of its emission block  [Tb][L+1]
+    int32_t f_off;     // frames of all earlier utterances: offset of its blank emissions [Tb]
+    int32_t reserved;
+    int64_t e_off;     // offset (floats) of its label emissions [Tb][L]
     int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][2(L+1)]
 };
-static_assert(sizeof(Utt) == 32, "Utt must stay 32 bytes");
+static_assert(sizeof(Utt) == 40, "Utt must stay 40 bytes");
 
 constexpr int kUttRuns = 1;
+
+// The lattice kernel reads emissions ahead of the recursion without bounds checks.  It
+// fetches kChunk steps at a time and, at the start of a pass that begins at step s0 <= Tb-1,
+// has requested steps up to s0 + 3*kChunk - 1: at most 3*kChunk - 1 rows past either end of
+// an utterance's block (past the end going forward, before the start going backward).  These
+// margins keep such reads inside the workspace; the values read there are never used.
+constexpr int kChunk = 16;            // steps whose emissions are fetched together
+constexpr int kOverFetchRows = 3 * kChunk;
+constexpr int kBlankSlack = kOverFetchRows + kChunk;                          // floats, each side
+constexpr int kLabelSlack = kOverFetchRows * (CTC_MAX_LABEL_LENGTH + 1);      // floats, each side
 
 // Byte offsets of the workspace regions, all multiples of 256.
 struct Layout {
@@ -29,13 +41,18 @@ struct Layout {
     size_t labels = 0;    // int32[sumL]
     size_t links = 0;     // int32[sumL]  next-occurrence links of equal symbols
     size_t logp = 0;      // double[B]    log2 of the alignment mass
+    size_t sink = 0;      // 256 bytes that lanes without a lattice pair may scribble on
+    size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
     size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits
-    size_t emit = 0;      // float[sum Tb*(L+1)]   log2 emissions of blank and each label position
+    size_t emit_blank = 0; // float[64 + sum Tb + 64]  log2 emission of blank per frame, slack both sides
+    size_t emit_label = 0; // float[slack + sum Tb*L + slack]  log2 emission of each label position;
+                           // the first float of the front slack holds the log-0 constant
     size_t alpha = 0;     // double[sum Tb*2(L+1)]
     size_t beta = 0;      // double[sum Tb*2(L+1)]
     size_t total = 0;
     size_t upload_bytes = 0;   // meta..labels are contiguous and sent in one copy
     int64_t sumL = 0;
+    int64_t frames = 0;
     int64_t emit_floats = 0;
     int64_t ab_doubles = 0;
 };
@@ -50,6 +67,7 @@ struct Launch {
     ctc_dtype_t dtype;
     int n_run;          // utterances whose lattice runs
     int max_waves;      // wavefronts per lattice block
+    int max_frames;     // longest utterance among those whose lattice runs
     const void* x;
     void* grads;
     float* costs;

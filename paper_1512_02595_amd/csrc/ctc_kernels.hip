@@ -91,9 +91,11 @@ __device__ __forceinline__ float block_max(float v, float* slot)
 // symbol is summed in a fixed order (positions ascending) and each symbol has one writer.
 __global__ __launch_bounds__(kRowThreads)
 void ctc_setup_kernel(const Utt* __restrict__ meta, const int* __restrict__ labels,
-                      int* __restrict__ links, float* __restrict__ costs)
+                      int* __restrict__ links, float* __restrict__ costs, int* __restrict__ chain_err,
+                      float* __restrict__ emit_label)
 {
     const int b = blockIdx.x;
+    if (b == 0 && threadIdx.x == 0) emit_label[0] = static_cast<float>(kNeg);   // read by lanes without a label state
     const Utt m = meta[b];
     const int* lab = labels + m.lab_off;
     for (int j = threadIdx.x; j < m.L; j += kRowThreads) {
@@ -106,6 +108,7 @@ void ctc_setup_kernel(const Utt* __restrict__ meta, const int* __restrict__ labe
             if (lab[i] == c) { first = false; break; }
         links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
     }
+    if (threadIdx.x == 0) chain_err[b] = 0;
     if (threadIdx.x == 0 && !(m.flags & kUttRuns)) {
         // No frames: the empty product (cost 0) for an empty label.  Otherwise no alignment.
         costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
@@ -118,7 +121,8 @@ template <typename T>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
                         const int* __restrict__ labels, float* __restrict__ lse,
-                        float* __restrict__ emit, int Tt, int B, int A, int blank)
+                        float* __restrict__ emit_blank, float* __restrict__ emit_label,
+                        int Tt, int B, int A, int blank)
 {
     __shared__ float red[8];
     const int t = blockIdx.x, b = blockIdx.y;
@@ -137,22 +141,21 @@ void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
     if (threadIdx.x == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
 
     if (!(m.flags & kUttRuns)) return;
-    const int P = m.L + 1;
-    float* erow = emit + m.e_off + static_cast<size_t>(t) * P;
+    if (threadIdx.x == 0)
+        emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
+    float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
-    for (int j = threadIdx.x; j < P; j += kRowThreads) {
-        const int sym = (j == 0) ? blank : lab[j - 1];
-        erow[j] = fmaf(load_elem(row, sym), kLog2e, -l2);
-    }
+    for (int j = threadIdx.x; j < m.L; j += kRowThreads)
+        erow[j] = fmaf(load_elem(row, lab[j]), kLog2e, -l2);
 }
 
 // ---- lattice recursions ------------------------------------------------------------------
 // log2(2^a + 2^b) for fp64 a, b with the exponentials taken on the fp32 difference.
 __device__ __forceinline__ double lse2(double a, double b)
 {
-    const double hi = fmax(a, b), lo = fmin(a, b);
-    const float d = static_cast<float>(lo - hi);
-    return hi + static_cast<double>(fast_log2(1.0f + fast_exp2(d)));
+    const double hi = fmax(a, b);
+    const float d = static_cast<float>(a - b);
+    return hi + static_cast<double>(fast_log2(1.0f + fast_exp2(-fabsf(d))));
 }
 __device__ __forceinline__ double lse3(double a, double b, double c)
 {
@@ -165,159 +168,260 @@ __device__ __forceinline__ double lse3(double a, double b, double c)
     return hi + static_cast<double>(fast_log2(1.0f + fast_exp2(mid) + fast_exp2(mn)));
 }
 
-// Value of lane-1 within the wavefront (DPP wave_shr:1); lane 0 receives `fill`.
-__device__ __forceinline__ double from_lower_lane(double v, double fill)
+// Lane i receives the value of lane i-1 (DPP wave_shr:1); lane 0 keeps `lane0`.
+__device__ __forceinline__ double shift_up(double v, double lane0)
 {
     int lo = __double2loint(v), hi = __double2hiint(v);
-    lo = __builtin_amdgcn_update_dpp(__double2loint(fill), lo, 0x138, 0xf, 0xf, false);
-    hi = __builtin_amdgcn_update_dpp(__double2hiint(fill), hi, 0x138, 0xf, 0xf, false);
+    lo = __builtin_amdgcn_update_dpp(__double2loint(lane0), lo, 0x138, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(__double2hiint(lane0), hi, 0x138, 0xf, 0xf, false);
     return __hiloint2double(hi, lo);
 }
 
-constexpr int kPrefetch = 8;   // frames of emissions kept in flight ahead of the recursion
+constexpr int kEmptyHi = -1;          // high word of an unwritten LDS slot (a NaN no result can be)
+constexpr int kSpinBudget = 1 << 22;  // polls a wavefront may spend waiting before it gives up
+
+enum class Sync { kNone, kSlots, kBarrier };
 
 // One chain = one direction of one utterance.  Thread j owns the pair
 //   forward : (blank state 2j,       label j        = state 2j+1)
 //   backward: (blank state 2(L-j),   label L-1-j    = state 2(L-j)-1)
 // so that in both directions the only value needed from a neighbour is the label entry of
-// pair j-1.  Forward carries alpha including the own frame's emission; backward carries beta
-// excluding it (so log alpha + log beta is the log mass of alignments through a state).
+// pair j-1, and both directions run the same recursion on the "inclusive" quantity
+//   w_step(state) = E_frame(state) + log2 sum over predecessors of 2^w_{step-1}
+// which is alpha going forward.  Going backward, the sum before E is added is the beta that
+// excludes its own frame's emission, and that is what gets stored, so that
+// log alpha + log beta is the log mass of alignments through a state.
 //
 // Storage (row pitch 2(L+1) doubles, i.e. the appendix's S = 2(L+1) rows with one that stays
-// at log 0): alpha_row[s] = alpha(s); beta_row[s+1] = beta(s).
-template <bool kBackward>
+// at or below log 0): alpha_row[s] = alpha(s); beta_row[s+1] = beta(s).
+//
+// A lone wavefront per SIMD issues one instruction every four clocks whatever its kind, so
+// the step is written for instruction count: pointers advance by adds, the blank emissions of
+// a chunk arrive in one load and are read by lane, lanes without a pair are switched off once.
+//
+// Wavefronts of one chain (64 pairs each) exchange one value per step.  With Sync::kSlots the
+// label value of lane 63 is published per step in an LDS slot of its own (row wave+1, column
+// step; rows start "empty", row 0 is all log 0 for wavefront 0), and every lane of the next
+// wavefront reads that slot (one broadcast read, issued a step early) and polls while it is
+// empty: no barrier, the wavefronts run skewed by a step or two.  A wavefront depends only on
+// lower ones and wavefront 0 never waits, so every wait ends; a poll budget bounds it anyway.
+template <bool kBackward, Sync kSync>
 __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* __restrict__ labels,
-                                          const float* __restrict__ emit, double* __restrict__ out,
-                                          double* __restrict__ logp, float* __restrict__ costs,
-                                          double (*xch)[16])
+                                          const float* __restrict__ emit_blank,
+                                          const float* __restrict__ emit_label,
+                                          double* __restrict__ out, double* __restrict__ logp,
+                                          float* __restrict__ costs, int* __restrict__ chain_err,
+                                          double* __restrict__ sink, double* lds)
 {
     const int L = m.L, Tb = m.Tb, P = L + 1;
     const int j = threadIdx.x, lane = j & 63, wave = j >> 6;
+    const bool active = j < P;                           // lanes beyond pair L only go through the motions
+    const int last_wave = L >> 6;                        // wavefront that holds pair L
     const int* lab = labels + m.lab_off;
     const bool has_label = j < L;
-    const bool active = j < P;
     const int li = kBackward ? (L - 1 - j) : j;          // label index of this pair's label state
-    bool skip = false;                                   // may the label state be entered from pair j-1's label?
-    if (has_label && j >= 1) skip = lab[li] != lab[kBackward ? (li + 1) : (li - 1)];
+    // May the label state be entered from pair j-1's label?  (Not across equal symbols.)
+    double skip_penalty = kNeg;
+    if (has_label && j >= 1 && lab[li] != lab[kBackward ? (li + 1) : (li - 1)]) skip_penalty = 0.0;
 
-    const float* ebase = emit + m.e_off;
-    const int ecol = has_label ? (1 + li) : 0;
-    double* obase = out + m.ab_off;
-    const int ocol = kBackward ? (2 * (L - j)) : (2 * j);
-    const size_t pitch = 2 * static_cast<size_t>(P);
+    // Frame of step s: s going forward, Tb-1-s going backward.
+    const int f0 = kBackward ? (Tb - 1) : 0;
+    const int fdir = kBackward ? -1 : 1;
+    // Label emissions: a per-lane pointer that moves one row per step.  The lane that holds
+    // pair L has no label state: it reads a constant log 0 and stays there.
+    const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * L + li
+                                : emit_label;
+    const int64_t estride = has_label ? static_cast<int64_t>(fdir) * L : 0;
+    // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i%8).
+    const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    // Output rows.
+    // Output rows; lanes without a pair write to a 16-byte sink instead.
+    double* op = active ? out + m.ab_off + static_cast<int64_t>(f0) * (2 * P) + (kBackward ? 2 * (L - j) : 2 * j)
+                        : sink;
+    const int64_t ostride = active ? static_cast<int64_t>(fdir) * (2 * P) : 0;
 
-    auto frame_of = [&](int step) { return kBackward ? (Tb - 1 - step) : step; };
-    auto store_row = [&](int frame, double blank_v, double label_v) {
-        if (!active) return;
-        double2 v = kBackward ? make_double2(label_v, blank_v) : make_double2(blank_v, label_v);
-        *reinterpret_cast<double2*>(obase + static_cast<size_t>(frame) * pitch + ocol) = v;
+    long long* slots = reinterpret_cast<long long*>(lds);
+    auto slot_load = [&](int row, int col) {
+        return __longlong_as_double(__hip_atomic_load(slots + static_cast<size_t>(row) * Tb + col,
+                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
     };
-    // Exchange: every lane gets the label value of pair j-1 (log 0 for pair 0).
-    auto from_prev_pair = [&](double v, int parity) {
-        double r = from_lower_lane(v, kNeg);
-        if (blockDim.x > 64) {
-            if (lane == 63) xch[parity][wave] = v;
+    const bool publishes = kSync == Sync::kSlots && lane == 63 && wave < last_wave;
+    int budget = kSpinBudget;
+    double pre = kNeg;                                   // neighbour value for the coming step
+
+    // Label value of pair j-1 after step s (log 0 for pair 0).  `mine` is this lane's.
+    auto from_prev_pair = [&](double mine, int s) {
+        if (kSync == Sync::kBarrier) {
+            double (*xch)[16] = reinterpret_cast<double (*)[16]>(lds);
+            double r = shift_up(mine, kNeg);
+            if (lane == 63) xch[s & 1][wave] = mine;
             __syncthreads();
-            if (lane == 0 && wave > 0) r = xch[parity][wave - 1];
+            if (lane == 0 && wave > 0) r = xch[s & 1][wave - 1];
+            return r;
         }
-        return r;
-    };
-
-    double v_blank, v_label;
-    if (!kBackward) {
-        const float eb = ebase[0], el = ebase[ecol];
-        v_blank = (j == 0) ? static_cast<double>(eb) : kNeg;
-        v_label = (j == 0 && has_label) ? static_cast<double>(el) : kNeg;
-    } else {
-        v_blank = (j == 0) ? 0.0 : kNeg;
-        v_label = (j == 0 && has_label) ? 0.0 : kNeg;
-    }
-    store_row(frame_of(0), v_blank, v_label);
-
-    // Emissions consumed at step s: forward uses frame s, backward uses frame Tb - s (the
-    // frame just left).  They do not depend on the recursion, so they are fetched a block of
-    // steps ahead.
-    auto emission_frame = [&](int step) {
-        int f = kBackward ? (Tb - step) : step;
-        return min(max(f, 0), Tb - 1);
-    };
-    float eb_cur[kPrefetch], el_cur[kPrefetch], eb_nxt[kPrefetch], el_nxt[kPrefetch];
-#pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) {
-        const float* r = ebase + static_cast<size_t>(emission_frame(1 + i)) * P;
-        eb_cur[i] = r[0];
-        el_cur[i] = r[ecol];
-    }
-    for (int s0 = 1; s0 < Tb; s0 += kPrefetch) {
-#pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) {
-            const float* r = ebase + static_cast<size_t>(emission_frame(s0 + kPrefetch + i)) * P;
-            eb_nxt[i] = r[0];
-            el_nxt[i] = r[ecol];
-        }
-#pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) {
-            const int step = s0 + i;
-            if (step < Tb) {
-                const double eb = static_cast<double>(eb_cur[i]);
-                const double el = static_cast<double>(el_cur[i]);
-                double nb, nl;
-                if (!kBackward) {
-                    const double prev = from_prev_pair(v_label, step & 1);
-                    nb = lse2(v_blank, prev) + eb;
-                    nl = lse3(v_label, v_blank, skip ? prev : kNeg) + el;
-                } else {
-                    const double wb = v_blank + eb, wl = v_label + el;
-                    const double prev = from_prev_pair(wl, step & 1);
-                    nb = lse2(wb, prev);
-                    nl = lse3(wl, wb, skip ? prev : kNeg);
+        if (kSync == Sync::kSlots) {
+            double v = pre;
+            if (__double2hiint(v) == kEmptyHi) {         // same for every lane of the wavefront
+                while (__double2hiint(v) == kEmptyHi && budget > 0) {
+                    --budget;
+                    v = slot_load(wave, s);
                 }
-                v_blank = active ? nb : kNeg;
-                v_label = has_label ? nl : kNeg;
-                store_row(frame_of(step), v_blank, v_label);
             }
+            return shift_up(mine, v);
         }
+        return shift_up(mine, kNeg);
+    };
+
+    double i_blank = (j == 0) ? 0.0 : kNeg;
+    double i_label = (j == 0 && has_label) ? 0.0 : kNeg;
+    double v_blank, v_label;
+
+    auto finish_step = [&](int step, float eb, float el) {
+        v_blank = i_blank + static_cast<double>(eb);
+        v_label = i_label + static_cast<double>(el);
+        if (publishes)
+            __hip_atomic_store(slots + static_cast<size_t>(wave + 1) * Tb + step, __double_as_longlong(v_label),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+        op += ostride;
+    };
+    auto advance = [&](int step, float eb, float el) {
+        const double prev = from_prev_pair(v_label, step - 1);
+        // start fetching the neighbour's value of this step; it is needed one step on
+        if (kSync == Sync::kSlots) pre = slot_load(wave, step);
+        i_blank = lse2(v_blank, prev);
+        i_label = lse3(v_label, v_blank, prev + skip_penalty);
+        finish_step(step, eb, el);
+    };
+    auto readlane = [](float v, int l) {
+        return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
+    };
+
+    // step 0
+    {
+        const float ebv = *bp;
+        const float el = *ep;
+        finish_step(0, readlane(ebv, 0), el);
+        if (kSync == Sync::kSlots) pre = slot_load(wave, 0);
+    }
+
+    // Emissions of steps 1..: two register sets, one in use, one being filled.
+    float el_a[kChunk], el_b[kChunk], eb_a, eb_b;
+    auto fetch = [&](float (&el)[kChunk], float& eb, int s0) {
+        eb = bp[fdir * s0];
 #pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) { eb_cur[i] = eb_nxt[i]; el_cur[i] = el_nxt[i]; }
+        for (int i = 0; i < kChunk; ++i) {
+            ep += estride;
+            el[i] = *ep;
+        }
+    };
+    auto run = [&](const float (&el)[kChunk], const float eb, int s0) {
+        if (s0 + kChunk <= Tb) {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i) advance(s0 + i, readlane(eb, i), el[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i)
+                if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
+        }
+    };
+    fetch(el_a, eb_a, 1);
+    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
+        fetch(el_b, eb_b, s0 + kChunk);
+        run(el_a, eb_a, s0);
+        fetch(el_a, eb_a, s0 + 2 * kChunk);
+        if (s0 + kChunk < Tb) run(el_b, eb_b, s0 + kChunk);
     }
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L-1.
-        const double prev = from_prev_pair(v_label, Tb & 1);
+        const double prev = from_prev_pair(v_label, Tb - 1);
         if (j == L) {
             const double lp = lse2(v_blank, prev);
             logp[u] = lp;
             costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
         }
     }
+    if (kSync == Sync::kSlots && budget <= 0) chain_err[u] = 1;
 }
 
-// grid = (utterances whose lattice runs, 2): y = 0 forward, y = 1 backward.
-// blockDim.x = 64 * (wavefronts of the longest label); wavefronts beyond an utterance's own
-// need only keep the barrier count.
-__global__ __launch_bounds__(1024)
-void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
-                        const int* __restrict__ labels, const float* __restrict__ emit,
-                        double* __restrict__ alpha, double* __restrict__ beta,
-                        double* __restrict__ logp, float* __restrict__ costs)
+template <Sync kSync>
+__device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
+                                             const int* __restrict__ labels,
+                                             const float* __restrict__ emit_blank,
+                                             const float* __restrict__ emit_label,
+                                             double* __restrict__ alpha, double* __restrict__ beta,
+                                             double* __restrict__ logp, float* __restrict__ costs,
+                                             int* __restrict__ chain_err, double* __restrict__ sink, double* lds)
 {
-    __shared__ double xch[2][16];
     const int u = order[blockIdx.x];
     const Utt m = meta[u];
     const int waves_needed = (m.L + 1 + 63) >> 6;
-    if (static_cast<int>(threadIdx.x >> 6) >= waves_needed) {
-        // Nothing to compute, but keep meeting the barriers of the working wavefronts:
-        // one per recursion step, plus the forward chain's final exchange.
-        if (blockDim.x > 64) {
+    const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves_needed;
+    if (kSync == Sync::kSlots) {
+        // row 0: log 0 for wavefront 0; rows 1..: empty until written
+        const int slots = waves_needed * m.Tb;
+        const double empty = __hiloint2double(kEmptyHi, -1);
+        for (int i = threadIdx.x; i < slots; i += blockDim.x) lds[i] = (i < m.Tb) ? kNeg : empty;
+        __syncthreads();
+        if (idle) return;
+    } else if (kSync == Sync::kBarrier) {
+        if (idle) {
+            // Nothing to compute, but keep meeting the barriers of the working wavefronts:
+            // one per recursion step, plus the forward chain's final exchange.
             const int barriers = (m.Tb - 1) + (blockIdx.y == 0 ? 1 : 0);
             for (int i = 0; i < barriers; ++i) __syncthreads();
+            return;
         }
-        return;
     }
     if (blockIdx.y == 0)
-        run_chain<false>(m, u, labels, emit, alpha, logp, costs, xch);
+        run_chain<false, kSync>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
     else
-        run_chain<true>(m, u, labels, emit, beta, logp, costs, xch);
+        run_chain<true, kSync>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+}
+
+// grid = (utterances whose lattice runs, 2): y = 0 forward, y = 1 backward.
+// blockDim.x = 64 * (wavefronts of the longest label).
+// Variant for batches whose labels all fit one wavefront: no exchange at all.
+__global__ __launch_bounds__(64)
+void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
+                           const int* __restrict__ labels, const float* __restrict__ emit_blank,
+                           const float* __restrict__ emit_label,
+                           double* __restrict__ alpha, double* __restrict__ beta,
+                           double* __restrict__ logp, float* __restrict__ costs,
+                           int* __restrict__ chain_err, double* __restrict__ sink)
+{
+    lattice_body<Sync::kNone>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+                              chain_err, sink, nullptr);
+}
+
+// Multi-wavefront chains, neighbours exchanged through per-step LDS slots (dynamic LDS:
+// wavefronts * max frames doubles).
+__global__ __launch_bounds__(1024)
+void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
+                        const int* __restrict__ labels, const float* __restrict__ emit_blank,
+                        const float* __restrict__ emit_label,
+                        double* __restrict__ alpha, double* __restrict__ beta,
+                        double* __restrict__ logp, float* __restrict__ costs,
+                        int* __restrict__ chain_err, double* __restrict__ sink)
+{
+    extern __shared__ double slot_lds[];
+    lattice_body<Sync::kSlots>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+                               chain_err, sink, slot_lds);
+}
+
+// Fallback when the slots would not fit in LDS: one barrier per step.
+__global__ __launch_bounds__(1024)
+void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restrict__ order,
+                                const int* __restrict__ labels, const float* __restrict__ emit_blank,
+                                const float* __restrict__ emit_label,
+                                double* __restrict__ alpha, double* __restrict__ beta,
+                                double* __restrict__ logp, float* __restrict__ costs,
+                                int* __restrict__ chain_err, double* __restrict__ sink)
+{
+    __shared__ double xch[2][16];
+    lattice_body<Sync::kBarrier>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+                                 chain_err, sink, &xch[0][0]);
 }
 
 // ---- gradient ------------------------------------------------------------------------------
@@ -331,12 +435,15 @@ void ctc_gradient_kernel(const T* __restrict__ x, T* __restrict__ grads,
                          const Utt* __restrict__ meta, const int* __restrict__ labels,
                          const int* __restrict__ links, const float* __restrict__ lse,
                          const double* __restrict__ alpha, const double* __restrict__ beta,
-                         const double* __restrict__ logp, int Tt, int B, int A, int blank)
+                         const double* __restrict__ logp, const int* __restrict__ chain_err,
+                         float* __restrict__ costs, int Tt, int B, int A, int blank)
 {
     __shared__ float red[8];
     __shared__ float g_label[CTC_MAX_LABEL_LENGTH + 1];
     const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const Utt m = meta[b];
+    // A lattice wavefront that ran out of its wait budget leaves no trustworthy result.
+    if (t == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
     T* grow = grads + row_off;
 
@@ -408,7 +515,9 @@ int launch_setup(const Launch& p, void* stream)
     auto* links = reinterpret_cast<int*>(p.ws + p.lay.links);
     return checked_launch([&] {
         hipLaunchKernelGGL(ctc_setup_kernel, dim3(p.B), dim3(kRowThreads), 0,
-                           static_cast<hipStream_t>(stream), meta, labels, links, p.costs);
+                           static_cast<hipStream_t>(stream), meta, labels, links, p.costs,
+                           reinterpret_cast<int*>(p.ws + p.lay.chain_err),
+                           reinterpret_cast<float*>(p.ws + p.lay.emit_label));
     });
 }
 
@@ -417,17 +526,18 @@ int launch_softmax(const Launch& p, void* stream)
     auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
     auto* labels = reinterpret_cast<const int*>(p.ws + p.lay.labels);
     auto* lse = reinterpret_cast<float*>(p.ws + p.lay.lse);
-    auto* emit = reinterpret_cast<float*>(p.ws + p.lay.emit);
+    auto* emit_blank = reinterpret_cast<float*>(p.ws + p.lay.emit_blank);
+    auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
     const dim3 grid(p.T, p.B), block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     return checked_launch([&] {
         if (p.dtype == CTC_DTYPE_F32)
             hipLaunchKernelGGL(ctc_softmax_kernel<float>, grid, block, 0, s,
-                               static_cast<const float*>(p.x), meta, labels, lse, emit,
+                               static_cast<const float*>(p.x), meta, labels, lse, emit_blank, emit_label,
                                p.T, p.B, p.A, p.blank);
         else
             hipLaunchKernelGGL(ctc_softmax_kernel<bf16_t>, grid, block, 0, s,
-                               static_cast<const bf16_t*>(p.x), meta, labels, lse, emit,
+                               static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank, emit_label,
                                p.T, p.B, p.A, p.blank);
     });
 }
@@ -438,14 +548,37 @@ int launch_lattice(const Launch& p, void* stream)
     auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
     auto* order = reinterpret_cast<const int*>(p.ws + p.lay.order);
     auto* labels = reinterpret_cast<const int*>(p.ws + p.lay.labels);
-    auto* emit = reinterpret_cast<const float*>(p.ws + p.lay.emit);
+    auto* emit_blank = reinterpret_cast<const float*>(p.ws + p.lay.emit_blank);
+    auto* emit_label = reinterpret_cast<const float*>(p.ws + p.lay.emit_label);
+    auto* sink = reinterpret_cast<double*>(p.ws + p.lay.sink);
     auto* alpha = reinterpret_cast<double*>(p.ws + p.lay.alpha);
     auto* beta = reinterpret_cast<double*>(p.ws + p.lay.beta);
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
+    auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
+    const dim3 grid(p.n_run, 2), block(64 * p.max_waves);
+    auto s = static_cast<hipStream_t>(stream);
+    if (p.max_waves == 1)
+        return checked_launch([&] {
+            hipLaunchKernelGGL(ctc_lattice_kernel_w1, grid, block, 0, s, meta, order, labels,
+                               emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+        });
+    // One LDS slot per step and per wavefront boundary.
+    const size_t ring_bytes = static_cast<size_t>(p.max_waves) * p.max_frames * sizeof(double);
+    static const size_t lds_limit = [] {
+        const size_t want = 160 * 1024;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ctc_lattice_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(want));
+        if (e != hipSuccess) { (void)hipGetLastError(); return static_cast<size_t>(64 * 1024); }
+        return want;
+    }();
+    if (ring_bytes <= lds_limit)
+        return checked_launch([&] {
+            hipLaunchKernelGGL(ctc_lattice_kernel, grid, block, ring_bytes, s, meta, order, labels,
+                               emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+        });
     return checked_launch([&] {
-        hipLaunchKernelGGL(ctc_lattice_kernel, dim3(p.n_run, 2), dim3(64 * p.max_waves), 0,
-                           static_cast<hipStream_t>(stream), meta, order, labels, emit, alpha,
-                           beta, logp, p.costs);
+        hipLaunchKernelGGL(ctc_lattice_kernel_barrier, grid, block, 0, s, meta, order, labels,
+                           emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
     });
 }
 
@@ -458,17 +591,20 @@ int launch_gradient(const Launch& p, void* stream)
     auto* alpha = reinterpret_cast<const double*>(p.ws + p.lay.alpha);
     auto* beta = reinterpret_cast<const double*>(p.ws + p.lay.beta);
     auto* logp = reinterpret_cast<const double*>(p.ws + p.lay.logp);
+    auto* chain_err = reinterpret_cast<const int*>(p.ws + p.lay.chain_err);
     const dim3 grid(p.T, p.B), block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     return checked_launch([&] {
         if (p.dtype == CTC_DTYPE_F32)
             hipLaunchKernelGGL(ctc_gradient_kernel<float>, grid, block, 0, s,
                                static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta,
-                               labels, links, lse, alpha, beta, logp, p.T, p.B, p.A, p.blank);
+                               labels, links, lse, alpha, beta, logp, chain_err, p.costs,
+                               p.T, p.B, p.A, p.blank);
         else
             hipLaunchKernelGGL(ctc_gradient_kernel<bf16_t>, grid, block, 0, s,
                                static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta,
-                               labels, links, lse, alpha, beta, logp, p.T, p.B, p.A, p.blank);
+                               labels, links, lse, alpha, beta, logp, chain_err, p.costs,
+                               p.T, p.B, p.A, p.blank);
     });
 }
 
