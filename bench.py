@@ -37,13 +37,12 @@ def kernel_bytes(batch, elem):
     pairs = int((batch.input_lengths.astype(np.int64) * (batch.label_lengths.astype(np.int64) + 1)).sum())
     cells = batch.lattice_cells
     return {
-        "ctc_setup_kernel": int(batch.flat_labels.size) * 8,
         # read every valid row once; write one statistic per row
-        "ctc_softmax_kernel": frames * A * elem + frames * 4,
+        "ctc_softmax": frames * A * elem + frames * 4,
         # one alpha and one beta value per lattice cell, 4 bytes each, written once
-        "ctc_lattice_kernel": cells * 8,
+        "ctc_lattice": cells * 8,
         # read every valid row again, write the whole gradient tensor
-        "ctc_gradient_kernel": frames * A * elem + batch.T * batch.B * A * elem,
+        "ctc_gradient": frames * A * elem + batch.T * batch.B * A * elem,
     }, pairs
 
 
@@ -104,7 +103,7 @@ def main():
                       "GBps": round(byt / (kavg[i] * 1e-3) / 1e9, 2) if kavg[i] > 0 else None}
     dom = int(np.argmax(kavg))
     dom_name = names[dom]
-    if dom_name == "ctc_lattice_kernel":
+    if dom_name == "ctc_lattice":
         pair_steps = 2.0 * float(np.mean([k[1] for k in kb]))       # both directions
         achieved = pair_steps * LANE_OPS_PER_PAIR_STEP / (kavg[dom] * 1e-3) / 1e12
         roofline = {"kernel": dom_name, "bound": "alu", "achieved": round(achieved, 4),

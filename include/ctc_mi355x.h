@@ -45,13 +45,13 @@ typedef enum {
 /* Longest label string one utterance may carry (lattice of 2*L+1 states). */
 #define CTC_MAX_LABEL_LENGTH 1023
 
-/* Kernels of one call, in launch order; index into ctc_profile_kernels' output. */
+/* Kernel launches of one call, in order; index into ctc_profile_kernels' output. */
 enum {
-    CTC_KERNEL_SETUP = 0,      /* per-utterance label links, costs of degenerate utterances */
-    CTC_KERNEL_SOFTMAX = 1,    /* row-wise log-softmax statistics + emission gather */
-    CTC_KERNEL_LATTICE = 2,    /* alpha and beta recursions, one launch */
-    CTC_KERNEL_GRADIENT = 3,   /* softmax minus normalised occupancy, zero fill of padding */
-    CTC_NUM_KERNELS = 4
+    CTC_KERNEL_SOFTMAX = 0,    /* row-wise log-softmax statistics + emission gather; also the
+                                  per-utterance label links and the costs of degenerate utterances */
+    CTC_KERNEL_LATTICE = 1,    /* alpha and beta recursions, one launch */
+    CTC_KERNEL_GRADIENT = 2,   /* softmax minus normalised occupancy, zero fill of padding */
+    CTC_NUM_KERNELS = 3
 };
 
 /*
@@ -129,7 +129,8 @@ ctc_status_t ctc_profile_kernels(const void *activations,
                                  void *stream,
                                  float *kernel_ms);
 
-/* Name of kernel `index` (0..CTC_NUM_KERNELS-1) as it appears in a profiler trace; NULL otherwise. */
+/* Prefix of the name under which launch `index` (0..CTC_NUM_KERNELS-1) appears in a profiler
+ * trace (the full name depends on the variant chosen for the batch shape); NULL otherwise. */
 const char *ctc_kernel_name(int index);
 
 /* Static, human-readable name of a status code. */

@@ -27,6 +27,7 @@ def command(out: str = LIB) -> list[str]:
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-x", "hip",
             "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+            *os.environ.get("CTC_EXTRA_HIPCC_FLAGS", "").split(),
             "-I", os.path.join(ROOT, "include"), "-I", CSRC,
             *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
 

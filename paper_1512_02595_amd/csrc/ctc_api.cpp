@@ -122,11 +122,12 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     int32_t* labels = reinterpret_cast<int32_t*>(image->data() + lay.labels);
 
     int64_t lab_off = 0, e_off = 0, ab_off = 0, f_off = 0;
-    int n_run = 0, max_waves = 1, max_frames = 0;
+    int n_run = 0, max_waves = 1, max_frames = 0, max_label = 0;
     for (int b = 0; b < c.B; ++b) {
         const int L = c.label_lengths[b], Tb = c.input_lengths[b];
         const int32_t* lab = c.flat_labels + lab_off;
         int repeats = 0;
+        max_label = std::max(max_label, L);
         for (int i = 0; i < L; ++i) {
             const int32_t s = lab[i];
             if (s < 0 || s >= c.A || s == c.blank) return CTC_STATUS_INVALID_VALUE;
@@ -169,6 +170,7 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     out->n_run = n_run;
     out->max_waves = max_waves;
     out->max_frames = max_frames;
+    out->max_label = max_label;
     out->x = c.x;
     out->grads = c.grads;
     out->costs = c.costs;
@@ -195,8 +197,8 @@ ctc_status_t run(const Call& c, float* kernel_ms)
             if (!record(hipEventCreate(&e))) return CTC_STATUS_HIP_ERROR;
         if (!record(hipEventRecord(ev[0], s))) return CTC_STATUS_HIP_ERROR;
     }
-    int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_setup, launch_softmax,
-                                                                  launch_lattice, launch_gradient};
+    int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_softmax, launch_lattice,
+                                                                  launch_gradient};
     for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
         if (!record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
         if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
@@ -250,10 +252,9 @@ ctc_status_t ctc_profile_kernels(const void* activations, const int32_t* flat_la
 const char* ctc_kernel_name(int index)
 {
     switch (index) {
-        case CTC_KERNEL_SETUP: return "ctc_setup_kernel";
-        case CTC_KERNEL_SOFTMAX: return "ctc_softmax_kernel";
-        case CTC_KERNEL_LATTICE: return "ctc_lattice_kernel";
-        case CTC_KERNEL_GRADIENT: return "ctc_gradient_kernel";
+        case CTC_KERNEL_SOFTMAX: return "ctc_softmax";
+        case CTC_KERNEL_LATTICE: return "ctc_lattice";
+        case CTC_KERNEL_GRADIENT: return "ctc_gradient";
         default: return nullptr;
     }
 }

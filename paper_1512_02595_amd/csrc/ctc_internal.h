@@ -68,6 +68,7 @@ struct Launch {
     int n_run;          // utterances whose lattice runs
     int max_waves;      // wavefronts per lattice block
     int max_frames;     // longest utterance among those whose lattice runs
+    int max_label;      // longest label of the batch
     const void* x;
     void* grads;
     float* costs;
@@ -76,7 +77,6 @@ struct Launch {
 };
 
 // Each returns a hipError_t as int (0 = success). `stream` is a hipStream_t.
-int launch_setup(const Launch& p, void* stream);
 int launch_softmax(const Launch& p, void* stream);
 int launch_lattice(const Launch& p, void* stream);
 int launch_gradient(const Launch& p, void* stream);

@@ -84,49 +84,59 @@ __device__ __forceinline__ float block_max(float v, float* slot)
     return fmaxf(fmaxf(slot[0], slot[1]), fmaxf(slot[2], slot[3]));
 }
 
-// ---- setup -------------------------------------------------------------------------------
-// One workgroup per utterance.  For label position j: the next position holding the same
-// symbol (0 = none, else index + 1) in the low 24 bits, and bit 31 set if j is the first
-// occurrence of its symbol.  The gradient kernel walks these chains, so the occupancy of a
-// symbol is summed in a fixed order (positions ascending) and each symbol has one writer.
-__global__ __launch_bounds__(kRowThreads)
-void ctc_setup_kernel(const Utt* __restrict__ meta, const int* __restrict__ labels,
-                      int* __restrict__ links, float* __restrict__ costs, int* __restrict__ chain_err,
-                      float* __restrict__ emit_label)
+// ---- setup role ----------------------------------------------------------------------------
+// Runs in the last x-column of the softmax launch, one workgroup per utterance.  For label
+// position j: the next position holding the same symbol (0 = none, else index + 1) in the low
+// 24 bits, and bit 31 set if j is the first occurrence of its symbol.  The gradient kernels
+// walk these chains, so the occupancy of a symbol is summed in a fixed order (positions
+// ascending) and each symbol has one writer.  This stands in for the appendix's one-off
+// key-value sort of the label: the same grouping of equal characters, amortised over all frames.
+struct SetupArgs {
+    int* links;
+    float* costs;
+    int* chain_err;
+    float* log0;          // the float that lanes without a label state read as their emission
+};
+
+__device__ __forceinline__ void setup_role(const Utt m, const int b, const int* __restrict__ labels,
+                                           const SetupArgs sa, int* s_lab)
 {
-    const int b = blockIdx.x;
-    if (b == 0 && threadIdx.x == 0) emit_label[0] = static_cast<float>(kNeg);   // read by lanes without a label state
-    const Utt m = meta[b];
+    if (b == 0 && threadIdx.x == 0) sa.log0[0] = static_cast<float>(kNeg);
     const int* lab = labels + m.lab_off;
+    for (int j = threadIdx.x; j < m.L; j += kRowThreads) s_lab[j] = lab[j];
+    __syncthreads();
     for (int j = threadIdx.x; j < m.L; j += kRowThreads) {
-        const int c = lab[j];
+        const int c = s_lab[j];
         int nxt = 0;
         for (int i = j + 1; i < m.L; ++i)
-            if (lab[i] == c) { nxt = i + 1; break; }
+            if (s_lab[i] == c) { nxt = i + 1; break; }
         bool first = true;
         for (int i = j - 1; i >= 0; --i)
-            if (lab[i] == c) { first = false; break; }
-        links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
+            if (s_lab[i] == c) { first = false; break; }
+        sa.links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
     }
-    if (threadIdx.x == 0) chain_err[b] = 0;
-    if (threadIdx.x == 0 && !(m.flags & kUttRuns)) {
+    if (threadIdx.x == 0) {
+        sa.chain_err[b] = 0;
         // No frames: the empty product (cost 0) for an empty label.  Otherwise no alignment.
-        costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
+        if (!(m.flags & kUttRuns)) sa.costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
     }
 }
 
 // ---- softmax statistics + emission gather --------------------------------------------------
-// One workgroup per valid frame row (t, b).
+// Wide alphabets: one workgroup per valid frame row (t, b); grid (T + 1, B), the extra column
+// does the setup role.
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
                         const int* __restrict__ labels, float* __restrict__ lse,
                         float* __restrict__ emit_blank, float* __restrict__ emit_label,
-                        int Tt, int B, int A, int blank)
+                        const SetupArgs sa, int Tt, int B, int A, int blank)
 {
     __shared__ float red[8];
+    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
     const int t = blockIdx.x, b = blockIdx.y;
     const Utt m = meta[b];
+    if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
     if (t >= m.Tb) return;
     const T* row = x + (static_cast<size_t>(t) * B + b) * A;
 
@@ -147,6 +157,58 @@ void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
     const int* lab = labels + m.lab_off;
     for (int j = threadIdx.x; j < m.L; j += kRowThreads)
         erow[j] = fmaf(load_elem(row, lab[j]), kLog2e, -l2);
+}
+
+// Narrow alphabets: a workgroup takes kRows consecutive frames of one utterance, 256 / kRows
+// threads per row.  The normalised log2 probabilities of those rows are kept in LDS
+// (kRows * A floats, dynamic), from where the emissions of all label positions are gathered
+// with the label symbols held in registers.  grid (ceil(T / kRows) + 1, B).
+template <typename T, int kRows>
+__global__ __launch_bounds__(kRowThreads)
+void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
+                             const int* __restrict__ labels, float* __restrict__ lse,
+                             float* __restrict__ emit_blank, float* __restrict__ emit_label,
+                             const SetupArgs sa, int Tt, int B, int A, int blank)
+{
+    constexpr int kPerRow = kRowThreads / kRows;          // threads per row, a power of two <= 64
+    extern __shared__ float lp[];                          // [kRows][A]
+    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const Utt m = meta[b];
+    if (blockIdx.x == gridDim.x - 1) { setup_role(m, b, labels, sa, s_lab); return; }
+    const int t0 = blockIdx.x * kRows;
+    if (t0 >= m.Tb) return;
+    const int r = tid / kPerRow, q = tid % kPerRow, t = t0 + r;
+    float* lrow = lp + r * A;
+    if (t < m.Tb) {
+        const T* row = x + (static_cast<size_t>(t) * B + b) * A;
+        float mx = -__builtin_inff();
+        for (int k = q; k < A; k += kPerRow) {
+            const float v = load_elem(row, k);
+            lrow[k] = v;
+            mx = fmaxf(mx, v);
+        }
+#pragma unroll
+        for (int o = kPerRow / 2; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        mx *= kLog2e;
+        float sum = 0.0f;
+        for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
+#pragma unroll
+        for (int o = kPerRow / 2; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        const float l2 = mx + fast_log2(sum);
+        for (int k = q; k < A; k += kPerRow) lrow[k] = fmaf(lrow[k], kLog2e, -l2);
+        if (q == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
+    }
+    if (!(m.flags & kUttRuns)) return;
+    __syncthreads();
+    const int rows = min(kRows, m.Tb - t0);
+    if (tid < rows) emit_blank[kBlankSlack + m.f_off + t0 + tid] = lp[tid * A + blank];
+    const int* lab = labels + m.lab_off;
+    float* ebase = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * m.L;
+    for (int j = tid; j < m.L; j += kRowThreads) {
+        const int c = lab[j];
+        for (int rr = 0; rr < rows; ++rr) ebase[static_cast<size_t>(rr) * m.L + j] = lp[rr * A + c];
+    }
 }
 
 // ---- lattice recursions ------------------------------------------------------------------
@@ -245,7 +307,11 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         return __longlong_as_double(__hip_atomic_load(slots + static_cast<size_t>(row) * Tb + col,
                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
     };
+#ifdef CTC_X_NO_SYNC
+    const bool publishes = false;
+#else
     const bool publishes = kSync == Sync::kSlots && lane == 63 && wave < last_wave;
+#endif
     int budget = kSpinBudget;
     double pre = kNeg;                                   // neighbour value for the coming step
 
@@ -259,6 +325,9 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             if (lane == 0 && wave > 0) r = xch[s & 1][wave - 1];
             return r;
         }
+#ifdef CTC_X_NO_SYNC
+        return shift_up(mine, kNeg);
+#endif
         if (kSync == Sync::kSlots) {
             double v = pre;
             if (__double2hiint(v) == kEmptyHi) {         // same for every lane of the wavefront
@@ -282,13 +351,17 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         if (publishes)
             __hip_atomic_store(slots + static_cast<size_t>(wave + 1) * Tb + step, __double_as_longlong(v_label),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#ifndef CTC_X_NO_STORE
         *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+#endif
         op += ostride;
     };
     auto advance = [&](int step, float eb, float el) {
         const double prev = from_prev_pair(v_label, step - 1);
         // start fetching the neighbour's value of this step; it is needed one step on
+#ifndef CTC_X_NO_SYNC
         if (kSync == Sync::kSlots) pre = slot_load(wave, step);
+#endif
         i_blank = lse2(v_blank, prev);
         i_label = lse3(v_label, v_blank, prev + skip_penalty);
         finish_step(step, eb, el);
@@ -499,6 +572,90 @@ void ctc_gradient_kernel(const T* __restrict__ x, T* __restrict__ grads,
         store_elem(grow, blank, fast_exp2(fmaf(load_elem(xrow, blank), kLog2e, -l2)) - zb * inv_z);
 }
 
+// Narrow alphabets: a workgroup takes kGradRows consecutive frames of one utterance, one
+// wavefront per row at a time.  Labels and their links sit in LDS; per wavefront, the label
+// states' mass shares (P floats) and the per-symbol occupancy (A floats).  Everything within a
+// row stays inside one wavefront, so no barrier is needed after the staging.
+// Dynamic LDS: 2 * L_max ints + 4 * (L_max + 1 + A) floats.
+constexpr int kGradRows = 16;
+
+template <typename T>
+__global__ __launch_bounds__(kRowThreads)
+void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
+                              const Utt* __restrict__ meta, const int* __restrict__ labels,
+                              const int* __restrict__ links, const float* __restrict__ lse,
+                              const double* __restrict__ alpha, const double* __restrict__ beta,
+                              const double* __restrict__ logp, const int* __restrict__ chain_err,
+                              float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax)
+{
+    extern __shared__ int g_lds[];
+    int* s_lab = g_lds;
+    int* s_lnk = g_lds + Lmax;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* g_label = reinterpret_cast<float*>(g_lds + 2 * Lmax) + wave * (Lmax + 1 + A);
+    float* occ = g_label + Lmax + 1;
+    const int b = blockIdx.y, t0 = blockIdx.x * kGradRows;
+    const Utt m = meta[b];
+    if (t0 == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
+    const bool runs = (m.flags & kUttRuns) != 0;
+    const int L = m.L, P = L + 1;
+    if (runs && t0 < m.Tb) {
+        for (int j = tid; j < L; j += kRowThreads) {
+            s_lab[j] = labels[m.lab_off + j];
+            s_lnk[j] = links[m.lab_off + j];
+        }
+        __syncthreads();
+    }
+    const size_t pitch = 2 * static_cast<size_t>(P);
+    const double lp = runs ? logp[b] : 0.0;
+    for (int t = t0 + wave; t < min(t0 + kGradRows, Tt); t += 4) {
+        const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
+        T* grow = grads + row_off;
+        if (t >= m.Tb || !runs) {
+            for (int k = lane; k < A; k += 64) store_elem(grow, k, 0.0f);
+            continue;
+        }
+        const T* xrow = x + row_off;
+        const double* arow = alpha + m.ab_off + static_cast<size_t>(t) * pitch;
+        const double* brow = beta + m.ab_off + static_cast<size_t>(t) * pitch;
+        float z = 0.0f, zb = 0.0f;
+        for (int j = lane; j < P; j += 64) {
+            const double2 a = *reinterpret_cast<const double2*>(arow + 2 * j);
+            const double bb = brow[2 * j + 1], bl = brow[j < L ? 2 * j + 2 : 0];
+            const float gb = fast_exp2(static_cast<float>(a.x + bb - lp));
+            const float gl = (j < L) ? fast_exp2(static_cast<float>(a.y + bl - lp)) : 0.0f;
+            g_label[j] = gl;
+            z += gb + gl;
+            zb += gb;
+        }
+        z = wave_sum(z);
+        zb = wave_sum(zb);
+        const float inv_z = 1.0f / z;
+        const float l2 = lse[static_cast<size_t>(b) * Tt + t];
+        for (int k = lane; k < A; k += 64) occ[k] = 0.0f;
+        // LDS operations of one wavefront complete in program order; the fence only keeps the
+        // compiler from moving them across.
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int j = lane; j < L; j += 64) {
+            const int link = s_lnk[j];
+            if (link < 0) {                   // first occurrence of its symbol: sum the chain
+                float o = g_label[j];
+                int nxt = link & 0xFFFFFF;
+                while (nxt) {
+                    o += g_label[nxt - 1];
+                    nxt = s_lnk[nxt - 1] & 0xFFFFFF;
+                }
+                occ[s_lab[j]] = o;
+            }
+        }
+        if (lane == 0) occ[blank] = zb;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int k = lane; k < A; k += 64)
+            store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k] * inv_z);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+}
+
 template <typename F>
 int checked_launch(F&& f)
 {
@@ -508,17 +665,8 @@ int checked_launch(F&& f)
 
 }  // namespace
 
-int launch_setup(const Launch& p, void* stream)
-{
-    auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
-    auto* labels = reinterpret_cast<const int*>(p.ws + p.lay.labels);
-    auto* links = reinterpret_cast<int*>(p.ws + p.lay.links);
-    return checked_launch([&] {
-        hipLaunchKernelGGL(ctc_setup_kernel, dim3(p.B), dim3(kRowThreads), 0,
-                           static_cast<hipStream_t>(stream), meta, labels, links, p.costs,
-                           reinterpret_cast<int*>(p.ws + p.lay.chain_err),
-                           reinterpret_cast<float*>(p.ws + p.lay.emit_label));
-    });
+namespace {
+constexpr int kRowsMaxA = 2048;        // alphabets up to this size use the multi-row kernels
 }
 
 int launch_softmax(const Launch& p, void* stream)
@@ -528,17 +676,45 @@ int launch_softmax(const Launch& p, void* stream)
     auto* lse = reinterpret_cast<float*>(p.ws + p.lay.lse);
     auto* emit_blank = reinterpret_cast<float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
-    const dim3 grid(p.T, p.B), block(kRowThreads);
+    const SetupArgs sa{reinterpret_cast<int*>(p.ws + p.lay.links), p.costs,
+                       reinterpret_cast<int*>(p.ws + p.lay.chain_err), emit_label};
+    const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
+    const bool f32 = p.dtype == CTC_DTYPE_F32;
     return checked_launch([&] {
-        if (p.dtype == CTC_DTYPE_F32)
-            hipLaunchKernelGGL(ctc_softmax_kernel<float>, grid, block, 0, s,
-                               static_cast<const float*>(p.x), meta, labels, lse, emit_blank, emit_label,
-                               p.T, p.B, p.A, p.blank);
-        else
-            hipLaunchKernelGGL(ctc_softmax_kernel<bf16_t>, grid, block, 0, s,
-                               static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank, emit_label,
-                               p.T, p.B, p.A, p.blank);
+        if (p.A <= 512) {
+            const dim3 grid((p.T + 15) / 16 + 1, p.B);
+            const size_t lds = static_cast<size_t>(16) * p.A * sizeof(float);
+            if (f32)
+                hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 16>), grid, block, lds, s,
+                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 16>), grid, block, lds, s,
+                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+        } else if (p.A <= kRowsMaxA) {
+            const dim3 grid((p.T + 3) / 4 + 1, p.B);
+            const size_t lds = static_cast<size_t>(4) * p.A * sizeof(float);
+            if (f32)
+                hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 4>), grid, block, lds, s,
+                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 4>), grid, block, lds, s,
+                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+        } else {
+            const dim3 grid(p.T + 1, p.B);
+            if (f32)
+                hipLaunchKernelGGL(ctc_softmax_kernel<float>, grid, block, 0, s,
+                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL(ctc_softmax_kernel<bf16_t>, grid, block, 0, s,
+                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+        }
     });
 }
 
@@ -562,8 +738,8 @@ int launch_lattice(const Launch& p, void* stream)
             hipLaunchKernelGGL(ctc_lattice_kernel_w1, grid, block, 0, s, meta, order, labels,
                                emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
         });
-    // One LDS slot per step and per wavefront boundary.
-    const size_t ring_bytes = static_cast<size_t>(p.max_waves) * p.max_frames * sizeof(double);
+    // One LDS slot per step and per wavefront.
+    const size_t slot_bytes = static_cast<size_t>(p.max_waves) * p.max_frames * sizeof(double);
     static const size_t lds_limit = [] {
         const size_t want = 160 * 1024;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ctc_lattice_kernel),
@@ -571,9 +747,9 @@ int launch_lattice(const Launch& p, void* stream)
         if (e != hipSuccess) { (void)hipGetLastError(); return static_cast<size_t>(64 * 1024); }
         return want;
     }();
-    if (ring_bytes <= lds_limit)
+    if (slot_bytes <= lds_limit)
         return checked_launch([&] {
-            hipLaunchKernelGGL(ctc_lattice_kernel, grid, block, ring_bytes, s, meta, order, labels,
+            hipLaunchKernelGGL(ctc_lattice_kernel, grid, block, slot_bytes, s, meta, order, labels,
                                emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
         });
     return checked_launch([&] {
@@ -592,19 +768,37 @@ int launch_gradient(const Launch& p, void* stream)
     auto* beta = reinterpret_cast<const double*>(p.ws + p.lay.beta);
     auto* logp = reinterpret_cast<const double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<const int*>(p.ws + p.lay.chain_err);
-    const dim3 grid(p.T, p.B), block(kRowThreads);
+    const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
+    const bool f32 = p.dtype == CTC_DTYPE_F32;
     return checked_launch([&] {
-        if (p.dtype == CTC_DTYPE_F32)
-            hipLaunchKernelGGL(ctc_gradient_kernel<float>, grid, block, 0, s,
-                               static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta,
-                               labels, links, lse, alpha, beta, logp, chain_err, p.costs,
-                               p.T, p.B, p.A, p.blank);
-        else
-            hipLaunchKernelGGL(ctc_gradient_kernel<bf16_t>, grid, block, 0, s,
-                               static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta,
-                               labels, links, lse, alpha, beta, logp, chain_err, p.costs,
-                               p.T, p.B, p.A, p.blank);
+        if (p.A <= kRowsMaxA) {
+            const dim3 grid((p.T + kGradRows - 1) / kGradRows, p.B);
+            const int Lmax = p.max_label;
+            const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + p.A)) * 4;
+            if (f32)
+                hipLaunchKernelGGL(ctc_gradient_rows_kernel<float>, grid, block, lds, s,
+                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta,
+                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
+                                   p.T, p.B, p.A, p.blank, Lmax);
+            else
+                hipLaunchKernelGGL(ctc_gradient_rows_kernel<bf16_t>, grid, block, lds, s,
+                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta,
+                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
+                                   p.T, p.B, p.A, p.blank, Lmax);
+        } else {
+            const dim3 grid(p.T, p.B);
+            if (f32)
+                hipLaunchKernelGGL(ctc_gradient_kernel<float>, grid, block, 0, s,
+                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta,
+                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
+                                   p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL(ctc_gradient_kernel<bf16_t>, grid, block, 0, s,
+                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta,
+                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
+                                   p.T, p.B, p.A, p.blank);
+        }
     });
 }
 

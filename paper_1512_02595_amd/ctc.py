@@ -24,7 +24,7 @@ DTYPE_F32 = 0
 DTYPE_BF16 = 1
 
 MAX_LABEL_LENGTH = 1023
-NUM_KERNELS = 4
+NUM_KERNELS = 3
 
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error")
