@@ -22,6 +22,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
+
 #include "ctc_internal.h"
 
 namespace ctc {
@@ -107,12 +109,15 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
     __syncthreads();
     for (int j = threadIdx.x; j < m.L; j += kRowThreads) {
         const int c = s_lab[j];
-        int nxt = 0;
-        for (int i = j + 1; i < m.L; ++i)
-            if (s_lab[i] == c) { nxt = i + 1; break; }
+        // No early exit: independent iterations keep the LDS reads (one broadcast each) in flight.
+        int nxt = INT_MAX;
         bool first = true;
-        for (int i = j - 1; i >= 0; --i)
-            if (s_lab[i] == c) { first = false; break; }
+        for (int i = 0; i < m.L; ++i) {
+            const bool same = s_lab[i] == c;
+            if (same && i > j) nxt = min(nxt, i);
+            if (same && i < j) first = false;
+        }
+        nxt = (nxt == INT_MAX) ? 0 : nxt + 1;
         sa.links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
     }
     if (threadIdx.x == 0) {
@@ -302,18 +307,26 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
                         : sink;
     const int64_t ostride = active ? static_cast<int64_t>(fdir) * (2 * P) : 0;
 
-    long long* slots = reinterpret_cast<long long*>(lds);
-    auto slot_load = [&](int row, int col) {
-        return __longlong_as_double(__hip_atomic_load(slots + static_cast<size_t>(row) * Tb + col,
-                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+    // LDS slots: row `wave` is read by this wavefront, row `wave + 1` is written by it; the
+    // column is the step.  Relaxed workgroup-scope atomics are plain LDS reads and writes that
+    // the compiler neither caches in registers nor fences.
+    long long* const slots = reinterpret_cast<long long*>(lds);
+#ifdef CTC_X_READ_ROW0
+    const long long* const rd = slots;
+#else
+    const long long* const rd = slots + static_cast<size_t>(wave) * Tb;
+#endif
+    long long* const wr = slots + static_cast<size_t>(wave + 1) * Tb;
+    auto slot_read = [&](int col) {
+        return __hip_atomic_load(rd + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
-#ifdef CTC_X_NO_SYNC
+#if defined(CTC_X_NO_SYNC) || defined(CTC_X_NO_PUBLISH)
     const bool publishes = false;
 #else
     const bool publishes = kSync == Sync::kSlots && lane == 63 && wave < last_wave;
 #endif
     int budget = kSpinBudget;
-    double pre = kNeg;                                   // neighbour value for the coming step
+    long long pre = 0;                                   // neighbour value (bits) for the coming step
 
     // Label value of pair j-1 after step s (log 0 for pair 0).  `mine` is this lane's.
     auto from_prev_pair = [&](double mine, int s) {
@@ -329,14 +342,18 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         return shift_up(mine, kNeg);
 #endif
         if (kSync == Sync::kSlots) {
-            double v = pre;
-            if (__double2hiint(v) == kEmptyHi) {         // same for every lane of the wavefront
-                while (__double2hiint(v) == kEmptyHi && budget > 0) {
+            // Every lane read the same slot, so the emptiness test is a scalar one.
+            long long bits = pre;
+            int hi = __builtin_amdgcn_readfirstlane(static_cast<int>(bits >> 32));
+            if (__builtin_expect(hi == kEmptyHi, 0)) {
+                while (budget > 0) {
                     --budget;
-                    v = slot_load(wave, s);
+                    bits = slot_read(s);
+                    hi = __builtin_amdgcn_readfirstlane(static_cast<int>(bits >> 32));
+                    if (hi != kEmptyHi) break;
                 }
             }
-            return shift_up(mine, v);
+            return shift_up(mine, __longlong_as_double(bits));
         }
         return shift_up(mine, kNeg);
     };
@@ -349,8 +366,8 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         v_blank = i_blank + static_cast<double>(eb);
         v_label = i_label + static_cast<double>(el);
         if (publishes)
-            __hip_atomic_store(slots + static_cast<size_t>(wave + 1) * Tb + step, __double_as_longlong(v_label),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_store(wr + step, __double_as_longlong(v_label), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
 #ifndef CTC_X_NO_STORE
         *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
 #endif
@@ -360,11 +377,13 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         const double prev = from_prev_pair(v_label, step - 1);
         // start fetching the neighbour's value of this step; it is needed one step on
 #ifndef CTC_X_NO_SYNC
-        if (kSync == Sync::kSlots) pre = slot_load(wave, step);
+        if (kSync == Sync::kSlots) pre = slot_read(step);
 #endif
         i_blank = lse2(v_blank, prev);
         i_label = lse3(v_label, v_blank, prev + skip_penalty);
         finish_step(step, eb, el);
+        // Keep the wait for `pre` at the top of the next step, a whole step after its issue.
+        if (kSync == Sync::kSlots) __builtin_amdgcn_sched_barrier(0);
     };
     auto readlane = [](float v, int l) {
         return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
@@ -375,7 +394,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         const float ebv = *bp;
         const float el = *ep;
         finish_step(0, readlane(ebv, 0), el);
-        if (kSync == Sync::kSlots) pre = slot_load(wave, 0);
+        if (kSync == Sync::kSlots) pre = slot_read(0);
     }
 
     // Emissions of steps 1..: two register sets, one in use, one being filled.
