@@ -55,6 +55,43 @@ __device__ __forceinline__ uint16_t to_bf16_bits(float v)
 }
 __device__ __forceinline__ void store_elem(bf16_t* p, size_t i, float v) { p[i].bits = to_bf16_bits(v); }
 
+// 16-byte vectors of activations: 4 floats or 8 bf16.
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void load(const float* p, float (&v)[4])
+    {
+        const float4 r = *reinterpret_cast<const float4*>(p);
+        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float (&v)[4])
+    {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8])
+    {
+        const uint4 r = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = static_cast<uint32_t>(to_bf16_bits(v[2 * i])) |
+                   (static_cast<uint32_t>(to_bf16_bits(v[2 * i + 1])) << 16);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
 // ---- workgroup reductions (256 threads = 4 wavefronts), fixed order => repeatable -------
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -161,6 +198,60 @@ void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = threadIdx.x; j < m.L; j += kRowThreads)
+        erow[j] = fmaf(load_elem(row, lab[j]), kLog2e, -l2);
+}
+
+// Wide alphabets, 16-byte aligned rows of at most 8192 symbols: the row is read once with
+// 16-byte loads and stays in registers between the maximum and the sum.
+constexpr int kWideMaxA = 8192;
+
+template <typename T>
+__global__ __launch_bounds__(kRowThreads)
+void ctc_softmax_wide_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
+                             const int* __restrict__ labels, float* __restrict__ lse,
+                             float* __restrict__ emit_blank, float* __restrict__ emit_label,
+                             const SetupArgs sa, int Tt, int B, int A, int blank)
+{
+    constexpr int N = Vec<T>::N;
+    constexpr int kVecs = kWideMaxA / (N * kRowThreads);      // vectors per thread
+    __shared__ float red[8];
+    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
+    const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const Utt m = meta[b];
+    if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
+    if (t >= m.Tb) return;
+    const T* row = x + (static_cast<size_t>(t) * B + b) * A;
+    const int nvec = A / N;
+
+    float v[kVecs][N];
+    float mx = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < kVecs; ++i) {
+        const int idx = tid + i * kRowThreads;
+        if (idx < nvec) {
+            Vec<T>::load(row + static_cast<size_t>(idx) * N, v[i]);
+#pragma unroll
+            for (int e = 0; e < N; ++e) mx = fmaxf(mx, v[i][e]);
+        }
+    }
+    mx = block_max(mx, red) * kLog2e;
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kVecs; ++i) {
+        if (tid + i * kRowThreads < nvec) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) sum += fast_exp2(fmaf(v[i][e], kLog2e, -mx));
+        }
+    }
+    sum = block_sum(sum, red + 4);
+    const float l2 = mx + fast_log2(sum);
+    if (tid == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
+
+    if (!(m.flags & kUttRuns)) return;
+    if (tid == 0) emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
+    float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
+    const int* lab = labels + m.lab_off;
+    for (int j = tid; j < m.L; j += kRowThreads)
         erow[j] = fmaf(load_elem(row, lab[j]), kLog2e, -l2);
 }
 
@@ -521,7 +612,7 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
 //   gamma_t(s) = 2^(alpha_t(s) + beta_t(s) - log2 p)        mass share of state s
 //   grad[k]    = y_t(k) - sum_{s: symbol(s) = k} gamma_t(s) / sum_s gamma_t(s)
 // Dividing by the row's own total (equal to 1 up to rounding) keeps every row summing to zero.
-template <typename T>
+template <typename T, bool kVector>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_gradient_kernel(const T* __restrict__ x, T* __restrict__ grads,
                          const Utt* __restrict__ meta, const int* __restrict__ labels,
@@ -539,8 +630,14 @@ void ctc_gradient_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
     T* grow = grads + row_off;
 
+    constexpr int N = Vec<T>::N;
     if (t >= m.Tb || !(m.flags & kUttRuns)) {
-        for (int k = tid; k < A; k += kRowThreads) store_elem(grow, k, 0.0f);
+        if (kVector) {
+            float zero[N] = {};
+            for (int i = tid; i < A / N; i += kRowThreads) Vec<T>::store(grow + static_cast<size_t>(i) * N, zero);
+        } else {
+            for (int k = tid; k < A; k += kRowThreads) store_elem(grow, k, 0.0f);
+        }
         return;
     }
     const T* xrow = x + row_off;
@@ -565,8 +662,18 @@ void ctc_gradient_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const float inv_z = 1.0f / z;
     const float l2 = lse[static_cast<size_t>(b) * Tt + t];
 
-    for (int k = tid; k < A; k += kRowThreads)
-        store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)));
+    if (kVector) {
+        for (int i = tid; i < A / N; i += kRowThreads) {
+            float v[N];
+            Vec<T>::load(xrow + static_cast<size_t>(i) * N, v);
+#pragma unroll
+            for (int e = 0; e < N; ++e) v[e] = fast_exp2(fmaf(v[e], kLog2e, -l2));
+            Vec<T>::store(grow + static_cast<size_t>(i) * N, v);
+        }
+    } else {
+        for (int k = tid; k < A; k += kRowThreads)
+            store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)));
+    }
     // The symbols that occur in the label are rewritten below by other threads of this
     // workgroup: make the stores above complete before any of those is issued.
     __threadfence_block();
@@ -686,6 +793,14 @@ int checked_launch(F&& f)
 
 namespace {
 constexpr int kRowsMaxA = 2048;        // alphabets up to this size use the multi-row kernels
+
+// Rows start on 16-byte boundaries and hold a whole number of 16-byte vectors.
+bool vector_ok(const Launch& p)
+{
+    const int n = (p.dtype == CTC_DTYPE_F32) ? 4 : 8;
+    return p.A % n == 0 && reinterpret_cast<uintptr_t>(p.x) % 16 == 0 &&
+           reinterpret_cast<uintptr_t>(p.grads) % 16 == 0;
+}
 }
 
 int launch_softmax(const Launch& p, void* stream)
@@ -721,6 +836,16 @@ int launch_softmax(const Launch& p, void* stream)
                                    emit_label, sa, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 4>), grid, block, lds, s,
+                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+        } else if (vector_ok(p) && p.A <= kWideMaxA) {
+            const dim3 grid(p.T + 1, p.B);
+            if (f32)
+                hipLaunchKernelGGL(ctc_softmax_wide_kernel<float>, grid, block, 0, s,
+                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL(ctc_softmax_wide_kernel<bf16_t>, grid, block, 0, s,
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
                                    emit_label, sa, p.T, p.B, p.A, p.blank);
         } else {
@@ -807,16 +932,16 @@ int launch_gradient(const Launch& p, void* stream)
                                    p.T, p.B, p.A, p.blank, Lmax);
         } else {
             const dim3 grid(p.T, p.B);
-            if (f32)
-                hipLaunchKernelGGL(ctc_gradient_kernel<float>, grid, block, 0, s,
-                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta,
-                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
-                                   p.T, p.B, p.A, p.blank);
-            else
-                hipLaunchKernelGGL(ctc_gradient_kernel<bf16_t>, grid, block, 0, s,
-                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta,
-                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
-                                   p.T, p.B, p.A, p.blank);
+            const bool vec = vector_ok(p);
+#define CTC_LAUNCH_GRADIENT(TYPE, VEC)                                                             \
+    hipLaunchKernelGGL((ctc_gradient_kernel<TYPE, VEC>), grid, block, 0, s,                         \
+                       static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,     \
+                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank)
+            if (f32 && vec) CTC_LAUNCH_GRADIENT(float, true);
+            else if (f32) CTC_LAUNCH_GRADIENT(float, false);
+            else if (vec) CTC_LAUNCH_GRADIENT(bf16_t, true);
+            else CTC_LAUNCH_GRADIENT(bf16_t, false);
+#undef CTC_LAUNCH_GRADIENT
         }
     });
 }

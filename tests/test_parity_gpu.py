@@ -74,6 +74,9 @@ def test_sweep_config_bf16():
     (6, dict(T=25, B=8, A=40, max_label=12, blank=39, sigma=4.0)),
     (7, dict(T=20, B=3, A=1030, max_label=10, blank=517)),         # alphabet not a multiple of 4
     (8, dict(T=64, B=5, A=64, max_label=63, feasible_only=True)),
+    (11, dict(T=9, B=3, A=2051, max_label=6, blank=2050)),          # wide alphabet, rows not 16-byte aligned
+    (12, dict(T=7, B=2, A=9000, max_label=5, blank=4000)),          # wider than the register-resident path
+    (13, dict(T=12, B=3, A=600, max_label=10, sigma=3.0)),          # mid-size alphabet (bigram-like)
 ])
 def test_random_shapes(seed, kw):
     check(wl.make_random(seed, **kw))
@@ -82,6 +85,8 @@ def test_random_shapes(seed, kw):
 def test_random_shapes_bf16():
     check(wl.make_random(9, T=50, B=6, A=29, max_label=20, sigma=2.0, feasible_only=True), ctc.DTYPE_BF16)
     check(wl.make_random(10, T=30, B=3, A=1001, max_label=10), ctc.DTYPE_BF16)
+    check(wl.make_random(14, T=8, B=2, A=4104, max_label=6), ctc.DTYPE_BF16)      # 16-byte vector path
+    check(wl.make_random(15, T=8, B=2, A=4101, max_label=6), ctc.DTYPE_BF16)      # scalar wide path
 
 
 def test_degenerate_lengths():
