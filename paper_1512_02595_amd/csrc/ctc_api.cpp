@@ -29,6 +29,34 @@ inline bool record(int err)
 
 }  // namespace
 
+// Wavefronts and halo width for a label of this length.  With one wavefront per SIMD (up to
+// 4) a step costs about 240 clocks and a hand-over about 300; with several per SIMD the
+// vector ALU is the limit (about 190 clocks per wavefront-step) and most of a hand-over's
+// latency hides behind the other wavefronts.
+WavePlan plan_waves(int label_length)
+{
+    const int pairs = label_length + 1;
+    if (pairs <= 64) return {1, 0, false};
+    const int w0 = (pairs + 62) / 63;
+    if (w0 > 16) return {16, 0, true};
+    WavePlan best{w0, 0, false};
+    double best_cost = 1e30;
+    for (int w = w0; w <= 16 && w <= w0 + 4; ++w) {
+        const int useful = (pairs + w - 1) / w;
+        // the lanes handed up must themselves be exact ones: halo <= 64 - halo
+        const int halo = std::min(64 - useful, 32);
+        if (halo < 1) continue;
+        const int per_simd = (w + 3) / 4;
+        // the last term prefers fewer wavefronts when the estimates are close
+        const double cost = ((per_simd == 1) ? 240.0 + 300.0 / halo : per_simd * 190.0 + 120.0 / halo) + 4.0 * w;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = {w, halo, false};
+        }
+    }
+    return best;
+}
+
 ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
                          const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay)
 {
@@ -56,7 +84,7 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
     l.frames = frames;
     l.ab_doubles = ab;
     size_t off = 0;
-    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 40 B each: stays 8-byte aligned
+    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 48 B each: stays 8-byte aligned
     l.order = off;  off += static_cast<size_t>(B) * sizeof(int32_t);
     l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
     l.upload_bytes = off;
@@ -123,6 +151,7 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
 
     int64_t lab_off = 0, e_off = 0, ab_off = 0, f_off = 0;
     int n_run = 0, max_waves = 1, max_frames = 0, max_label = 0;
+    bool needs_barrier = false;
     for (int b = 0; b < c.B; ++b) {
         const int L = c.label_lengths[b], Tb = c.input_lengths[b];
         const int32_t* lab = c.flat_labels + lab_off;
@@ -142,6 +171,9 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
         m.lab_off = static_cast<int32_t>(lab_off);
         m.flags = runs ? kUttRuns : 0;
         m.f_off = static_cast<int32_t>(f_off);
+        const WavePlan wp = plan_waves(L);
+        m.waves = wp.waves;
+        m.halo = wp.halo;
         m.reserved = 0;
         m.e_off = e_off;
         m.ab_off = ab_off;
@@ -151,15 +183,16 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
         ab_off += static_cast<int64_t>(Tb) * 2 * (L + 1);
         if (runs) {
             order[n_run++] = b;
-            max_waves = std::max(max_waves, (L + 1 + 63) / 64);
+            max_waves = std::max(max_waves, wp.waves);
+            needs_barrier = needs_barrier || wp.barrier;
             max_frames = std::max(max_frames, Tb);
         }
     }
     for (int i = n_run; i < c.B; ++i) order[i] = -1;
     // Heaviest chains first, so the longest recursion does not start last.
     std::stable_sort(order, order + n_run, [&](int a, int b) {
-        const int64_t wa = static_cast<int64_t>(meta[a].Tb) * ((meta[a].L + 64) / 64);
-        const int64_t wb = static_cast<int64_t>(meta[b].Tb) * ((meta[b].L + 64) / 64);
+        const int64_t wa = static_cast<int64_t>(meta[a].Tb) * meta[a].waves;
+        const int64_t wb = static_cast<int64_t>(meta[b].Tb) * meta[b].waves;
         return wa > wb;
     });
 
@@ -171,6 +204,7 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     out->max_waves = max_waves;
     out->max_frames = max_frames;
     out->max_label = max_label;
+    out->needs_barrier = needs_barrier;
     out->x = c.x;
     out->grads = c.grads;
     out->costs = c.costs;

@@ -9,18 +9,28 @@
 
 namespace ctc {
 
-// Per-utterance record, identical on host and device (40 bytes).
+// Per-utterance record, identical on host and device (48 bytes).
 struct Utt {
     int32_t Tb;        // frames of this utterance (input_lengths[b])
     int32_t L;         // label length
     int32_t lab_off;   // offset of its label string in the flat label array
     int32_t flags;     // bit 0: the lattice runs (Tb > 0 and an alignment exists)
     int32_t f_off;     // frames of all earlier utterances: offset of its blank emissions [Tb]
+    int32_t waves;     // wavefronts its lattice chains use
+    int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
     int32_t reserved;
     int64_t e_off;     // offset (floats) of its label emissions [Tb][L]
     int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][2(L+1)]
 };
-static_assert(sizeof(Utt) == 40, "Utt must stay 40 bytes");
+static_assert(sizeof(Utt) == 48, "Utt must stay 48 bytes");
+
+// How the L+1 state pairs of a chain are spread over wavefronts.
+struct WavePlan {
+    int waves;
+    int halo;
+    bool barrier;      // too long for a halo: 64 pairs per wavefront, one barrier per step
+};
+WavePlan plan_waves(int label_length);
 
 constexpr int kUttRuns = 1;
 
@@ -29,7 +39,7 @@ constexpr int kUttRuns = 1;
 // has requested steps up to s0 + 3*kChunk - 1: at most 3*kChunk - 1 rows past either end of
 // an utterance's block (past the end going forward, before the start going backward).  These
 // margins keep such reads inside the workspace; the values read there are never used.
-constexpr int kChunk = 16;            // steps whose emissions are fetched together
+constexpr int kChunk = 8;             // steps whose emissions are fetched together
 constexpr int kOverFetchRows = 3 * kChunk;
 constexpr int kBlankSlack = kOverFetchRows + kChunk;                          // floats, each side
 constexpr int kLabelSlack = kOverFetchRows * (CTC_MAX_LABEL_LENGTH + 1);      // floats, each side
@@ -69,6 +79,7 @@ struct Launch {
     int max_waves;      // wavefronts per lattice block
     int max_frames;     // longest utterance among those whose lattice runs
     int max_label;      // longest label of the batch
+    bool needs_barrier; // some utterance's label leaves no room for a halo
     const void* x;
     void* grads;
     float* costs;

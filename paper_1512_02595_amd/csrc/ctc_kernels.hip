@@ -335,16 +335,24 @@ __device__ __forceinline__ double shift_up(double v, double lane0)
     return __hiloint2double(hi, lo);
 }
 
-constexpr int kEmptyHi = -1;          // high word of an unwritten LDS slot (a NaN no result can be)
 constexpr int kSpinBudget = 1 << 22;  // polls a wavefront may spend waiting before it gives up
+constexpr int kHaloEntries = 64;      // 16-byte entries of one wavefront boundary's exchange buffer (2 x 32)
 
-enum class Sync { kNone, kSlots, kBarrier };
+enum class Sync { kNone, kHalo, kBarrier };
 
-// One chain = one direction of one utterance.  Thread j owns the pair
+// LDS of the halo exchange: per wavefront w, what w hands to w+1.
+struct HaloLds {
+    double2 data[16][kHaloEntries];
+    int ready[16];                    // last generation wavefront w has published
+    int done[16];                     // last generation wavefront w has taken from w-1
+};
+
+// One chain = one direction of one utterance.  A lane owns the pair
 //   forward : (blank state 2j,       label j        = state 2j+1)
 //   backward: (blank state 2(L-j),   label L-1-j    = state 2(L-j)-1)
 // so that in both directions the only value needed from a neighbour is the label entry of
-// pair j-1, and both directions run the same recursion on the "inclusive" quantity
+// pair j-1 (one DPP shift), and both directions run the same recursion on the "inclusive"
+// quantity
 //   w_step(state) = E_frame(state) + log2 sum over predecessors of 2^w_{step-1}
 // which is alpha going forward.  Going backward, the sum before E is added is the beta that
 // excludes its own frame's emission, and that is what gets stored, so that
@@ -355,28 +363,34 @@ enum class Sync { kNone, kSlots, kBarrier };
 //
 // A lone wavefront per SIMD issues one instruction every four clocks whatever its kind, so
 // the step is written for instruction count: pointers advance by adds, the blank emissions of
-// a chunk arrive in one load and are read by lane, lanes without a pair are switched off once.
+// a chunk arrive in one load and are read by lane, lanes without a pair write to a sink.
 //
-// Wavefronts of one chain (64 pairs each) exchange one value per step.  With Sync::kSlots the
-// label value of lane 63 is published per step in an LDS slot of its own (row wave+1, column
-// step; rows start "empty", row 0 is all log 0 for wavefront 0), and every lane of the next
-// wavefront reads that slot (one broadcast read, issued a step early) and polls while it is
-// empty: no barrier, the wavefronts run skewed by a step or two.  A wavefront depends only on
-// lower ones and wavefront 0 never waits, so every wait ends; a poll budget bounds it anyway.
+// Labels of more than 63 symbols span several wavefronts.  Exchanging a value at every step
+// costs more than a third of the step, so with Sync::kHalo each wavefront recomputes, in its
+// first `halo` lanes, the last `halo` pairs of the wavefront below it:
+//     pair of (wave, lane) = wave * (64 - halo) + lane - halo.
+// An error at lane 0 (whose neighbour is missing) moves up one lane per step, so the lanes
+// from `halo` on stay exact for `halo` steps.  Every `halo` steps the lower wavefront hands
+// over the exact state of those pairs through LDS (a small ring per boundary, guarded by two
+// counters: `ready` written by the producer after the data, `done` by the consumer after its
+// read).  No barrier; the wavefronts run skewed.  A wavefront waits for data only on lower
+// ones and for space only on higher ones, wavefront 0 needs no data and the last one no space,
+// so every wait ends; a poll budget bounds them regardless and raises chain_err when spent.
 template <bool kBackward, Sync kSync>
 __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
                                           double* __restrict__ out, double* __restrict__ logp,
                                           float* __restrict__ costs, int* __restrict__ chain_err,
-                                          double* __restrict__ sink, double* lds)
+                                          double* __restrict__ sink, void* lds)
 {
     const int L = m.L, Tb = m.Tb, P = L + 1;
-    const int j = threadIdx.x, lane = j & 63, wave = j >> 6;
-    const bool active = j < P;                           // lanes beyond pair L only go through the motions
-    const int last_wave = L >> 6;                        // wavefront that holds pair L
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
+    const int j = wave * (64 - halo) + lane - halo;      // may be negative in wavefront 0: no such pair
     const int* lab = labels + m.lab_off;
-    const bool has_label = j < L;
+    const bool has_label = j >= 0 && j < L;
+    const bool active = lane >= halo && j <= L;          // this lane stores pair j
     const int li = kBackward ? (L - 1 - j) : j;          // label index of this pair's label state
     // May the label state be entered from pair j-1's label?  (Not across equal symbols.)
     double skip_penalty = kNeg;
@@ -385,107 +399,134 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     // Frame of step s: s going forward, Tb-1-s going backward.
     const int f0 = kBackward ? (Tb - 1) : 0;
     const int fdir = kBackward ? -1 : 1;
-    // Label emissions: a per-lane pointer that moves one row per step.  The lane that holds
-    // pair L has no label state: it reads a constant log 0 and stays there.
+    // Label emissions: a per-lane pointer that moves one row per step.  A lane without a label
+    // state reads a constant log 0 and stays there.
     const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * L + li
                                 : emit_label;
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * L : 0;
-    // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i%8).
+    // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
-    // Output rows.
-    // Output rows; lanes without a pair write to a 16-byte sink instead.
+    // Output rows; lanes that store nothing write to a 16-byte sink instead.
     double* op = active ? out + m.ab_off + static_cast<int64_t>(f0) * (2 * P) + (kBackward ? 2 * (L - j) : 2 * j)
                         : sink;
     const int64_t ostride = active ? static_cast<int64_t>(fdir) * (2 * P) : 0;
 
-    // LDS slots: row `wave` is read by this wavefront, row `wave + 1` is written by it; the
-    // column is the step.  Relaxed workgroup-scope atomics are plain LDS reads and writes that
-    // the compiler neither caches in registers nor fences.
-    long long* const slots = reinterpret_cast<long long*>(lds);
-#ifdef CTC_X_READ_ROW0
-    const long long* const rd = slots;
-#else
-    const long long* const rd = slots + static_cast<size_t>(wave) * Tb;
-#endif
-    long long* const wr = slots + static_cast<size_t>(wave + 1) * Tb;
-    auto slot_read = [&](int col) {
-        return __hip_atomic_load(rd + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    };
-#if defined(CTC_X_NO_SYNC) || defined(CTC_X_NO_PUBLISH)
-    const bool publishes = false;
-#else
-    const bool publishes = kSync == Sync::kSlots && lane == 63 && wave < last_wave;
-#endif
+    HaloLds* const hl = static_cast<HaloLds*>(lds);
+    const int last_wave = m.waves - 1;
     int budget = kSpinBudget;
-    long long pre = 0;                                   // neighbour value (bits) for the coming step
-
-    // Label value of pair j-1 after step s (log 0 for pair 0).  `mine` is this lane's.
-    auto from_prev_pair = [&](double mine, int s) {
-        if (kSync == Sync::kBarrier) {
-            double (*xch)[16] = reinterpret_cast<double (*)[16]>(lds);
-            double r = shift_up(mine, kNeg);
-            if (lane == 63) xch[s & 1][wave] = mine;
-            __syncthreads();
-            if (lane == 0 && wave > 0) r = xch[s & 1][wave - 1];
-            return r;
-        }
-#ifdef CTC_X_NO_SYNC
-        return shift_up(mine, kNeg);
-#endif
-        if (kSync == Sync::kSlots) {
-            // Every lane read the same slot, so the emptiness test is a scalar one.
-            long long bits = pre;
-            int hi = __builtin_amdgcn_readfirstlane(static_cast<int>(bits >> 32));
-            if (__builtin_expect(hi == kEmptyHi, 0)) {
-                while (budget > 0) {
-                    --budget;
-                    bits = slot_read(s);
-                    hi = __builtin_amdgcn_readfirstlane(static_cast<int>(bits >> 32));
-                    if (hi != kEmptyHi) break;
-                }
-            }
-            return shift_up(mine, __longlong_as_double(bits));
-        }
-        return shift_up(mine, kNeg);
-    };
+    int until_refresh = halo;                            // steps until the next hand-over
+    int generation = 0;
+    // Each boundary's buffer is used as two halves of 32 entries, alternating by generation
+    // (halo <= 32), so a producer may run one hand-over ahead of its consumer.
+    int half = 0;                                        // entry offset of the half in use: 0 or 32
+    double2* const wr_base = (kSync == Sync::kHalo)
+        ? &hl->data[wave][lane >= 64 - halo ? lane - (64 - halo) : 0] : nullptr;
+    const double2* const rd_base = (kSync == Sync::kHalo)
+        ? &hl->data[wave > 0 ? wave - 1 : 0][lane < halo ? lane : 0] : nullptr;
+    int* const my_ready = &hl->ready[wave];
+    int* const my_done = &hl->done[wave];
+    int* const up_done = &hl->done[wave < 15 ? wave + 1 : 15];
+    int* const low_ready = &hl->ready[wave > 0 ? wave - 1 : 0];
 
     double i_blank = (j == 0) ? 0.0 : kNeg;
     double i_label = (j == 0 && has_label) ? 0.0 : kNeg;
     double v_blank, v_label;
 
-    auto finish_step = [&](int step, float eb, float el) {
+    auto counter = [&](int* p) {
+        return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto uniform = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+    int done_seen = 0;                                   // a (possibly old) reading of done[wave + 1]
+    // After a step whose number is a multiple of `halo`: pass the exact state of the top `halo`
+    // pairs up, take the exact state of the halo pairs from below.
+    auto hand_over = [&]() {
+        ++generation;
+        half ^= 32;
+        if (wave < last_wave) {
+            // Space: the consumer must have taken generation - 2.  The reading from the last
+            // hand-over usually shows that already.
+            int seen = uniform(done_seen);
+            if (__builtin_expect(seen < generation - 2, 0)) {
+                while (seen < generation - 2 && budget > 0) {
+                    --budget;
+                    seen = uniform(counter(up_done));
+                }
+            }
+            if (lane >= 64 - halo) wr_base[half] = make_double2(v_blank, v_label);
+            // LDS operations of a wavefront complete in order: the counter follows the data.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 63) __hip_atomic_store(my_ready, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            done_seen = counter(up_done);                // consumed at the next hand-over
+        }
+        if (wave > 0) {
+            // Counter and data are read back to back; the data count only if the counter,
+            // read first, already showed this generation.
+            int ready = counter(low_ready);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            double2 v = rd_base[half];
+            ready = uniform(ready);
+            if (__builtin_expect(ready < generation, 0)) {
+                while (ready < generation && budget > 0) {
+                    --budget;
+                    ready = counter(low_ready);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    v = rd_base[half];
+                    ready = uniform(ready);
+                }
+            }
+            if (lane < halo) {
+                v_blank = v.x;
+                v_label = v.y;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 0) __hip_atomic_store(my_done, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    };
+
+    // Label value of pair j-1 after step s (log 0 for pair 0).  `mine` is this lane's.
+    auto from_prev_pair = [&](double mine, int s) {
+        double r = shift_up(mine, kNeg);
+        if (kSync == Sync::kBarrier) {
+            double (*xch)[16] = static_cast<double (*)[16]>(lds);
+            if (lane == 63) xch[s & 1][wave] = mine;
+            __syncthreads();
+            if (lane == 0 && wave > 0) r = xch[s & 1][wave - 1];
+        }
+        return r;
+    };
+
+    auto finish_step = [&](float eb, float el) {
         v_blank = i_blank + static_cast<double>(eb);
         v_label = i_label + static_cast<double>(el);
-        if (publishes)
-            __hip_atomic_store(wr + step, __double_as_longlong(v_label), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
-#ifndef CTC_X_NO_STORE
         *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
-#endif
         op += ostride;
+        if (kSync == Sync::kHalo) {
+            if (--until_refresh == 0) {
+#ifndef CTC_X_NO_SYNC
+                hand_over();
+#endif
+                until_refresh = halo;
+            }
+        }
     };
     auto advance = [&](int step, float eb, float el) {
         const double prev = from_prev_pair(v_label, step - 1);
-        // start fetching the neighbour's value of this step; it is needed one step on
-#ifndef CTC_X_NO_SYNC
-        if (kSync == Sync::kSlots) pre = slot_read(step);
-#endif
         i_blank = lse2(v_blank, prev);
         i_label = lse3(v_label, v_blank, prev + skip_penalty);
-        finish_step(step, eb, el);
-        // Keep the wait for `pre` at the top of the next step, a whole step after its issue.
-        if (kSync == Sync::kSlots) __builtin_amdgcn_sched_barrier(0);
+        finish_step(eb, el);
     };
     auto readlane = [](float v, int l) {
         return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
     };
 
-    // step 0
+    // step 0: every lane starts from the exact state of its pair, halo lanes included
     {
         const float ebv = *bp;
         const float el = *ep;
-        finish_step(0, readlane(ebv, 0), el);
-        if (kSync == Sync::kSlots) pre = slot_read(0);
+        v_blank = i_blank + static_cast<double>(readlane(ebv, 0));
+        v_label = i_label + static_cast<double>(el);
+        *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+        op += ostride;
     }
 
     // Emissions of steps 1..: two register sets, one in use, one being filled.
@@ -498,15 +539,12 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             el[i] = *ep;
         }
     };
+    // One copy of the step per chunk position and register set: the kernel has to stay well
+    // inside the instruction cache that two compute units share.
     auto run = [&](const float (&el)[kChunk], const float eb, int s0) {
-        if (s0 + kChunk <= Tb) {
 #pragma unroll
-            for (int i = 0; i < kChunk; ++i) advance(s0 + i, readlane(eb, i), el[i]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < kChunk; ++i)
-                if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
-        }
+        for (int i = 0; i < kChunk; ++i)
+            if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
     };
     fetch(el_a, eb_a, 1);
     for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
@@ -518,14 +556,16 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L-1.
+        // Pair L sits in a lane >= halo, so the lane below it is exact (a hand-over that fell
+        // due after the last step has already been done by finish_step).
         const double prev = from_prev_pair(v_label, Tb - 1);
-        if (j == L) {
+        if (active && j == L) {
             const double lp = lse2(v_blank, prev);
             logp[u] = lp;
             costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
         }
     }
-    if (kSync == Sync::kSlots && budget <= 0) chain_err[u] = 1;
+    if (kSync == Sync::kHalo && budget <= 0 && lane == 0) chain_err[u] = 1;
 }
 
 template <Sync kSync>
@@ -535,17 +575,18 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
                                              const float* __restrict__ emit_label,
                                              double* __restrict__ alpha, double* __restrict__ beta,
                                              double* __restrict__ logp, float* __restrict__ costs,
-                                             int* __restrict__ chain_err, double* __restrict__ sink, double* lds)
+                                             int* __restrict__ chain_err, double* __restrict__ sink,
+                                             void* lds)
 {
     const int u = order[blockIdx.x];
     const Utt m = meta[u];
-    const int waves_needed = (m.L + 1 + 63) >> 6;
-    const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves_needed;
-    if (kSync == Sync::kSlots) {
-        // row 0: log 0 for wavefront 0; rows 1..: empty until written
-        const int slots = waves_needed * m.Tb;
-        const double empty = __hiloint2double(kEmptyHi, -1);
-        for (int i = threadIdx.x; i < slots; i += blockDim.x) lds[i] = (i < m.Tb) ? kNeg : empty;
+    const bool idle = static_cast<int>(threadIdx.x >> 6) >= m.waves;
+    if (kSync == Sync::kHalo) {
+        HaloLds* hl = static_cast<HaloLds*>(lds);
+        if (threadIdx.x < 16) {
+            hl->ready[threadIdx.x] = 0;
+            hl->done[threadIdx.x] = 0;
+        }
         __syncthreads();
         if (idle) return;
     } else if (kSync == Sync::kBarrier) {
@@ -564,7 +605,7 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
 }
 
 // grid = (utterances whose lattice runs, 2): y = 0 forward, y = 1 backward.
-// blockDim.x = 64 * (wavefronts of the longest label).
+// blockDim.x = 64 * (most wavefronts any utterance of the batch uses).
 // Variant for batches whose labels all fit one wavefront: no exchange at all.
 __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
@@ -578,8 +619,7 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
                               chain_err, sink, nullptr);
 }
 
-// Multi-wavefront chains, neighbours exchanged through per-step LDS slots (dynamic LDS:
-// wavefronts * max frames doubles).
+// Multi-wavefront chains with the halo exchange.
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -588,12 +628,13 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         double* __restrict__ logp, float* __restrict__ costs,
                         int* __restrict__ chain_err, double* __restrict__ sink)
 {
-    extern __shared__ double slot_lds[];
-    lattice_body<Sync::kSlots>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
-                               chain_err, sink, slot_lds);
+    __shared__ HaloLds halo_lds;
+    lattice_body<Sync::kHalo>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+                              chain_err, sink, &halo_lds);
 }
 
-// Fallback when the slots would not fit in LDS: one barrier per step.
+// Labels too long to leave room for a halo (more than 16 * 63 pairs): 64 pairs per wavefront
+// and one barrier per step.
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restrict__ order,
                                 const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -882,18 +923,9 @@ int launch_lattice(const Launch& p, void* stream)
             hipLaunchKernelGGL(ctc_lattice_kernel_w1, grid, block, 0, s, meta, order, labels,
                                emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
         });
-    // One LDS slot per step and per wavefront.
-    const size_t slot_bytes = static_cast<size_t>(p.max_waves) * p.max_frames * sizeof(double);
-    static const size_t lds_limit = [] {
-        const size_t want = 160 * 1024;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ctc_lattice_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(want));
-        if (e != hipSuccess) { (void)hipGetLastError(); return static_cast<size_t>(64 * 1024); }
-        return want;
-    }();
-    if (slot_bytes <= lds_limit)
+    if (!p.needs_barrier)
         return checked_launch([&] {
-            hipLaunchKernelGGL(ctc_lattice_kernel, grid, block, slot_bytes, s, meta, order, labels,
+            hipLaunchKernelGGL(ctc_lattice_kernel, grid, block, 0, s, meta, order, labels,
                                emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
         });
     return checked_launch([&] {
