@@ -30,6 +30,11 @@ ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 LANE_OPS_PER_PAIR_STEP = 45
 
 
+# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
+# the rocprofv3 --pmc runs summarised in profiles/english_B64_A29_T750_hbm_traffic.md.
+MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 19.0e6, "ctc_lattice": 139.6e6, "ctc_gradient": 129.2e6}}
+
+
 def kernel_bytes(batch, elem):
     """Algorithmic HBM bytes of each kernel for one launch on `batch`."""
     frames = batch.frames
@@ -56,6 +61,8 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct minibatches rotated through")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of known size (reference for HBM counters)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -66,6 +73,16 @@ def main():
     from paper_1512_02595_amd import ctc, harness, workloads
 
     dev = harness.require_gpu()
+    if args.calibrate_copy:
+        n = 256 << 20                                   # 256 MiB read + 256 MiB written per copy
+        src = torch.ones(n // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize(dev)
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n,
+                          "copies": 5}), flush=True)
+        return
     ctc.load()
     dtype = ctc.DTYPE_F32 if args.dtype == "f32" else ctc.DTYPE_BF16
     elem = 4 if dtype == ctc.DTYPE_F32 else 2
@@ -103,17 +120,18 @@ def main():
                       "GBps": round(byt / (kavg[i] * 1e-3) / 1e9, 2) if kavg[i] > 0 else None}
     dom = int(np.argmax(kavg))
     dom_name = names[dom]
+    traffic = MEASURED_TRAFFIC.get((args.config, args.dtype), {}).get(dom_name)
     if dom_name == "ctc_lattice":
         pair_steps = 2.0 * float(np.mean([k[1] for k in kb]))       # both directions
         achieved = pair_steps * LANE_OPS_PER_PAIR_STEP / (kavg[dom] * 1e-3) / 1e12
         roofline = {"kernel": dom_name, "bound": "alu", "achieved": round(achieved, 4),
                     "peak": round(ALU_PEAK_TOPS, 2), "unit": "TFLOP/s",
-                    "frac": round(achieved / ALU_PEAK_TOPS, 5), "traffic": None,
+                    "frac": round(achieved / ALU_PEAK_TOPS, 5), "traffic": traffic,
                     "note": "flop = one non-packed VALU lane-operation; transcendental = 4"}
     else:
         achieved = kernels[dom_name]["GBps"]
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None}
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic}
 
     out = {
         "metric": "ctc_loss_grad_utterances_per_s",
@@ -145,14 +163,20 @@ def main():
             nb = max(1, int(np.searchsorted(np.cumsum(w), budget_cells)))
         nlab = int(b.label_lengths[:nb].sum())
         xs = np.ascontiguousarray(x64[:, :nb, :])
-        reps, times = 3, []
+        # About 15 core-seconds of oracle work: time one run, then size the repetitions.
+        cores = orc.max_threads()
+        c0 = time.perf_counter()
+        orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank)
+        first = time.perf_counter() - c0
+        reps = int(min(200, max(3, np.ceil(15.0 / max(first * cores, 1e-6)))))
+        times = []
         for _ in range(reps):
             c0 = time.perf_counter()
             orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank)
             times.append(time.perf_counter() - c0)
         tmed = float(np.median(times))
         out["cpu_baseline"] = {"value": round(nb / tmed, 2), "unit": "utterances/s",
-                               "cores": orc.max_threads(), "kind": "oracle",
+                               "cores": cores, "kind": "oracle",
                                "sample": "first %d of %d utterances of minibatch 0, median of %d runs, %.3f s each"
                                          % (nb, b.B, reps, tmed),
                                "activation_frames_per_s": round(float(b.input_lengths[:nb].sum()) / tmed, 1)}
