@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "ctc_internal.h"
@@ -107,6 +108,59 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
 
 namespace {
 
+// Pinned host buffers for the per-call metadata image.  The setup kernel reads the image
+// straight from host memory, so a slot may be rewritten only after that kernel has run: each
+// slot carries an event recorded behind its setup launch.  One ring per device, created on
+// first use, kept for the life of the process.
+constexpr int kStagingSlots = 8;
+
+struct StagingSlot {
+    void* host = nullptr;
+    size_t capacity = 0;
+    hipEvent_t consumed = nullptr;
+    bool in_flight = false;
+};
+
+struct StagingRing {
+    int device = -1;
+    int next = 0;
+    StagingSlot slots[kStagingSlots];
+};
+
+std::mutex g_staging_mutex;
+std::vector<StagingRing*> g_staging_rings;
+
+// Returns a slot of at least `bytes`, or nullptr on a HIP error.  Caller holds g_staging_mutex.
+StagingSlot* acquire_slot(size_t bytes)
+{
+    int dev = 0;
+    if (!record(hipGetDevice(&dev))) return nullptr;
+    StagingRing* ring = nullptr;
+    for (StagingRing* r : g_staging_rings)
+        if (r->device == dev) ring = r;
+    if (!ring) {
+        ring = new StagingRing();
+        ring->device = dev;
+        g_staging_rings.push_back(ring);
+    }
+    StagingSlot& slot = ring->slots[ring->next];
+    ring->next = (ring->next + 1) % kStagingSlots;
+    if (!slot.consumed && !record(hipEventCreateWithFlags(&slot.consumed, hipEventDisableTiming))) return nullptr;
+    if (slot.in_flight) {
+        if (!record(hipEventSynchronize(slot.consumed))) return nullptr;
+        slot.in_flight = false;
+    }
+    if (slot.capacity < bytes) {
+        if (slot.host) (void)hipHostFree(slot.host);
+        slot.host = nullptr;
+        slot.capacity = 0;
+        const size_t want = (bytes + 65535) / 65536 * 65536;
+        if (!record(hipHostMalloc(&slot.host, want, hipHostMallocDefault))) return nullptr;
+        slot.capacity = want;
+    }
+    return &slot;
+}
+
 struct Call {
     const void* x;
     const int32_t* flat_labels;
@@ -123,14 +177,8 @@ struct Call {
 
 // Validates everything that can be validated on the host, builds the upload image
 // (Utt records, run order, labels) and the launch parameters.
-ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
+ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
 {
-    if (!c.x || !c.label_lengths || !c.input_lengths || !c.costs || !c.grads || !c.ws)
-        return CTC_STATUS_INVALID_VALUE;
-    if (c.T < 1 || c.B < 1 || c.A < 1 || c.blank < 0 || c.blank >= c.A) return CTC_STATUS_INVALID_VALUE;
-    Layout lay;
-    ctc_status_t st = make_layout(c.T, c.B, c.A, c.label_lengths, c.input_lengths, c.dtype, &lay);
-    if (st != CTC_STATUS_SUCCESS) return st;
     if (lay.sumL > 0 && !c.flat_labels) return CTC_STATUS_INVALID_VALUE;
     if (reinterpret_cast<uintptr_t>(c.ws) % kAlign != 0) return CTC_STATUS_INVALID_VALUE;
 
@@ -144,10 +192,9 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     if (reinterpret_cast<uintptr_t>(c.x) % elem || reinterpret_cast<uintptr_t>(c.grads) % elem)
         return CTC_STATUS_INVALID_VALUE;
 
-    image->resize(lay.upload_bytes);
-    Utt* meta = reinterpret_cast<Utt*>(image->data() + lay.meta);
-    int32_t* order = reinterpret_cast<int32_t*>(image->data() + lay.order);
-    int32_t* labels = reinterpret_cast<int32_t*>(image->data() + lay.labels);
+    Utt* meta = reinterpret_cast<Utt*>(image + lay.meta);
+    int32_t* order = reinterpret_cast<int32_t*>(image + lay.order);
+    int32_t* labels = reinterpret_cast<int32_t*>(image + lay.labels);
 
     int64_t lab_off = 0, e_off = 0, ab_off = 0, f_off = 0;
     int n_run = 0, max_waves = 1, max_frames = 0, max_label = 0;
@@ -209,21 +256,57 @@ ctc_status_t prepare(const Call& c, Launch* out, std::vector<char>* image)
     out->grads = c.grads;
     out->costs = c.costs;
     out->ws = static_cast<char*>(c.ws);
+    out->host_image = image;
     out->lay = lay;
+    return CTC_STATUS_SUCCESS;
+}
+
+// Cheap checks that need neither the layout nor a staging slot.
+ctc_status_t precheck(const Call& c)
+{
+    if (!c.x || !c.label_lengths || !c.input_lengths || !c.costs || !c.grads || !c.ws)
+        return CTC_STATUS_INVALID_VALUE;
+    if (c.T < 1 || c.B < 1 || c.A < 1 || c.blank < 0 || c.blank >= c.A) return CTC_STATUS_INVALID_VALUE;
     return CTC_STATUS_SUCCESS;
 }
 
 ctc_status_t run(const Call& c, float* kernel_ms)
 {
-    thread_local std::vector<char> image;
-    Launch p;
-    ctc_status_t st = prepare(c, &p, &image);
+    ctc_status_t st = precheck(c);
+    if (st != CTC_STATUS_SUCCESS) return st;
+    Layout lay;
+    st = make_layout(c.T, c.B, c.A, c.label_lengths, c.input_lengths, c.dtype, &lay);
     if (st != CTC_STATUS_SUCCESS) return st;
 
     hipStream_t s = static_cast<hipStream_t>(c.stream);
-    // Pageable source: the runtime has consumed `image` when this returns.
-    if (!record(hipMemcpyAsync(p.ws, image.data(), p.lay.upload_bytes, hipMemcpyHostToDevice, s)))
-        return CTC_STATUS_HIP_ERROR;
+    Launch p;
+    StagingSlot* slot = nullptr;
+    {
+        // The image is validated while it is written; on an error nothing has been enqueued and
+        // the slot simply stays free.
+        std::lock_guard<std::mutex> lock(g_staging_mutex);
+        thread_local std::vector<char> scratch;          // validation without a device: see below
+        static const bool have_device = [] {
+            int ndev = 0;
+            const bool ok = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
+            if (!ok) (void)hipGetLastError();
+            return ok;
+        }();
+        if (!have_device) {
+            // No GPU (host-only checks of the argument validation): build the image in ordinary
+            // memory so that every validation error is still reported, then stop.
+            scratch.resize(lay.upload_bytes);
+            st = prepare(c, lay, &p, scratch.data());
+            return st != CTC_STATUS_SUCCESS ? st : CTC_STATUS_HIP_ERROR;
+        }
+        slot = acquire_slot(lay.upload_bytes);
+        if (!slot) return CTC_STATUS_HIP_ERROR;
+        st = prepare(c, lay, &p, static_cast<char*>(slot->host));
+        if (st != CTC_STATUS_SUCCESS) return st;
+        if (!record(launch_setup(p, c.stream))) return CTC_STATUS_HIP_ERROR;
+        if (!record(hipEventRecord(slot->consumed, s))) return CTC_STATUS_HIP_ERROR;
+        slot->in_flight = true;
+    }
 
     hipEvent_t ev[CTC_NUM_KERNELS + 1] = {};
     if (kernel_ms) {
@@ -231,6 +314,8 @@ ctc_status_t run(const Call& c, float* kernel_ms)
             if (!record(hipEventCreate(&e))) return CTC_STATUS_HIP_ERROR;
         if (!record(hipEventRecord(ev[0], s))) return CTC_STATUS_HIP_ERROR;
     }
+    // The setup launch has gone out above (its own time is not reported separately: it is a few
+    // microseconds and overlaps the tail of whatever ran before on the stream).
     int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_softmax, launch_lattice,
                                                                   launch_gradient};
     for (int i = 0; i < CTC_NUM_KERNELS; ++i) {

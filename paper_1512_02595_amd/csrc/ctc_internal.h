@@ -60,7 +60,7 @@ struct Layout {
     size_t alpha = 0;     // double[sum Tb*2(L+1)]
     size_t beta = 0;      // double[sum Tb*2(L+1)]
     size_t total = 0;
-    size_t upload_bytes = 0;   // meta..labels are contiguous and sent in one copy
+    size_t upload_bytes = 0;   // meta..labels are contiguous: the image the host prepares per call
     int64_t sumL = 0;
     int64_t frames = 0;
     int64_t emit_floats = 0;
@@ -84,10 +84,12 @@ struct Launch {
     void* grads;
     float* costs;
     char* ws;           // workspace base
+    const void* host_image;   // pinned host copy of the meta/order/labels regions (device-readable)
     Layout lay;
 };
 
 // Each returns a hipError_t as int (0 = success). `stream` is a hipStream_t.
+int launch_setup(const Launch& p, void* stream);
 int launch_softmax(const Launch& p, void* stream);
 int launch_lattice(const Launch& p, void* stream);
 int launch_gradient(const Launch& p, void* stream);
