@@ -41,13 +41,21 @@ def kernel_bytes(batch, elem):
     A = batch.A
     pairs = int((batch.input_lengths.astype(np.int64) * (batch.label_lengths.astype(np.int64) + 1)).sum())
     cells = batch.lattice_cells
+    full = batch.T * batch.B * A * elem
+    if A > 2048:
+        # wide alphabets: the softmax launch also writes the dense gradient (y, or zeros for
+        # padding); the gradient launch only rewrites the label columns and the blank
+        touched = int((batch.input_lengths.astype(np.int64) * (batch.label_lengths.astype(np.int64) + 2)).sum())
+        soft, grad = frames * A * elem + full, 2 * touched * elem
+    else:
+        # read every valid row once, write one statistic per row / read the rows again and write
+        # the whole gradient tensor
+        soft, grad = frames * A * elem + frames * 4, frames * A * elem + full
     return {
-        # read every valid row once; write one statistic per row
-        "ctc_softmax": frames * A * elem + frames * 4,
+        "ctc_softmax": soft,
         # one alpha and one beta value per lattice cell, 4 bytes each, written once
         "ctc_lattice": cells * 8,
-        # read every valid row again, write the whole gradient tensor
-        "ctc_gradient": frames * A * elem + batch.T * batch.B * A * elem,
+        "ctc_gradient": grad,
     }, pairs
 
 
@@ -80,8 +88,16 @@ def main():
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize(dev)
+        ms = e0.elapsed_time(e1) / 20
         print(json.dumps({"calibrate_copy": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n,
-                          "copies": 5}), flush=True)
+                          "copies": 25, "ms_per_copy": round(ms, 4),
+                          "copy_GBps_read_plus_write": round(2 * n / (ms * 1e-3) / 1e9, 1)}), flush=True)
         return
     ctc.load()
     dtype = ctc.DTYPE_F32 if args.dtype == "f32" else ctc.DTYPE_BF16

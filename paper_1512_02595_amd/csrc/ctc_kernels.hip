@@ -185,10 +185,16 @@ void ctc_setup_kernel(const char* __restrict__ host_image, char* __restrict__ ws
 }
 
 // ---- softmax statistics + emission gather --------------------------------------------------
-// Wide alphabets: one workgroup per valid frame row (t, b); grid (T, B).
+// Wide alphabets (A > 2048): one workgroup per row (t, b) of the tensor; grid (T, B).
+// The gradient of a wide alphabet is the softmax itself except in the few columns whose symbol
+// occurs in the label, so these kernels also write the dense part of the gradient while they
+// hold the row: y for valid rows, zeros for padding rows and for utterances without an
+// alignment.  The activations are then never read a second time; the label columns are
+// corrected after the recursions by the sparse variant of the gradient kernel.
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
-void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
+void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
+                        const Utt* __restrict__ meta,
                         const int* __restrict__ labels, float* __restrict__ lse,
                         float* __restrict__ emit_blank, float* __restrict__ emit_label,
                         int Tt, int B, int A, int blank)
@@ -196,8 +202,14 @@ void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
     __shared__ float red[8];
     const int t = blockIdx.x, b = blockIdx.y;
     const Utt m = meta[b];
-    if (t >= m.Tb) return;
-    const T* row = x + (static_cast<size_t>(t) * B + b) * A;
+    const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
+    T* grow = grads + row_off;
+    const bool runs = (m.flags & kUttRuns) != 0;
+    if (t >= m.Tb || !runs) {
+        for (int k = threadIdx.x; k < A; k += kRowThreads) store_elem(grow, k, 0.0f);
+        return;
+    }
+    const T* row = x + row_off;
 
     float mx = -__builtin_inff();
     for (int k = threadIdx.x; k < A; k += kRowThreads) mx = fmaxf(mx, load_elem(row, k));
@@ -209,7 +221,8 @@ void ctc_softmax_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
     const float l2 = mx + fast_log2(s);
     if (threadIdx.x == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
 
-    if (!(m.flags & kUttRuns)) return;
+    for (int k = threadIdx.x; k < A; k += kRowThreads)
+        store_elem(grow, k, fast_exp2(fmaf(load_elem(row, k), kLog2e, -l2)));
     if (threadIdx.x == 0)
         emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
@@ -224,7 +237,8 @@ constexpr int kWideMaxA = 8192;
 
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
-void ctc_softmax_wide_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
+void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
+                             const Utt* __restrict__ meta,
                              const int* __restrict__ labels, float* __restrict__ lse,
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
                              int Tt, int B, int A, int blank)
@@ -234,9 +248,16 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     __shared__ float red[8];
     const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const Utt m = meta[b];
-    if (t >= m.Tb) return;
-    const T* row = x + (static_cast<size_t>(t) * B + b) * A;
+    const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
+    T* grow = grads + row_off;
     const int nvec = A / N;
+    const bool runs = (m.flags & kUttRuns) != 0;
+    if (t >= m.Tb || !runs) {
+        const float zero[N] = {};
+        for (int i = tid; i < nvec; i += kRowThreads) Vec<T>::store(grow + static_cast<size_t>(i) * N, zero);
+        return;
+    }
+    const T* row = x + row_off;
 
     float v[kVecs][N];
     float mx = -__builtin_inff();
@@ -262,7 +283,16 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     const float l2 = mx + fast_log2(sum);
     if (tid == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
 
-    if (!(m.flags & kUttRuns)) return;
+#pragma unroll
+    for (int i = 0; i < kVecs; ++i) {
+        const int idx = tid + i * kRowThreads;
+        if (idx < nvec) {
+            float y[N];
+#pragma unroll
+            for (int e = 0; e < N; ++e) y[e] = fast_exp2(fmaf(v[i][e], kLog2e, -l2));
+            Vec<T>::store(grow + static_cast<size_t>(idx) * N, y);
+        }
+    }
     if (tid == 0) emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
@@ -673,119 +703,38 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
 }
 
 // ---- gradient ------------------------------------------------------------------------------
-// One workgroup per row (t, b) of the output, padding rows included.
 //   gamma_t(s) = 2^(alpha_t(s) + beta_t(s) - log2 p)        mass share of state s
 //   grad[k]    = y_t(k) - sum_{s: symbol(s) = k} gamma_t(s) / sum_s gamma_t(s)
 // Dividing by the row's own total (equal to 1 up to rounding) keeps every row summing to zero.
-template <typename T, bool kVector>
-__global__ __launch_bounds__(kRowThreads)
-void ctc_gradient_kernel(const T* __restrict__ x, T* __restrict__ grads,
-                         const Utt* __restrict__ meta, const int* __restrict__ labels,
-                         const int* __restrict__ links, const float* __restrict__ lse,
-                         const double* __restrict__ alpha, const double* __restrict__ beta,
-                         const double* __restrict__ logp, const int* __restrict__ chain_err,
-                         float* __restrict__ costs, int Tt, int B, int A, int blank)
-{
-    __shared__ float red[8];
-    __shared__ float g_label[CTC_MAX_LABEL_LENGTH + 1];
-    const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const Utt m = meta[b];
-    // A lattice wavefront that ran out of its wait budget leaves no trustworthy result.
-    if (t == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
-    const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
-    T* grow = grads + row_off;
+//
+// A workgroup takes rows_per_group consecutive frames of one utterance (16 dense, 4 sparse),
+// one wavefront per row at a time.  Labels and their links sit in LDS; per wavefront, the label states' mass shares
+// (P floats).  Everything within a row stays inside one wavefront, so no barrier is needed
+// after the staging.  The first occurrence of a symbol walks its chain of links and is the
+// only writer of that symbol's occupancy; the blank's L+1 states are a wavefront reduction.
+//   dense  (A <= 2048): occupancies go to A floats of LDS per wavefront, then the whole row
+//          y - occupancy is written, and padding rows are zero-filled;
+//   sparse (wider):     the dense part of the row was written by the softmax launch; only the
+//          label columns and the blank column are rewritten (no A-bin histogram).
+// Dynamic LDS: 2 * L_max ints + 4 * (L_max + 1 + (dense ? A : 0)) floats.
 
-    constexpr int N = Vec<T>::N;
-    if (t >= m.Tb || !(m.flags & kUttRuns)) {
-        if (kVector) {
-            float zero[N] = {};
-            for (int i = tid; i < A / N; i += kRowThreads) Vec<T>::store(grow + static_cast<size_t>(i) * N, zero);
-        } else {
-            for (int k = tid; k < A; k += kRowThreads) store_elem(grow, k, 0.0f);
-        }
-        return;
-    }
-    const T* xrow = x + row_off;
-    const int L = m.L, P = L + 1;
-    const size_t pitch = 2 * static_cast<size_t>(P);
-    const double* arow = alpha + m.ab_off + static_cast<size_t>(t) * pitch;
-    const double* brow = beta + m.ab_off + static_cast<size_t>(t) * pitch;
-    const double lp = logp[b];
-
-    float z = 0.0f, zb = 0.0f;
-    for (int j = tid; j < P; j += kRowThreads) {
-        const double2 a = *reinterpret_cast<const double2*>(arow + 2 * j);
-        const double bb = brow[2 * j + 1], bl = brow[2 * j + 2 < static_cast<int>(pitch) ? 2 * j + 2 : 0];
-        const float gb = fast_exp2(static_cast<float>(a.x + bb - lp));
-        const float gl = (j < L) ? fast_exp2(static_cast<float>(a.y + bl - lp)) : 0.0f;
-        g_label[j] = gl;
-        z += gb + gl;
-        zb += gb;
-    }
-    z = block_sum(z, red);
-    zb = block_sum(zb, red + 4);
-    const float inv_z = 1.0f / z;
-    const float l2 = lse[static_cast<size_t>(b) * Tt + t];
-
-    if (kVector) {
-        for (int i = tid; i < A / N; i += kRowThreads) {
-            float v[N];
-            Vec<T>::load(xrow + static_cast<size_t>(i) * N, v);
-#pragma unroll
-            for (int e = 0; e < N; ++e) v[e] = fast_exp2(fmaf(v[e], kLog2e, -l2));
-            Vec<T>::store(grow + static_cast<size_t>(i) * N, v);
-        }
-    } else {
-        for (int k = tid; k < A; k += kRowThreads)
-            store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)));
-    }
-    // The symbols that occur in the label are rewritten below by other threads of this
-    // workgroup: make the stores above complete before any of those is issued.
-    __threadfence_block();
-    __syncthreads();
-
-    const int* lab = labels + m.lab_off;
-    const int* lnk = links + m.lab_off;
-    for (int j = tid; j < L; j += kRowThreads) {
-        int link = lnk[j];
-        if (link < 0) {                       // first occurrence of its symbol: sum the chain
-            float occ = g_label[j];
-            int nxt = link & 0xFFFFFF;
-            while (nxt) {
-                occ += g_label[nxt - 1];
-                nxt = lnk[nxt - 1] & 0xFFFFFF;
-            }
-            const int c = lab[j];
-            store_elem(grow, c, fast_exp2(fmaf(load_elem(xrow, c), kLog2e, -l2)) - occ * inv_z);
-        }
-    }
-    if (tid == 0)
-        store_elem(grow, blank, fast_exp2(fmaf(load_elem(xrow, blank), kLog2e, -l2)) - zb * inv_z);
-}
-
-// Narrow alphabets: a workgroup takes kGradRows consecutive frames of one utterance, one
-// wavefront per row at a time.  Labels and their links sit in LDS; per wavefront, the label
-// states' mass shares (P floats) and the per-symbol occupancy (A floats).  Everything within a
-// row stays inside one wavefront, so no barrier is needed after the staging.
-// Dynamic LDS: 2 * L_max ints + 4 * (L_max + 1 + A) floats.
-constexpr int kGradRows = 16;
-
-template <typename T>
+template <typename T, bool kSparse>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                               const Utt* __restrict__ meta, const int* __restrict__ labels,
                               const int* __restrict__ links, const float* __restrict__ lse,
                               const double* __restrict__ alpha, const double* __restrict__ beta,
                               const double* __restrict__ logp, const int* __restrict__ chain_err,
-                              float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax)
+                              float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
+                              int rows_per_group)
 {
     extern __shared__ int g_lds[];
     int* s_lab = g_lds;
     int* s_lnk = g_lds + Lmax;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float* g_label = reinterpret_cast<float*>(g_lds + 2 * Lmax) + wave * (Lmax + 1 + A);
+    float* g_label = reinterpret_cast<float*>(g_lds + 2 * Lmax) + wave * (Lmax + 1 + (kSparse ? 0 : A));
     float* occ = g_label + Lmax + 1;
-    const int b = blockIdx.y, t0 = blockIdx.x * kGradRows;
+    const int b = blockIdx.y, t0 = blockIdx.x * rows_per_group;
     const Utt m = meta[b];
     if (t0 == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
     const bool runs = (m.flags & kUttRuns) != 0;
@@ -799,11 +748,12 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     }
     const size_t pitch = 2 * static_cast<size_t>(P);
     const double lp = runs ? logp[b] : 0.0;
-    for (int t = t0 + wave; t < min(t0 + kGradRows, Tt); t += 4) {
+    for (int t = t0 + wave; t < min(t0 + rows_per_group, Tt); t += 4) {
         const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
         T* grow = grads + row_off;
         if (t >= m.Tb || !runs) {
-            for (int k = lane; k < A; k += 64) store_elem(grow, k, 0.0f);
+            if (!kSparse)
+                for (int k = lane; k < A; k += 64) store_elem(grow, k, 0.0f);
             continue;
         }
         const T* xrow = x + row_off;
@@ -828,7 +778,8 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         zb = wave_sum(zb);
         const float inv_z = 1.0f / z;
         const float l2 = lse[static_cast<size_t>(b) * Tt + t];
-        for (int k = lane; k < A; k += 64) occ[k] = 0.0f;
+        if (!kSparse)
+            for (int k = lane; k < A; k += 64) occ[k] = 0.0f;
         // LDS operations of one wavefront complete in program order; the fence only keeps the
         // compiler from moving them across.
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -841,13 +792,22 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                     o += g_label[nxt - 1];
                     nxt = s_lnk[nxt - 1] & 0xFFFFFF;
                 }
-                occ[s_lab[j]] = o;
+                const int c = s_lab[j];
+                if (kSparse)
+                    store_elem(grow, c, fast_exp2(fmaf(load_elem(xrow, c), kLog2e, -l2)) - o * inv_z);
+                else
+                    occ[c] = o;
             }
         }
-        if (lane == 0) occ[blank] = zb;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        for (int k = lane; k < A; k += 64)
-            store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k] * inv_z);
+        if (kSparse) {
+            if (lane == 0)
+                store_elem(grow, blank, fast_exp2(fmaf(load_elem(xrow, blank), kLog2e, -l2)) - zb * inv_z);
+        } else {
+            if (lane == 0) occ[blank] = zb;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            for (int k = lane; k < A; k += 64)
+                store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k] * inv_z);
+        }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
 }
@@ -919,21 +879,21 @@ int launch_softmax(const Launch& p, void* stream)
             const dim3 grid(p.T, p.B);
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_wide_kernel<float>, grid, block, 0, s,
-                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels, lse, emit_blank,
                                    emit_label, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL(ctc_softmax_wide_kernel<bf16_t>, grid, block, 0, s,
-                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta, labels, lse, emit_blank,
                                    emit_label, p.T, p.B, p.A, p.blank);
         } else {
             const dim3 grid(p.T, p.B);
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_kernel<float>, grid, block, 0, s,
-                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels, lse, emit_blank,
                                    emit_label, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL(ctc_softmax_kernel<bf16_t>, grid, block, 0, s,
-                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta, labels, lse, emit_blank,
                                    emit_label, p.T, p.B, p.A, p.blank);
         }
     });
@@ -993,35 +953,22 @@ int launch_gradient(const Launch& p, void* stream)
     const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;
-    return checked_launch([&] {
-        if (p.A <= kRowsMaxA) {
-            const dim3 grid((p.T + kGradRows - 1) / kGradRows, p.B);
-            const int Lmax = p.max_label;
-            const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + p.A)) * 4;
-            if (f32)
-                hipLaunchKernelGGL(ctc_gradient_rows_kernel<float>, grid, block, lds, s,
-                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta,
-                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
-                                   p.T, p.B, p.A, p.blank, Lmax);
-            else
-                hipLaunchKernelGGL(ctc_gradient_rows_kernel<bf16_t>, grid, block, lds, s,
-                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta,
-                                   labels, links, lse, alpha, beta, logp, chain_err, p.costs,
-                                   p.T, p.B, p.A, p.blank, Lmax);
-        } else {
-            const dim3 grid(p.T, p.B);
-            const bool vec = vector_ok(p);
-#define CTC_LAUNCH_GRADIENT(TYPE, VEC)                                                             \
-    hipLaunchKernelGGL((ctc_gradient_kernel<TYPE, VEC>), grid, block, 0, s,                         \
+    const int Lmax = p.max_label;
+    const bool sparse = p.A > kRowsMaxA;
+    const int rows = sparse ? 4 : 16;
+    const dim3 grid((p.T + rows - 1) / rows, p.B);
+    const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + (sparse ? 0 : p.A))) * 4;
+#define CTC_LAUNCH_GRADIENT(TYPE, SPARSE)                                                          \
+    hipLaunchKernelGGL((ctc_gradient_rows_kernel<TYPE, SPARSE>), grid, block, lds, s,               \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,     \
-                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank)
-            if (f32 && vec) CTC_LAUNCH_GRADIENT(float, true);
-            else if (f32) CTC_LAUNCH_GRADIENT(float, false);
-            else if (vec) CTC_LAUNCH_GRADIENT(bf16_t, true);
-            else CTC_LAUNCH_GRADIENT(bf16_t, false);
-#undef CTC_LAUNCH_GRADIENT
-        }
+                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank, Lmax, rows)
+    return checked_launch([&] {
+        if (f32 && sparse) CTC_LAUNCH_GRADIENT(float, true);
+        else if (f32) CTC_LAUNCH_GRADIENT(float, false);
+        else if (sparse) CTC_LAUNCH_GRADIENT(bf16_t, true);
+        else CTC_LAUNCH_GRADIENT(bf16_t, false);
     });
+#undef CTC_LAUNCH_GRADIENT
 }
 
 }  // namespace ctc
