@@ -16,7 +16,9 @@
  * the scratch workspace, belongs to the caller (Section 4.3 motivates keeping
  * allocation off the training step).  All device work is enqueued on the given
  * stream and the calls return without waiting for it; host arrays are consumed
- * before the call returns.
+ * before the call returns.  The only memory the library itself holds is a small ring of
+ * pinned host buffers per device (the per-call metadata image the setup kernel reads), created
+ * on first use and kept until the process ends.
  */
 #ifndef CTC_MI355X_H
 #define CTC_MI355X_H
@@ -47,10 +49,12 @@ typedef enum {
 
 /* Kernel launches of one call, in order; index into ctc_profile_kernels' output. */
 enum {
-    CTC_KERNEL_SOFTMAX = 0,    /* row-wise log-softmax statistics + emission gather; also the
-                                  per-utterance label links and the costs of degenerate utterances */
+    CTC_KERNEL_SOFTMAX = 0,    /* row-wise log-softmax statistics + emission gather (for alphabets
+                                  wider than 2048 also the dense part of the gradient) */
     CTC_KERNEL_LATTICE = 1,    /* alpha and beta recursions, one launch */
     CTC_KERNEL_GRADIENT = 2,   /* softmax minus normalised occupancy, zero fill of padding */
+    /* A short setup launch (metadata from pinned host memory into the workspace, label links,
+       costs of degenerate utterances) precedes these three and is not timed separately. */
     CTC_NUM_KERNELS = 3
 };
 
