@@ -33,6 +33,9 @@ def check(batch, dtype=ctc.DTYPE_F32, nthreads=0):
     assert err_c.size == 0 or err_c.max() <= rtol, f"cost rel err {err_c.max()}"
     assert not np.isnan(grads).any()
     err_g = np.abs(grads - ref_g).max()
+    print(f"  max cost rel err {err_c.max() if err_c.size else 0.0:.3e}  max grad abs err {err_g:.3e}"
+          f"  (cost range {np.min(ref_c[fin]) if fin.any() else 0:.1f}..{np.max(ref_c[fin]) if fin.any() else 0:.1f} nats)",
+          flush=True)
     assert err_g <= atol, f"grad abs err {err_g}"
     for b in range(batch.B):                       # padding rows are exact zeros
         assert not grads[batch.input_lengths[b]:, b, :].any()
@@ -87,6 +90,38 @@ def test_random_shapes_bf16():
     check(wl.make_random(10, T=30, B=3, A=1001, max_label=10), ctc.DTYPE_BF16)
     check(wl.make_random(14, T=8, B=2, A=4104, max_label=6), ctc.DTYPE_BF16)      # 16-byte vector path
     check(wl.make_random(15, T=8, B=2, A=4101, max_label=6), ctc.DTYPE_BF16)      # scalar wide path
+
+
+def test_peaky_logits_like_a_trained_model():
+    """Large-magnitude logits (per-frame probabilities from 1 - 1e-9 down to 1e-30): the mass sits on
+    a thin band of the lattice, far below the maxima of alpha and of beta elsewhere."""
+    rng = np.random.default_rng(77)
+    T, B, A = 400, 6, 29
+    lab_len = rng.integers(40, 120, size=B)
+    labs = [rng.integers(1, A, size=n) for n in lab_len]
+    x = rng.standard_normal((T, B, A)).astype(np.float32) * 2.0
+    for b in range(B):                          # a plausible alignment gets +25, blanks elsewhere +20
+        pos = np.sort(rng.choice(T, size=lab_len[b], replace=False))
+        x[:, b, 0] += 20.0
+        for i, t in enumerate(pos):
+            x[t, b, 0] -= 20.0
+            x[t, b, labs[b][i]] += 25.0
+    batch = wl.CTCBatch(name="peaky", T=T, B=B, A=A, blank=0, logits=x,
+                        flat_labels=np.concatenate(labs).astype(np.int32),
+                        label_lengths=lab_len.astype(np.int32),
+                        input_lengths=rng.integers(380, T + 1, size=B).astype(np.int32))
+    check(batch)
+
+
+def test_worst_case_spread_of_random_logits():
+    """sigma = 6 logits without any structure: costs of several thousand nats per utterance."""
+    check(wl.make_random(78, T=600, B=4, A=29, max_label=170, min_input=550, sigma=6.0, feasible_only=True))
+
+
+def test_single_symbol_alphabet_long_repeats():
+    """Every label position repeats its predecessor: each needs a blank in between."""
+    check(wl.make_random(79, T=500, B=3, A=2, max_label=240, min_input=490, blank=0, sigma=3.0,
+                         feasible_only=True))
 
 
 def test_degenerate_lengths():
