@@ -78,7 +78,7 @@ def test_sweep_config_bf16():
     (7, dict(T=20, B=3, A=1030, max_label=10, blank=517)),         # alphabet not a multiple of 4
     (8, dict(T=64, B=5, A=64, max_label=63, feasible_only=True)),
     (11, dict(T=9, B=3, A=2051, max_label=6, blank=2050)),          # wide alphabet, rows not 16-byte aligned
-    (12, dict(T=7, B=2, A=9000, max_label=5, blank=4000)),          # wider than the register-resident path
+    (12, dict(T=9, B=3, A=9000, max_label=5, min_input=6, blank=4000, feasible_only=True)),          # wider than the register-resident path
     (13, dict(T=12, B=3, A=600, max_label=10, sigma=3.0)),          # mid-size alphabet (bigram-like)
 ])
 def test_random_shapes(seed, kw):
