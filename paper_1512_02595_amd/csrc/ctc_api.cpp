@@ -74,8 +74,8 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
         emit += Tb * L;
         frames += Tb;
         // per-utterance byte offsets inside the kernels are 32-bit
-        if (Tb * 2 * (L + 1) * 8 > INT32_MAX) too_long = true;
-        ab += Tb * 2 * (L + 1);
+        if (Tb * (L + 1) * 8 > INT32_MAX) too_long = true;
+        ab += Tb * (L + 1);
     }
     if (too_long) return CTC_STATUS_UNSUPPORTED;
     if (sumL > INT32_MAX || frames > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
@@ -227,7 +227,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         lab_off += L;
         e_off += static_cast<int64_t>(Tb) * L;
         f_off += Tb;
-        ab_off += static_cast<int64_t>(Tb) * 2 * (L + 1);
+        ab_off += static_cast<int64_t>(Tb) * (L + 1);
         if (runs) {
             order[n_run++] = b;
             max_waves = std::max(max_waves, wp.waves);

@@ -20,7 +20,7 @@ struct Utt {
     int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
     int32_t reserved;
     int64_t e_off;     // offset (floats) of its label emissions [Tb][L]
-    int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][2(L+1)]
+    int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][L+1]
 };
 static_assert(sizeof(Utt) == 48, "Utt must stay 48 bytes");
 
@@ -51,14 +51,14 @@ struct Layout {
     size_t labels = 0;    // int32[sumL]
     size_t links = 0;     // int32[sumL]  next-occurrence links of equal symbols
     size_t logp = 0;      // double[B]    log2 of the alignment mass
-    size_t sink = 0;      // 256 bytes that lanes without a lattice pair may scribble on
+    size_t sink = 0;      // 256 bytes that lanes with nothing to store may scribble on
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
     size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits
     size_t emit_blank = 0; // float[64 + sum Tb + 64]  log2 emission of blank per frame, slack both sides
     size_t emit_label = 0; // float[slack + sum Tb*L + slack]  log2 emission of each label position;
                            // the first float of the front slack holds the log-0 constant
-    size_t alpha = 0;     // double[sum Tb*2(L+1)]
-    size_t beta = 0;      // double[sum Tb*2(L+1)]
+    size_t alpha = 0;     // double[sum Tb*(L+1)]   label states only
+    size_t beta = 0;      // double[sum Tb*(L+1)]
     size_t total = 0;
     size_t upload_bytes = 0;   // meta..labels are contiguous: the image the host prepares per call
     int64_t sumL = 0;

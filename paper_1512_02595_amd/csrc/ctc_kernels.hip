@@ -401,8 +401,10 @@ struct HaloLds {
 // excludes its own frame's emission, and that is what gets stored, so that
 // log alpha + log beta is the log mass of alignments through a state.
 //
-// Storage (row pitch 2(L+1) doubles, i.e. the appendix's S = 2(L+1) rows with one that stays
-// at or below log 0): alpha_row[s] = alpha(s); beta_row[s+1] = beta(s).
+// Storage: only the label states are written, alpha_row[i] = alpha(2i+1), beta_row[i] =
+// beta(2i+1), row pitch L+1 doubles.  The blank states are needed by the recursion but not by
+// the gradient, which takes the blank's occupancy as 1 minus that of all label states
+// (sum_s alpha_t(s) beta_t(s) = p at every frame).
 //
 // A lone wavefront per SIMD issues one instruction every four clocks whatever its kind, so
 // the step is written for instruction count: pointers advance by adds, the blank emissions of
@@ -449,10 +451,12 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * L : 0;
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
-    // Output rows; lanes that store nothing write to a 16-byte sink instead.
-    double* op = active ? out + m.ab_off + static_cast<int64_t>(f0) * (2 * P) + (kBackward ? 2 * (L - j) : 2 * j)
-                        : sink;
-    const int64_t ostride = active ? static_cast<int64_t>(fdir) * (2 * P) : 0;
+    // Output: only the label state of each pair is kept (row pitch L+1 doubles, column = label
+    // index, in both directions); the gradient gets the blank's share as the complement.
+    // Lanes that store nothing write to a sink instead.
+    const bool stores = active && has_label;
+    double* op = stores ? out + m.ab_off + static_cast<int64_t>(f0) * P + li : sink;
+    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * P : 0;
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
@@ -545,10 +549,9 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         if (kStream) {
             // Too much lattice to stay in the caches until the gradient kernel reads it:
             // streaming stores (measured 15 % faster on both kernels for the 512-utterance batch).
-            __builtin_nontemporal_store(kBackward ? i_label : v_blank, op);
-            __builtin_nontemporal_store(kBackward ? i_blank : v_label, op + 1);
+            __builtin_nontemporal_store(kBackward ? i_label : v_label, op);
         } else {
-            *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+            *op = kBackward ? i_label : v_label;
         }
 #endif
         op += ostride;
@@ -577,7 +580,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         const float el = *ep;
         v_blank = i_blank + static_cast<double>(readlane(ebv, 0));
         v_label = i_label + static_cast<double>(el);
-        *reinterpret_cast<double2*>(op) = kBackward ? make_double2(i_label, i_blank) : make_double2(v_blank, v_label);
+        *op = kBackward ? i_label : v_label;
         op += ostride;
     }
 
@@ -704,8 +707,10 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
 
 // ---- gradient ------------------------------------------------------------------------------
 //   gamma_t(s) = 2^(alpha_t(s) + beta_t(s) - log2 p)        mass share of state s
-//   grad[k]    = y_t(k) - sum_{s: symbol(s) = k} gamma_t(s) / sum_s gamma_t(s)
-// Dividing by the row's own total (equal to 1 up to rounding) keeps every row summing to zero.
+//   grad[k]    = y_t(k) - sum_{s: symbol(s) = k} gamma_t(s)
+// Only the label states' gamma are computed from the stored lattice; the blank column gets
+// 1 - (sum over label states), which is the blank states' share because the shares of all
+// states of a frame add up to 1.  Every row of the gradient therefore sums to zero.
 //
 // A workgroup takes rows_per_group consecutive frames of one utterance (16 dense, 4 sparse),
 // one wavefront per row at a time.  Labels and their links sit in LDS; per wavefront, the label states' mass shares
@@ -746,7 +751,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         __syncthreads();
     }
-    const size_t pitch = 2 * static_cast<size_t>(P);
+    const size_t pitch = static_cast<size_t>(P);
     const double lp = runs ? logp[b] : 0.0;
     for (int t = t0 + wave; t < min(t0 + rows_per_group, Tt); t += 4) {
         const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
@@ -759,24 +764,14 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         const T* xrow = x + row_off;
         const double* arow = alpha + m.ab_off + static_cast<size_t>(t) * pitch;
         const double* brow = beta + m.ab_off + static_cast<size_t>(t) * pitch;
-        float z = 0.0f, zb = 0.0f;
-        for (int j = lane; j < P; j += 64) {
-#ifdef CTC_X_NT_LOAD
-            const double2 a = make_double2(__builtin_nontemporal_load(arow + 2 * j), __builtin_nontemporal_load(arow + 2 * j + 1));
-            const double bb = __builtin_nontemporal_load(brow + 2 * j + 1), bl = __builtin_nontemporal_load(brow + (j < L ? 2 * j + 2 : 0));
-#else
-            const double2 a = *reinterpret_cast<const double2*>(arow + 2 * j);
-            const double bb = brow[2 * j + 1], bl = brow[j < L ? 2 * j + 2 : 0];
-#endif
-            const float gb = fast_exp2(static_cast<float>(a.x + bb - lp));
-            const float gl = (j < L) ? fast_exp2(static_cast<float>(a.y + bl - lp)) : 0.0f;
+        // Mass share of every label state; the blank states share what is left of 1.
+        float zl = 0.0f;
+        for (int j = lane; j < L; j += 64) {
+            const float gl = fast_exp2(static_cast<float>(arow[j] + brow[j] - lp));
             g_label[j] = gl;
-            z += gb + gl;
-            zb += gb;
+            zl += gl;
         }
-        z = wave_sum(z);
-        zb = wave_sum(zb);
-        const float inv_z = 1.0f / z;
+        const float zb = 1.0f - wave_sum(zl);
         const float l2 = lse[static_cast<size_t>(b) * Tt + t];
         if (!kSparse)
             for (int k = lane; k < A; k += 64) occ[k] = 0.0f;
@@ -794,19 +789,19 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                 }
                 const int c = s_lab[j];
                 if (kSparse)
-                    store_elem(grow, c, fast_exp2(fmaf(load_elem(xrow, c), kLog2e, -l2)) - o * inv_z);
+                    store_elem(grow, c, fast_exp2(fmaf(load_elem(xrow, c), kLog2e, -l2)) - o);
                 else
                     occ[c] = o;
             }
         }
         if (kSparse) {
             if (lane == 0)
-                store_elem(grow, blank, fast_exp2(fmaf(load_elem(xrow, blank), kLog2e, -l2)) - zb * inv_z);
+                store_elem(grow, blank, fast_exp2(fmaf(load_elem(xrow, blank), kLog2e, -l2)) - zb);
         } else {
             if (lane == 0) occ[blank] = zb;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             for (int k = lane; k < A; k += 64)
-                store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k] * inv_z);
+                store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k]);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }

@@ -47,21 +47,22 @@ def test_workspace_size_grows_with_the_lattice(lib):
     small = ctc.workspace_size(50, 4, 29, [5, 6, 7, 8], [30, 40, 50, 45])
     big = ctc.workspace_size(50, 4, 29, [15, 16, 17, 18], [30, 40, 50, 45])
     assert small % 256 == 0 and big % 256 == 0 and big > small > 0
-    # alpha and beta in fp64, 2(L+1) entries per frame, dominate for long utterances
+    # alpha and beta of the label states in fp64 (L+1 entries per frame each) plus the fp32
+    # label emissions dominate for long utterances
     T, L = 1500, 500
     n = ctc.workspace_size(T, 1, 29, [L], [T])
-    assert n >= 2 * T * 2 * (L + 1) * 8
-    assert n <= 2 * T * 2 * (L + 1) * 8 + T * L * 4 + (1 << 20)
+    assert n >= 2 * T * (L + 1) * 8 + T * L * 4
+    assert n <= 2 * T * (L + 1) * 8 + T * L * 4 + (1 << 20)
     # zero-frame and zero-label utterances are fine
     assert ctc.workspace_size(10, 3, 5, [0, 0, 3], [0, 10, 0]) > 0
 
 
 def test_workspace_size_of_the_five_configs(lib):
-    expect_min = {0: 0, 1: 100e6, 3: 500e6, 4: 700e6}
+    expect_min = {0: 0, 1: 60e6, 3: 250e6, 4: 400e6}
     for idx in (0, 1, 3, 4):
         b = wl.make_config(idx)
         n = ctc.workspace_size(b.T, b.B, b.A, b.label_lengths, b.input_lengths)
-        assert n >= 16 * b.lattice_cells and n >= expect_min[idx]
+        assert n >= 8 * b.lattice_cells and n >= expect_min[idx]
 
 
 def test_workspace_size_rejects_bad_shapes(lib):
