@@ -30,10 +30,10 @@ inline bool record(int err)
 
 }  // namespace
 
-// Wavefronts and halo width for a label of this length.  With one wavefront per SIMD (up to
-// 4) a step costs about 240 clocks and a hand-over about 300; with several per SIMD the
-// vector ALU is the limit (about 190 clocks per wavefront-step) and most of a hand-over's
-// latency hides behind the other wavefronts.
+// Wavefronts and halo width for a label of this length.  Measured on gfx950: with one
+// wavefront per SIMD (up to 4) a step costs about 250 clocks and a hand-over about 500; with
+// several per SIMD the vector ALU is the limit (about 200 clocks per wavefront-step) and part
+// of a hand-over's latency hides behind the other wavefronts (about 350).
 WavePlan plan_waves(int label_length)
 {
     const int pairs = label_length + 1;
@@ -49,7 +49,7 @@ WavePlan plan_waves(int label_length)
         if (halo < 1) continue;
         const int per_simd = (w + 3) / 4;
         // the last term prefers fewer wavefronts when the estimates are close
-        const double cost = ((per_simd == 1) ? 240.0 + 300.0 / halo : per_simd * 190.0 + 120.0 / halo) + 4.0 * w;
+        const double cost = ((per_simd == 1) ? 250.0 + 500.0 / halo : per_simd * 200.0 + 350.0 / halo) + 4.0 * w;
         if (cost < best_cost) {
             best_cost = cost;
             best = {w, halo, false};
