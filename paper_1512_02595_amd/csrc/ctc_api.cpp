@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <thread>
 #include <vector>
 
 #include "ctc_internal.h"
@@ -108,17 +109,22 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
 
 namespace {
 
-// Pinned host buffers for the per-call metadata image.  The setup kernel reads the image
-// straight from host memory, so a slot may be rewritten only after that kernel has run: each
-// slot carries an event recorded behind its setup launch.  One ring per device, created on
-// first use, kept for the life of the process.
+// Pinned host buffers for the per-call metadata image.  The upload kernel reads the image
+// straight from host memory, so a slot may be rewritten only after that kernel has run: the
+// launch that follows it on the stream stores the slot's generation number into a pinned flag
+// word, which the host checks before it reuses the slot (no event, so no marker packet sits
+// between two kernels of a call).  One ring per device, created on first use, kept for the
+// life of the process.
 constexpr int kStagingSlots = 8;
+constexpr size_t kFlagBytes = 64;            // the flag word sits in front of the image
 
 struct StagingSlot {
-    void* host = nullptr;
-    size_t capacity = 0;
-    hipEvent_t consumed = nullptr;
+    char* host = nullptr;                    // kFlagBytes of flag, then the image
+    size_t capacity = 0;                     // of the image part
+    int generation = 0;                      // value the device stores once the image is free
     bool in_flight = false;
+    int* flag() const { return reinterpret_cast<int*>(host); }
+    char* image() const { return host + kFlagBytes; }
 };
 
 struct StagingRing {
@@ -145,9 +151,16 @@ StagingSlot* acquire_slot(size_t bytes)
     }
     StagingSlot& slot = ring->slots[ring->next];
     ring->next = (ring->next + 1) % kStagingSlots;
-    if (!slot.consumed && !record(hipEventCreateWithFlags(&slot.consumed, hipEventDisableTiming))) return nullptr;
     if (slot.in_flight) {
-        if (!record(hipEventSynchronize(slot.consumed))) return nullptr;
+        // Seven calls have been enqueued since this slot was used: normally long done.
+        volatile int* flag = slot.flag();
+        for (long spins = 0; *flag != slot.generation; ++spins) {
+            if (spins > (1L << 26)) {        // minutes: the stream is stuck or was destroyed
+                g_last_hip_error = static_cast<int>(hipErrorNotReady);
+                return nullptr;
+            }
+            std::this_thread::yield();
+        }
         slot.in_flight = false;
     }
     if (slot.capacity < bytes) {
@@ -155,8 +168,12 @@ StagingSlot* acquire_slot(size_t bytes)
         slot.host = nullptr;
         slot.capacity = 0;
         const size_t want = (bytes + 65535) / 65536 * 65536;
-        if (!record(hipHostMalloc(&slot.host, want, hipHostMallocDefault))) return nullptr;
+        void* mem = nullptr;
+        if (!record(hipHostMalloc(&mem, want + kFlagBytes, hipHostMallocDefault))) return nullptr;
+        slot.host = static_cast<char*>(mem);
         slot.capacity = want;
+        *slot.flag() = 0;
+        slot.generation = 0;
     }
     return &slot;
 }
@@ -301,10 +318,12 @@ ctc_status_t run(const Call& c, float* kernel_ms)
         }
         slot = acquire_slot(lay.upload_bytes);
         if (!slot) return CTC_STATUS_HIP_ERROR;
-        st = prepare(c, lay, &p, static_cast<char*>(slot->host));
+        st = prepare(c, lay, &p, slot->image());
         if (st != CTC_STATUS_SUCCESS) return st;
+        slot->generation += 1;
+        p.host_flag = slot->flag();
+        p.host_flag_value = slot->generation;
         if (!record(launch_setup(p, c.stream))) return CTC_STATUS_HIP_ERROR;
-        if (!record(hipEventRecord(slot->consumed, s))) return CTC_STATUS_HIP_ERROR;
         slot->in_flight = true;
     }
 

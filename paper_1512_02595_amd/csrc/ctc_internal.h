@@ -85,6 +85,8 @@ struct Launch {
     float* costs;
     char* ws;           // workspace base
     const void* host_image;   // pinned host copy of the meta/order/labels regions (device-readable)
+    int* host_flag;           // pinned host word the device sets to host_flag_value when the image is free
+    int host_flag_value;
     Layout lay;
 };
 

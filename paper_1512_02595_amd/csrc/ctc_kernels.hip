@@ -123,45 +123,43 @@ __device__ __forceinline__ float block_max(float v, float* slot)
     return fmaxf(fmaxf(slot[0], slot[1]), fmaxf(slot[2], slot[3]));
 }
 
-// ---- upload + setup ------------------------------------------------------------------------
-// First launch of a call, one workgroup per utterance.  The per-call metadata (utterance
-// records, run order, labels) was written by the host into pinned host memory; this kernel
-// reads it from there and leaves a copy in the workspace for the launches that follow, so that
-// no stream-ordered copy engine transfer (about 18 us of latency per call) sits between two
-// calls.  It also builds, for label position j, the next position holding the same symbol
-// (0 = none, else index + 1) in the low 24 bits, with bit 31 set if j is the first occurrence of
-// its symbol.  The gradient kernels walk these chains, so the occupancy of a symbol is summed
-// in a fixed order (positions ascending) and each symbol has one writer.  This stands in for
-// the appendix's one-off key-value sort of the label: the same grouping of equal characters,
-// done once per utterance and reused by every frame.
+// ---- upload --------------------------------------------------------------------------------
+// First launch of a call.  The per-call metadata (utterance records, run order, labels) was
+// written by the host into pinned host memory; this kernel copies it word by word into the
+// workspace, every read in flight at once, so that no stream-ordered copy-engine transfer
+// (about 18 us of latency per call) sits between two calls.
 __global__ __launch_bounds__(kRowThreads)
-void ctc_setup_kernel(const char* __restrict__ host_image, char* __restrict__ ws, const Layout lay,
-                      float* __restrict__ costs)
+void ctc_upload_kernel(const int* __restrict__ host_image, int* __restrict__ ws, int words)
 {
-    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
-    __shared__ Utt s_utt;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    constexpr int kUttWords = sizeof(Utt) / 4;
-    const int* src_utt = reinterpret_cast<const int*>(host_image + lay.meta) + b * kUttWords;
-    int* dst_utt = reinterpret_cast<int*>(ws + lay.meta) + b * kUttWords;
-    if (tid < kUttWords) {
-        const int w = src_utt[tid];
-        reinterpret_cast<int*>(&s_utt)[tid] = w;
-        dst_utt[tid] = w;
-    }
-    if (tid == kUttWords)
-        reinterpret_cast<int*>(ws + lay.order)[b] = reinterpret_cast<const int*>(host_image + lay.order)[b];
+    const int i = blockIdx.x * kRowThreads + threadIdx.x;
+    if (i < words) ws[i] = host_image[i];
+}
+
+// ---- setup role ----------------------------------------------------------------------------
+// Runs in one extra grid column of the softmax launch, one workgroup per utterance, beside
+// the row work.  For label position j: the next position holding the same symbol (0 = none,
+// else index + 1) in the low 24 bits, with bit 31 set if j is the first occurrence of its
+// symbol.  The gradient kernels walk these chains, so the occupancy of a symbol is summed in a
+// fixed order (positions ascending) and each symbol has one writer.  This stands in for the
+// appendix's one-off key-value sort of the label: the same grouping of equal characters, done
+// once per utterance and reused by every frame.  Also: costs of utterances without a lattice,
+// the per-utterance error flags, the log-0 constant of the emission array.
+struct SetupArgs {
+    int* links;
+    float* costs;
+    int* chain_err;
+    float* log0;          // the float that lattice lanes without a label state read as their emission
+    int* host_flag;       // pinned host word: receives flag_value once the upload has been consumed
+    int flag_value;
+};
+
+__device__ __forceinline__ void setup_role(const Utt m, const int b, const int* __restrict__ labels,
+                                           const SetupArgs sa, int* s_lab)
+{
+    const int tid = threadIdx.x;
+    const int* lab = labels + m.lab_off;
+    for (int j = tid; j < m.L; j += kRowThreads) s_lab[j] = lab[j];
     __syncthreads();
-    const Utt m = s_utt;
-    const int* src_lab = reinterpret_cast<const int*>(host_image + lay.labels) + m.lab_off;
-    int* dst_lab = reinterpret_cast<int*>(ws + lay.labels) + m.lab_off;
-    for (int j = tid; j < m.L; j += kRowThreads) {
-        const int c = src_lab[j];
-        s_lab[j] = c;
-        dst_lab[j] = c;
-    }
-    __syncthreads();
-    int* links = reinterpret_cast<int*>(ws + lay.links);
     for (int j = tid; j < m.L; j += kRowThreads) {
         const int c = s_lab[j];
         // No early exit: independent iterations keep the LDS reads (one broadcast each) in flight.
@@ -173,19 +171,24 @@ void ctc_setup_kernel(const char* __restrict__ host_image, char* __restrict__ ws
             if (same && i < j) first = false;
         }
         nxt = (nxt == INT_MAX) ? 0 : nxt + 1;
-        links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
+        sa.links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
     }
     if (tid == 0) {
-        reinterpret_cast<int*>(ws + lay.chain_err)[b] = 0;
-        // the float that lattice lanes without a label state read as their emission
-        if (b == 0) reinterpret_cast<float*>(ws + lay.emit_label)[0] = static_cast<float>(kNeg);
+        sa.chain_err[b] = 0;
+        if (b == 0) {
+            sa.log0[0] = static_cast<float>(kNeg);
+            // This launch follows the upload kernel on the stream, so the host may now reuse
+            // the pinned image.
+            __hip_atomic_store(sa.host_flag, sa.flag_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
         // No frames: the empty product (cost 0) for an empty label.  Otherwise no alignment.
-        if (!(m.flags & kUttRuns)) costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
+        if (!(m.flags & kUttRuns)) sa.costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
     }
 }
 
 // ---- softmax statistics + emission gather --------------------------------------------------
-// Wide alphabets (A > 2048): one workgroup per row (t, b) of the tensor; grid (T, B).
+// Wide alphabets (A > 2048): one workgroup per row (t, b) of the tensor; grid (T + 1, B), the
+// extra column does the setup role.
 // The gradient of a wide alphabet is the softmax itself except in the few columns whose symbol
 // occurs in the label, so these kernels also write the dense part of the gradient while they
 // hold the row: y for valid rows, zeros for padding rows and for utterances without an
@@ -197,11 +200,13 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
                         const Utt* __restrict__ meta,
                         const int* __restrict__ labels, float* __restrict__ lse,
                         float* __restrict__ emit_blank, float* __restrict__ emit_label,
-                        int Tt, int B, int A, int blank)
+                        const SetupArgs sa, int Tt, int B, int A, int blank)
 {
     __shared__ float red[8];
+    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
     const int t = blockIdx.x, b = blockIdx.y;
     const Utt m = meta[b];
+    if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
     T* grow = grads + row_off;
     const bool runs = (m.flags & kUttRuns) != 0;
@@ -241,13 +246,15 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
                              const Utt* __restrict__ meta,
                              const int* __restrict__ labels, float* __restrict__ lse,
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
-                             int Tt, int B, int A, int blank)
+                             const SetupArgs sa, int Tt, int B, int A, int blank)
 {
     constexpr int N = Vec<T>::N;
     constexpr int kVecs = kWideMaxA / (N * kRowThreads);      // vectors per thread
     __shared__ float red[8];
+    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
     const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const Utt m = meta[b];
+    if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
     T* grow = grads + row_off;
     const int nvec = A / N;
@@ -303,18 +310,21 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
 // Narrow alphabets: a workgroup takes kRows consecutive frames of one utterance, 256 / kRows
 // threads per row.  The normalised log2 probabilities of those rows are kept in LDS
 // (kRows * A floats, dynamic), from where the emissions of all label positions are gathered
-// with the label symbols held in registers.  grid (ceil(T / kRows), B).
+// with the label symbols held in registers.  grid (ceil(T / kRows) + 1, B), the extra column
+// does the setup role.
 template <typename T, int kRows>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
                              const int* __restrict__ labels, float* __restrict__ lse,
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
-                             int Tt, int B, int A, int blank)
+                             const SetupArgs sa, int Tt, int B, int A, int blank)
 {
     constexpr int kPerRow = kRowThreads / kRows;          // threads per row, a power of two <= 64
     extern __shared__ float lp[];                          // [kRows][A]
+    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
     const int b = blockIdx.y, tid = threadIdx.x;
     const Utt m = meta[b];
+    if (blockIdx.x == gridDim.x - 1) { setup_role(m, b, labels, sa, s_lab); return; }
     const int t0 = blockIdx.x * kRows;
     if (t0 >= m.Tb) return;
     const int r = tid / kPerRow, q = tid % kPerRow, t = t0 + r;
@@ -830,10 +840,11 @@ bool vector_ok(const Launch& p)
 
 int launch_setup(const Launch& p, void* stream)
 {
+    const int words = static_cast<int>(p.lay.upload_bytes / 4);
     return checked_launch([&] {
-        hipLaunchKernelGGL(ctc_setup_kernel, dim3(p.B), dim3(kRowThreads), 0,
-                           static_cast<hipStream_t>(stream), static_cast<const char*>(p.host_image),
-                           p.ws, p.lay, p.costs);
+        hipLaunchKernelGGL(ctc_upload_kernel, dim3((words + kRowThreads - 1) / kRowThreads), dim3(kRowThreads),
+                           0, static_cast<hipStream_t>(stream), static_cast<const int*>(p.host_image),
+                           reinterpret_cast<int*>(p.ws), words);
     });
 }
 
@@ -844,52 +855,55 @@ int launch_softmax(const Launch& p, void* stream)
     auto* lse = reinterpret_cast<float*>(p.ws + p.lay.lse);
     auto* emit_blank = reinterpret_cast<float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
+    const SetupArgs sa{reinterpret_cast<int*>(p.ws + p.lay.links), p.costs,
+                       reinterpret_cast<int*>(p.ws + p.lay.chain_err), emit_label,
+                       p.host_flag, p.host_flag_value};
     const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;
     return checked_launch([&] {
         if (p.A <= 512) {
-            const dim3 grid((p.T + 15) / 16, p.B);
+            const dim3 grid((p.T + 15) / 16 + 1, p.B);
             const size_t lds = static_cast<size_t>(16) * p.A * sizeof(float);
             if (f32)
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 16>), grid, block, lds, s,
                                    static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 16>), grid, block, lds, s,
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
         } else if (p.A <= kRowsMaxA) {
-            const dim3 grid((p.T + 3) / 4, p.B);
+            const dim3 grid((p.T + 3) / 4 + 1, p.B);
             const size_t lds = static_cast<size_t>(4) * p.A * sizeof(float);
             if (f32)
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 4>), grid, block, lds, s,
                                    static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 4>), grid, block, lds, s,
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
         } else if (vector_ok(p) && p.A <= kWideMaxA) {
-            const dim3 grid(p.T, p.B);
+            const dim3 grid(p.T + 1, p.B);
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_wide_kernel<float>, grid, block, 0, s,
                                    static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL(ctc_softmax_wide_kernel<bf16_t>, grid, block, 0, s,
                                    static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
         } else {
-            const dim3 grid(p.T, p.B);
+            const dim3 grid(p.T + 1, p.B);
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_kernel<float>, grid, block, 0, s,
                                    static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL(ctc_softmax_kernel<bf16_t>, grid, block, 0, s,
                                    static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta, labels, lse, emit_blank,
-                                   emit_label, p.T, p.B, p.A, p.blank);
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
         }
     });
 }
