@@ -179,7 +179,7 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
             sa.log0[0] = static_cast<float>(kNeg);
             // This launch follows the upload kernel on the stream, so the host may now reuse
             // the pinned image.
-            __hip_atomic_store(sa.host_flag, sa.flag_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(sa.host_flag, sa.flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         // No frames: the empty product (cost 0) for an empty label.  Otherwise no alignment.
         if (!(m.flags & kUttRuns)) sa.costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
