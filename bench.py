@@ -32,7 +32,7 @@ LANE_OPS_PER_PAIR_STEP = 45
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
 # the rocprofv3 --pmc runs summarised in profiles/english_B64_A29_T750_hbm_traffic.md.
-MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 19.0e6, "ctc_lattice": 139.6e6, "ctc_gradient": 129.2e6}}
+MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 19.0e6, "ctc_lattice": 79.8e6, "ctc_gradient": 72.0e6}}
 
 
 def kernel_bytes(batch, elem):
