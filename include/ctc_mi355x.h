@@ -17,7 +17,7 @@
  * allocation off the training step).  All device work is enqueued on the given
  * stream and the calls return without waiting for it; host arrays are consumed
  * before the call returns.  The only memory the library itself holds is a small ring of
- * pinned host buffers per device (the per-call metadata image the setup kernel reads), created
+ * pinned host buffers per device (the per-call metadata image the first kernel reads), created
  * on first use and kept until the process ends.
  */
 #ifndef CTC_MI355X_H
@@ -53,8 +53,9 @@ enum {
                                   wider than 2048 also the dense part of the gradient) */
     CTC_KERNEL_LATTICE = 1,    /* alpha and beta recursions, one launch */
     CTC_KERNEL_GRADIENT = 2,   /* softmax minus normalised occupancy, zero fill of padding */
-    /* A short setup launch (metadata from pinned host memory into the workspace, label links,
-       costs of degenerate utterances) precedes these three and is not timed separately. */
+    /* A short copy launch (the per-call metadata, from pinned host memory into the workspace)
+       precedes these three and is not timed separately; the label links and the costs of
+       degenerate utterances are prepared by extra workgroups of the softmax launch. */
     CTC_NUM_KERNELS = 3
 };
 

@@ -333,7 +333,7 @@ ctc_status_t run(const Call& c, float* kernel_ms)
             if (!record(hipEventCreate(&e))) return CTC_STATUS_HIP_ERROR;
         if (!record(hipEventRecord(ev[0], s))) return CTC_STATUS_HIP_ERROR;
     }
-    // The setup launch has gone out above (its own time is not reported separately: it is a few
+    // The upload launch has gone out above (its own time is not reported separately: it is a few
     // microseconds and overlaps the tail of whatever ran before on the stream).
     int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_softmax, launch_lattice,
                                                                   launch_gradient};
