@@ -49,7 +49,7 @@ struct Layout {
     size_t meta = 0;      // Utt[B]
     size_t order = 0;     // int32[B]     utterances whose lattice runs, heaviest first
     size_t labels = 0;    // int32[sumL]
-    size_t links = 0;     // int32[sumL]  next-occurrence links of equal symbols
+    size_t links = 0;     // int32[sumL]  grouping of the label positions by symbol (slot, count, first)
     size_t logp = 0;      // double[B]    log2 of the alignment mass
     size_t sink = 0;      // 256 bytes that lanes with nothing to store may scribble on
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour

@@ -2,8 +2,8 @@
 //
 // Pipeline of one call (appendix "GPU Implementation of CTC Loss Function"; cost of
 // Section 3.3 Eq. (ctc); softmax of Section 3.1):
-//   setup     per utterance: links between equal label symbols (replaces the appendix's
-//             key-value sort: same purpose, one ordered walk per symbol), degenerate costs
+//   setup     per utterance: label positions grouped by symbol (the appendix's one-off
+//             key-value sort, done by counting), degenerate costs; rides in the softmax launch
 //   softmax   per frame row: log2-sum-exp2 of the scaled logits, and the log2 emissions of
 //             blank and of every label position, gathered once so that the recursions read
 //             them coalesced
@@ -21,8 +21,6 @@
 // Only the bounded differences that enter exp2/log2 are narrowed to fp32.
 
 #include <hip/hip_runtime.h>
-
-#include <climits>
 
 #include "ctc_internal.h"
 
@@ -94,17 +92,42 @@ template <> struct Vec<bf16_t> {
 
 // ---- workgroup reductions (256 threads = 4 wavefronts), fixed order => repeatable -------
 
+// Lane permutations inside a row of 16 lanes, as DPP operands of the add / max itself (no trip
+// through the LDS crossbar): neighbours, pairs, then the mirrored half-row and the mirrored row.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_permute(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xf, 0xf, true));
+}
+// Every lane receives the sum (maximum) over its row of 16 lanes.  All 16 lanes must be active.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_permute<0xB1>(v);      // quad_perm [1,0,3,2]
+    v += dpp_permute<0x4E>(v);      // quad_perm [2,3,0,1]
+    v += dpp_permute<0x141>(v);     // row_half_mirror
+    v += dpp_permute<0x140>(v);     // row_mirror
+    return v;
+}
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = fmaxf(v, dpp_permute<0xB1>(v));
+    v = fmaxf(v, dpp_permute<0x4E>(v));
+    v = fmaxf(v, dpp_permute<0x141>(v));
+    v = fmaxf(v, dpp_permute<0x140>(v));
+    return v;
+}
+// Whole wavefront (all 64 lanes active); the four row results are combined in a fixed order.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    const int r = __float_as_int(row16_sum(v));
+    return (__int_as_float(__builtin_amdgcn_readlane(r, 0)) + __int_as_float(__builtin_amdgcn_readlane(r, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(r, 32)) + __int_as_float(__builtin_amdgcn_readlane(r, 48)));
 }
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    const int r = __float_as_int(row16_max(v));
+    return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(r, 0)), __int_as_float(__builtin_amdgcn_readlane(r, 16))),
+                 fmaxf(__int_as_float(__builtin_amdgcn_readlane(r, 32)), __int_as_float(__builtin_amdgcn_readlane(r, 48))));
 }
 
 // `slot` is 4 floats of LDS private to this reduction.
@@ -137,13 +160,20 @@ void ctc_upload_kernel(const int* __restrict__ host_image, int* __restrict__ ws,
 
 // ---- setup role ----------------------------------------------------------------------------
 // Runs in one extra grid column of the softmax launch, one workgroup per utterance, beside
-// the row work.  For label position j: the next position holding the same symbol (0 = none,
-// else index + 1) in the low 24 bits, with bit 31 set if j is the first occurrence of its
-// symbol.  The gradient kernels walk these chains, so the occupancy of a symbol is summed in a
-// fixed order (positions ascending) and each symbol has one writer.  This stands in for the
-// appendix's one-off key-value sort of the label: the same grouping of equal characters, done
-// once per utterance and reused by every frame.  Also: costs of utterances without a lattice,
-// the per-utterance error flags, the log-0 constant of the emission array.
+// the row work.  It groups the label positions by symbol, once per utterance, for every frame
+// of the gradient to reuse -- the purpose of the appendix's one-off key-value sort of the
+// label.  Word of label position j:
+//   bits  0..9   its slot in the order (symbol ascending, then position ascending): the
+//                positions of one symbol occupy consecutive slots
+//   bits 12..21  how often its symbol occurs in the label
+//   bit  31      set if j is the first occurrence of its symbol (its slot then starts the run)
+// The gradient kernels write each state's mass share to its slot and let the first occurrence
+// add up the run in slot order, so a symbol's occupancy has one writer and a fixed order of
+// summation.  Also here: costs of utterances without a lattice, the per-utterance error
+// flags, the log-0 constant of the emission array.
+constexpr int kLinkSlotMask = 0x3FF, kLinkCountShift = 12;
+static_assert(CTC_MAX_LABEL_LENGTH <= kLinkSlotMask, "slot and count fields hold 10 bits");
+
 struct SetupArgs {
     int* links;
     float* costs;
@@ -162,16 +192,16 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
     __syncthreads();
     for (int j = tid; j < m.L; j += kRowThreads) {
         const int c = s_lab[j];
-        // No early exit: independent iterations keep the LDS reads (one broadcast each) in flight.
-        int nxt = INT_MAX;
-        bool first = true;
+        // Independent iterations keep the LDS reads (one broadcast each) in flight.
+        int below = 0, before = 0, count = 0;
         for (int i = 0; i < m.L; ++i) {
-            const bool same = s_lab[i] == c;
-            if (same && i > j) nxt = min(nxt, i);
-            if (same && i < j) first = false;
+            const int ci = s_lab[i];
+            below += ci < c;
+            count += ci == c;
+            before += (ci == c) & (i < j);
         }
-        nxt = (nxt == INT_MAX) ? 0 : nxt + 1;
-        sa.links[m.lab_off + j] = nxt | (first ? static_cast<int>(0x80000000u) : 0);
+        sa.links[m.lab_off + j] = (below + before) | (count << kLinkCountShift) |
+                                  (before == 0 ? static_cast<int>(0x80000000u) : 0);
     }
     if (tid == 0) {
         sa.chain_err[b] = 0;
@@ -319,7 +349,8 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
                              const SetupArgs sa, int Tt, int B, int A, int blank)
 {
-    constexpr int kPerRow = kRowThreads / kRows;          // threads per row, a power of two <= 64
+    constexpr int kPerRow = kRowThreads / kRows;          // threads per row: a 16-lane row or a wavefront
+    static_assert(kPerRow == 16 || kPerRow == 64, "row reductions exist for 16 and 64 lanes");
     extern __shared__ float lp[];                          // [kRows][A]
     __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
     const int b = blockIdx.y, tid = threadIdx.x;
@@ -329,6 +360,9 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     if (t0 >= m.Tb) return;
     const int r = tid / kPerRow, q = tid % kPerRow, t = t0 + r;
     float* lrow = lp + r * A;
+    // Requested before the row work so that its latency overlaps the row's.
+    const int* lab = labels + m.lab_off;
+    const int c_first = (tid < m.L) ? lab[tid] : 0;
     if (t < m.Tb) {
         const T* row = x + (static_cast<size_t>(t) * B + b) * A;
         float mx = -__builtin_inff();
@@ -337,13 +371,11 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
             lrow[k] = v;
             mx = fmaxf(mx, v);
         }
-#pragma unroll
-        for (int o = kPerRow / 2; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        mx = (kPerRow == 16) ? row16_max(mx) : wave_max(mx);
         mx *= kLog2e;
         float sum = 0.0f;
         for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
-#pragma unroll
-        for (int o = kPerRow / 2; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        sum = (kPerRow == 16) ? row16_sum(sum) : wave_sum(sum);
         const float l2 = mx + fast_log2(sum);
         for (int k = q; k < A; k += kPerRow) lrow[k] = fmaf(lrow[k], kLog2e, -l2);
         if (q == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
@@ -352,10 +384,9 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     __syncthreads();
     const int rows = min(kRows, m.Tb - t0);
     if (tid < rows) emit_blank[kBlankSlack + m.f_off + t0 + tid] = lp[tid * A + blank];
-    const int* lab = labels + m.lab_off;
     float* ebase = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * m.L;
     for (int j = tid; j < m.L; j += kRowThreads) {
-        const int c = lab[j];
+        const int c = (j == tid) ? c_first : lab[j];
         for (int rr = 0; rr < rows; ++rr) ebase[static_cast<size_t>(rr) * m.L + j] = lp[rr * A + c];
     }
 }
@@ -722,16 +753,19 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
 // 1 - (sum over label states), which is the blank states' share because the shares of all
 // states of a frame add up to 1.  Every row of the gradient therefore sums to zero.
 //
-// A workgroup takes rows_per_group consecutive frames of one utterance (16 dense, 4 sparse),
-// one wavefront per row at a time.  Labels and their links sit in LDS; per wavefront, the label states' mass shares
-// (P floats).  Everything within a row stays inside one wavefront, so no barrier is needed
-// after the staging.  The first occurrence of a symbol walks its chain of links and is the
-// only writer of that symbol's occupancy; the blank's L+1 states are a wavefront reduction.
+// A workgroup takes rows_per_group consecutive frames of one utterance (8 or 16 dense, 4 sparse),
+// one wavefront per row at a time.  Labels and their grouping words sit in LDS; per wavefront,
+// the label states' mass shares in slot order (P floats).  Everything within a row stays inside
+// one wavefront, so no barrier is needed after the staging.  The first occurrence of a symbol
+// adds up the run of slots of its symbol and is the only writer of that symbol's occupancy; the
+// blank's L+1 states are a wavefront reduction.
 //   dense  (A <= 2048): occupancies go to A floats of LDS per wavefront, then the whole row
 //          y - occupancy is written, and padding rows are zero-filled;
 //   sparse (wider):     the dense part of the row was written by the softmax launch; only the
 //          label columns and the blank column are rewritten (no A-bin histogram).
 // Dynamic LDS: 2 * L_max ints + 4 * (L_max + 1 + (dense ? A : 0)) floats.
+
+constexpr int kAhead = 4;             // 64-state pieces of a row requested together
 
 template <typename T, bool kSparse>
 __global__ __launch_bounds__(kRowThreads)
@@ -763,7 +797,38 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     }
     const size_t pitch = static_cast<size_t>(P);
     const double lp = runs ? logp[b] : 0.0;
-    for (int t = t0 + wave; t < min(t0 + rows_per_group, Tt); t += 4) {
+    const int tend = min(t0 + rows_per_group, Tt);
+    const double* const abase = alpha + m.ab_off;
+    const double* const bbase = beta + m.ab_off;
+
+    // What a row needs from memory, requested in one go before any of it is used, so that a
+    // row costs one memory latency: the lattice values of the first kAhead * 64 label states
+    // (longer labels read the rest in line), the row's log-sum-exp and, dense form, the first
+    // 64 activations.  (Requesting the next row during the current one was measured slower:
+    // the extra registers cost more wavefronts per SIMD than the overlap gains.)
+    struct RowData {
+        double a[kAhead], b[kAhead];
+        float l2, x0;
+    };
+    auto request = [&](int t, RowData& d) {
+        if (t >= tend || t >= m.Tb || !runs) return;
+        const double* arow = abase + static_cast<size_t>(t) * pitch;
+        const double* brow = bbase + static_cast<size_t>(t) * pitch;
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int j = u * 64 + lane;
+            if (j < L) {
+                d.a[u] = arow[j];
+                d.b[u] = brow[j];
+            }
+        }
+        d.l2 = lse[static_cast<size_t>(b) * Tt + t];
+        if (!kSparse && lane < A) d.x0 = load_elem(x + (static_cast<size_t>(t) * B + b) * A, lane);
+    };
+
+    for (int t = t0 + wave; t < tend; t += 4) {
+        RowData cur = {};
+        request(t, cur);
         const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
         T* grow = grads + row_off;
         if (t >= m.Tb || !runs) {
@@ -772,17 +837,43 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
             continue;
         }
         const T* xrow = x + row_off;
-        const double* arow = alpha + m.ab_off + static_cast<size_t>(t) * pitch;
-        const double* brow = beta + m.ab_off + static_cast<size_t>(t) * pitch;
         // Mass share of every label state; the blank states share what is left of 1.
         float zl = 0.0f;
-        for (int j = lane; j < L; j += 64) {
-            const float gl = fast_exp2(static_cast<float>(arow[j] + brow[j] - lp));
-            g_label[j] = gl;
-            zl += gl;
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int j = u * 64 + lane;
+            if (j < L) {
+                const float gl = fast_exp2(static_cast<float>(cur.a[u] + cur.b[u] - lp));
+                g_label[s_lnk[j] & kLinkSlotMask] = gl;
+                zl += gl;
+            }
+        }
+        if (L > kAhead * 64) {
+            const double* arow = abase + static_cast<size_t>(t) * pitch;
+            const double* brow = bbase + static_cast<size_t>(t) * pitch;
+            for (int j0 = kAhead * 64; j0 < L; j0 += kAhead * 64) {
+                double a[kAhead], bb[kAhead];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int j = j0 + u * 64 + lane;
+                    if (j < L) {
+                        a[u] = arow[j];
+                        bb[u] = brow[j];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int j = j0 + u * 64 + lane;
+                    if (j < L) {
+                        const float gl = fast_exp2(static_cast<float>(a[u] + bb[u] - lp));
+                        g_label[s_lnk[j] & kLinkSlotMask] = gl;
+                        zl += gl;
+                    }
+                }
+            }
         }
         const float zb = 1.0f - wave_sum(zl);
-        const float l2 = lse[static_cast<size_t>(b) * Tt + t];
+        const float l2 = cur.l2;
         if (!kSparse)
             for (int k = lane; k < A; k += 64) occ[k] = 0.0f;
         // LDS operations of one wavefront complete in program order; the fence only keeps the
@@ -790,12 +881,18 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         for (int j = lane; j < L; j += 64) {
             const int link = s_lnk[j];
-            if (link < 0) {                   // first occurrence of its symbol: sum the chain
-                float o = g_label[j];
-                int nxt = link & 0xFFFFFF;
-                while (nxt) {
-                    o += g_label[nxt - 1];
-                    nxt = s_lnk[nxt - 1] & 0xFFFFFF;
+            if (link < 0) {                   // first occurrence of its symbol: add up its run
+                const int first = link & kLinkSlotMask;
+                const int count = (link >> kLinkCountShift) & kLinkSlotMask;
+                float o = 0.0f;
+                // Eight independent reads at a time; slots past the run add an exact zero, so
+                // the order of summation is the run's own.
+                for (int i0 = 0; i0 < count; i0 += 8) {
+                    float g[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) g[i] = g_label[min(first + i0 + i, L - 1)];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) o += (i0 + i < count) ? g[i] : 0.0f;
                 }
                 const int c = s_lab[j];
                 if (kSparse)
@@ -810,7 +907,8 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         } else {
             if (lane == 0) occ[blank] = zb;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            for (int k = lane; k < A; k += 64)
+            if (lane < A) store_elem(grow, lane, fast_exp2(fmaf(cur.x0, kLog2e, -l2)) - occ[lane]);
+            for (int k = 64 + lane; k < A; k += 64)
                 store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k]);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -964,7 +1062,10 @@ int launch_gradient(const Launch& p, void* stream)
     const bool f32 = p.dtype == CTC_DTYPE_F32;
     const int Lmax = p.max_label;
     const bool sparse = p.A > kRowsMaxA;
-    const int rows = sparse ? 4 : 16;
+    // Dense form: 16 rows per workgroup amortise the label staging best once the grid is large;
+    // smaller grids finish sooner with twice as many, shorter workgroups (measured on the
+    // 64- and 512-utterance minibatches).
+    const int rows = sparse ? 4 : (static_cast<int64_t>(p.T) * p.B <= (1 << 17) ? 8 : 16);
     const dim3 grid((p.T + rows - 1) / rows, p.B);
     const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + (sparse ? 0 : p.A))) * 4;
 #define CTC_LAUNCH_GRADIENT(TYPE, SPARSE)                                                          \
