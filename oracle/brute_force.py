@@ -71,3 +71,26 @@ def count_alignments(T, label, A, blank):
     """Number of length-T strings over A symbols that collapse to `label` (exact integer)."""
     label = tuple(int(k) for k in label)
     return sum(1 for path in itertools.product(range(A), repeat=T) if collapse(path, blank) == label)
+
+
+def best_alignments(x, label, blank):
+    """(max probability, [every alignment that attains it]) by enumeration; x is [T,A] logits.
+
+    Section 5.1 (alignment step): l* = argmax over Align(x, y) of prod_t y_t(l_t).
+    Alignments are tuples of frame-level symbols.  (0.0, []) when none exists.
+    """
+    y = softmax_rows(x)
+    T, A = y.shape
+    label = tuple(int(k) for k in label)
+    best, arg = 0.0, []
+    for path in itertools.product(range(A), repeat=T):
+        if collapse(path, blank) != label:
+            continue
+        mass = 1.0
+        for t, k in enumerate(path):
+            mass *= y[t, k]
+        if mass > best:
+            best, arg = mass, [path]
+        elif mass == best and mass > 0.0:
+            arg.append(path)
+    return best, arg

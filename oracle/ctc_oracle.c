@@ -38,6 +38,15 @@
  * sum over all labelings = 1, finite differences, closed forms, alignment
  * counts under uniform logits, reversal and relabelling symmetries, and a
  * library CTC routine.
+ *
+ * Second function, ctc_oracle_best_path: the single most probable alignment
+ *     l* = argmax over alignments pi of prod_t y_t(pi_t)
+ * (Section 5.1, "Dataset Construction": the alignment step of the segmentation
+ * pipeline, which the paper calls essentially a Viterbi alignment), by the
+ * same lattice with max in place of the sum and a table of predecessors.
+ * Pins (tests/test_best_path_pins.py): enumeration of every alignment, the
+ * bracket cost <= -ln p(l*) <= cost + ln(number of alignments), forced
+ * alignments, planted alignments, and validity of the returned path.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -228,4 +237,121 @@ int ctc_oracle_max_threads(void)
 #else
     return 1;
 #endif
+}
+
+/*
+ * Most probable alignment of one utterance (max-product over the same lattice).
+ * states[t] receives the lattice state of frame t (0-based index into the
+ * blank-interleaved label: even = blank, odd s = label[(s-1)/2]) for t < Tb and
+ * -1 for Tb <= t < Tfull.  *score = -ln of that alignment's probability, +inf
+ * (and all states -1) when no alignment exists.  Among equally good
+ * predecessors the one with the highest state index wins; callers must not
+ * rely on that.
+ */
+static int best_path_one(const double *x, long stride, int Tb, int A, int blank,
+                         const int *label, int L, int Tfull, double *score, int *states)
+{
+    const int S = 2 * L + 1;
+    int t, s, k;
+    for (t = 0; t < Tfull; ++t) states[t] = -1;
+    if (Tb == 0) {
+        *score = (L == 0) ? 0.0 : INFINITY;
+        return 0;
+    }
+    double *lp = (double *)malloc(sizeof(double) * (size_t)Tb * A);
+    double *v = (double *)malloc(sizeof(double) * (size_t)Tb * S);
+    int *from = (int *)malloc(sizeof(int) * (size_t)Tb * S);
+    int *ext = (int *)malloc(sizeof(int) * (size_t)S);
+    if (!lp || !v || !from || !ext) {
+        free(lp); free(v); free(from); free(ext);
+        return 1;
+    }
+    for (s = 0; s < S; ++s) ext[s] = (s % 2 == 0) ? blank : label[(s - 1) / 2];
+    for (t = 0; t < Tb; ++t) {
+        const double *row = x + t * stride;
+        double mx = row[0], sum = 0.0;
+        for (k = 1; k < A; ++k) if (row[k] > mx) mx = row[k];
+        for (k = 0; k < A; ++k) sum += exp(row[k] - mx);
+        double lse = mx + log(sum);
+        for (k = 0; k < A; ++k) lp[(size_t)t * A + k] = row[k] - lse;
+    }
+    for (s = 0; s < S; ++s) { v[s] = -INFINITY; from[s] = -1; }
+    v[0] = lp[blank];
+    if (S > 1) v[1] = lp[ext[1]];
+    for (t = 1; t < Tb; ++t) {
+        const double *prev = v + (size_t)(t - 1) * S;
+        for (s = 0; s < S; ++s) {
+            double best = prev[s];
+            int arg = s;
+            if (s >= 1 && prev[s - 1] >= best) { best = prev[s - 1]; arg = s - 1; }
+            if (s >= 2 && ext[s] != blank && ext[s] != ext[s - 2] && prev[s - 2] >= best) {
+                best = prev[s - 2];
+                arg = s - 2;
+            }
+            if (best == -INFINITY) {
+                v[(size_t)t * S + s] = -INFINITY;
+                from[(size_t)t * S + s] = -1;
+            } else {
+                v[(size_t)t * S + s] = best + lp[(size_t)t * A + ext[s]];
+                from[(size_t)t * S + s] = arg;
+            }
+        }
+    }
+    const double *last = v + (size_t)(Tb - 1) * S;
+    int end = S - 1;
+    if (S > 1 && last[S - 2] > last[S - 1]) end = S - 2;
+    if (last[end] == -INFINITY) {
+        *score = INFINITY;
+    } else {
+        *score = -last[end];
+        s = end;
+        for (t = Tb - 1; t >= 0; --t) {
+            states[t] = s;
+            s = from[(size_t)t * S + s];
+        }
+    }
+    free(lp); free(v); free(from); free(ext);
+    return 0;
+}
+
+/*
+ * Batched most probable alignment.
+ *   x            [T, B, A] doubles, A fastest
+ *   scores       [B]
+ *   states       [B][T] ints (utterance-major)
+ * Return codes as ctc_oracle.
+ */
+int ctc_oracle_best_path(const double *x, int T, int B, int A,
+                         const int *flat_labels, const int *label_lengths, const int *input_lengths,
+                         int blank, double *scores, int *states, int nthreads)
+{
+    if (T < 0 || B < 0 || A < 1 || blank < 0 || blank >= A) return 2;
+    long *offs = (long *)malloc(sizeof(long) * (size_t)(B + 1));
+    if (!offs) return 1;
+    offs[0] = 0;
+    for (int b = 0; b < B; ++b) {
+        if (label_lengths[b] < 0 || input_lengths[b] < 0 || input_lengths[b] > T) { free(offs); return 2; }
+        offs[b + 1] = offs[b] + label_lengths[b];
+    }
+    for (long i = 0; i < offs[B]; ++i)
+        if (flat_labels[i] < 0 || flat_labels[i] >= A || flat_labels[i] == blank) { free(offs); return 2; }
+    int failed = 0;
+    const long stride = (long)B * A;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+#endif
+    for (int b = 0; b < B; ++b) {
+        int rc = best_path_one(x + (long)b * A, stride, input_lengths[b], A, blank,
+                               flat_labels + offs[b], label_lengths[b], T, &scores[b],
+                               states + (size_t)b * T);
+        if (rc) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+    }
+    free(offs);
+    return failed;
 }

@@ -41,6 +41,9 @@ def _load():
             lib.ctc_oracle.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ip, ip, ip,
                                        ctypes.c_int, dp, dp, dp, dp, ctypes.c_int, ctypes.c_int]
             lib.ctc_oracle_max_threads.restype = ctypes.c_int
+            lib.ctc_oracle_best_path.restype = ctypes.c_int
+            lib.ctc_oracle_best_path.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ip, ip, ip,
+                                                 ctypes.c_int, dp, ip, ctypes.c_int]
             _lib = lib
     return _lib
 
@@ -94,3 +97,32 @@ def ctc_loss_and_grad(logits, flat_labels, label_lengths, input_lengths, blank=0
     if want_lattice:
         out = out + (la, lb)
     return out
+
+
+def ctc_best_path(logits, flat_labels, label_lengths, input_lengths, blank=0, *, nthreads=0):
+    """Most probable alignment per utterance (Section 5.1, alignment step).
+
+    Returns (scores [B] float64: -ln of the alignment's probability, +inf if none exists;
+    states [B,T] int32: lattice state per frame, index into the blank-interleaved label
+    (even = blank, odd s = label[(s-1)//2]), -1 for padding frames and infeasible utterances).
+    """
+    x = np.ascontiguousarray(logits, dtype=np.float64)
+    if x.ndim != 3:
+        raise ValueError("logits must be [T,B,A]")
+    T, B, A = x.shape
+    lab = np.ascontiguousarray(flat_labels, dtype=np.int32).reshape(-1)
+    ll = np.ascontiguousarray(label_lengths, dtype=np.int32).reshape(-1)
+    il = np.ascontiguousarray(input_lengths, dtype=np.int32).reshape(-1)
+    if len(ll) != B or len(il) != B or int(ll.sum()) != len(lab):
+        raise ValueError("length arrays do not match the batch")
+    if len(lab) == 0:
+        lab = np.zeros(1, dtype=np.int32)
+    scores = np.empty(B, dtype=np.float64)
+    states = np.empty((B, T), dtype=np.int32)
+    rc = _load().ctc_oracle_best_path(_dptr(x), T, B, A, _iptr(lab), _iptr(ll), _iptr(il), int(blank),
+                                      _dptr(scores), _iptr(states), int(nthreads))
+    if rc == 2:
+        raise ValueError("oracle: invalid arguments (lengths or label ids out of range)")
+    if rc != 0:
+        raise MemoryError("oracle: allocation failed")
+    return scores, states
