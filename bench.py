@@ -2,10 +2,13 @@
 """Benchmark of the batched CTC cost + gradient on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--dtype f32|bf16]
+                    [--mode grad|loss|align]
 
 A step is one ctc_loss_and_grad call (host launcher + all kernels) over one synthetic
 minibatch whose activations already sit in HBM.  The default workload is the English-shaped
 per-GPU minibatch (config index 1: B=64, A=29, T<=750).  Prints one JSON line.
+--mode loss times the cost-only call (grads == NULL), --mode align the most probable
+alignment (ctc_best_path); the default, grad, is the headline metric.
 """
 from __future__ import annotations
 
@@ -28,6 +31,8 @@ ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # Lane-operations of one step of one (blank, label) state pair in one direction:
 # 5 transcendentals at quarter rate (= 20) + 25 plain operations.
 LANE_OPS_PER_PAIR_STEP = 45
+# The max recursion of the alignment has no transcendentals: compares, selects, two fp64 adds.
+LANE_OPS_PER_PAIR_STEP_ALIGN = 22
 
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
@@ -35,13 +40,25 @@ LANE_OPS_PER_PAIR_STEP = 45
 MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 19.0e6, "ctc_lattice": 79.8e6, "ctc_gradient": 72.0e6}}
 
 
-def kernel_bytes(batch, elem):
+def kernel_bytes(batch, elem, mode="grad"):
     """Algorithmic HBM bytes of each kernel for one launch on `batch`."""
     frames = batch.frames
     A = batch.A
     pairs = int((batch.input_lengths.astype(np.int64) * (batch.label_lengths.astype(np.int64) + 1)).sum())
     cells = batch.lattice_cells
     full = batch.T * batch.B * A * elem
+    if mode != "grad":
+        # cost only / alignment: the activations are read once; the chain reads one emission per
+        # state pair and frame (4 bytes) and, for the alignment, writes one byte of choices per pair
+        # and frame, which the backtrace reads along the path (at most 64 per frame) before it
+        # writes one int32 per frame of the tensor
+        out = {"ctc_softmax": frames * A * elem + frames * 4,
+               "ctc_lattice": pairs * 4 + (pairs if mode == "align" else 0)}
+        if mode == "align":
+            out["ctc_backtrace"] = frames * 64 + batch.T * batch.B * 4
+        else:
+            out["ctc_gradient"] = 0
+        return out, pairs
     if A > 2048:
         # wide alphabets: the softmax launch also writes the dense gradient (y, or zeros for
         # padding); the gradient launch only rewrites the label columns and the blank
@@ -66,6 +83,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="0..4, index into the workload list")
     ap.add_argument("--dtype", choices=("f32", "bf16"), default="f32")
+    ap.add_argument("--mode", choices=("grad", "loss", "align"), default="grad",
+                    help="grad: cost + gradient (headline); loss: cost only; align: most probable alignment")
     ap.add_argument("--buffers", type=int, default=4, help="distinct minibatches rotated through")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -107,28 +126,37 @@ def main():
                for i in range(args.buffers)]
     dbs = [harness.DeviceBatch(b, dtype, dev, poison=False) for b in batches]
     stream = torch.cuda.current_stream(dev).cuda_stream
+    step = {"grad": harness.DeviceBatch.run, "loss": harness.DeviceBatch.run_loss,
+            "align": harness.DeviceBatch.run_best_path}[args.mode]
 
     for i in range(args.warmup):
-        dbs[i % len(dbs)].run(stream)
+        step(dbs[i % len(dbs)], stream)
     torch.cuda.synchronize(dev)
     t0 = time.perf_counter()
     for i in range(args.steps):
-        dbs[i % len(dbs)].run(stream)
+        step(dbs[i % len(dbs)], stream)
     torch.cuda.synchronize(dev)
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     B = batches[0].B
     frames = float(np.mean([b.frames for b in batches]))
-    compulsory = float(np.mean([b.compulsory_bytes(elem) for b in batches]))
+    if args.mode == "grad":
+        compulsory = float(np.mean([b.compulsory_bytes(elem) for b in batches]))
+    else:       # the valid activations once; the alignment also writes one int32 per frame of the tensor
+        compulsory = float(np.mean([b.frames * b.A * elem for b in batches]))
+        if args.mode == "align":
+            compulsory += batches[0].T * batches[0].B * 4
 
     # Per-kernel device time, HIP events on the launch stream (ctc_profile_kernels).
     kms = np.zeros((args.profile_steps, ctc.NUM_KERNELS), dtype=np.float32)
     for i in range(args.profile_steps):
-        dbs[i % len(dbs)].run(stream, kernel_ms=kms[i])
+        step(dbs[i % len(dbs)], stream, kernel_ms=kms[i])
     kavg = [float(v) for v in kms.mean(axis=0)] if args.profile_steps else [1e-9] * ctc.NUM_KERNELS
     names = [ctc.kernel_name(i) for i in range(ctc.NUM_KERNELS)]
-    kb = [kernel_bytes(b, elem) for b in batches]
+    if args.mode == "align":
+        names[2] = ctc.kernel_name(ctc.KERNEL_BACKTRACE)
+    kb = [kernel_bytes(b, elem, args.mode) for b in batches]
     kernels = {}
     for i, n in enumerate(names):
         byt = float(np.mean([k[0][n] for k in kb]))
@@ -136,10 +164,12 @@ def main():
                       "GBps": round(byt / (kavg[i] * 1e-3) / 1e9, 2) if kavg[i] > 0 else None}
     dom = int(np.argmax(kavg))
     dom_name = names[dom]
-    traffic = MEASURED_TRAFFIC.get((args.config, args.dtype), {}).get(dom_name)
+    traffic = MEASURED_TRAFFIC.get((args.config, args.dtype), {}).get(dom_name) if args.mode == "grad" else None
     if dom_name == "ctc_lattice":
-        pair_steps = 2.0 * float(np.mean([k[1] for k in kb]))       # both directions
-        achieved = pair_steps * LANE_OPS_PER_PAIR_STEP / (kavg[dom] * 1e-3) / 1e12
+        directions = 2.0 if args.mode == "grad" else 1.0
+        lane_ops = LANE_OPS_PER_PAIR_STEP_ALIGN if args.mode == "align" else LANE_OPS_PER_PAIR_STEP
+        pair_steps = directions * float(np.mean([k[1] for k in kb]))
+        achieved = pair_steps * lane_ops / (kavg[dom] * 1e-3) / 1e12
         roofline = {"kernel": dom_name, "bound": "alu", "achieved": round(achieved, 4),
                     "peak": round(ALU_PEAK_TOPS, 2), "unit": "TFLOP/s",
                     "frac": round(achieved / ALU_PEAK_TOPS, 5), "traffic": traffic,
@@ -150,7 +180,8 @@ def main():
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic}
 
     out = {
-        "metric": "ctc_loss_grad_utterances_per_s",
+        "metric": {"grad": "ctc_loss_grad_utterances_per_s", "loss": "ctc_loss_only_utterances_per_s",
+                   "align": "ctc_best_path_utterances_per_s"}[args.mode],
         "value": round(B / (ms_per_step * 1e-3), 1),
         "unit": "utterances/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -159,7 +190,8 @@ def main():
         "dtype": "f64 lattice state, f32 transcendentals, %s activations" % args.dtype,
         "data": "synthetic",
         "config": {"workload": "config[%d] %s: B=%d A=%d T=%d, %d rotating minibatches"
-                   % (args.config, batches[0].name, B, batches[0].A, batches[0].T, len(batches))},
+                   % (args.config, batches[0].name, B, batches[0].A, batches[0].T, len(batches)),
+                   "mode": args.mode},
         "activation_frames_per_s": round(frames / (ms_per_step * 1e-3), 1),
         "hbm_roofline_frac_end_to_end": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
         "compulsory_bytes": int(compulsory),
@@ -181,14 +213,21 @@ def main():
         xs = np.ascontiguousarray(x64[:, :nb, :])
         # About 15 core-seconds of oracle work: time one run, then size the repetitions.
         cores = orc.max_threads()
+        if args.mode == "align":
+            def oracle_call():
+                orc.ctc_best_path(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank)
+        else:
+            def oracle_call():
+                orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb],
+                                      b.blank, want_grad=(args.mode == "grad"))
         c0 = time.perf_counter()
-        orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank)
+        oracle_call()
         first = time.perf_counter() - c0
         reps = int(min(200, max(3, np.ceil(15.0 / max(first * cores, 1e-6)))))
         times = []
         for _ in range(reps):
             c0 = time.perf_counter()
-            orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank)
+            oracle_call()
             times.append(time.perf_counter() - c0)
         tmed = float(np.median(times))
         out["cpu_baseline"] = {"value": round(nb / tmed, 2), "unit": "utterances/s",

@@ -56,7 +56,8 @@ enum {
     /* A short copy launch (the per-call metadata, from pinned host memory into the workspace)
        precedes these three and is not timed separately; the label links and the costs of
        degenerate utterances are prepared by extra workgroups of the softmax launch. */
-    CTC_NUM_KERNELS = 3
+    CTC_NUM_KERNELS = 3,       /* timed launches of any one call */
+    CTC_KERNEL_BACKTRACE = 3   /* name index only: third launch of ctc_best_path (in place of the gradient) */
 };
 
 /*
@@ -93,6 +94,8 @@ ctc_status_t ctc_workspace_size(int T, int B, int A,
  *   grads         (device) [T, B, A] of type `dtype`: d cost_b / d activations.
  *                 Rows t >= input_lengths[b], and all rows of an utterance with
  *                 infinite cost, are written as zeros.  Must not overlap activations.
+ *                 NULL: costs only (the raw CTC cost that Section 5.1 uses as a filter
+ *                 feature); the backward recursion and the gradient pass are then left out.
  *   workspace     (device) 256-byte aligned scratch of at least ctc_workspace_size bytes;
  *                 contents on entry are irrelevant, contents on exit are unspecified
  *   stream        a hipStream_t (passed as void* so that this header needs no HIP
@@ -120,7 +123,8 @@ ctc_status_t ctc_loss_and_grad(const void *activations,
  * this call in milliseconds.  For measurement (the per-kernel timings that the
  * paper's Table "gpucpuctc" aggregates per epoch), not for the training loop.
  *
- *   kernel_ms     (host) [CTC_NUM_KERNELS]
+ *   kernel_ms     (host) [CTC_NUM_KERNELS]; with grads == NULL the third entry is the
+ *                 short check launch that follows the forward recursion (0 if not needed)
  */
 ctc_status_t ctc_profile_kernels(const void *activations,
                                  const int32_t *flat_labels,
@@ -134,7 +138,55 @@ ctc_status_t ctc_profile_kernels(const void *activations,
                                  void *stream,
                                  float *kernel_ms);
 
-/* Prefix of the name under which launch `index` (0..CTC_NUM_KERNELS-1) appears in a profiler
+/*
+ * Most probable alignment of each utterance (Section 5.1, "Dataset Construction": the
+ * alignment step of the segmentation pipeline),
+ *
+ *     l*_b = argmax_{pi in Align(x_b, y_b)}  prod_{t < T_b}  softmax(x[t,b,:])[pi_t],
+ *
+ * found on the same blank-interleaved lattice with the maximum in place of the sum and a
+ * backtrace over the recorded predecessor choices.
+ *
+ *   activations, flat_labels, label_lengths, input_lengths, T, B, A, blank, dtype,
+ *   workspace, workspace_bytes, stream: as for ctc_loss_and_grad (same workspace size)
+ *   scores        (device) [B] float: -ln of the probability of l*_b, in nats; +inf when
+ *                 no alignment exists; 0 for an empty label with zero frames
+ *   alignment     (device) [B, T] int32, T fastest (utterance-major, unlike the activations):
+ *                 for t < input_lengths[b] the lattice state of frame t, an index s into the
+ *                 blank-interleaved label (s even: blank; s odd: label symbol (s-1)/2 of the
+ *                 utterance), from which the frame's symbol and its position in the
+ *                 transcript both follow; -1 for t >= input_lengths[b] and for every frame
+ *                 of an utterance without an alignment.  Must not overlap the workspace.
+ *
+ * When several alignments are equally probable one of them is returned, the same one on
+ * every run.  Status and error behaviour as for ctc_loss_and_grad.
+ */
+ctc_status_t ctc_best_path(const void *activations,
+                           const int32_t *flat_labels,
+                           const int32_t *label_lengths,
+                           const int32_t *input_lengths,
+                           int T, int B, int A, int blank,
+                           ctc_dtype_t dtype,
+                           float *scores,
+                           int32_t *alignment,
+                           void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/* ctc_best_path with per-launch device times, as ctc_profile_kernels:
+ * kernel_ms (host) [CTC_NUM_KERNELS] = softmax, lattice (max recursion), backtrace. */
+ctc_status_t ctc_profile_best_path(const void *activations,
+                                   const int32_t *flat_labels,
+                                   const int32_t *label_lengths,
+                                   const int32_t *input_lengths,
+                                   int T, int B, int A, int blank,
+                                   ctc_dtype_t dtype,
+                                   float *scores,
+                                   int32_t *alignment,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *stream,
+                                   float *kernel_ms);
+
+/* Prefix of the name under which launch `index` (0..CTC_KERNEL_BACKTRACE) appears in a profiler
  * trace (the full name depends on the variant chosen for the batch shape); NULL otherwise. */
 const char *ctc_kernel_name(int index);
 

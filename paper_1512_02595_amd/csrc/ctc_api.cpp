@@ -1,6 +1,6 @@
 // Host side of the CTC library: argument validation, workspace layout, the per-call plan
 // (which utterances run, in which order, how wide the lattice workgroups are) and the
-// enqueueing of the four kernels.  No device memory is allocated here or anywhere else in
+// enqueueing of the kernels (upload, softmax, lattice, then gradient or backtrace).  No device memory is allocated here or anywhere else in
 // the library (Section 4.3: allocation is kept off the training step; the caller hands in
 // one workspace and this file carves it).
 
@@ -179,6 +179,7 @@ StagingSlot* acquire_slot(size_t bytes)
 }
 
 struct Call {
+    Mode mode;
     const void* x;
     const int32_t* flat_labels;
     const int32_t* label_lengths;
@@ -186,7 +187,8 @@ struct Call {
     int T, B, A, blank;
     ctc_dtype_t dtype;
     float* costs;
-    void* grads;
+    void* grads;             // kGrad only
+    int32_t* alignment;      // kBest only
     void* ws;
     size_t ws_bytes;
     void* stream;
@@ -201,12 +203,14 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
 
     const size_t elem = (c.dtype == CTC_DTYPE_F32) ? 4 : 2;
     const size_t tensor_bytes = static_cast<size_t>(c.T) * c.B * c.A * elem;
-    {
+    if (c.mode == Mode::kGrad) {
         const char* xa = static_cast<const char*>(c.x);
         const char* ga = static_cast<const char*>(c.grads);
         if (xa < ga + tensor_bytes && ga < xa + tensor_bytes) return CTC_STATUS_INVALID_VALUE;
+        if (reinterpret_cast<uintptr_t>(c.grads) % elem) return CTC_STATUS_INVALID_VALUE;
     }
-    if (reinterpret_cast<uintptr_t>(c.x) % elem || reinterpret_cast<uintptr_t>(c.grads) % elem)
+    if (reinterpret_cast<uintptr_t>(c.x) % elem) return CTC_STATUS_INVALID_VALUE;
+    if (c.mode == Mode::kBest && reinterpret_cast<uintptr_t>(c.alignment) % sizeof(int32_t))
         return CTC_STATUS_INVALID_VALUE;
 
     Utt* meta = reinterpret_cast<Utt*>(image + lay.meta);
@@ -262,6 +266,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
 
     if (c.ws_bytes < lay.total) return CTC_STATUS_WORKSPACE_TOO_SMALL;
 
+    out->mode = c.mode;
     out->T = c.T; out->B = c.B; out->A = c.A; out->blank = c.blank;
     out->dtype = c.dtype;
     out->n_run = n_run;
@@ -270,7 +275,8 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->max_label = max_label;
     out->needs_barrier = needs_barrier;
     out->x = c.x;
-    out->grads = c.grads;
+    out->grads = (c.mode == Mode::kGrad) ? c.grads : nullptr;
+    out->alignment = (c.mode == Mode::kBest) ? c.alignment : nullptr;
     out->costs = c.costs;
     out->ws = static_cast<char*>(c.ws);
     out->host_image = image;
@@ -281,8 +287,9 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
 // Cheap checks that need neither the layout nor a staging slot.
 ctc_status_t precheck(const Call& c)
 {
-    if (!c.x || !c.label_lengths || !c.input_lengths || !c.costs || !c.grads || !c.ws)
-        return CTC_STATUS_INVALID_VALUE;
+    if (!c.x || !c.label_lengths || !c.input_lengths || !c.costs || !c.ws) return CTC_STATUS_INVALID_VALUE;
+    if (c.mode == Mode::kGrad && !c.grads) return CTC_STATUS_INVALID_VALUE;
+    if (c.mode == Mode::kBest && !c.alignment) return CTC_STATUS_INVALID_VALUE;
     if (c.T < 1 || c.B < 1 || c.A < 1 || c.blank < 0 || c.blank >= c.A) return CTC_STATUS_INVALID_VALUE;
     return CTC_STATUS_SUCCESS;
 }
@@ -335,8 +342,9 @@ ctc_status_t run(const Call& c, float* kernel_ms)
     }
     // The upload launch has gone out above (its own time is not reported separately: it is a few
     // microseconds and overlaps the tail of whatever ran before on the stream).
-    int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_softmax, launch_lattice,
-                                                                  launch_gradient};
+    int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {
+        launch_softmax, launch_lattice,
+        c.mode == Mode::kGrad ? launch_gradient : (c.mode == Mode::kLoss ? launch_chain_check : launch_backtrace)};
     for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
         if (!record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
         if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
@@ -370,8 +378,8 @@ ctc_status_t ctc_loss_and_grad(const void* activations, const int32_t* flat_labe
                                int T, int B, int A, int blank, ctc_dtype_t dtype, float* costs,
                                void* grads, void* workspace, size_t workspace_bytes, void* stream)
 {
-    ctc::Call c{activations, flat_labels, label_lengths, input_lengths, T, B, A, blank, dtype,
-                costs, grads, workspace, workspace_bytes, stream};
+    ctc::Call c{grads ? ctc::Mode::kGrad : ctc::Mode::kLoss, activations, flat_labels, label_lengths,
+                input_lengths, T, B, A, blank, dtype, costs, grads, nullptr, workspace, workspace_bytes, stream};
     return ctc::run(c, nullptr);
 }
 
@@ -382,8 +390,30 @@ ctc_status_t ctc_profile_kernels(const void* activations, const int32_t* flat_la
                                  float* kernel_ms)
 {
     if (!kernel_ms) return CTC_STATUS_INVALID_VALUE;
-    ctc::Call c{activations, flat_labels, label_lengths, input_lengths, T, B, A, blank, dtype,
-                costs, grads, workspace, workspace_bytes, stream};
+    ctc::Call c{grads ? ctc::Mode::kGrad : ctc::Mode::kLoss, activations, flat_labels, label_lengths,
+                input_lengths, T, B, A, blank, dtype, costs, grads, nullptr, workspace, workspace_bytes, stream};
+    return ctc::run(c, kernel_ms);
+}
+
+ctc_status_t ctc_best_path(const void* activations, const int32_t* flat_labels,
+                           const int32_t* label_lengths, const int32_t* input_lengths,
+                           int T, int B, int A, int blank, ctc_dtype_t dtype, float* scores,
+                           int32_t* alignment, void* workspace, size_t workspace_bytes, void* stream)
+{
+    ctc::Call c{ctc::Mode::kBest, activations, flat_labels, label_lengths, input_lengths, T, B, A, blank,
+                dtype, scores, nullptr, alignment, workspace, workspace_bytes, stream};
+    return ctc::run(c, nullptr);
+}
+
+ctc_status_t ctc_profile_best_path(const void* activations, const int32_t* flat_labels,
+                                   const int32_t* label_lengths, const int32_t* input_lengths,
+                                   int T, int B, int A, int blank, ctc_dtype_t dtype, float* scores,
+                                   int32_t* alignment, void* workspace, size_t workspace_bytes,
+                                   void* stream, float* kernel_ms)
+{
+    if (!kernel_ms) return CTC_STATUS_INVALID_VALUE;
+    ctc::Call c{ctc::Mode::kBest, activations, flat_labels, label_lengths, input_lengths, T, B, A, blank,
+                dtype, scores, nullptr, alignment, workspace, workspace_bytes, stream};
     return ctc::run(c, kernel_ms);
 }
 
@@ -393,6 +423,7 @@ const char* ctc_kernel_name(int index)
         case CTC_KERNEL_SOFTMAX: return "ctc_softmax";
         case CTC_KERNEL_LATTICE: return "ctc_lattice";
         case CTC_KERNEL_GRADIENT: return "ctc_gradient";
+        case CTC_KERNEL_BACKTRACE: return "ctc_backtrace";
         default: return nullptr;
     }
 }

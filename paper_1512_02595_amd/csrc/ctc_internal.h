@@ -71,8 +71,16 @@ struct Layout {
 ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
                          const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay);
 
+// What a call computes, and so what its chains are run for:
+//   kGrad  sum over alignments, label states of every frame stored (cost and gradient)
+//   kLoss  sum over alignments, nothing stored (cost only; forward chain only)
+//   kBest  maximum over alignments, one byte of predecessor choices stored per state pair and
+//          frame (most probable alignment; forward chain only)
+enum class Mode { kGrad, kLoss, kBest };
+
 // Kernel launch parameters shared by all stages.
 struct Launch {
+    Mode mode;
     int T, B, A, blank;
     ctc_dtype_t dtype;
     int n_run;          // utterances whose lattice runs
@@ -81,7 +89,8 @@ struct Launch {
     int max_label;      // longest label of the batch
     bool needs_barrier; // some utterance's label leaves no room for a halo
     const void* x;
-    void* grads;
+    void* grads;        // nullptr unless mode == kGrad
+    int32_t* alignment; // [B][T], mode == kBest only
     float* costs;
     char* ws;           // workspace base
     const void* host_image;   // pinned host copy of the meta/order/labels regions (device-readable)
@@ -94,6 +103,8 @@ struct Launch {
 int launch_setup(const Launch& p, void* stream);
 int launch_softmax(const Launch& p, void* stream);
 int launch_lattice(const Launch& p, void* stream);
-int launch_gradient(const Launch& p, void* stream);
+int launch_gradient(const Launch& p, void* stream);   // kGrad
+int launch_chain_check(const Launch& p, void* stream); // kLoss
+int launch_backtrace(const Launch& p, void* stream);   // kBest
 
 }  // namespace ctc

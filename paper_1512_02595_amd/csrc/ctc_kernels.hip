@@ -222,7 +222,7 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
 // The gradient of a wide alphabet is the softmax itself except in the few columns whose symbol
 // occurs in the label, so these kernels also write the dense part of the gradient while they
 // hold the row: y for valid rows, zeros for padding rows and for utterances without an
-// alignment.  The activations are then never read a second time; the label columns are
+// alignment (skipped when no gradient is asked for: grads == nullptr).  The activations are then never read a second time; the label columns are
 // corrected after the recursions by the sparse variant of the gradient kernel.
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
@@ -241,7 +241,8 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
     T* grow = grads + row_off;
     const bool runs = (m.flags & kUttRuns) != 0;
     if (t >= m.Tb || !runs) {
-        for (int k = threadIdx.x; k < A; k += kRowThreads) store_elem(grow, k, 0.0f);
+        if (grads)
+            for (int k = threadIdx.x; k < A; k += kRowThreads) store_elem(grow, k, 0.0f);
         return;
     }
     const T* row = x + row_off;
@@ -256,8 +257,9 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const float l2 = mx + fast_log2(s);
     if (threadIdx.x == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
 
-    for (int k = threadIdx.x; k < A; k += kRowThreads)
-        store_elem(grow, k, fast_exp2(fmaf(load_elem(row, k), kLog2e, -l2)));
+    if (grads)
+        for (int k = threadIdx.x; k < A; k += kRowThreads)
+            store_elem(grow, k, fast_exp2(fmaf(load_elem(row, k), kLog2e, -l2)));
     if (threadIdx.x == 0)
         emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
@@ -291,7 +293,8 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const bool runs = (m.flags & kUttRuns) != 0;
     if (t >= m.Tb || !runs) {
         const float zero[N] = {};
-        for (int i = tid; i < nvec; i += kRowThreads) Vec<T>::store(grow + static_cast<size_t>(i) * N, zero);
+        if (grads)
+            for (int i = tid; i < nvec; i += kRowThreads) Vec<T>::store(grow + static_cast<size_t>(i) * N, zero);
         return;
     }
     const T* row = x + row_off;
@@ -323,7 +326,7 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
 #pragma unroll
     for (int i = 0; i < kVecs; ++i) {
         const int idx = tid + i * kRowThreads;
-        if (idx < nvec) {
+        if (grads && idx < nvec) {
             float y[N];
 #pragma unroll
             for (int e = 0; e < N; ++e) y[e] = fast_exp2(fmaf(v[i][e], kLog2e, -l2));
@@ -424,6 +427,12 @@ constexpr int kHaloEntries = 64;      // 16-byte entries of one wavefront bounda
 
 enum class Sync { kNone, kHalo, kBarrier };
 
+// Predecessor choices of a pair at one frame, as stored for the backtrace: bits 0..1 for the
+// label state (0 = stayed, 1 = came from the pair's blank, 2 = came from the label of the pair
+// before, skipping the blank), bit 2 for the blank state (0 = stayed, 1 = came from the label
+// of the pair before).
+constexpr int kFromSame = 0, kFromBlank = 1, kFromPrevLabel = 2, kBlankFromPrevLabel = 4;
+
 // LDS of the halo exchange: per wavefront w, what w hands to w+1.
 struct HaloLds {
     double2 data[16][kHaloEntries];
@@ -462,14 +471,15 @@ struct HaloLds {
 // read).  No barrier; the wavefronts run skewed.  A wavefront waits for data only on lower
 // ones and for space only on higher ones, wavefront 0 needs no data and the last one no space,
 // so every wait ends; a poll budget bounds them regardless and raises chain_err when spent.
-template <bool kBackward, Sync kSync, bool kStream>
+template <bool kBackward, Sync kSync, bool kStream, Mode kMode>
 __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
-                                          double* __restrict__ out, double* __restrict__ logp,
+                                          void* __restrict__ out, double* __restrict__ logp,
                                           float* __restrict__ costs, int* __restrict__ chain_err,
                                           double* __restrict__ sink, void* lds)
 {
+    static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
     const int L = m.L, Tb = m.Tb, P = L + 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
@@ -495,9 +505,15 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     // Output: only the label state of each pair is kept (row pitch L+1 doubles, column = label
     // index, in both directions); the gradient gets the blank's share as the complement.
     // Lanes that store nothing write to a sink instead.
-    const bool stores = active && has_label;
-    double* op = stores ? out + m.ab_off + static_cast<int64_t>(f0) * P + li : sink;
-    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * P : 0;
+    // With Mode::kBest the same block holds one byte per pair and frame instead (row pitch
+    // L+1 bytes, column = pair), pair L included: its blank state has a choice to record.
+    constexpr int64_t kOutBytes = (kMode == Mode::kBest) ? 1 : 8;
+    const bool stores = (kMode == Mode::kBest) ? active : (active && has_label);
+    char* op = stores ? static_cast<char*>(out) +
+                            (m.ab_off + static_cast<int64_t>(f0) * P + (kMode == Mode::kBest ? j : li)) * kOutBytes
+                      : reinterpret_cast<char*>(sink);
+    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * P * kOutBytes : 0;
+    int choice = 0;
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
@@ -586,29 +602,41 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     auto finish_step = [&](float eb, float el) {
         v_blank = i_blank + static_cast<double>(eb);
         v_label = i_label + static_cast<double>(el);
-#ifndef CTC_X_NO_STORE
-        if (kStream) {
+        if (kMode == Mode::kBest) {
+            *op = static_cast<unsigned char>(choice);
+        } else if (kMode == Mode::kLoss) {
+            // nothing is kept
+        } else if (kStream) {
             // Too much lattice to stay in the caches until the gradient kernel reads it:
             // streaming stores (measured 15 % faster on both kernels for the 512-utterance batch).
-            __builtin_nontemporal_store(kBackward ? i_label : v_label, op);
+            __builtin_nontemporal_store(kBackward ? i_label : v_label, reinterpret_cast<double*>(op));
         } else {
-            *op = kBackward ? i_label : v_label;
+            *reinterpret_cast<double*>(op) = kBackward ? i_label : v_label;
         }
-#endif
         op += ostride;
         if (kSync == Sync::kHalo) {
             if (--until_refresh == 0) {
-#ifndef CTC_X_NO_SYNC
                 hand_over();
-#endif
                 until_refresh = halo;
             }
         }
     };
     auto advance = [&](int step, float eb, float el) {
         const double prev = from_prev_pair(v_label, step - 1);
-        i_blank = lse2(v_blank, prev);
-        i_label = lse3(v_label, v_blank, prev + skip_penalty);
+        if (kMode == Mode::kBest) {
+            const double via_skip = prev + skip_penalty;
+            const bool blank_moves = prev > v_blank;
+            i_blank = blank_moves ? prev : v_blank;
+            double best = v_label;
+            choice = kFromSame;
+            if (v_blank > best) { best = v_blank; choice = kFromBlank; }
+            if (via_skip > best) { best = via_skip; choice = kFromPrevLabel; }
+            i_label = best;
+            choice |= blank_moves ? kBlankFromPrevLabel : 0;
+        } else {
+            i_blank = lse2(v_blank, prev);
+            i_label = lse3(v_label, v_blank, prev + skip_penalty);
+        }
         finish_step(eb, el);
     };
     auto readlane = [](float v, int l) {
@@ -621,7 +649,8 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         const float el = *ep;
         v_blank = i_blank + static_cast<double>(readlane(ebv, 0));
         v_label = i_label + static_cast<double>(el);
-        *op = kBackward ? i_label : v_label;
+        // (the predecessor choices of frame 0 are never looked at: nothing is written for it)
+        if (kMode == Mode::kGrad) *reinterpret_cast<double*>(op) = kBackward ? i_label : v_label;
         op += ostride;
     }
 
@@ -656,15 +685,23 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         // due after the last step has already been done by finish_step).
         const double prev = from_prev_pair(v_label, Tb - 1);
         if (active && j == L) {
-            const double lp = lse2(v_blank, prev);
-            logp[u] = lp;
-            costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
+            if (kMode == Mode::kBest) {
+                // the better of the two end states; logp carries which one to the backtrace
+                const bool ends_on_label = prev > v_blank;
+                const double lp = ends_on_label ? prev : v_blank;
+                logp[u] = static_cast<double>(2 * L - (ends_on_label ? 1 : 0));
+                costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
+            } else {
+                const double lp = lse2(v_blank, prev);
+                logp[u] = lp;
+                costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
+            }
         }
     }
     if (kSync == Sync::kHalo && budget <= 0 && lane == 0) chain_err[u] = 1;
 }
 
-template <Sync kSync, bool kStream>
+template <Sync kSync, bool kStream, Mode kMode>
 __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
@@ -694,16 +731,18 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
             return;
         }
     }
-    if (blockIdx.y == 0)
-        run_chain<false, kSync, kStream>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+    if (kMode != Mode::kGrad || blockIdx.y == 0)
+        run_chain<false, kSync, kStream, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
     else
-        run_chain<true, kSync, kStream>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+        run_chain<true, kSync, kStream, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
 }
 
-// grid = (utterances whose lattice runs, 2): y = 0 forward, y = 1 backward.
+// grid = (utterances whose lattice runs, 2) for Mode::kGrad: y = 0 forward, y = 1 backward;
+// (utterances, 1) for the other modes, which only run forward (`alpha` is then the block that
+// receives the predecessor choices, or unused).
 // blockDim.x = 64 * (most wavefronts any utterance of the batch uses).
 // Variant for batches whose labels all fit one wavefront: no exchange at all.
-template <bool kStream>
+template <bool kStream, Mode kMode>
 __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
                            const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -712,12 +751,12 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
                            double* __restrict__ logp, float* __restrict__ costs,
                            int* __restrict__ chain_err, double* __restrict__ sink)
 {
-    lattice_body<Sync::kNone, kStream>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
-                              chain_err, sink, nullptr);
+    lattice_body<Sync::kNone, kStream, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+                                              costs, chain_err, sink, nullptr);
 }
 
 // Multi-wavefront chains with the halo exchange.
-template <bool kStream>
+template <bool kStream, Mode kMode>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -727,12 +766,13 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ HaloLds halo_lds;
-    lattice_body<Sync::kHalo, kStream>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
-                              chain_err, sink, &halo_lds);
+    lattice_body<Sync::kHalo, kStream, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+                                              costs, chain_err, sink, &halo_lds);
 }
 
 // Labels too long to leave room for a halo (more than 16 * 63 pairs): 64 pairs per wavefront
 // and one barrier per step.
+template <Mode kMode>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restrict__ order,
                                 const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -742,8 +782,83 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
                                 int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ double xch[2][16];
-    lattice_body<Sync::kBarrier, false>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp, costs,
-                                 chain_err, sink, &xch[0][0]);
+    lattice_body<Sync::kBarrier, false, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+                                               costs, chain_err, sink, &xch[0][0]);
+}
+
+// ---- after a forward-only chain -------------------------------------------------------------
+// Cost-only calls: a chain whose wavefronts lost touch (chain_err) reports NaN, as the
+// gradient kernel does for the full call.  One thread per utterance.
+__global__ __launch_bounds__(kRowThreads)
+void ctc_chain_check_kernel(const int* __restrict__ chain_err, float* __restrict__ costs, int B)
+{
+    const int b = blockIdx.x * kRowThreads + threadIdx.x;
+    if (b < B && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
+}
+
+// Most probable alignment: walk the stored predecessor choices back from the better end state.
+// One wavefront per utterance; alignment is [B][T] (utterance-major): the lattice state of each
+// frame (index into the blank-interleaved label), -1 for frames past the utterance's end and
+// for utterances without an alignment.
+//
+// The walk is serial, one dependent read per frame, so the choices are staged through LDS in
+// tiles of kTile frames x kTile pairs: going back kTile frames the walk can move down by at
+// most kTile - 1 pairs (one per frame), so the tile whose top right corner is the walk's
+// position holds everything those frames can touch.  All lanes walk in step (same addresses:
+// LDS broadcasts); the states of a tile are collected in LDS and written out together.
+constexpr int kTile = 64;
+
+__global__ __launch_bounds__(64)
+void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __restrict__ choices,
+                          const double* __restrict__ end_state, const int* __restrict__ chain_err,
+                          float* __restrict__ costs, int* __restrict__ alignment, int Tt)
+{
+    __shared__ unsigned char tile[kTile][kTile + 4];     // [frame][pair], rows padded to whole words
+    __shared__ int states[kTile];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const Utt m = meta[b];
+    int* arow = alignment + static_cast<size_t>(b) * Tt;
+    const bool runs = (m.flags & kUttRuns) != 0;
+    const bool bad = runs && chain_err[b] != 0;
+    if (bad && lane == 0) costs[b] = __uint_as_float(0x7FC00000u);
+    const int valid = (runs && !bad) ? m.Tb : 0;
+    for (int t = valid + lane; t < Tt; t += 64) arow[t] = -1;
+    if (valid == 0) return;
+
+    const int P = m.L + 1;
+    const unsigned char* base = choices + m.ab_off;
+    int state = min(max(static_cast<int>(end_state[b]), 0), 2 * m.L);   // state of frame t
+    int t = m.Tb - 1;
+    if (lane == 0) arow[t] = state;
+    // Frames t, t-1, ..., 1 each hold the choice that leads to the state of the frame before.
+    while (t >= 1) {
+        const int pair_hi = state >> 1;                   // both states of a pair share its byte
+        const int pair_lo = max(pair_hi - (kTile - 1), 0);
+        const int rows = min(kTile, t);                   // frames t, t-1, ..., t-rows+1
+        // lane = pair column; every row's read is one contiguous run of bytes
+        const int col = pair_lo + lane;
+        if (col <= pair_hi) {
+#pragma unroll 8
+            for (int r = 0; r < rows; ++r)
+                tile[r][lane] = base[static_cast<size_t>(t - r) * P + col];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int r = 0; r < rows; ++r) {
+            const int c = tile[r][(state >> 1) - pair_lo];
+            if (state & 1) {
+                const int from = c & 3;
+                state -= (from == kFromBlank) ? 1 : (from == kFromPrevLabel ? 2 : 0);
+            } else {
+                state -= (c & kBlankFromPrevLabel) ? 1 : 0;
+            }
+            state = max(state, 0);
+            if (lane == 0) states[r] = state;             // state of frame t - r - 1
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (lane < rows) arow[t - 1 - lane] = states[lane];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        t -= rows;
+    }
 }
 
 // ---- gradient ------------------------------------------------------------------------------
@@ -1019,31 +1134,54 @@ int launch_lattice(const Launch& p, void* stream)
     auto* beta = reinterpret_cast<double*>(p.ws + p.lay.beta);
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
-    const dim3 grid(p.n_run, 2), block(64 * p.max_waves);
+    const dim3 grid(p.n_run, p.mode == Mode::kGrad ? 2 : 1), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
     // Stream the lattice past the caches when it is too large to still be there for the gradient.
-    const bool stream_out = static_cast<size_t>(p.lay.ab_doubles) * 16 > (static_cast<size_t>(192) << 20);
-    if (p.max_waves == 1)
-        return checked_launch([&] {
-            if (stream_out)
-                hipLaunchKernelGGL(ctc_lattice_kernel_w1<true>, grid, block, 0, s, meta, order, labels,
-                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
-            else
-                hipLaunchKernelGGL(ctc_lattice_kernel_w1<false>, grid, block, 0, s, meta, order, labels,
-                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
-        });
-    if (!p.needs_barrier)
-        return checked_launch([&] {
-            if (stream_out)
-                hipLaunchKernelGGL(ctc_lattice_kernel<true>, grid, block, 0, s, meta, order, labels,
-                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
-            else
-                hipLaunchKernelGGL(ctc_lattice_kernel<false>, grid, block, 0, s, meta, order, labels,
-                                   emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
-        });
+    const bool stream_out = p.mode == Mode::kGrad &&
+                            static_cast<size_t>(p.lay.ab_doubles) * 16 > (static_cast<size_t>(192) << 20);
+#define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
+    hipLaunchKernelGGL(KERNEL, grid, block, 0, s, meta, order, labels, emit_blank, emit_label,     \
+                       alpha, beta, logp, p.costs, chain_err, sink)
     return checked_launch([&] {
-        hipLaunchKernelGGL(ctc_lattice_kernel_barrier, grid, block, 0, s, meta, order, labels,
-                           emit_blank, emit_label, alpha, beta, logp, p.costs, chain_err, sink);
+        if (p.max_waves == 1) {
+            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<false, Mode::kLoss>));
+            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<false, Mode::kBest>));
+            else if (stream_out) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<true, Mode::kGrad>));
+            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<false, Mode::kGrad>));
+        } else if (!p.needs_barrier) {
+            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<false, Mode::kLoss>));
+            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<false, Mode::kBest>));
+            else if (stream_out) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<true, Mode::kGrad>));
+            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel<false, Mode::kGrad>));
+        } else {
+            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kLoss>);
+            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kBest>);
+            else CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kGrad>);
+        }
+    });
+#undef CTC_LAUNCH_LATTICE
+}
+
+int launch_chain_check(const Launch& p, void* stream)
+{
+    // Only chains spread over several wavefronts can lose touch.
+    if (p.n_run == 0 || p.max_waves == 1) return 0;
+    auto* chain_err = reinterpret_cast<const int*>(p.ws + p.lay.chain_err);
+    return checked_launch([&] {
+        hipLaunchKernelGGL(ctc_chain_check_kernel, dim3((p.B + kRowThreads - 1) / kRowThreads), dim3(kRowThreads),
+                           0, static_cast<hipStream_t>(stream), chain_err, p.costs, p.B);
+    });
+}
+
+int launch_backtrace(const Launch& p, void* stream)
+{
+    auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
+    auto* choices = reinterpret_cast<const unsigned char*>(p.ws + p.lay.alpha);
+    auto* end_state = reinterpret_cast<const double*>(p.ws + p.lay.logp);
+    auto* chain_err = reinterpret_cast<const int*>(p.ws + p.lay.chain_err);
+    return checked_launch([&] {
+        hipLaunchKernelGGL(ctc_backtrace_kernel, dim3(p.B), dim3(64), 0, static_cast<hipStream_t>(stream),
+                           meta, choices, end_state, chain_err, p.costs, p.alignment, p.T);
     });
 }
 

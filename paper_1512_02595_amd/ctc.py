@@ -26,7 +26,10 @@ DTYPE_BF16 = 1
 MAX_LABEL_LENGTH = 1023
 NUM_KERNELS = 3
 
+KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
+
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
+           "ctc_best_path", "ctc_profile_best_path",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error")
 
 _lib = None
@@ -56,6 +59,10 @@ def load() -> ctypes.CDLL:
     lib.ctc_loss_and_grad.argtypes = common
     lib.ctc_profile_kernels.restype = st
     lib.ctc_profile_kernels.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
+    lib.ctc_best_path.restype = st
+    lib.ctc_best_path.argtypes = common
+    lib.ctc_profile_best_path.restype = st
+    lib.ctc_profile_best_path.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
     lib.ctc_kernel_name.restype = ctypes.c_char_p
     lib.ctc_kernel_name.argtypes = [ci]
     lib.ctc_status_string.restype = ctypes.c_char_p
@@ -106,7 +113,7 @@ def loss_and_grad_status(activations_ptr, flat_labels, label_lengths, input_leng
                          dtype, costs_ptr, grads_ptr, workspace_ptr, workspace_bytes, stream=0,
                          kernel_ms=None) -> int:
     """Raw call; returns the status.  With `kernel_ms` (float32 numpy array of NUM_KERNELS)
-    the profiling entry point is used and the array is filled."""
+    the profiling entry point is used and the array is filled.  grads_ptr None (or 0): costs only."""
     _fl, flp = _i32(flat_labels, allow_none=True)
     _ll, llp = _i32(label_lengths, allow_none=True)
     _il, ilp = _i32(input_lengths, allow_none=True)
@@ -129,3 +136,31 @@ def loss_and_grad(activations_ptr, flat_labels, label_lengths, input_lengths, T,
     if st != STATUS_SUCCESS:
         extra = f" (hipError {last_hip_error()})" if st == STATUS_HIP_ERROR else ""
         raise CTCError(st, "ctc_loss_and_grad" + extra)
+
+
+def best_path_status(activations_ptr, flat_labels, label_lengths, input_lengths, T, B, A, blank,
+                     dtype, scores_ptr, alignment_ptr, workspace_ptr, workspace_bytes, stream=0,
+                     kernel_ms=None) -> int:
+    """Raw ctc_best_path (ctc_profile_best_path with `kernel_ms`); returns the status."""
+    _fl, flp = _i32(flat_labels, allow_none=True)
+    _ll, llp = _i32(label_lengths, allow_none=True)
+    _il, ilp = _i32(input_lengths, allow_none=True)
+    args = [ctypes.c_void_p(activations_ptr), flp, llp, ilp, int(T), int(B), int(A), int(blank),
+            int(dtype), ctypes.c_void_p(scores_ptr), ctypes.c_void_p(alignment_ptr),
+            ctypes.c_void_p(workspace_ptr), ctypes.c_size_t(workspace_bytes), ctypes.c_void_p(stream)]
+    lib = load()
+    if kernel_ms is None:
+        return int(lib.ctc_best_path(*args))
+    assert kernel_ms.dtype == np.float32 and kernel_ms.size >= NUM_KERNELS
+    return int(lib.ctc_profile_best_path(*args, kernel_ms.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
+
+
+def best_path(activations_ptr, flat_labels, label_lengths, input_lengths, T, B, A, blank,
+              dtype, scores_ptr, alignment_ptr, workspace_ptr, workspace_bytes, stream=0,
+              kernel_ms=None) -> None:
+    st = best_path_status(activations_ptr, flat_labels, label_lengths, input_lengths, T, B, A,
+                          blank, dtype, scores_ptr, alignment_ptr, workspace_ptr, workspace_bytes,
+                          stream, kernel_ms)
+    if st != STATUS_SUCCESS:
+        extra = f" (hipError {last_hip_error()})" if st == STATUS_HIP_ERROR else ""
+        raise CTCError(st, "ctc_best_path" + extra)

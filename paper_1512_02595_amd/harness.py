@@ -53,6 +53,29 @@ class DeviceBatch:
                           b.T, b.B, b.A, b.blank, self.dtype, self.costs.data_ptr(),
                           self.grads.data_ptr(), self.ws_ptr, self.ws_bytes, s, kernel_ms)
 
+    def run_loss(self, stream=None, kernel_ms=None):
+        """Costs only (grads == NULL)."""
+        b = self.batch
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        ctc.loss_and_grad(self.x.data_ptr(), b.flat_labels, b.label_lengths, b.input_lengths,
+                          b.T, b.B, b.A, b.blank, self.dtype, self.costs.data_ptr(),
+                          None, self.ws_ptr, self.ws_bytes, s, kernel_ms)
+
+    def run_best_path(self, stream=None, kernel_ms=None):
+        """Most probable alignment: scores go to self.costs, states to self.alignment [B,T]."""
+        b = self.batch
+        if getattr(self, "alignment", None) is None:
+            self.alignment = torch.full((b.B, b.T), -7, dtype=torch.int32, device=self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        ctc.best_path(self.x.data_ptr(), b.flat_labels, b.label_lengths, b.input_lengths,
+                      b.T, b.B, b.A, b.blank, self.dtype, self.costs.data_ptr(),
+                      self.alignment.data_ptr(), self.ws_ptr, self.ws_bytes, s, kernel_ms)
+
+    def best_path_results(self):
+        """(scores float32 [B], states int32 [B,T]) on the host, after synchronising."""
+        torch.cuda.synchronize(self.device)
+        return self.costs.cpu().numpy(), self.alignment.cpu().numpy()
+
     def results(self):
         """(costs float32 [B], grads float32 [T,B,A]) on the host, after synchronising."""
         torch.cuda.synchronize(self.device)

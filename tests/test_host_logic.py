@@ -39,7 +39,8 @@ def test_status_strings_and_kernel_names(lib):
     assert len({ctc.status_string(i) for i in range(5)}) == 5
     names = [ctc.kernel_name(i) for i in range(ctc.NUM_KERNELS)]
     assert names == ["ctc_softmax", "ctc_lattice", "ctc_gradient"]
-    assert ctc.kernel_name(ctc.NUM_KERNELS) is None and ctc.kernel_name(-1) is None
+    assert ctc.kernel_name(ctc.KERNEL_BACKTRACE) == "ctc_backtrace"
+    assert ctc.kernel_name(ctc.KERNEL_BACKTRACE + 1) is None and ctc.kernel_name(-1) is None
     assert ctc.last_hip_error() == 0
 
 
@@ -102,7 +103,9 @@ def test_loss_and_grad_validates_before_any_device_work(lib):
 
     assert call(activations_ptr=0) == ctc.STATUS_INVALID_VALUE
     assert call(costs_ptr=0) == ctc.STATUS_INVALID_VALUE
-    assert call(grads_ptr=0) == ctc.STATUS_INVALID_VALUE
+    # no gradient buffer is the cost-only form: it passes validation (and, without a device, stops there)
+    assert call(grads_ptr=None) == ctc.STATUS_HIP_ERROR
+    assert call(grads_ptr=None, workspace_bytes=n - 1) == ctc.STATUS_WORKSPACE_TOO_SMALL
     assert call(workspace_ptr=0) == ctc.STATUS_INVALID_VALUE
     assert call(workspace_ptr=ws + 8) == ctc.STATUS_INVALID_VALUE          # not 256-byte aligned
     assert call(blank=-1) == ctc.STATUS_INVALID_VALUE
@@ -116,6 +119,32 @@ def test_loss_and_grad_validates_before_any_device_work(lib):
     assert call(workspace_bytes=n - 1) == ctc.STATUS_WORKSPACE_TOO_SMALL
     assert call(label_lengths=[ctc.MAX_LABEL_LENGTH + 1, 1]) == ctc.STATUS_UNSUPPORTED
     assert call(dtype=5) == ctc.STATUS_INVALID_VALUE
+    kms = np.zeros(ctc.NUM_KERNELS, dtype=np.float32)
+    assert call(workspace_bytes=n - 1, kernel_ms=kms) == ctc.STATUS_WORKSPACE_TOO_SMALL
+
+
+def test_best_path_validates_before_any_device_work(lib):
+    T, B, A = 10, 2, 5
+    ll, il, lab = [2, 1], [10, 8], [1, 2, 3]
+    x, al, c, ws = 0x10000, 0x200000, 0x300000, 0x400000
+    n = ctc.workspace_size(T, B, A, ll, il)
+
+    def call(**kw):
+        a = dict(activations_ptr=x, flat_labels=lab, label_lengths=ll, input_lengths=il, T=T, B=B, A=A,
+                 blank=0, dtype=ctc.DTYPE_F32, scores_ptr=c, alignment_ptr=al, workspace_ptr=ws,
+                 workspace_bytes=n)
+        a.update(kw)
+        return ctc.best_path_status(**a)
+
+    assert call(activations_ptr=0) == ctc.STATUS_INVALID_VALUE
+    assert call(scores_ptr=0) == ctc.STATUS_INVALID_VALUE
+    assert call(alignment_ptr=0) == ctc.STATUS_INVALID_VALUE
+    assert call(alignment_ptr=al + 2) == ctc.STATUS_INVALID_VALUE           # not int32-aligned
+    assert call(blank=A) == ctc.STATUS_INVALID_VALUE
+    assert call(flat_labels=[1, 0, 3]) == ctc.STATUS_INVALID_VALUE
+    assert call(input_lengths=[10, 11]) == ctc.STATUS_INVALID_VALUE
+    assert call(workspace_bytes=n - 1) == ctc.STATUS_WORKSPACE_TOO_SMALL
+    assert call(label_lengths=[ctc.MAX_LABEL_LENGTH + 1, 1]) == ctc.STATUS_UNSUPPORTED
     kms = np.zeros(ctc.NUM_KERNELS, dtype=np.float32)
     assert call(workspace_bytes=n - 1, kernel_ms=kms) == ctc.STATUS_WORKSPACE_TOO_SMALL
 
