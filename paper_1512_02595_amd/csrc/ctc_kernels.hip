@@ -427,11 +427,11 @@ constexpr int kHaloEntries = 64;      // 16-byte entries of one wavefront bounda
 
 enum class Sync { kNone, kHalo, kBarrier };
 
-// Predecessor choices of a pair at one frame, as stored for the backtrace: bits 0..1 for the
-// label state (0 = stayed, 1 = came from the pair's blank, 2 = came from the label of the pair
-// before, skipping the blank), bit 2 for the blank state (0 = stayed, 1 = came from the label
-// of the pair before).
-constexpr int kFromSame = 0, kFromBlank = 1, kFromPrevLabel = 2, kBlankFromPrevLabel = 4;
+// Predecessor choices of a pair at one frame, as stored for the backtrace; each field is the
+// number of states the walk moves down.  Bits 2..3, the label state: 0 = stayed, 1 = came from
+// the pair's blank, 2 = came from the label of the pair before (skipping the blank).  Bit 0, the
+// blank state: 0 = stayed, 1 = came from the label of the pair before.
+constexpr int kFromSame = 0, kFromBlank = 1 << 2, kFromPrevLabel = 2 << 2, kBlankFromPrevLabel = 1;
 
 // LDS of the halo exchange: per wavefront w, what w hands to w+1.
 struct HaloLds {
@@ -801,11 +801,13 @@ void ctc_chain_check_kernel(const int* __restrict__ chain_err, float* __restrict
 // frame (index into the blank-interleaved label), -1 for frames past the utterance's end and
 // for utterances without an alignment.
 //
-// The walk is serial, one dependent read per frame, so the choices are staged through LDS in
-// tiles of kTile frames x kTile pairs: going back kTile frames the walk can move down by at
-// most kTile - 1 pairs (one per frame), so the tile whose top right corner is the walk's
-// position holds everything those frames can touch.  All lanes walk in step (same addresses:
-// LDS broadcasts); the states of a tile are collected in LDS and written out together.
+// The walk is serial, one dependent look-up per frame, so it is kept on the scalar unit: the
+// choices are fetched in tiles of kTile frames x kTile pairs, lane = pair column, one register
+// per frame.  Going back kTile frames the walk moves down by at most kTile - 1 pairs (one per
+// frame), so the tile whose top right corner is the walk's position holds everything those
+// frames can touch.  A step is then a v_readlane at the walk's column, a shift, a mask and a
+// subtraction in scalar registers, and a v_writelane that files the state for the tile's
+// one coalesced store.
 constexpr int kTile = 64;
 
 __global__ __launch_bounds__(64)
@@ -813,8 +815,6 @@ void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __r
                           const double* __restrict__ end_state, const int* __restrict__ chain_err,
                           float* __restrict__ costs, int* __restrict__ alignment, int Tt)
 {
-    __shared__ unsigned char tile[kTile][kTile + 4];     // [frame][pair], rows padded to whole words
-    __shared__ int states[kTile];
     const int b = blockIdx.x, lane = threadIdx.x;
     const Utt m = meta[b];
     int* arow = alignment + static_cast<size_t>(b) * Tt;
@@ -827,7 +827,8 @@ void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __r
 
     const int P = m.L + 1;
     const unsigned char* base = choices + m.ab_off;
-    int state = min(max(static_cast<int>(end_state[b]), 0), 2 * m.L);   // state of frame t
+    // state of frame t; clamped so that no stored value can lead the reads astray
+    int state = __builtin_amdgcn_readfirstlane(min(max(static_cast<int>(end_state[b]), 0), 2 * m.L));
     int t = m.Tb - 1;
     if (lane == 0) arow[t] = state;
     // Frames t, t-1, ..., 1 each hold the choice that leads to the state of the frame before.
@@ -835,29 +836,27 @@ void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __r
         const int pair_hi = state >> 1;                   // both states of a pair share its byte
         const int pair_lo = max(pair_hi - (kTile - 1), 0);
         const int rows = min(kTile, t);                   // frames t, t-1, ..., t-rows+1
-        // lane = pair column; every row's read is one contiguous run of bytes
-        const int col = pair_lo + lane;
-        if (col <= pair_hi) {
-#pragma unroll 8
-            for (int r = 0; r < rows; ++r)
-                tile[r][lane] = base[static_cast<size_t>(t - r) * P + col];
+        const unsigned col = static_cast<unsigned>(min(pair_lo + lane, pair_hi));
+        // A last, partial tile repeats frame 1 in the rows below it and walks on through them:
+        // those steps stay inside the tile (the state is kept >= 0) and their results are not
+        // stored.  (An utterance's block is smaller than 2^31 bytes: 32-bit offsets.)
+        int tile[kTile];
+#pragma unroll
+        for (int r = 0; r < kTile; ++r)
+            tile[r] = base[static_cast<unsigned>(max(t - r, 1)) * static_cast<unsigned>(P) + col];
+        int filed = 0;
+#pragma unroll
+        for (int r = 0; r < kTile; ++r) {
+            const int c = __builtin_amdgcn_readlane(tile[r], (state >> 1) - pair_lo);
+            // how far down the state of this frame came from: bits 2..3 if it is a label state
+            // (odd), bits 0..1 if it is a blank
+            state = max(state - ((c >> ((state << 1) & 2)) & 3), 0);
+            // lane r of `filed` = state of frame t - r - 1
+            asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(filed) : "s"(state), "n"(r));
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        for (int r = 0; r < rows; ++r) {
-            const int c = tile[r][(state >> 1) - pair_lo];
-            if (state & 1) {
-                const int from = c & 3;
-                state -= (from == kFromBlank) ? 1 : (from == kFromPrevLabel ? 2 : 0);
-            } else {
-                state -= (c & kBlankFromPrevLabel) ? 1 : 0;
-            }
-            state = max(state, 0);
-            if (lane == 0) states[r] = state;             // state of frame t - r - 1
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (lane < rows) arow[t - 1 - lane] = states[lane];
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        t -= rows;
+        if (lane < rows) arow[t - 1 - lane] = filed;
+        if (rows < kTile) break;
+        t -= kTile;
     }
 }
 
