@@ -81,7 +81,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="0..4, index into the workload list")
+    ap.add_argument("--config", type=int, default=1, help="0..4: the five headline workloads (1 = the metric's); 5: bigram alphabet")
     ap.add_argument("--dtype", choices=("f32", "bf16"), default="f32")
     ap.add_argument("--mode", choices=("grad", "loss", "align"), default="grad",
                     help="grad: cost + gradient (headline); loss: cost only; align: most probable alignment")

@@ -369,10 +369,20 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     if (t < m.Tb) {
         const T* row = x + (static_cast<size_t>(t) * B + b) * A;
         float mx = -__builtin_inff();
-        for (int k = q; k < A; k += kPerRow) {
-            const float v = load_elem(row, k);
-            lrow[k] = v;
-            mx = fmaxf(mx, v);
+        // eight reads in flight per thread: a row costs a few memory latencies, not A / kPerRow
+        for (int k0 = q; k0 < A; k0 += 8 * kPerRow) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + u * kPerRow;
+                v[u] = (k < A) ? load_elem(row, k) : -__builtin_inff();
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + u * kPerRow;
+                if (k < A) lrow[k] = v[u];
+                mx = fmaxf(mx, v[u]);
+            }
         }
         mx = (kPerRow == 16) ? row16_max(mx) : wave_max(mx);
         mx *= kLog2e;
@@ -1022,8 +1032,19 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
             if (lane == 0) occ[blank] = zb;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (lane < A) store_elem(grow, lane, fast_exp2(fmaf(cur.x0, kLog2e, -l2)) - occ[lane]);
-            for (int k = 64 + lane; k < A; k += 64)
-                store_elem(grow, k, fast_exp2(fmaf(load_elem(xrow, k), kLog2e, -l2)) - occ[k]);
+            for (int k0 = 64 + lane; k0 < A; k0 += 8 * 64) {      // eight reads in flight
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = k0 + u * 64;
+                    v[u] = (k < A) ? load_elem(xrow, k) : 0.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = k0 + u * 64;
+                    if (k < A) store_elem(grow, k, fast_exp2(fmaf(v[u], kLog2e, -l2)) - occ[k]);
+                }
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }

@@ -101,7 +101,7 @@ def check_best(batch, dtype=ctc.DTYPE_F32, min_same=0.8):
 
 # ---------------------------------------------------------------- cost only
 
-@pytest.mark.parametrize("index", [0, 1, 2, 3])
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 5])
 def test_loss_only_configs(index):
     check_loss(wl.make_config(index))
 
@@ -119,7 +119,7 @@ def test_loss_only_odd_shapes():
 
 # ---------------------------------------------------------------- most probable alignment
 
-@pytest.mark.parametrize("index", [0, 1, 2, 3])
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 5])
 def test_best_path_configs(index):
     check_best(wl.make_config(index))
 

@@ -152,7 +152,7 @@ def test_best_path_validates_before_any_device_work(lib):
 def test_workload_generator_is_seeded_and_feasible():
     a, b = wl.make_config(1), wl.make_config(1)
     assert np.array_equal(a.logits, b.logits) and np.array_equal(a.flat_labels, b.flat_labels)
-    for idx in (0, 1, 3, 4):
+    for idx in (0, 1, 3, 4, 5):
         c = wl.make_config(idx)
         assert c.logits.shape == (c.T, c.B, c.A) and c.logits.dtype == np.float32
         assert c.input_lengths.max() <= c.T and c.label_lengths.max() <= ctc.MAX_LABEL_LENGTH

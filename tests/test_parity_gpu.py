@@ -68,6 +68,12 @@ def test_sweep_config_bf16():
     check(wl.make_config(4), ctc.DTYPE_BF16)
 
 
+def test_bigram_alphabet_config():
+    """Mid-size alphabet (Section 3.5: bigrams + unigrams, stride 3), fp32 and bf16."""
+    check(wl.make_config(5))
+    check(wl.make_config(5), ctc.DTYPE_BF16)
+
+
 @pytest.mark.parametrize("seed,kw", [
     (1, dict(T=12, B=5, A=6, max_label=4)),
     (2, dict(T=40, B=9, A=9, max_label=30)),                       # many infeasible pairs
