@@ -140,6 +140,23 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # The same loop once more with an event pair around every call (median and minimum of the
+    # device time of single calls), and on one minibatch only (cache-warm: its buffers may still
+    # sit in the 256 MB infinity cache from the call before).
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        step(dbs[i % len(dbs)], stream)
+        e1.record()
+    torch.cuda.synchronize(dev)
+    per_call = np.array([e0.elapsed_time(e1) for e0, e1 in evs])
+    torch.cuda.synchronize(dev)
+    w0 = time.perf_counter()
+    for i in range(args.steps):
+        step(dbs[0], stream)
+    torch.cuda.synchronize(dev)
+    warm_ms = (time.perf_counter() - w0) * 1e3 / args.steps
+
     B = batches[0].B
     frames = float(np.mean([b.frames for b in batches]))
     if args.mode == "grad":
@@ -187,6 +204,10 @@ def main():
         "unit": "utterances/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
+        "ms_per_call_median": round(float(np.median(per_call)), 5),
+        "ms_per_call_min": round(float(per_call.min()), 5),
+        "ms_per_step_cache_warm": round(warm_ms, 5),
+        "rotating_bytes": int(sum(d.x.numel() * d.x.element_size() * 2 + d.ws_bytes for d in dbs)),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64 lattice state, f32 transcendentals, %s activations" % args.dtype,
         "data": "synthetic",
@@ -231,8 +252,17 @@ def main():
             oracle_call()
             times.append(time.perf_counter() - c0)
         tmed = float(np.median(times))
+        c0 = time.perf_counter()
+        if args.mode == "align":
+            orc.ctc_best_path(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb], b.blank,
+                              nthreads=1)
+        else:
+            orc.ctc_loss_and_grad(xs, b.flat_labels[:nlab], b.label_lengths[:nb], b.input_lengths[:nb],
+                                  b.blank, want_grad=(args.mode == "grad"), nthreads=1)
+        t_single = time.perf_counter() - c0
         out["cpu_baseline"] = {"value": round(nb / tmed, 2), "unit": "utterances/s",
                                "cores": cores, "kind": "oracle",
+                               "single_thread_value": round(nb / t_single, 2),
                                "sample": "first %d of %d utterances of minibatch 0, median of %d runs, %.3f s each"
                                          % (nb, b.B, reps, tmed),
                                "activation_frames_per_s": round(float(b.input_lengths[:nb].sum()) / tmed, 1)}
