@@ -86,6 +86,11 @@ def main():
     ap.add_argument("--dtype", choices=("f32", "bf16"), default="f32")
     ap.add_argument("--mode", choices=("grad", "loss", "align"), default="grad",
                     help="grad: cost + gradient (headline); loss: cost only; align: most probable alignment")
+    ap.add_argument("--metadata", choices=("host", "device"), default="host",
+                    help="device: ctc_loss_and_grad_device (lengths and labels resident on the GPU, workspace "
+                         "sized by bounds); no per-kernel times, so no roofline object")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --metadata device: record each minibatch's call into a HIP graph and time replays")
     ap.add_argument("--buffers", type=int, default=4, help="distinct minibatches rotated through")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -125,10 +130,43 @@ def main():
 
     batches = [workloads.make_config(args.config, seed=workloads.BASE_SEED + args.config + 1000 * i)
                for i in range(args.buffers)]
-    dbs = [harness.DeviceBatch(b, dtype, dev, poison=False) for b in batches]
     stream = torch.cuda.current_stream(dev).cuda_stream
-    step = {"grad": harness.DeviceBatch.run, "loss": harness.DeviceBatch.run_loss,
-            "align": harness.DeviceBatch.run_best_path}[args.mode]
+    if args.metadata == "device":
+        if args.mode == "align":
+            sys.exit("bench.py: --metadata device covers the grad and loss modes")
+        max_label = max(int(b.label_lengths.max()) for b in batches)
+        dbs = []
+        for b in batches:
+            d = harness.DeviceMetaBatch(b.T, b.B, b.A, max_label, b.blank, dtype, dev)
+            d.load(b)
+            dbs.append(d)
+        want_grad = args.mode == "grad"
+        if args.graph:
+            side = torch.cuda.Stream()
+            graphs = {}
+            for d in dbs:
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    d.run(stream=side.cuda_stream, want_grad=want_grad)          # warm-up outside the capture
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize(dev)
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    d.run(stream=torch.cuda.current_stream().cuda_stream, want_grad=want_grad)
+                graphs[id(d)] = g
+
+            def step(d, stream, kernel_ms=None):
+                graphs[id(d)].replay()
+        else:
+            def step(d, stream, kernel_ms=None):
+                d.run(stream, want_grad=want_grad)
+        args.profile_steps = 0
+    else:
+        if args.graph:
+            sys.exit("bench.py: --graph needs --metadata device (the host-metadata call reads host memory)")
+        dbs = [harness.DeviceBatch(b, dtype, dev, poison=False) for b in batches]
+        step = {"grad": harness.DeviceBatch.run, "loss": harness.DeviceBatch.run_loss,
+                "align": harness.DeviceBatch.run_best_path}[args.mode]
 
     for i in range(args.warmup):
         step(dbs[i % len(dbs)], stream)
@@ -178,12 +216,16 @@ def main():
     kernels = {}
     for i, n in enumerate(names):
         byt = float(np.mean([k[0][n] for k in kb]))
-        kernels[n] = {"ms": round(kavg[i], 5), "algorithmic_bytes": int(byt),
-                      "GBps": round(byt / (kavg[i] * 1e-3) / 1e9, 2) if kavg[i] > 0 else None}
+        kernels[n] = {"ms": round(kavg[i], 5) if args.profile_steps else None, "algorithmic_bytes": int(byt),
+                      "GBps": round(byt / (kavg[i] * 1e-3) / 1e9, 2) if args.profile_steps and kavg[i] > 0 else None}
     dom = int(np.argmax(kavg))
     dom_name = names[dom]
+    if args.profile_steps == 0:
+        dom_name = None
     traffic = MEASURED_TRAFFIC.get((args.config, args.dtype), {}).get(dom_name) if args.mode == "grad" else None
-    if dom_name == "ctc_lattice":
+    if dom_name is None:
+        roofline = None
+    elif dom_name == "ctc_lattice":
         directions = 2.0 if args.mode == "grad" else 1.0
         lane_ops = LANE_OPS_PER_PAIR_STEP_ALIGN if args.mode == "align" else LANE_OPS_PER_PAIR_STEP
         pair_steps = directions * float(np.mean([k[1] for k in kb]))
@@ -213,7 +255,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "config[%d] %s: B=%d A=%d T=%d, %d rotating minibatches"
                    % (args.config, batches[0].name, B, batches[0].A, batches[0].T, len(batches)),
-                   "mode": args.mode},
+                   "mode": args.mode, "metadata": args.metadata, "graph": bool(args.graph)},
         "activation_frames_per_s": round(frames / (ms_per_step * 1e-3), 1),
         "hbm_roofline_frac_end_to_end": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
         "compulsory_bytes": int(compulsory),

@@ -139,6 +139,53 @@ ctc_status_t ctc_profile_kernels(const void *activations,
                                  float *kernel_ms);
 
 /*
+ * The same computation for callers that keep lengths and labels on the device and cannot
+ * take a detour through the host: code recorded into a HIP graph and replayed with new
+ * contents in the same buffers, or a training step whose batch metadata never leaves the GPU
+ * (keeping host work and transfers off the step: the theme of Section 4.3).  The call only
+ * enqueues kernels on `stream`: it reads no host memory, copies nothing, waits for nothing and
+ * touches no memory of the library's own, so it may be captured; every replay reads the
+ * device arrays afresh.
+ *
+ * Since the host sees no lengths, the caller states bounds instead and everything is laid out
+ * for the largest utterance they allow:
+ *
+ *   labels            (device) [B, max_label_length] int32, one padded row per utterance;
+ *                     only the first label_lengths[b] entries of row b are read
+ *   label_lengths     (device) [B]
+ *   input_lengths     (device) [B]
+ *   max_label_length  0..CTC_MAX_LABEL_LENGTH; B is limited to 4096
+ *   status_out        (device) [1] int32: what the host-side validation reports for the other
+ *                     entry points, found on the device.  CTC_STATUS_SUCCESS, or
+ *                     CTC_STATUS_INVALID_VALUE if some length is out of range (label_lengths[b]
+ *                     not in 0..max_label_length, input_lengths[b] not in 0..T) or some label is
+ *                     outside [0, A) or equal to blank; the utterances concerned get a NaN cost
+ *                     and a zero gradient, the others are computed as usual.
+ *   workspace         at least ctc_workspace_size_device bytes (larger than the exact-size
+ *                     query of the host-metadata calls: T x B x (max_label_length + 1) lattice pairs)
+ *   grads             may be NULL (costs only), as for ctc_loss_and_grad
+ *   everything else as for ctc_loss_and_grad; results are bitwise the same as its results.
+ *
+ * The return value covers what the host can check (pointers, T, B, A, blank, dtype, bounds,
+ * workspace size, launch errors).
+ */
+ctc_status_t ctc_workspace_size_device(int T, int B, int A, int max_label_length,
+                                       ctc_dtype_t dtype, size_t *bytes_out);
+
+ctc_status_t ctc_loss_and_grad_device(const void *activations,
+                                      const int32_t *labels,
+                                      const int32_t *label_lengths,
+                                      const int32_t *input_lengths,
+                                      int max_label_length,
+                                      int T, int B, int A, int blank,
+                                      ctc_dtype_t dtype,
+                                      float *costs,
+                                      void *grads,
+                                      int32_t *status_out,
+                                      void *workspace, size_t workspace_bytes,
+                                      void *stream);
+
+/*
  * Most probable alignment of each utterance (Section 5.1, "Dataset Construction": the
  * alignment step of the segmentation pipeline),
  *

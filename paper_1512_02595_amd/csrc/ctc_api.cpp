@@ -31,55 +31,10 @@ inline bool record(int err)
 
 }  // namespace
 
-// Wavefronts and halo width for a label of this length.  Measured on gfx950: with one
-// wavefront per SIMD (up to 4) a step costs about 250 clocks and a hand-over about 500; with
-// several per SIMD the vector ALU is the limit (about 200 clocks per wavefront-step) and part
-// of a hand-over's latency hides behind the other wavefronts (about 350).
-WavePlan plan_waves(int label_length)
+namespace {
+// Region offsets from the batch totals (label symbols, label emissions, frames, lattice pairs).
+void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab, Layout* lay)
 {
-    const int pairs = label_length + 1;
-    if (pairs <= 64) return {1, 0, false};
-    const int w0 = (pairs + 62) / 63;
-    if (w0 > 16) return {16, 0, true};
-    WavePlan best{w0, 0, false};
-    double best_cost = 1e30;
-    for (int w = w0; w <= 16 && w <= w0 + 4; ++w) {
-        const int useful = (pairs + w - 1) / w;
-        // the lanes handed up must themselves be exact ones: halo <= 64 - halo
-        const int halo = std::min(64 - useful, 32);
-        if (halo < 1) continue;
-        const int per_simd = (w + 3) / 4;
-        // the last term prefers fewer wavefronts when the estimates are close
-        const double cost = ((per_simd == 1) ? 250.0 + 500.0 / halo : per_simd * 200.0 + 350.0 / halo) + 4.0 * w;
-        if (cost < best_cost) {
-            best_cost = cost;
-            best = {w, halo, false};
-        }
-    }
-    return best;
-}
-
-ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
-                         const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay)
-{
-    if (!label_lengths || !input_lengths || !lay) return CTC_STATUS_INVALID_VALUE;
-    if (T < 1 || B < 1 || A < 1) return CTC_STATUS_INVALID_VALUE;
-    if (dtype != CTC_DTYPE_F32 && dtype != CTC_DTYPE_BF16) return CTC_STATUS_INVALID_VALUE;
-    int64_t sumL = 0, emit = 0, ab = 0, frames = 0;
-    bool too_long = false;
-    for (int b = 0; b < B; ++b) {
-        const int64_t L = label_lengths[b], Tb = input_lengths[b];
-        if (L < 0 || Tb < 0 || Tb > T) return CTC_STATUS_INVALID_VALUE;
-        if (L > CTC_MAX_LABEL_LENGTH) too_long = true;
-        sumL += L;
-        emit += Tb * L;
-        frames += Tb;
-        // per-utterance byte offsets inside the kernels are 32-bit
-        if (Tb * (L + 1) * 8 > INT32_MAX) too_long = true;
-        ab += Tb * (L + 1);
-    }
-    if (too_long) return CTC_STATUS_UNSUPPORTED;
-    if (sumL > INT32_MAX || frames > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
     Layout l;
     l.sumL = sumL;
     l.emit_floats = emit;
@@ -104,6 +59,44 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
     l.beta = off;   off = align_up(off + static_cast<size_t>(ab) * sizeof(double));
     l.total = off;
     *lay = l;
+}
+}  // namespace
+
+ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
+                         const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay)
+{
+    if (!label_lengths || !input_lengths || !lay) return CTC_STATUS_INVALID_VALUE;
+    if (T < 1 || B < 1 || A < 1) return CTC_STATUS_INVALID_VALUE;
+    if (dtype != CTC_DTYPE_F32 && dtype != CTC_DTYPE_BF16) return CTC_STATUS_INVALID_VALUE;
+    int64_t sumL = 0, emit = 0, ab = 0, frames = 0;
+    bool too_long = false;
+    for (int b = 0; b < B; ++b) {
+        const int64_t L = label_lengths[b], Tb = input_lengths[b];
+        if (L < 0 || Tb < 0 || Tb > T) return CTC_STATUS_INVALID_VALUE;
+        if (L > CTC_MAX_LABEL_LENGTH) too_long = true;
+        sumL += L;
+        emit += Tb * L;
+        frames += Tb;
+        // per-utterance byte offsets inside the kernels are 32-bit
+        if (Tb * (L + 1) * 8 > INT32_MAX) too_long = true;
+        ab += Tb * (L + 1);
+    }
+    if (too_long) return CTC_STATUS_UNSUPPORTED;
+    if (sumL > INT32_MAX || frames > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
+    carve(T, B, sumL, emit, frames, ab, lay);
+    return CTC_STATUS_SUCCESS;
+}
+
+// Layout for the device-metadata entry point: every utterance gets the room of the largest one
+// the caller allows (T frames, max_label symbols), so that offsets need no lengths.
+ctc_status_t make_layout_bounds(int T, int B, int A, int max_label, ctc_dtype_t dtype, Layout* lay)
+{
+    if (!lay || T < 1 || B < 1 || A < 1 || max_label < 0) return CTC_STATUS_INVALID_VALUE;
+    if (dtype != CTC_DTYPE_F32 && dtype != CTC_DTYPE_BF16) return CTC_STATUS_INVALID_VALUE;
+    if (max_label > CTC_MAX_LABEL_LENGTH || B > kMaxDeviceMetaB) return CTC_STATUS_UNSUPPORTED;
+    const int64_t Tl = T, Bl = B, Ll = max_label;
+    if (Tl * (Ll + 1) * 8 > INT32_MAX || Bl * Ll > INT32_MAX || Bl * Tl > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
+    carve(T, B, Bl * Ll, Bl * Tl * Ll, Bl * Tl, Bl * Tl * (Ll + 1), lay);
     return CTC_STATUS_SUCCESS;
 }
 
@@ -279,7 +272,11 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->alignment = (c.mode == Mode::kBest) ? c.alignment : nullptr;
     out->costs = c.costs;
     out->ws = static_cast<char*>(c.ws);
+    out->labels = reinterpret_cast<const int32_t*>(static_cast<char*>(c.ws) + lay.labels);
     out->host_image = image;
+    out->dev_label_lengths = nullptr;
+    out->dev_input_lengths = nullptr;
+    out->dev_status = nullptr;
     out->lay = lay;
     return CTC_STATUS_SUCCESS;
 }
@@ -358,10 +355,88 @@ ctc_status_t run(const Call& c, float* kernel_ms)
     return CTC_STATUS_SUCCESS;
 }
 
+// Device-metadata call: nothing about the batch is known on the host beyond its bounds, so
+// the launch shapes come from the bounds and a planning kernel fills in the rest.  Only kernel
+// launches are enqueued (no copies, no host memory, no waiting), so the call may be recorded
+// into a HIP graph.
+ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* label_lengths,
+                        const int32_t* input_lengths, int max_label, int T, int B, int A, int blank,
+                        ctc_dtype_t dtype, float* costs, void* grads, int32_t* status, void* ws,
+                        size_t ws_bytes, void* stream)
+{
+    if (!x || !label_lengths || !input_lengths || !costs || !status || !ws) return CTC_STATUS_INVALID_VALUE;
+    if (max_label > 0 && !labels) return CTC_STATUS_INVALID_VALUE;
+    if (T < 1 || B < 1 || A < 1 || blank < 0 || blank >= A) return CTC_STATUS_INVALID_VALUE;
+    Layout lay;
+    ctc_status_t st = make_layout_bounds(T, B, A, max_label, dtype, &lay);
+    if (st != CTC_STATUS_SUCCESS) return st;
+    if (reinterpret_cast<uintptr_t>(ws) % kAlign != 0) return CTC_STATUS_INVALID_VALUE;
+    const size_t elem = (dtype == CTC_DTYPE_F32) ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(x) % elem || reinterpret_cast<uintptr_t>(grads) % elem)
+        return CTC_STATUS_INVALID_VALUE;
+    if (grads) {
+        const size_t tensor_bytes = static_cast<size_t>(T) * B * A * elem;
+        const char* xa = static_cast<const char*>(x);
+        const char* ga = static_cast<const char*>(grads);
+        if (xa < ga + tensor_bytes && ga < xa + tensor_bytes) return CTC_STATUS_INVALID_VALUE;
+    }
+    if (ws_bytes < lay.total) return CTC_STATUS_WORKSPACE_TOO_SMALL;
+
+    Launch p;
+    p.mode = grads ? Mode::kGrad : Mode::kLoss;
+    p.T = T; p.B = B; p.A = A; p.blank = blank;
+    p.dtype = dtype;
+    p.n_run = B;                       // one lattice workgroup per utterance; those that do not run leave at once
+    p.max_waves = 1;
+    for (int L = 0; L <= max_label; ++L) p.max_waves = std::max(p.max_waves, plan_waves(L).waves);
+    p.max_frames = T;
+    p.max_label = max_label;
+    p.needs_barrier = plan_waves(max_label).barrier;
+    p.x = x;
+    p.grads = grads;
+    p.alignment = nullptr;
+    p.costs = costs;
+    p.ws = static_cast<char*>(ws);
+    p.labels = labels;
+    p.host_image = nullptr;
+    p.host_flag = nullptr;
+    p.host_flag_value = 0;
+    p.dev_label_lengths = label_lengths;
+    p.dev_input_lengths = input_lengths;
+    p.dev_status = status;
+    p.lay = lay;
+    int (*const stages[4])(const Launch&, void*) = {
+        launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : launch_chain_check};
+    for (auto stage : stages)
+        if (!record(stage(p, stream))) return CTC_STATUS_HIP_ERROR;
+    return CTC_STATUS_SUCCESS;
+}
+
 }  // namespace
 }  // namespace ctc
 
 extern "C" {
+
+ctc_status_t ctc_workspace_size_device(int T, int B, int A, int max_label_length, ctc_dtype_t dtype,
+                                       size_t* bytes_out)
+{
+    if (!bytes_out) return CTC_STATUS_INVALID_VALUE;
+    ctc::Layout lay;
+    ctc_status_t st = ctc::make_layout_bounds(T, B, A, max_label_length, dtype, &lay);
+    if (st == CTC_STATUS_SUCCESS) *bytes_out = lay.total;
+    return st;
+}
+
+ctc_status_t ctc_loss_and_grad_device(const void* activations, const int32_t* labels,
+                                      const int32_t* label_lengths, const int32_t* input_lengths,
+                                      int max_label_length, int T, int B, int A, int blank,
+                                      ctc_dtype_t dtype, float* costs, void* grads, int32_t* status_out,
+                                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    return ctc::run_device(activations, labels, label_lengths, input_lengths, max_label_length, T, B, A,
+                           blank, dtype, costs, grads, status_out, workspace, workspace_bytes, stream);
+}
+
 
 ctc_status_t ctc_workspace_size(int T, int B, int A, const int32_t* label_lengths,
                                 const int32_t* input_lengths, ctc_dtype_t dtype, size_t* bytes_out)

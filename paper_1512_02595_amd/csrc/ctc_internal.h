@@ -14,7 +14,8 @@ struct Utt {
     int32_t Tb;        // frames of this utterance (input_lengths[b])
     int32_t L;         // label length
     int32_t lab_off;   // offset of its label string in the flat label array
-    int32_t flags;     // bit 0: the lattice runs (Tb > 0 and an alignment exists)
+    int32_t flags;     // bit 0: the lattice runs (Tb > 0 and an alignment exists);
+                       // bit 1: lengths or labels failed the device-side checks (cost NaN)
     int32_t f_off;     // frames of all earlier utterances: offset of its blank emissions [Tb]
     int32_t waves;     // wavefronts its lattice chains use
     int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
@@ -24,15 +25,51 @@ struct Utt {
 };
 static_assert(sizeof(Utt) == 48, "Utt must stay 48 bytes");
 
+#if defined(__HIPCC__)
+#define CTC_HOST_DEVICE __host__ __device__
+#else
+#define CTC_HOST_DEVICE
+#endif
+
 // How the L+1 state pairs of a chain are spread over wavefronts.
 struct WavePlan {
     int waves;
     int halo;
     bool barrier;      // too long for a halo: 64 pairs per wavefront, one barrier per step
 };
-WavePlan plan_waves(int label_length);
+
+// Wavefronts and halo width for a label of this length.  Measured on gfx950: with one
+// wavefront per SIMD (up to 4) a step costs about 250 clocks and a hand-over about 500; with
+// several per SIMD the vector ALU is the limit (about 200 clocks per wavefront-step) and part
+// of a hand-over's latency hides behind the other wavefronts (about 350).
+// (Host and device: the launcher plans on the host, the device-metadata entry point on the GPU.)
+CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length)
+{
+    const int pairs = label_length + 1;
+    if (pairs <= 64) return {1, 0, false};
+    const int w0 = (pairs + 62) / 63;
+    if (w0 > 16) return {16, 0, true};
+    WavePlan best{w0, 0, false};
+    float best_cost = 1e30f;
+    for (int w = w0; w <= 16 && w <= w0 + 4; ++w) {
+        const int useful = (pairs + w - 1) / w;
+        // the lanes handed up must themselves be exact ones: halo <= 64 - halo
+        const int halo = (64 - useful < 32) ? 64 - useful : 32;
+        if (halo < 1) continue;
+        const int per_simd = (w + 3) / 4;
+        // the last term prefers fewer wavefronts when the estimates are close
+        const float cost = ((per_simd == 1) ? 250.0f + 500.0f / halo : per_simd * 200.0f + 350.0f / halo) + 4.0f * w;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = {w, halo, false};
+        }
+    }
+    return best;
+}
 
 constexpr int kUttRuns = 1;
+constexpr int kUttInvalid = 2;
+constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ranks in LDS
 
 // The lattice kernel reads emissions ahead of the recursion without bounds checks.  It
 // fetches kChunk steps at a time and, at the start of a pass that begins at step s0 <= Tb-1,
@@ -78,6 +115,10 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
 //          frame (most probable alignment; forward chain only)
 enum class Mode { kGrad, kLoss, kBest };
 
+// The same for the device-metadata entry point: sized for B utterances of T frames and
+// max_label symbols each.
+ctc_status_t make_layout_bounds(int T, int B, int A, int max_label, ctc_dtype_t dtype, Layout* lay);
+
 // Kernel launch parameters shared by all stages.
 struct Launch {
     Mode mode;
@@ -93,14 +134,22 @@ struct Launch {
     int32_t* alignment; // [B][T], mode == kBest only
     float* costs;
     char* ws;           // workspace base
+    const int32_t* labels;    // device: the label strings, addressed by Utt::lab_off (inside the workspace
+                              // for the host-metadata entry points, the caller's array otherwise)
     const void* host_image;   // pinned host copy of the meta/order/labels regions (device-readable)
-    int* host_flag;           // pinned host word the device sets to host_flag_value when the image is free
+    int* host_flag;           // pinned host word the device sets to host_flag_value when the image is free;
+                              // nullptr when there is no image
     int host_flag_value;
+    // device-metadata entry point only
+    const int32_t* dev_label_lengths;
+    const int32_t* dev_input_lengths;
+    int32_t* dev_status;
     Layout lay;
 };
 
 // Each returns a hipError_t as int (0 = success). `stream` is a hipStream_t.
-int launch_setup(const Launch& p, void* stream);
+int launch_setup(const Launch& p, void* stream);       // host metadata: copies the image
+int launch_plan(const Launch& p, void* stream);        // device metadata: builds meta and order on the GPU
 int launch_softmax(const Launch& p, void* stream);
 int launch_lattice(const Launch& p, void* stream);
 int launch_gradient(const Launch& p, void* stream);   // kGrad

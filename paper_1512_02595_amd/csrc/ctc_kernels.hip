@@ -158,6 +158,76 @@ void ctc_upload_kernel(const int* __restrict__ host_image, int* __restrict__ ws,
     if (i < words) ws[i] = host_image[i];
 }
 
+// ---- device-side planning -------------------------------------------------------------------
+// The device-metadata entry point has no host image: lengths and labels are device arrays that
+// the host never sees, so this kernel (one workgroup) does what the host launcher does
+// otherwise.  Per utterance: range checks, the count of adjacent repeats (an alignment exists
+// iff T_b >= L + repeats), the wavefront plan, and the offsets of its blocks, which are laid
+// out with the strides of the largest utterance the caller allows (labels [B][max_label],
+// emissions b * T * max_label, lattice b * T * (max_label + 1), frames b * T).  Then the run
+// order: heaviest chains first (rank by T_b x wavefronts, ties by index), -1 for the rest.
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads)
+void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ label_lengths,
+                     const int* __restrict__ input_lengths, Utt* __restrict__ meta,
+                     int* __restrict__ order, int* __restrict__ status,
+                     int Tt, int B, int A, int blank, int max_label)
+{
+    __shared__ long long weight[kMaxDeviceMetaB];     // T_b x wavefronts; -1: does not run
+    __shared__ int s_bad;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_bad = 0;
+    for (int i = tid; i < B; i += kPlanThreads) order[i] = -1;
+    __syncthreads();
+    for (int b = wave; b < B; b += kPlanThreads / 64) {
+        const int L = label_lengths[b], Tb = input_lengths[b];
+        bool bad = L < 0 || L > max_label || Tb < 0 || Tb > Tt;
+        const int* lab = labels + static_cast<size_t>(b) * max_label;
+        int repeats = 0;
+        if (!bad) {
+            for (int j = lane; j < L; j += 64) {
+                const int c = lab[j];
+                bad = bad || c < 0 || c >= A || c == blank;
+                if (j > 0 && c == lab[j - 1]) ++repeats;
+            }
+        }
+        bad = __any(bad);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) repeats += __shfl_xor(repeats, o, 64);
+        const bool runs = !bad && Tb > 0 && Tb >= L + repeats;
+        const WavePlan wp = plan_waves(bad ? 0 : L);
+        if (lane == 0) {
+            Utt m;
+            m.Tb = bad ? 0 : Tb;
+            m.L = bad ? 0 : L;
+            m.lab_off = b * max_label;
+            m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0);
+            m.f_off = b * Tt;
+            m.waves = wp.waves;
+            m.halo = wp.halo;
+            m.reserved = 0;
+            m.e_off = static_cast<int64_t>(b) * Tt * max_label;
+            m.ab_off = static_cast<int64_t>(b) * Tt * (max_label + 1);
+            meta[b] = m;
+            weight[b] = runs ? static_cast<long long>(Tb) * wp.waves : -1;
+            if (bad) s_bad = 1;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) *status = s_bad ? CTC_STATUS_INVALID_VALUE : CTC_STATUS_SUCCESS;
+    for (int i = tid; i < B; i += kPlanThreads) {
+        const long long wi = weight[i];
+        if (wi < 0) continue;
+        int rank = 0;
+        for (int j = 0; j < B; ++j) {
+            const long long wj = weight[j];
+            rank += (wj > wi) || (wj == wi && j < i);
+        }
+        order[rank] = i;
+    }
+}
+
 // ---- setup role ----------------------------------------------------------------------------
 // Runs in one extra grid column of the softmax launch, one workgroup per utterance, beside
 // the row work.  It groups the label positions by symbol, once per utterance, for every frame
@@ -209,10 +279,12 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
             sa.log0[0] = static_cast<float>(kNeg);
             // This launch follows the upload kernel on the stream, so the host may now reuse
             // the pinned image.
-            __hip_atomic_store(sa.host_flag, sa.flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (sa.host_flag)
+                __hip_atomic_store(sa.host_flag, sa.flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         // No frames: the empty product (cost 0) for an empty label.  Otherwise no alignment.
-        if (!(m.flags & kUttRuns)) sa.costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
+        if (m.flags & kUttInvalid) sa.costs[b] = __uint_as_float(0x7FC00000u);
+        else if (!(m.flags & kUttRuns)) sa.costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
     }
 }
 
@@ -722,6 +794,7 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
                                              void* lds)
 {
     const int u = order[blockIdx.x];
+    if (u < 0) return;                  // device-planned batches launch one workgroup per utterance, running or not
     const Utt m = meta[u];
     const bool idle = static_cast<int>(threadIdx.x >> 6) >= m.waves;
     if (kSync == Sync::kHalo) {
@@ -1081,10 +1154,20 @@ int launch_setup(const Launch& p, void* stream)
     });
 }
 
+int launch_plan(const Launch& p, void* stream)
+{
+    return checked_launch([&] {
+        hipLaunchKernelGGL(ctc_plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(stream),
+                           p.labels, p.dev_label_lengths, p.dev_input_lengths,
+                           reinterpret_cast<Utt*>(p.ws + p.lay.meta), reinterpret_cast<int*>(p.ws + p.lay.order),
+                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label);
+    });
+}
+
 int launch_softmax(const Launch& p, void* stream)
 {
     auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
-    auto* labels = reinterpret_cast<const int*>(p.ws + p.lay.labels);
+    const int* labels = p.labels;
     auto* lse = reinterpret_cast<float*>(p.ws + p.lay.lse);
     auto* emit_blank = reinterpret_cast<float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
@@ -1146,7 +1229,7 @@ int launch_lattice(const Launch& p, void* stream)
     if (p.n_run == 0) return 0;
     auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
     auto* order = reinterpret_cast<const int*>(p.ws + p.lay.order);
-    auto* labels = reinterpret_cast<const int*>(p.ws + p.lay.labels);
+    const int* labels = p.labels;
     auto* emit_blank = reinterpret_cast<const float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<const float*>(p.ws + p.lay.emit_label);
     auto* sink = reinterpret_cast<double*>(p.ws + p.lay.sink);
@@ -1208,7 +1291,7 @@ int launch_backtrace(const Launch& p, void* stream)
 int launch_gradient(const Launch& p, void* stream)
 {
     auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
-    auto* labels = reinterpret_cast<const int*>(p.ws + p.lay.labels);
+    const int* labels = p.labels;
     auto* links = reinterpret_cast<const int*>(p.ws + p.lay.links);
     auto* lse = reinterpret_cast<const float*>(p.ws + p.lay.lse);
     auto* alpha = reinterpret_cast<const double*>(p.ws + p.lay.alpha);

@@ -30,6 +30,7 @@ KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
 
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
+           "ctc_workspace_size_device", "ctc_loss_and_grad_device",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error")
 
 _lib = None
@@ -63,6 +64,11 @@ def load() -> ctypes.CDLL:
     lib.ctc_best_path.argtypes = common
     lib.ctc_profile_best_path.restype = st
     lib.ctc_profile_best_path.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
+    lib.ctc_workspace_size_device.restype = st
+    lib.ctc_workspace_size_device.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ctypes.c_size_t)]
+    lib.ctc_loss_and_grad_device.restype = st
+    lib.ctc_loss_and_grad_device.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp,
+                                             ctypes.c_size_t, vp]
     lib.ctc_kernel_name.restype = ctypes.c_char_p
     lib.ctc_kernel_name.argtypes = [ci]
     lib.ctc_status_string.restype = ctypes.c_char_p
@@ -164,3 +170,35 @@ def best_path(activations_ptr, flat_labels, label_lengths, input_lengths, T, B, 
     if st != STATUS_SUCCESS:
         extra = f" (hipError {last_hip_error()})" if st == STATUS_HIP_ERROR else ""
         raise CTCError(st, "ctc_best_path" + extra)
+
+
+def workspace_size_device_status(T, B, A, max_label_length, dtype=DTYPE_F32):
+    out = ctypes.c_size_t(0)
+    st = load().ctc_workspace_size_device(int(T), int(B), int(A), int(max_label_length), int(dtype),
+                                          ctypes.byref(out))
+    return int(st), int(out.value)
+
+
+def workspace_size_device(T, B, A, max_label_length, dtype=DTYPE_F32) -> int:
+    st, n = workspace_size_device_status(T, B, A, max_label_length, dtype)
+    if st != STATUS_SUCCESS:
+        raise CTCError(st, "ctc_workspace_size_device")
+    return n
+
+
+def loss_and_grad_device_status(activations_ptr, labels_ptr, label_lengths_ptr, input_lengths_ptr,
+                                max_label_length, T, B, A, blank, dtype, costs_ptr, grads_ptr,
+                                status_ptr, workspace_ptr, workspace_bytes, stream=0) -> int:
+    """Raw ctc_loss_and_grad_device: every array argument is a device address."""
+    return int(load().ctc_loss_and_grad_device(
+        ctypes.c_void_p(activations_ptr), ctypes.c_void_p(labels_ptr), ctypes.c_void_p(label_lengths_ptr),
+        ctypes.c_void_p(input_lengths_ptr), int(max_label_length), int(T), int(B), int(A), int(blank),
+        int(dtype), ctypes.c_void_p(costs_ptr), ctypes.c_void_p(grads_ptr), ctypes.c_void_p(status_ptr),
+        ctypes.c_void_p(workspace_ptr), ctypes.c_size_t(workspace_bytes), ctypes.c_void_p(stream)))
+
+
+def loss_and_grad_device(*args, **kw) -> None:
+    st = loss_and_grad_device_status(*args, **kw)
+    if st != STATUS_SUCCESS:
+        extra = f" (hipError {last_hip_error()})" if st == STATUS_HIP_ERROR else ""
+        raise CTCError(st, "ctc_loss_and_grad_device" + extra)

@@ -91,3 +91,66 @@ def run_batch(batch: workloads.CTCBatch, dtype: int = ctc.DTYPE_F32):
     db = DeviceBatch(batch, dtype)
     db.run()
     return db.results()
+
+
+class DeviceMetaBatch:
+    """Buffers for ctc_loss_and_grad_device: lengths and padded labels live on the GPU.
+
+    Sized by bounds (T, B, A, max_label); `load` writes one CTCBatch of that shape into the
+    same device buffers, so a recorded graph can be replayed on new contents.
+    """
+
+    def __init__(self, T, B, A, max_label, blank=0, dtype: int = ctc.DTYPE_F32, device=None):
+        self.device = device or require_gpu()
+        self.T, self.B, self.A, self.max_label, self.blank, self.dtype = T, B, A, max_label, blank, dtype
+        tdtype = torch.float32 if dtype == ctc.DTYPE_F32 else torch.bfloat16
+        self.x = torch.zeros((T, B, A), dtype=tdtype, device=self.device)
+        self.grads = torch.empty_like(self.x)
+        self.costs = torch.empty(B, dtype=torch.float32, device=self.device)
+        self.labels = torch.zeros((B, max(max_label, 1)), dtype=torch.int32, device=self.device)
+        self.label_lengths = torch.zeros(B, dtype=torch.int32, device=self.device)
+        self.input_lengths = torch.zeros(B, dtype=torch.int32, device=self.device)
+        self.status = torch.full((1,), -1, dtype=torch.int32, device=self.device)
+        self.ws_bytes = ctc.workspace_size_device(T, B, A, max_label, dtype)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
+
+    def load(self, batch: workloads.CTCBatch, raw_labels=None):
+        """Copies a batch into the device buffers (in place).  `raw_labels` [B, max_label] overrides
+        the padded label matrix (to plant invalid entries)."""
+        assert (batch.T, batch.B, batch.A) == (self.T, self.B, self.A)
+        if self.dtype == ctc.DTYPE_F32:
+            self.x.copy_(torch.from_numpy(np.ascontiguousarray(batch.logits, dtype=np.float32)))
+        else:
+            bits = workloads.bf16_bits(batch.logits).view(np.int16)
+            self.x.copy_(torch.from_numpy(bits).view(torch.bfloat16))
+        pad = np.zeros((self.B, max(self.max_label, 1)), dtype=np.int32)
+        off = 0
+        for b in range(self.B):
+            L = int(batch.label_lengths[b])
+            pad[b, :min(L, self.max_label)] = batch.flat_labels[off:off + L][:self.max_label]
+            off += L
+        if raw_labels is not None:
+            pad = np.ascontiguousarray(raw_labels, dtype=np.int32)
+        self.labels.copy_(torch.from_numpy(pad))
+        self.label_lengths.copy_(torch.from_numpy(np.ascontiguousarray(batch.label_lengths, dtype=np.int32)))
+        self.input_lengths.copy_(torch.from_numpy(np.ascontiguousarray(batch.input_lengths, dtype=np.int32)))
+
+    def poison(self):
+        self.ws.fill_(0xFF)
+        self.grads.view(torch.uint8).fill_(0xFF)
+        self.costs.fill_(float("nan"))
+        self.status.fill_(-1)
+
+    def run(self, stream=None, want_grad=True):
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        ctc.loss_and_grad_device(self.x.data_ptr(), self.labels.data_ptr(), self.label_lengths.data_ptr(),
+                                 self.input_lengths.data_ptr(), self.max_label, self.T, self.B, self.A,
+                                 self.blank, self.dtype, self.costs.data_ptr(),
+                                 self.grads.data_ptr() if want_grad else None, self.status.data_ptr(),
+                                 self.ws_ptr, self.ws_bytes, s)
+
+    def results(self):
+        """(status int, costs float32 [B], grads float32 [T,B,A]) on the host, after synchronising."""
+        torch.cuda.synchronize(self.device)
+        return int(self.status.item()), self.costs.cpu().numpy(), self.grads.float().cpu().numpy()

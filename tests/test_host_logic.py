@@ -171,3 +171,31 @@ def test_bf16_rounding_helpers():
     assert np.array_equal(wl.bf16_bits_to_f32(wl.bf16_bits(x)), r)
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.015625      # ties to even, then up
     assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
+
+
+def test_device_metadata_call_validates_on_the_host_what_the_host_can_see(lib):
+    T, B, A, Lmax = 10, 2, 5, 3
+    st, n = ctc.workspace_size_device_status(T, B, A, Lmax)
+    assert st == ctc.STATUS_SUCCESS
+    exact = ctc.workspace_size(T, B, A, [Lmax] * B, [T] * B)
+    assert n == exact                                   # the bound layout is the exact one of a full-size batch
+    assert ctc.workspace_size_device_status(T, B, A, ctc.MAX_LABEL_LENGTH + 1)[0] == ctc.STATUS_UNSUPPORTED
+    assert ctc.workspace_size_device_status(T, 4097, A, Lmax)[0] == ctc.STATUS_UNSUPPORTED
+    assert ctc.workspace_size_device_status(T, B, 0, Lmax)[0] == ctc.STATUS_INVALID_VALUE
+    assert ctc.workspace_size_device_status(T, B, A, -1)[0] == ctc.STATUS_INVALID_VALUE
+    x, lab, ll, il, c, g, stw, ws = (0x10000 * (i + 1) for i in range(8))     # fake aligned addresses
+    args = [x, lab, ll, il, Lmax, T, B, A, 0, ctc.DTYPE_F32, c, g, stw, ws, n]
+
+    def call(i, v):
+        a = list(args)
+        a[i] = v
+        return ctc.loss_and_grad_device_status(*a)
+
+    for i in (0, 2, 3, 10, 12, 13):                     # activations, lengths, costs, status word, workspace
+        assert call(i, None) == ctc.STATUS_INVALID_VALUE
+    assert call(1, None) == ctc.STATUS_INVALID_VALUE    # labels missing although max_label_length > 0
+    assert call(8, A) == ctc.STATUS_INVALID_VALUE
+    assert call(9, 7) == ctc.STATUS_INVALID_VALUE
+    assert call(14, n - 1) == ctc.STATUS_WORKSPACE_TOO_SMALL
+    assert call(13, ws + 8) == ctc.STATUS_INVALID_VALUE
+    assert call(11, x + 16) == ctc.STATUS_INVALID_VALUE
