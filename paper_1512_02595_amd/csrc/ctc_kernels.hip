@@ -571,8 +571,8 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     const bool active = lane >= halo && j <= L;          // this lane stores pair j
     const int li = kBackward ? (L - 1 - j) : j;          // label index of this pair's label state
     // May the label state be entered from pair j-1's label?  (Not across equal symbols.)
-    double skip_penalty = kNeg;
-    if (has_label && j >= 1 && lab[li] != lab[kBackward ? (li + 1) : (li - 1)]) skip_penalty = 0.0;
+    const bool skip_ok = has_label && j >= 1 && lab[li] != lab[kBackward ? (li + 1) : (li - 1)];
+    const double skip_penalty = skip_ok ? 0.0 : kNeg;
 
     // Frame of step s: s going forward, Tb-1-s going backward.
     const int f0 = kBackward ? (Tb - 1) : 0;
@@ -716,8 +716,12 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             i_label = best;
             choice |= blank_moves ? kBlankFromPrevLabel : 0;
         } else {
+            // The blank state sums its own value and the label of the pair before; where the
+            // label state may also be entered from that label (skip), its three-term sum is
+            // its own value plus exactly the blank state's new sum, else plus the old blank:
+            // two two-term sums per pair instead of a two- and a three-term one.
             i_blank = lse2(v_blank, prev);
-            i_label = lse3(v_label, v_blank, prev + skip_penalty);
+            i_label = lse2(v_label, skip_ok ? i_blank : v_blank);
         }
         finish_step(eb, el);
     };
