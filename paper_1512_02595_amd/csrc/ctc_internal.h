@@ -39,26 +39,28 @@ struct WavePlan {
 };
 
 // Wavefronts and halo width for a label of this length.  Measured on gfx950: with one
-// wavefront per SIMD (up to 4) a step costs about 250 clocks and a hand-over about 500; with
-// several per SIMD the vector ALU is the limit (about 200 clocks per wavefront-step) and part
+// wavefront per SIMD (up to 4) a step costs about 210 clocks and a hand-over about 500; with
+// several per SIMD the vector ALU is the limit (about 170 clocks per wavefront-step) and part
 // of a hand-over's latency hides behind the other wavefronts (about 350).
 // (Host and device: the launcher plans on the host, the device-metadata entry point on the GPU.)
 CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length)
 {
     const int pairs = label_length + 1;
     if (pairs <= 64) return {1, 0, false};
-    const int w0 = (pairs + 62) / 63;
-    if (w0 > 16) return {16, 0, true};
-    WavePlan best{w0, 0, false};
+    // Hand-overs happen on chunk boundaries: the halo is a multiple of kChunk (8 .. 32), and
+    // the lanes handed up must themselves be exact ones (halo <= 64 - halo).
+    WavePlan best{16, 0, true};
     float best_cost = 1e30f;
+    const int w0 = (pairs - 8 + 55) / 56;       // fewest wavefronts with a halo of 8: w * 56 + 8 >= pairs
     for (int w = w0; w <= 16 && w <= w0 + 4; ++w) {
-        const int useful = (pairs + w - 1) / w;
-        // the lanes handed up must themselves be exact ones: halo <= 64 - halo
-        const int halo = (64 - useful < 32) ? 64 - useful : 32;
-        if (halo < 1) continue;
+        // w * (64 - halo) + halo >= pairs
+        int halo = (64 * w - pairs) / (w - 1);
+        if (halo > 32) halo = 32;
+        halo -= halo % 8;
+        if (halo < 8) continue;
         const int per_simd = (w + 3) / 4;
         // the last term prefers fewer wavefronts when the estimates are close
-        const float cost = ((per_simd == 1) ? 250.0f + 500.0f / halo : per_simd * 200.0f + 350.0f / halo) + 4.0f * w;
+        const float cost = ((per_simd == 1) ? 210.0f + 500.0f / halo : per_simd * 170.0f + 350.0f / halo) + 4.0f * w;
         if (cost < best_cost) {
             best_cost = cost;
             best = {w, halo, false};
@@ -76,7 +78,7 @@ constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ra
 // has requested steps up to s0 + 3*kChunk - 1: at most 3*kChunk - 1 rows past either end of
 // an utterance's block (past the end going forward, before the start going backward).  These
 // margins keep such reads inside the workspace; the values read there are never used.
-constexpr int kChunk = 8;             // steps whose emissions are fetched together
+constexpr int kChunk = 8;             // steps whose emissions are fetched together (plan_waves: halo % 8 == 0)
 constexpr int kOverFetchRows = 3 * kChunk;
 constexpr int kBlankSlack = kOverFetchRows + kChunk;                          // floats, each side
 constexpr int kLabelSlack = kOverFetchRows * (CTC_MAX_LABEL_LENGTH + 1);      // floats, each side

@@ -545,9 +545,11 @@ struct HaloLds {
 // Labels of more than 63 symbols span several wavefronts.  Exchanging a value at every step
 // costs more than a third of the step, so with Sync::kHalo each wavefront recomputes, in its
 // first `halo` lanes, the last `halo` pairs of the wavefront below it:
-//     pair of (wave, lane) = wave * (64 - halo) + lane - halo.
+//     pair of (wave, lane) = wave * (64 - halo) + lane
+// (wavefront 0 has nothing below it: all its 64 lanes are exact, its lane 0 is pair 0).
 // An error at lane 0 (whose neighbour is missing) moves up one lane per step, so the lanes
-// from `halo` on stay exact for `halo` steps.  Every `halo` steps the lower wavefront hands
+// from `halo` on stay exact for `halo` steps.  Every `halo` steps (a whole number of chunks)
+// the lower wavefront hands
 // over the exact state of those pairs through LDS (a small ring per boundary, guarded by two
 // counters: `ready` written by the producer after the data, `done` by the consumer after its
 // read).  No barrier; the wavefronts run skewed.  A wavefront waits for data only on lower
@@ -565,10 +567,10 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     const int L = m.L, Tb = m.Tb, P = L + 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
-    const int j = wave * (64 - halo) + lane - halo;      // may be negative in wavefront 0: no such pair
+    const int j = wave * (64 - halo) + lane;
     const int* lab = labels + m.lab_off;
     const bool has_label = j >= 0 && j < L;
-    const bool active = lane >= halo && j <= L;          // this lane stores pair j
+    const bool active = (wave == 0 || lane >= halo) && j <= L;   // this lane stores pair j
     const int li = kBackward ? (L - 1 - j) : j;          // label index of this pair's label state
     // May the label state be entered from pair j-1's label?  (Not across equal symbols.)
     const bool skip_ok = has_label && j >= 1 && lab[li] != lab[kBackward ? (li + 1) : (li - 1)];
@@ -600,7 +602,10 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
     int budget = kSpinBudget;
-    int until_refresh = halo;                            // steps until the next hand-over
+    // Hand-overs fall on chunk boundaries (the halo is a multiple of kChunk), so the step
+    // itself carries no countdown and the hand-over code exists once per chunk, not per step.
+    const int chunks_per_hand_over = halo / kChunk;
+    int until_hand_over = chunks_per_hand_over;          // chunks until the next hand-over
     int generation = 0;
     // Each boundary's buffer is used as two halves of 32 entries, alternating by generation
     // (halo <= 32), so a producer may run one hand-over ahead of its consumer.
@@ -696,10 +701,14 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             *reinterpret_cast<double*>(op) = kBackward ? i_label : v_label;
         }
         op += ostride;
+    };
+    // After the last step of a chunk (the last chunk of a chain may be short: its hand-over
+    // then comes early, which every wavefront of the chain does alike).
+    auto end_chunk = [&]() {
         if (kSync == Sync::kHalo) {
-            if (--until_refresh == 0) {
+            if (--until_hand_over == 0) {
                 hand_over();
-                until_refresh = halo;
+                until_hand_over = chunks_per_hand_over;
             }
         }
     };
@@ -761,14 +770,19 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
         fetch(el_b, eb_b, s0 + kChunk);
         run(el_a, eb_a, s0);
+        end_chunk();
         fetch(el_a, eb_a, s0 + 2 * kChunk);
-        if (s0 + kChunk < Tb) run(el_b, eb_b, s0 + kChunk);
+        if (s0 + kChunk < Tb) {
+            run(el_b, eb_b, s0 + kChunk);
+            end_chunk();
+        }
     }
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L-1.
-        // Pair L sits in a lane >= halo, so the lane below it is exact (a hand-over that fell
-        // due after the last step has already been done by finish_step).
+        // Pair L sits in an exact lane, and so does the lane below it or, if that is the last
+        // halo lane, it is still exact: the error from lane 0 needs `halo` steps to get there,
+        // and a hand-over that fell due after the last step has been done by end_chunk.
         const double prev = from_prev_pair(v_label, Tb - 1);
         if (active && j == L) {
             if (kMode == Mode::kBest) {
