@@ -761,10 +761,17 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     };
     // One copy of the step per chunk position and register set: the kernel has to stay well
     // inside the instruction cache that two compute units share.
+    // Whole chunks run without looking at the step number; only the last, short chunk of a
+    // chain checks every step against the end.
     auto run = [&](const float (&el)[kChunk], const float eb, int s0) {
+        if (s0 + kChunk <= Tb) {
 #pragma unroll
-        for (int i = 0; i < kChunk; ++i)
-            if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
+            for (int i = 0; i < kChunk; ++i) advance(s0 + i, readlane(eb, i), el[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i)
+                if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
+        }
     };
     fetch(el_a, eb_a, 1);
     for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
