@@ -42,7 +42,8 @@ MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 19.0e6, "ctc_lattice": 79.8e6, "
 
 
 def kernel_bytes(batch, elem, mode="grad"):
-    """Algorithmic HBM bytes of each kernel for one launch on `batch`."""
+    """Algorithmic HBM bytes of each kernel for one launch on `batch`: what the kernel must read and
+    write once, per frame, per row of the tensor and per lattice cell, as the comments below state."""
     frames = batch.frames
     A = batch.A
     pairs = int((batch.input_lengths.astype(np.int64) * (batch.label_lengths.astype(np.int64) + 1)).sum())

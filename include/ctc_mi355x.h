@@ -123,8 +123,8 @@ ctc_status_t ctc_loss_and_grad(const void *activations,
  * this call in milliseconds.  For measurement (the per-kernel timings that the
  * paper's Table "gpucpuctc" aggregates per epoch), not for the training loop.
  *
- *   kernel_ms     (host) [CTC_NUM_KERNELS]; with grads == NULL the third entry is the
- *                 short check launch that follows the forward recursion (0 if not needed)
+ *   kernel_ms     (host) [CTC_NUM_KERNELS]; with grads == NULL there is no third launch and
+ *                 the third entry is (close to) zero
  */
 ctc_status_t ctc_profile_kernels(const void *activations,
                                  const int32_t *flat_labels,

@@ -339,11 +339,12 @@ ctc_status_t run(const Call& c, float* kernel_ms)
     }
     // The upload launch has gone out above (its own time is not reported separately: it is a few
     // microseconds and overlaps the tail of whatever ran before on the stream).
+    // Cost-only calls end with the lattice launch.
     int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {
         launch_softmax, launch_lattice,
-        c.mode == Mode::kGrad ? launch_gradient : (c.mode == Mode::kLoss ? launch_chain_check : launch_backtrace)};
+        c.mode == Mode::kGrad ? launch_gradient : (c.mode == Mode::kLoss ? nullptr : launch_backtrace)};
     for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
-        if (!record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
+        if (stages[i] && !record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
         if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
     }
     if (kernel_ms) {
@@ -406,9 +407,9 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.dev_status = status;
     p.lay = lay;
     int (*const stages[4])(const Launch&, void*) = {
-        launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : launch_chain_check};
+        launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : nullptr};
     for (auto stage : stages)
-        if (!record(stage(p, stream))) return CTC_STATUS_HIP_ERROR;
+        if (stage && !record(stage(p, stream))) return CTC_STATUS_HIP_ERROR;
     return CTC_STATUS_SUCCESS;
 }
 

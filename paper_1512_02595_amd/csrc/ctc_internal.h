@@ -155,7 +155,6 @@ int launch_plan(const Launch& p, void* stream);        // device metadata: build
 int launch_softmax(const Launch& p, void* stream);
 int launch_lattice(const Launch& p, void* stream);
 int launch_gradient(const Launch& p, void* stream);   // kGrad
-int launch_chain_check(const Launch& p, void* stream); // kLoss
 int launch_backtrace(const Launch& p, void* stream);   // kBest
 
 }  // namespace ctc

@@ -520,6 +520,10 @@ struct HaloLds {
     double2 data[16][kHaloEntries];
     int ready[16];                    // last generation wavefront w has published
     int done[16];                     // last generation wavefront w has taken from w-1
+    // Cost-only chains: the last wavefront to finish writes the cost (or NaN if any gave up).
+    int finished;                     // wavefronts that have reached the end of the chain
+    int gave_up;
+    float cost;
 };
 
 // One chain = one direction of one utterance.  A lane owns the pair
@@ -801,11 +805,31 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             } else {
                 const double lp = lse2(v_blank, prev);
                 logp[u] = lp;
-                costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
+                const float cost = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
+                if (kSync == Sync::kHalo && kMode == Mode::kLoss) hl->cost = cost;
+                else costs[u] = cost;
             }
         }
     }
-    if (kSync == Sync::kHalo && budget <= 0 && lane == 0) chain_err[u] = 1;
+    if (kSync == Sync::kHalo && kMode == Mode::kLoss) {
+        // No kernel follows that could turn a lost exchange into a NaN cost, so the cost is
+        // written by whichever wavefront finishes last, once it has seen whether any gave up.
+        // (One wavefront's LDS operations complete in order: flag and cost precede its count.)
+        if (budget <= 0 && lane == 0) hl->gave_up = 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        int before = 0;
+        if (lane == 0)
+            before = __hip_atomic_fetch_add(&hl->finished, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        before = __builtin_amdgcn_readfirstlane(before);
+        if (before == m.waves - 1 && lane == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int lost = __hip_atomic_load(&hl->gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const float cost = hl->cost;
+            costs[u] = lost ? __uint_as_float(0x7FC00000u) : cost;
+        }
+    } else if (kSync == Sync::kHalo && budget <= 0 && lane == 0) {
+        chain_err[u] = 1;
+    }
 }
 
 template <Sync kSync, bool kStream, Mode kMode>
@@ -827,6 +851,10 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         if (threadIdx.x < 16) {
             hl->ready[threadIdx.x] = 0;
             hl->done[threadIdx.x] = 0;
+        }
+        if (threadIdx.x == 0) {
+            hl->finished = 0;
+            hl->gave_up = 0;
         }
         __syncthreads();
         if (idle) return;
@@ -895,15 +923,6 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
 }
 
 // ---- after a forward-only chain -------------------------------------------------------------
-// Cost-only calls: a chain whose wavefronts lost touch (chain_err) reports NaN, as the
-// gradient kernel does for the full call.  One thread per utterance.
-__global__ __launch_bounds__(kRowThreads)
-void ctc_chain_check_kernel(const int* __restrict__ chain_err, float* __restrict__ costs, int B)
-{
-    const int b = blockIdx.x * kRowThreads + threadIdx.x;
-    if (b < B && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
-}
-
 // Most probable alignment: walk the stored predecessor choices back from the better end state.
 // One wavefront per utterance; alignment is [B][T] (utterance-major): the lattice state of each
 // frame (index into the blank-interleaved label), -1 for frames past the utterance's end and
@@ -1288,17 +1307,6 @@ int launch_lattice(const Launch& p, void* stream)
         }
     });
 #undef CTC_LAUNCH_LATTICE
-}
-
-int launch_chain_check(const Launch& p, void* stream)
-{
-    // Only chains spread over several wavefronts can lose touch.
-    if (p.n_run == 0 || p.max_waves == 1) return 0;
-    auto* chain_err = reinterpret_cast<const int*>(p.ws + p.lay.chain_err);
-    return checked_launch([&] {
-        hipLaunchKernelGGL(ctc_chain_check_kernel, dim3((p.B + kRowThreads - 1) / kRowThreads), dim3(kRowThreads),
-                           0, static_cast<hipStream_t>(stream), chain_err, p.costs, p.B);
-    });
 }
 
 int launch_backtrace(const Launch& p, void* stream)
