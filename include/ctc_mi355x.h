@@ -243,6 +243,16 @@ const char *ctc_status_string(ctc_status_t status);
 /* Raw hipError_t value of the most recent HIP failure seen by the calling thread (0 if none). */
 int ctc_last_hip_error(void);
 
+/*
+ * Diagnostics.  The wavefronts that share a long label's recursion wait for each other by
+ * polling a counter in LDS, at most `polls` times per wavefront and call (default 2^22, which
+ * only a stuck neighbour exhausts); a wavefront that runs out carries on with what it has and
+ * the utterance's cost is reported as NaN.  Setting the budget to 0 makes every such wait give
+ * up at once, which lets a test see that error path with every kernel still running to its
+ * end.  Negative values restore the default.  Applies to calls made afterwards, process-wide.
+ */
+void ctc_debug_set_poll_budget(int polls);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <thread>
@@ -19,6 +20,7 @@ namespace ctc {
 namespace {
 
 thread_local int g_last_hip_error = 0;
+std::atomic<int> g_poll_budget{kDefaultPollBudget};
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -235,7 +237,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         const WavePlan wp = plan_waves(L);
         m.waves = wp.waves;
         m.halo = wp.halo;
-        m.reserved = 0;
+        m.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
         m.e_off = e_off;
         m.ab_off = ab_off;
         lab_off += L;
@@ -277,6 +279,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->dev_label_lengths = nullptr;
     out->dev_input_lengths = nullptr;
     out->dev_status = nullptr;
+    out->poll_budget = g_poll_budget.load(std::memory_order_relaxed);
     out->lay = lay;
     return CTC_STATUS_SUCCESS;
 }
@@ -405,6 +408,7 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.dev_label_lengths = label_lengths;
     p.dev_input_lengths = input_lengths;
     p.dev_status = status;
+    p.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
     p.lay = lay;
     int (*const stages[4])(const Launch&, void*) = {
         launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : nullptr};
@@ -517,5 +521,10 @@ const char* ctc_status_string(ctc_status_t status)
 }
 
 int ctc_last_hip_error(void) { return ctc::g_last_hip_error; }
+
+void ctc_debug_set_poll_budget(int polls)
+{
+    ctc::g_poll_budget.store(polls < 0 ? ctc::kDefaultPollBudget : polls, std::memory_order_relaxed);
+}
 
 }  // extern "C"

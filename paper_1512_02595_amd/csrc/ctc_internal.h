@@ -19,7 +19,7 @@ struct Utt {
     int32_t f_off;     // frames of all earlier utterances: offset of its blank emissions [Tb]
     int32_t waves;     // wavefronts its lattice chains use
     int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
-    int32_t reserved;
+    int32_t poll_budget; // LDS polls a wavefront of its chains may spend waiting on a neighbour before it gives up
     int64_t e_off;     // offset (floats) of its label emissions [Tb][L]
     int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][L+1]
 };
@@ -71,6 +71,7 @@ CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length)
 
 constexpr int kUttRuns = 1;
 constexpr int kUttInvalid = 2;
+constexpr int kDefaultPollBudget = 1 << 22;   // enough for seconds of waiting: only a stuck neighbour exhausts it
 constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ranks in LDS
 
 // The lattice kernel reads emissions ahead of the recursion without bounds checks.  It
@@ -146,6 +147,7 @@ struct Launch {
     const int32_t* dev_label_lengths;
     const int32_t* dev_input_lengths;
     int32_t* dev_status;
+    int poll_budget;          // copied into every Utt record
     Layout lay;
 };
 

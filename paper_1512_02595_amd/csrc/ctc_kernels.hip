@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kPlanThreads)
 void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ label_lengths,
                      const int* __restrict__ input_lengths, Utt* __restrict__ meta,
                      int* __restrict__ order, int* __restrict__ status,
-                     int Tt, int B, int A, int blank, int max_label)
+                     int Tt, int B, int A, int blank, int max_label, int poll_budget)
 {
     __shared__ long long weight[kMaxDeviceMetaB];     // T_b x wavefronts; -1: does not run
     __shared__ int s_bad;
@@ -206,7 +206,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
             m.f_off = b * Tt;
             m.waves = wp.waves;
             m.halo = wp.halo;
-            m.reserved = 0;
+            m.poll_budget = poll_budget;
             m.e_off = static_cast<int64_t>(b) * Tt * max_label;
             m.ab_off = static_cast<int64_t>(b) * Tt * (max_label + 1);
             meta[b] = m;
@@ -504,7 +504,6 @@ __device__ __forceinline__ double shift_up(double v, double lane0)
     return __hiloint2double(hi, lo);
 }
 
-constexpr int kSpinBudget = 1 << 22;  // polls a wavefront may spend waiting before it gives up
 constexpr int kHaloEntries = 64;      // 16-byte entries of one wavefront boundary's exchange buffer (2 x 32)
 
 enum class Sync { kNone, kHalo, kBarrier };
@@ -605,7 +604,8 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
-    int budget = kSpinBudget;
+    int budget = m.poll_budget;                          // polls left before this wavefront gives up waiting
+    bool lost = false;                                   // it did give up: what it computed since is not to be trusted
     // Hand-overs fall on chunk boundaries (the halo is a multiple of kChunk), so the step
     // itself carries no countdown and the hand-over code exists once per chunk, not per step.
     const int chunks_per_hand_over = halo / kChunk;
@@ -646,6 +646,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
                     --budget;
                     seen = uniform(counter(up_done));
                 }
+                lost = lost || seen < generation - 2;
             }
             if (lane >= 64 - halo) wr_base[half] = make_double2(v_blank, v_label);
             // LDS operations of a wavefront complete in order: the counter follows the data.
@@ -668,6 +669,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
                     v = rd_base[half];
                     ready = uniform(ready);
                 }
+                lost = lost || ready < generation;
             }
             if (lane < halo) {
                 v_blank = v.x;
@@ -815,7 +817,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
         // No kernel follows that could turn a lost exchange into a NaN cost, so the cost is
         // written by whichever wavefront finishes last, once it has seen whether any gave up.
         // (One wavefront's LDS operations complete in order: flag and cost precede its count.)
-        if (budget <= 0 && lane == 0) hl->gave_up = 1;
+        if (lost && lane == 0) hl->gave_up = 1;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         int before = 0;
         if (lane == 0)
@@ -827,7 +829,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             const float cost = hl->cost;
             costs[u] = lost ? __uint_as_float(0x7FC00000u) : cost;
         }
-    } else if (kSync == Sync::kHalo && budget <= 0 && lane == 0) {
+    } else if (kSync == Sync::kHalo && lost && lane == 0) {
         chain_err[u] = 1;
     }
 }
@@ -1204,7 +1206,7 @@ int launch_plan(const Launch& p, void* stream)
         hipLaunchKernelGGL(ctc_plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(stream),
                            p.labels, p.dev_label_lengths, p.dev_input_lengths,
                            reinterpret_cast<Utt*>(p.ws + p.lay.meta), reinterpret_cast<int*>(p.ws + p.lay.order),
-                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label);
+                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label, p.poll_budget);
     });
 }
 

@@ -31,7 +31,7 @@ KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
            "ctc_workspace_size_device", "ctc_loss_and_grad_device",
-           "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error")
+           "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget")
 
 _lib = None
 
@@ -75,6 +75,8 @@ def load() -> ctypes.CDLL:
     lib.ctc_status_string.argtypes = [st]
     lib.ctc_last_hip_error.restype = ci
     lib.ctc_last_hip_error.argtypes = []
+    lib.ctc_debug_set_poll_budget.restype = None
+    lib.ctc_debug_set_poll_budget.argtypes = [ci]
     _lib = lib
     return lib
 
@@ -202,3 +204,8 @@ def loss_and_grad_device(*args, **kw) -> None:
     if st != STATUS_SUCCESS:
         extra = f" (hipError {last_hip_error()})" if st == STATUS_HIP_ERROR else ""
         raise CTCError(st, "ctc_loss_and_grad_device" + extra)
+
+
+def debug_set_poll_budget(polls: int) -> None:
+    """LDS polls a lattice wavefront may spend waiting on its neighbour (negative: default)."""
+    load().ctc_debug_set_poll_budget(int(polls))

@@ -204,3 +204,38 @@ def test_best_path_repeats_bitwise_and_leaves_the_other_calls_intact():
     c_ref, g_ref = db2.results()
     assert np.array_equal(c_full, c_ref) and np.array_equal(g_full, g_ref)
     assert (s1 >= c_ref - 1e-3).all()            # the best alignment cannot beat the sum over all
+
+
+def test_a_lost_wavefront_exchange_is_reported_as_nan_cost():
+    """With a poll budget of zero every wait between the wavefronts of a long label gives up at once:
+    all kernels still run to their end, and the utterances concerned report NaN in all three calls,
+    while labels that fit one wavefront are unaffected."""
+    rng = np.random.default_rng(51)
+    T, A = 160, 7
+    lengths = np.asarray([150, 40, 150, 10, 120, 63], dtype=np.int32)
+    # labels without adjacent repeats, so that every utterance has an alignment
+    labs = [(1 + np.cumsum(rng.integers(1, A - 1, size=n)) % (A - 1)).astype(np.int32) for n in lengths]
+    batch = wl.CTCBatch(name="lost-exchange", T=T, B=len(lengths), A=A, blank=0,
+                        logits=(rng.standard_normal((T, len(lengths), A)) * 2.0).astype(np.float32),
+                        flat_labels=np.concatenate(labs), label_lengths=lengths,
+                        input_lengths=np.full(len(lengths), T, dtype=np.int32), seed=51)
+    multi = lengths + 1 > 64
+    ref = orc.ctc_loss_and_grad(batch.logits, batch.flat_labels, batch.label_lengths, batch.input_lengths,
+                                batch.blank, want_grad=False)[0]
+    assert np.isfinite(ref).all()
+    try:
+        ctc.debug_set_poll_budget(0)
+        db = harness.DeviceBatch(batch)
+        for run in (db.run, db.run_loss, db.run_best_path):
+            db.poison()
+            run()
+            costs, _ = db.results()
+            assert np.isnan(costs[multi]).all(), (run.__name__, costs)
+            assert np.isfinite(costs[~multi]).all(), (run.__name__, costs)
+        assert (db.alignment.cpu().numpy()[multi] == -1).all()
+    finally:
+        ctc.debug_set_poll_budget(-1)
+    db = harness.DeviceBatch(batch)
+    db.run()
+    costs, _ = db.results()
+    assert np.abs(costs - ref).max() <= 1e-4 * np.abs(ref).max()
