@@ -1169,6 +1169,112 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     }
 }
 
+// Alphabets of at most 64 symbols (the English one has 29): lane k of a row's wavefront is
+// symbol k.  It adds up the run of slots of its symbol (start and length per symbol are put
+// into LDS once per workgroup) and writes grad[k] = y_k - occupancy_k straight away: no scan
+// over the label for first occurrences and no occupancy array per row.
+template <typename T>
+__global__ __launch_bounds__(kRowThreads)
+void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
+                                const Utt* __restrict__ meta, const int* __restrict__ labels,
+                                const int* __restrict__ links, const float* __restrict__ lse,
+                                const double* __restrict__ alpha, const double* __restrict__ beta,
+                                const double* __restrict__ logp, const int* __restrict__ chain_err,
+                                float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
+                                int rows_per_group)
+{
+    extern __shared__ int g_lds[];
+    int* s_slot = g_lds;                         // [Lmax]  slot of each label position
+    int* s_start = g_lds + Lmax;                 // [64]    first slot of each symbol's run
+    int* s_count = s_start + 64;                 // [64]    length of the run (0: symbol not in the label)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* g_slot = reinterpret_cast<float*>(s_count + 64) + wave * (Lmax + 1);   // mass shares in slot order
+    const int b = blockIdx.y, t0 = blockIdx.x * rows_per_group;
+    const Utt m = meta[b];
+    if (t0 == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
+    const bool runs = (m.flags & kUttRuns) != 0;
+    const int L = m.L, P = L + 1;
+    if (runs && t0 < m.Tb) {
+        if (tid < 64) {
+            s_start[tid] = 0;
+            s_count[tid] = 0;
+        }
+        __syncthreads();
+        for (int j = tid; j < L; j += kRowThreads) {
+            const int link = links[m.lab_off + j];
+            s_slot[j] = link & kLinkSlotMask;
+            if (link < 0) {
+                const int c = labels[m.lab_off + j];
+                s_start[c] = link & kLinkSlotMask;
+                s_count[c] = (link >> kLinkCountShift) & kLinkSlotMask;
+            }
+        }
+        __syncthreads();
+    }
+    const size_t pitch = static_cast<size_t>(P);
+    const double lp = runs ? logp[b] : 0.0;
+    const int tend = min(t0 + rows_per_group, Tt);
+    const double* const abase = alpha + m.ab_off;
+    const double* const bbase = beta + m.ab_off;
+    for (int t = t0 + wave; t < tend; t += 4) {
+        const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
+        T* grow = grads + row_off;
+        if (t >= m.Tb || !runs) {
+            if (lane < A) store_elem(grow, lane, 0.0f);
+            continue;
+        }
+        const double* arow = abase + static_cast<size_t>(t) * pitch;
+        const double* brow = bbase + static_cast<size_t>(t) * pitch;
+        // everything the row needs from memory is requested before the first use
+        double a[kAhead], bb[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int j = u * 64 + lane;
+            if (j < L) {
+                a[u] = arow[j];
+                bb[u] = brow[j];
+            }
+        }
+        const float l2 = lse[static_cast<size_t>(b) * Tt + t];
+        const float x0 = (lane < A) ? load_elem(x + row_off, lane) : 0.0f;
+        float zl = 0.0f;
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int j = u * 64 + lane;
+            if (j < L) {
+                const float gl = fast_exp2(static_cast<float>(a[u] + bb[u] - lp));
+                g_slot[s_slot[j]] = gl;
+                zl += gl;
+            }
+        }
+        for (int j = kAhead * 64 + lane; j < L; j += 64) {
+            const float gl = fast_exp2(static_cast<float>(arow[j] + brow[j] - lp));
+            g_slot[s_slot[j]] = gl;
+            zl += gl;
+        }
+        const float zb = 1.0f - wave_sum(zl);      // the blank states share what is left of 1
+        // LDS operations of one wavefront complete in program order; the fence only keeps the
+        // compiler from moving them across.
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        float o = 0.0f;
+        if (lane < A) {
+            const int first = s_start[lane], count = s_count[lane];
+            // Eight independent reads at a time; slots past the run add an exact zero, so the
+            // order of summation is the run's own (positions ascending).
+            for (int i0 = 0; i0 < count; i0 += 8) {
+                float g[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) g[i] = g_slot[min(first + i0 + i, L - 1)];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o += (i0 + i < count) ? g[i] : 0.0f;
+            }
+            if (lane == blank) o = zb;
+            store_elem(grow, lane, fast_exp2(fmaf(x0, kLog2e, -l2)) - o);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+}
+
 template <typename F>
 int checked_launch(F&& f)
 {
@@ -1344,6 +1450,21 @@ int launch_gradient(const Launch& p, void* stream)
     const int rows = sparse ? 4 : (static_cast<int64_t>(p.T) * p.B <= (1 << 17) ? 8 : 16);
     const dim3 grid((p.T + rows - 1) / rows, p.B);
     const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + (sparse ? 0 : p.A))) * 4;
+    if (p.A <= 64) {
+        const size_t nlds = (static_cast<size_t>(Lmax) + 128 + 4 * (static_cast<size_t>(Lmax) + 1)) * 4;
+        return checked_launch([&] {
+            if (f32)
+                hipLaunchKernelGGL(ctc_gradient_narrow_kernel<float>, grid, block, nlds, s,
+                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels,
+                                   links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,
+                                   Lmax, rows);
+            else
+                hipLaunchKernelGGL(ctc_gradient_narrow_kernel<bf16_t>, grid, block, nlds, s,
+                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta, labels,
+                                   links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,
+                                   Lmax, rows);
+        });
+    }
 #define CTC_LAUNCH_GRADIENT(TYPE, SPARSE)                                                          \
     hipLaunchKernelGGL((ctc_gradient_rows_kernel<TYPE, SPARSE>), grid, block, lds, s,               \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,     \
