@@ -212,6 +212,11 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     int32_t* order = reinterpret_cast<int32_t*>(image + lay.order);
     int32_t* labels = reinterpret_cast<int32_t*>(image + lay.labels);
 
+    // Would the launch, planned for latency, put more than two wavefronts on every SIMD?
+    int64_t latency_waves = 0;
+    for (int b = 0; b < c.B; ++b) latency_waves += plan_waves(c.label_lengths[b]).waves;
+    const bool crowded = latency_waves * (c.mode == Mode::kGrad ? 2 : 1) > kCrowdedWaves;
+
     int64_t lab_off = 0, e_off = 0, ab_off = 0, f_off = 0;
     int n_run = 0, max_waves = 1, max_frames = 0, max_label = 0;
     bool needs_barrier = false;
@@ -234,7 +239,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.lab_off = static_cast<int32_t>(lab_off);
         m.flags = runs ? kUttRuns : 0;
         m.f_off = static_cast<int32_t>(f_off);
-        const WavePlan wp = plan_waves(L);
+        const WavePlan wp = plan_waves(L, crowded);
         m.waves = wp.waves;
         m.halo = wp.halo;
         m.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
@@ -280,6 +285,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->dev_input_lengths = nullptr;
     out->dev_status = nullptr;
     out->poll_budget = g_poll_budget.load(std::memory_order_relaxed);
+    out->crowded = crowded;
     out->lay = lay;
     return CTC_STATUS_SUCCESS;
 }
@@ -392,7 +398,8 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.dtype = dtype;
     p.n_run = B;                       // one lattice workgroup per utterance; those that do not run leave at once
     p.max_waves = 1;
-    for (int L = 0; L <= max_label; ++L) p.max_waves = std::max(p.max_waves, plan_waves(L).waves);
+    p.crowded = static_cast<int64_t>(B) * plan_waves(max_label).waves * (grads ? 2 : 1) > 2 * kCrowdedWaves;
+    for (int L = 0; L <= max_label; ++L) p.max_waves = std::max(p.max_waves, plan_waves(L, p.crowded).waves);
     p.max_frames = T;
     p.max_label = max_label;
     p.needs_barrier = plan_waves(max_label).barrier;

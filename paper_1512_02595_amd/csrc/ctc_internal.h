@@ -43,7 +43,9 @@ struct WavePlan {
 // several per SIMD the vector ALU is the limit (about 170 clocks per wavefront-step) and part
 // of a hand-over's latency hides behind the other wavefronts (about 350).
 // (Host and device: the launcher plans on the host, the device-metadata entry point on the GPU.)
-CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length)
+// `crowded`: the launch has more wavefronts than the chip runs side by side at one per SIMD, so
+// what counts is the total work (wavefront-steps plus hand-overs), not one chain's latency.
+CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length, bool crowded = false)
 {
     const int pairs = label_length + 1;
     if (pairs <= 64) return {1, 0, false};
@@ -60,7 +62,8 @@ CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length)
         if (halo < 8) continue;
         const int per_simd = (w + 3) / 4;
         // the last term prefers fewer wavefronts when the estimates are close
-        const float cost = ((per_simd == 1) ? 210.0f + 500.0f / halo : per_simd * 170.0f + 350.0f / halo) + 4.0f * w;
+        const float cost = crowded ? w * (170.0f + 350.0f / halo)
+                                   : ((per_simd == 1) ? 210.0f + 500.0f / halo : per_simd * 170.0f + 350.0f / halo) + 4.0f * w;
         if (cost < best_cost) {
             best_cost = cost;
             best = {w, halo, false};
@@ -71,6 +74,9 @@ CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length)
 
 constexpr int kUttRuns = 1;
 constexpr int kUttInvalid = 2;
+// Lattice wavefronts of one launch beyond which chains are planned for total work: two per SIMD
+// of the 256 compute units.
+constexpr int kCrowdedWaves = 2 * 4 * 256;
 constexpr int kDefaultPollBudget = 1 << 22;   // enough for seconds of waiting: only a stuck neighbour exhausts it
 constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ranks in LDS
 
@@ -148,6 +154,7 @@ struct Launch {
     const int32_t* dev_input_lengths;
     int32_t* dev_status;
     int poll_budget;          // copied into every Utt record
+    bool crowded;             // plan the chains for total work rather than latency (device planner)
     Layout lay;
 };
 

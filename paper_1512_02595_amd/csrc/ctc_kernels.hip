@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kPlanThreads)
 void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ label_lengths,
                      const int* __restrict__ input_lengths, Utt* __restrict__ meta,
                      int* __restrict__ order, int* __restrict__ status,
-                     int Tt, int B, int A, int blank, int max_label, int poll_budget)
+                     int Tt, int B, int A, int blank, int max_label, int poll_budget, bool crowded)
 {
     __shared__ long long weight[kMaxDeviceMetaB];     // T_b x wavefronts; -1: does not run
     __shared__ int s_bad;
@@ -196,7 +196,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) repeats += __shfl_xor(repeats, o, 64);
         const bool runs = !bad && Tb > 0 && Tb >= L + repeats;
-        const WavePlan wp = plan_waves(bad ? 0 : L);
+        const WavePlan wp = plan_waves(bad ? 0 : L, crowded);
         if (lane == 0) {
             Utt m;
             m.Tb = bad ? 0 : Tb;
@@ -1312,7 +1312,7 @@ int launch_plan(const Launch& p, void* stream)
         hipLaunchKernelGGL(ctc_plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(stream),
                            p.labels, p.dev_label_lengths, p.dev_input_lengths,
                            reinterpret_cast<Utt*>(p.ws + p.lay.meta), reinterpret_cast<int*>(p.ws + p.lay.order),
-                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label, p.poll_budget);
+                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label, p.poll_budget, p.crowded);
     });
 }
 
