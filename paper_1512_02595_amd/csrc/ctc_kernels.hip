@@ -495,13 +495,14 @@ __device__ __forceinline__ double lse3(double a, double b, double c)
     return hi + static_cast<double>(fast_log2(1.0f + fast_exp2(mid) + fast_exp2(mn)));
 }
 
-// Lane i receives the value of lane i-1 (DPP wave_shr:1); lane 0 keeps `lane0`.
-__device__ __forceinline__ double shift_up(double v, double lane0)
+// Lane i receives the value of lane i-1 (DPP wave_shr:1).  The shift writes nothing into lane 0,
+// which therefore keeps what `into` held there: initialised once to log 0 and passed back in at
+// every step, it needs no refill (two moves per step otherwise).
+__device__ __forceinline__ double shift_up(double v, int& into_lo, int& into_hi)
 {
-    int lo = __double2loint(v), hi = __double2hiint(v);
-    lo = __builtin_amdgcn_update_dpp(__double2loint(lane0), lo, 0x138, 0xf, 0xf, false);
-    hi = __builtin_amdgcn_update_dpp(__double2hiint(lane0), hi, 0x138, 0xf, 0xf, false);
-    return __hiloint2double(hi, lo);
+    into_lo = __builtin_amdgcn_update_dpp(into_lo, __double2loint(v), 0x138, 0xf, 0xf, false);
+    into_hi = __builtin_amdgcn_update_dpp(into_hi, __double2hiint(v), 0x138, 0xf, 0xf, false);
+    return __hiloint2double(into_hi, into_lo);
 }
 
 constexpr int kHaloEntries = 64;      // 16-byte entries of one wavefront boundary's exchange buffer (2 x 32)
@@ -681,8 +682,9 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     };
 
     // Label value of pair j-1 after step s (log 0 for pair 0).  `mine` is this lane's.
+    int prev_lo = __double2loint(kNeg), prev_hi = __double2hiint(kNeg);
     auto from_prev_pair = [&](double mine, int s) {
-        double r = shift_up(mine, kNeg);
+        double r = shift_up(mine, prev_lo, prev_hi);
         if (kSync == Sync::kBarrier) {
             double (*xch)[16] = static_cast<double (*)[16]>(lds);
             if (lane == 63) xch[s & 1][wave] = mine;
