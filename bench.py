@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # (The published 157.3 TFLOP/s fp32 vector figure counts 2 for packing and 2 for FMA on top.)
 ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # Lane-operations of one step of one (blank, label) state pair in one direction:
-# 5 transcendentals at quarter rate (= 20) + 25 plain operations.
-LANE_OPS_PER_PAIR_STEP = 45
+# 4 transcendentals (two exp2, two log2) at quarter rate (= 16) + 25 plain operations.
+LANE_OPS_PER_PAIR_STEP = 41
 # The max recursion of the alignment has no transcendentals: compares, selects, two fp64 adds.
 LANE_OPS_PER_PAIR_STEP_ALIGN = 22
 
