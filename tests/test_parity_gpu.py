@@ -220,3 +220,35 @@ def test_device_side_errors_are_reported_as_status():
                                   costs_ptr=db.costs.data_ptr(), grads_ptr=db.x.data_ptr(),
                                   workspace_ptr=db.ws_ptr, workspace_bytes=db.ws_bytes, **args)
     assert st == ctc.STATUS_INVALID_VALUE
+
+
+def test_every_wavefront_plan_boundary():
+    """Label lengths on both sides of every change of the wavefront plan (1 to 16 wavefronts with halos of
+    8 to 32 pairs, then the barrier kernel), all three calls: the exchange between wavefronts is exercised in
+    every configuration the planner can produce."""
+    rng = np.random.default_rng(77)
+    A = 6
+    lengths = sorted({62, 63, 64, 65, 95, 96, 97, 119, 120, 121, 159, 160, 161, 183, 184, 199, 200, 201, 231, 232, 233,
+                      271, 272, 287, 288, 327, 328, 343, 344, 399, 400, 455, 456, 511, 512, 567, 568, 623, 624,
+                      679, 680, 735, 736, 791, 792, 847, 848, 895, 896, 902, 903, 904, 960, 1023})
+    T = 1040
+    labs = [(1 + np.cumsum(rng.integers(1, A - 1, size=n)) % (A - 1)).astype(np.int32) for n in lengths]
+    t_b = np.asarray([min(T, max(n + 3, int(n * rng.uniform(1.0, 1.3)) + 2)) for n in lengths], dtype=np.int32)
+    batch = wl.CTCBatch(name="plan-boundaries", T=T, B=len(lengths), A=A, blank=0,
+                        logits=(rng.standard_normal((T, len(lengths), A)) * 2.0).astype(np.float32),
+                        flat_labels=np.concatenate(labs), label_lengths=np.asarray(lengths, dtype=np.int32),
+                        input_lengths=t_b, seed=77)
+    costs, grads, _, _ = check(batch)
+    assert np.isfinite(costs).all()
+    # the cost-only call and the best path run the same chains in their own modes
+    db = harness.DeviceBatch(batch)
+    db.run_loss()
+    loss_only, _ = db.results()
+    assert np.array_equal(loss_only, costs)
+    db.run_best_path()
+    scores, states = db.best_path_results()
+    ref_s, ref_a = orc.ctc_best_path(batch.logits, batch.flat_labels, batch.label_lengths, batch.input_lengths, 0)
+    assert np.abs(scores - ref_s).max() <= 1e-4 * np.abs(ref_s).max()
+    same = sum(np.array_equal(states[b], ref_a[b]) for b in range(batch.B))
+    print(f"  best path: {same}/{batch.B} alignments identical to the oracle's", flush=True)
+    assert same >= 0.9 * batch.B
