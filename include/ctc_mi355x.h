@@ -64,7 +64,8 @@ enum {
  * Bytes of device workspace that ctc_loss_and_grad needs for this batch shape.
  * (Workspace sizing for the memory-allocation concern of Section 4.3.)
  *
- *   T, B, A          time steps of the tensor, utterances, alphabet size incl. blank; all >= 1
+ *   T, B, A          time steps of the tensor, utterances, alphabet size incl. blank; all >= 1;
+ *                    more than 65535 utterances per call are refused (UNSUPPORTED)
  *   label_lengths    (host) [B], each in 0..CTC_MAX_LABEL_LENGTH
  *   input_lengths    (host) [B], each in 0..T
  *   bytes_out        (host) receives the size; the workspace must be 256-byte aligned

@@ -85,6 +85,7 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
     }
     if (too_long) return CTC_STATUS_UNSUPPORTED;
     if (sumL > INT32_MAX || frames > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
+    if (B > kMaxBatch) return CTC_STATUS_UNSUPPORTED;
     carve(T, B, sumL, emit, frames, ab, lay);
     return CTC_STATUS_SUCCESS;
 }

@@ -78,6 +78,7 @@ constexpr int kUttInvalid = 2;
 // of the 256 compute units.
 constexpr int kCrowdedWaves = 2 * 4 * 256;
 constexpr int kDefaultPollBudget = 1 << 22;   // enough for seconds of waiting: only a stuck neighbour exhausts it
+constexpr int kMaxBatch = 65535;         // utterances index the second grid dimension of the row kernels
 constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ranks in LDS
 
 // The lattice kernel reads emissions ahead of the recursion without bounds checks.  It

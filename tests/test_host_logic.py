@@ -86,6 +86,9 @@ def test_workspace_size_rejects_bad_shapes(lib):
     st = lib.ctc_workspace_size(10, 2, 5, (ctypes.c_int32 * 2)(3, 4), (ctypes.c_int32 * 2)(10, 10), 0, None)
     assert st == ctc.STATUS_INVALID_VALUE
     assert ctc.workspace_size_status(10, 2, 5, [3, ctc.MAX_LABEL_LENGTH], ok_i)[0] == ctc.STATUS_SUCCESS
+    big = 65536
+    assert ctc.workspace_size_status(4, big, 3, [1] * big, [4] * big)[0] == ctc.STATUS_UNSUPPORTED
+    assert ctc.workspace_size_status(4, big - 1, 3, [1] * (big - 1), [4] * (big - 1))[0] == ctc.STATUS_SUCCESS
 
 
 def test_loss_and_grad_validates_before_any_device_work(lib):
