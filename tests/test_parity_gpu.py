@@ -145,6 +145,30 @@ def test_degenerate_lengths():
     assert costs[0] == 0.0 and np.isinf(costs[2]) and np.isinf(costs[4]) and np.isfinite(costs[5])
 
 
+def test_smallest_shapes():
+    """One frame, one utterance, one symbol (the blank alone), and a single all-padding tensor."""
+    rng = np.random.default_rng(2)
+    def one(T, B, A, labels, in_len, blank=0):
+        return wl.CTCBatch(name="smallest", T=T, B=B, A=A, blank=blank,
+                           logits=rng.standard_normal((T, B, A), dtype=np.float32),
+                           flat_labels=np.array([k for l in labels for k in l], dtype=np.int32),
+                           label_lengths=np.array([len(l) for l in labels], dtype=np.int32),
+                           input_lengths=np.array(in_len, dtype=np.int32))
+    costs, grads, _, _ = check(one(1, 1, 1, [[]], [1]))             # the blank is the whole alphabet
+    assert abs(costs[0]) < 1e-6 and np.abs(grads).max() < 1e-6
+    check(one(1, 1, 2, [[1]], [1]))
+    check(one(1, 1, 2, [[1]], [1], blank=0))
+    check(one(3, 2, 1, [[], []], [3, 0]))
+    costs, grads, _, _ = check(one(4, 3, 5, [[1], [2, 2], []], [0, 0, 0]))   # no valid frame at all
+    assert np.isinf(costs[0]) and np.isinf(costs[1]) and costs[2] == 0.0 and not grads.any()
+    for b in (one(1, 1, 2, [[1]], [1]), one(5, 2, 3, [[1, 2], []], [5, 2])):
+        db = harness.DeviceBatch(b)
+        db.run_best_path()
+        scores, states = db.best_path_results()
+        ref_s, ref_a = orc.ctc_best_path(b.logits, b.flat_labels, b.label_lengths, b.input_lengths, b.blank)
+        assert np.allclose(scores, ref_s, rtol=1e-5) and np.array_equal(states, ref_a)
+
+
 def test_longest_supported_label():
     L = ctc.MAX_LABEL_LENGTH
     rng = np.random.default_rng(1)
