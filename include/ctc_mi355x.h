@@ -10,6 +10,8 @@
  * forward (alpha) / backward (beta) passes over the blank-interleaved label and
  * the per-character reduction described in the appendix "GPU Implementation of
  * CTC Loss Function".  The output softmax of Section 3.1 is fused into the path.
+ * On the same lattice it also finds the most probable alignment of Section 5.1
+ * (ctc_best_path).
  *
  * Plain C ABI: pointers and sizes only.  Each pointer argument is marked (host)
  * or (device).  The library allocates no device memory: every buffer, including
@@ -18,7 +20,7 @@
  * stream and the calls return without waiting for it; host arrays are consumed
  * before the call returns.  The only memory the library itself holds is a small ring of
  * pinned host buffers per device (the per-call metadata image the first kernel reads), created
- * on first use and kept until the process ends.
+ * on first use and kept until the process ends; ctc_loss_and_grad_device does without it.
  */
 #ifndef CTC_MI355X_H
 #define CTC_MI355X_H
@@ -35,7 +37,8 @@ typedef enum {
     CTC_STATUS_INVALID_VALUE = 1,       /* null pointer, size or id out of range, overlapping buffers */
     CTC_STATUS_WORKSPACE_TOO_SMALL = 2, /* workspace_bytes below what ctc_workspace_size reports */
     CTC_STATUS_HIP_ERROR = 3,           /* a HIP runtime call failed; see ctc_last_hip_error */
-    CTC_STATUS_UNSUPPORTED = 4          /* a label longer than CTC_MAX_LABEL_LENGTH */
+    CTC_STATUS_UNSUPPORTED = 4          /* a size beyond what the kernels index: a label longer than
+                                           CTC_MAX_LABEL_LENGTH, more than 65535 utterances, ... */
 } ctc_status_t;
 
 /* Element type of activations AND gradients.  Arithmetic is always fp32/fp64 inside. */
@@ -54,8 +57,9 @@ enum {
     CTC_KERNEL_LATTICE = 1,    /* alpha and beta recursions, one launch */
     CTC_KERNEL_GRADIENT = 2,   /* softmax minus normalised occupancy, zero fill of padding */
     /* A short copy launch (the per-call metadata, from pinned host memory into the workspace)
-       precedes these three and is not timed separately; the label links and the costs of
-       degenerate utterances are prepared by extra workgroups of the softmax launch. */
+       precedes these three and is not timed separately; the grouping of each label's positions
+       by symbol and the costs of degenerate utterances are prepared by extra workgroups of the
+       softmax launch. */
     CTC_NUM_KERNELS = 3,       /* timed launches of any one call */
     CTC_KERNEL_BACKTRACE = 3   /* name index only: third launch of ctc_best_path (in place of the gradient) */
 };
