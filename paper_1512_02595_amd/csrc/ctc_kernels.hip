@@ -1,14 +1,18 @@
 // HIP kernels of the batched CTC cost + gradient for gfx950 (wave64, CDNA4).
 //
 // Pipeline of one call (appendix "GPU Implementation of CTC Loss Function"; cost of
-// Section 3.3 Eq. (ctc); softmax of Section 3.1):
+// Section 3.3 Eq. (ctc); softmax of Section 3.1; most probable alignment of Section 5.1):
+//   upload    the per-call metadata from pinned host memory into the workspace
+//             (or plan: the same records built on the GPU from device-resident lengths and labels)
 //   setup     per utterance: label positions grouped by symbol (the appendix's one-off
 //             key-value sort, done by counting), degenerate costs; rides in the softmax launch
 //   softmax   per frame row: log2-sum-exp2 of the scaled logits, and the log2 emissions of
 //             blank and of every label position, gathered once so that the recursions read
 //             them coalesced
 //   lattice   alpha and beta recursions, both in one launch on different workgroups
+//             (cost only: alpha alone; alignment: the max recursion with recorded choices)
 //   gradient  softmax minus the normalised per-symbol occupancy; zero fill of padding
+//             (alignment: the backtrace instead)
 //
 // All lattice quantities are base-2 logarithms: v_exp_f32 / v_log_f32 are base 2, so the
 // recursion carries no scaling multiplies.  log(0) is represented by kNeg, a large finite
