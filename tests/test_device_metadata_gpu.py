@@ -51,6 +51,13 @@ def test_matches_the_host_metadata_call_on_other_shapes(maker):
     both_paths(maker())
 
 
+def test_bounds_far_above_the_actual_labels():
+    """A label bound that only the barrier kernel serves, on a batch of short labels; and a bound that makes
+    the launch as wide as sixteen wavefronts while the labels need one or two."""
+    both_paths(wl.make_random(31, T=60, B=3, A=5, max_label=20, min_input=30), max_label=ctc.MAX_LABEL_LENGTH)
+    both_paths(wl.make_random(32, T=150, B=5, A=6, max_label=100, min_input=120, feasible_only=True), max_label=900)
+
+
 def test_bf16_and_cost_only():
     batch = wl.make_config(4, B=32)
     both_paths(batch, ctc.DTYPE_BF16)
