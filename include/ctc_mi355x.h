@@ -125,7 +125,8 @@ ctc_status_t ctc_loss_and_grad(const void *activations,
 /*
  * Same computation as ctc_loss_and_grad, but brackets each kernel with HIP events
  * on `stream`, waits for the stream, and reports the device time of each kernel of
- * this call in milliseconds.  For measurement (the per-kernel timings that the
+ * this call in milliseconds (each interval less what two events recorded back to back
+ * read, i.e. the cost of the bracketing itself).  For measurement (the per-kernel timings that the
  * paper's Table "gpucpuctc" aggregates per epoch), not for the training loop.
  *
  *   kernel_ms     (host) [CTC_NUM_KERNELS]; with grads == NULL there is no third launch and

@@ -341,7 +341,9 @@ ctc_status_t run(const Call& c, float* kernel_ms)
         slot->in_flight = true;
     }
 
-    hipEvent_t ev[CTC_NUM_KERNELS + 1] = {};
+    // Events 0..CTC_NUM_KERNELS bracket the launches; the last two are recorded back to back
+    // and give what an interval with nothing in it reads, which is taken off every interval.
+    hipEvent_t ev[CTC_NUM_KERNELS + 3] = {};
     if (kernel_ms) {
         for (auto& e : ev)
             if (!record(hipEventCreate(&e))) return CTC_STATUS_HIP_ERROR;
@@ -358,9 +360,16 @@ ctc_status_t run(const Call& c, float* kernel_ms)
         if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
     }
     if (kernel_ms) {
+        if (!record(hipEventRecord(ev[CTC_NUM_KERNELS + 1], s))) return CTC_STATUS_HIP_ERROR;
+        if (!record(hipEventRecord(ev[CTC_NUM_KERNELS + 2], s))) return CTC_STATUS_HIP_ERROR;
         if (!record(hipStreamSynchronize(s))) return CTC_STATUS_HIP_ERROR;
-        for (int i = 0; i < CTC_NUM_KERNELS; ++i)
+        float empty = 0.0f;
+        if (!record(hipEventElapsedTime(&empty, ev[CTC_NUM_KERNELS + 1], ev[CTC_NUM_KERNELS + 2])))
+            return CTC_STATUS_HIP_ERROR;
+        for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
             if (!record(hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]))) return CTC_STATUS_HIP_ERROR;
+            kernel_ms[i] = stages[i] ? std::max(kernel_ms[i] - empty, 0.0f) : 0.0f;
+        }
         for (auto& e : ev) (void)hipEventDestroy(e);
     }
     return CTC_STATUS_SUCCESS;
