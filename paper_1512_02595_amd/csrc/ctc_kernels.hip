@@ -300,8 +300,8 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
 }
 
 // ---- softmax statistics + emission gather --------------------------------------------------
-// Wide alphabets (A > 2048): one workgroup per row (t, b) of the tensor; grid (T + 1, B), the
-// extra column does the setup role.
+// Wide alphabets (A > 2048): one workgroup per row (t, b) of the tensor; grid (T + 1, B) for the
+// scalar kernel, (B, T + 1) for the vector kernel; the extra column (row) does the setup role.
 // The gradient of a wide alphabet is the softmax itself except in the few columns whose symbol
 // occurs in the label, so these kernels also write the dense part of the gradient while they
 // hold the row: y for valid rows, zeros for padding rows and for utterances without an
@@ -367,7 +367,8 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
     constexpr int kVecs = kWideMaxA / (N * kRowThreads);      // vectors per thread
     __shared__ float red[8];
     __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
-    const int t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    // Utterance fastest: consecutive workgroups take consecutive rows of the tensor.
+    const int t = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
     const Utt m = meta[b];
     if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
@@ -1366,7 +1367,7 @@ int launch_softmax(const Launch& p, void* stream)
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
                                    emit_label, sa, p.T, p.B, p.A, p.blank);
         } else if (vector_ok(p) && p.A <= kWideMaxA) {
-            const dim3 grid(p.T + 1, p.B);
+            const dim3 grid(p.B, p.T + 1);
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_wide_kernel<float>, grid, block, 0, s,
                                    static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels, lse, emit_blank,
