@@ -276,3 +276,24 @@ def test_every_wavefront_plan_boundary():
     same = sum(np.array_equal(states[b], ref_a[b]) for b in range(batch.B))
     print(f"  best path: {same}/{batch.B} alignments identical to the oracle's", flush=True)
     assert same >= 0.9 * batch.B
+
+
+def test_many_random_shapes():
+    """Forty seeded shapes drawn over the ranges the kernels switch on (alphabet 2 .. 2500, labels 0 .. 400,
+    frames 1 .. 450, both activation types, any blank id), each through the full call and the cost-only call."""
+    rng = np.random.default_rng(2025)
+    for case in range(40):
+        A = int(rng.choice([2, 3, 5, 16, 29, 64, 65, 300, 513, 2048, 2049, 2500]))
+        T = int(rng.integers(1, 450))
+        B = int(rng.integers(1, 9))
+        max_label = int(min(T, rng.choice([0, 3, 20, 63, 64, 130, 400])))
+        blank = int(rng.integers(0, A))
+        dtype = ctc.DTYPE_BF16 if case % 5 == 4 else ctc.DTYPE_F32
+        batch = wl.make_random(5000 + case, T=T, B=B, A=A, blank=blank, max_label=max_label,
+                               min_input=int(rng.integers(0, T + 1)), sigma=float(rng.choice([1.0, 2.0, 5.0])),
+                               feasible_only=bool(case % 3))
+        costs, _, _, _ = check(batch, dtype)
+        db = harness.DeviceBatch(batch, dtype)
+        db.run_loss()
+        loss_only, _ = db.results()
+        assert np.array_equal(loss_only, costs)
