@@ -77,7 +77,7 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
         if (L < 0 || Tb < 0 || Tb > T) return CTC_STATUS_INVALID_VALUE;
         if (L > CTC_MAX_LABEL_LENGTH) too_long = true;
         sumL += L;
-        emit += Tb * L;
+        emit += Tb * (A <= kDirectMaxA ? A : L);
         frames += Tb;
         // per-utterance byte offsets inside the kernels are 32-bit
         if (Tb * (L + 1) * 8 > INT32_MAX) too_long = true;
@@ -99,7 +99,7 @@ ctc_status_t make_layout_bounds(int T, int B, int A, int max_label, ctc_dtype_t 
     if (max_label > CTC_MAX_LABEL_LENGTH || B > kMaxDeviceMetaB) return CTC_STATUS_UNSUPPORTED;
     const int64_t Tl = T, Bl = B, Ll = max_label;
     if (Tl * (Ll + 1) * 8 > INT32_MAX || Bl * Ll > INT32_MAX || Bl * Tl > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
-    carve(T, B, Bl * Ll, Bl * Tl * Ll, Bl * Tl, Bl * Tl * (Ll + 1), lay);
+    carve(T, B, Bl * Ll, Bl * Tl * (A <= kDirectMaxA ? A : Ll), Bl * Tl, Bl * Tl * (Ll + 1), lay);
     return CTC_STATUS_SUCCESS;
 }
 
@@ -246,8 +246,10 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
         m.e_off = e_off;
         m.ab_off = ab_off;
+        m.e_direct = c.A <= kDirectMaxA ? 1 : 0;
+        m.e_pitch = m.e_direct ? c.A : L;
         lab_off += L;
-        e_off += static_cast<int64_t>(Tb) * L;
+        e_off += static_cast<int64_t>(Tb) * (c.A <= kDirectMaxA ? c.A : L);
         f_off += Tb;
         ab_off += static_cast<int64_t>(Tb) * (L + 1);
         if (runs) {

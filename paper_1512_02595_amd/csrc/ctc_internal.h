@@ -20,10 +20,20 @@ struct Utt {
     int32_t waves;     // wavefronts its lattice chains use
     int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
     int32_t poll_budget; // LDS polls a wavefront of its chains may spend waiting on a neighbour before it gives up
-    int64_t e_off;     // offset (floats) of its label emissions [Tb][L]
+    int64_t e_off;     // offset (floats) of its label emissions, [Tb][e_pitch]
     int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][L+1]
+    int32_t e_pitch;   // floats per frame of its emission block: L (one gathered emission per label
+                       // position) or, for alphabets of at most kDirectMaxA symbols, A (the frame's
+                       // whole row of log2 probabilities, indexed by symbol)
+    int32_t e_direct;  // 1: the block holds whole rows and a label state reads column label[i];
+                       // 0: it holds gathered emissions and the state reads column i
 };
-static_assert(sizeof(Utt) == 48, "Utt must stay 48 bytes");
+static_assert(sizeof(Utt) == 56, "Utt is copied word by word and read with scalar loads: keep it 8-byte sized");
+
+// Alphabets up to this size skip the emission gather: a frame's normalised row is as small as
+// the gathered emissions would be (at most two cache lines), and every lattice lane finds its
+// symbol's column in it.
+constexpr int kDirectMaxA = 64;
 
 #if defined(__HIPCC__)
 #define CTC_HOST_DEVICE __host__ __device__

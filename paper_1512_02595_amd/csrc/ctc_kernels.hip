@@ -218,7 +218,9 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
             m.waves = wp.waves;
             m.halo = wp.halo;
             m.poll_budget = poll_budget;
-            m.e_off = static_cast<int64_t>(b) * Tt * max_label;
+            m.e_direct = A <= kDirectMaxA ? 1 : 0;
+            m.e_pitch = m.e_direct ? A : m.L;
+            m.e_off = static_cast<int64_t>(b) * Tt * (m.e_direct ? A : max_label);
             m.ab_off = static_cast<int64_t>(b) * Tt * (max_label + 1);
             meta[b] = m;
             weight[b] = runs ? static_cast<long long>(Tb) * wp.waves : -1;
@@ -449,7 +451,7 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     float* lrow = lp + r * A;
     // Requested before the row work so that its latency overlaps the row's.
     const int* lab = labels + m.lab_off;
-    const int c_first = (tid < m.L) ? lab[tid] : 0;
+    const int c_first = (!m.e_direct && tid < m.L) ? lab[tid] : 0;
     if (t < m.Tb) {
         const T* row = x + (static_cast<size_t>(t) * B + b) * A;
         float mx = -__builtin_inff();
@@ -481,6 +483,12 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
     __syncthreads();
     const int rows = min(kRows, m.Tb - t0);
     if (tid < rows) emit_blank[kBlankSlack + m.f_off + t0 + tid] = lp[tid * A + blank];
+    if (m.e_direct) {
+        // Small alphabet: the rows themselves are the emission block (row pitch A).
+        float* out = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * A;
+        for (int i = tid; i < rows * A; i += kRowThreads) out[i] = lp[i];
+        return;
+    }
     float* ebase = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * m.L;
     for (int j = tid; j < m.L; j += kRowThreads) {
         const int c = (j == tid) ? c_first : lab[j];
@@ -597,9 +605,10 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     const int fdir = kBackward ? -1 : 1;
     // Label emissions: a per-lane pointer that moves one row per step.  A lane without a label
     // state reads a constant log 0 and stays there.
-    const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * L + li
+    const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch +
+                                      (m.e_direct ? lab[li] : li)
                                 : emit_label;
-    const int64_t estride = has_label ? static_cast<int64_t>(fdir) * L : 0;
+    const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
     // Output: only the label state of each pair is kept (row pitch L+1 doubles, column = label

@@ -48,12 +48,16 @@ def test_workspace_size_grows_with_the_lattice(lib):
     small = ctc.workspace_size(50, 4, 29, [5, 6, 7, 8], [30, 40, 50, 45])
     big = ctc.workspace_size(50, 4, 29, [15, 16, 17, 18], [30, 40, 50, 45])
     assert small % 256 == 0 and big % 256 == 0 and big > small > 0
-    # alpha and beta of the label states in fp64 (L+1 entries per frame each) plus the fp32
-    # label emissions dominate for long utterances
+    # alpha and beta of the label states in fp64 (L+1 entries per frame each) dominate for long
+    # utterances; the fp32 emissions are one per label position and frame, or, for alphabets of at
+    # most 64 symbols, the frame's whole row
     T, L = 1500, 500
-    n = ctc.workspace_size(T, 1, 29, [L], [T])
+    n = ctc.workspace_size(T, 1, 100, [L], [T])
     assert n >= 2 * T * (L + 1) * 8 + T * L * 4
     assert n <= 2 * T * (L + 1) * 8 + T * L * 4 + (1 << 20)
+    n = ctc.workspace_size(T, 1, 29, [L], [T])
+    assert n >= 2 * T * (L + 1) * 8 + T * 29 * 4
+    assert n <= 2 * T * (L + 1) * 8 + T * 29 * 4 + (1 << 20)
     # zero-frame and zero-label utterances are fine
     assert ctc.workspace_size(10, 3, 5, [0, 0, 3], [0, 10, 0]) > 0
 
