@@ -37,8 +37,8 @@ LANE_OPS_PER_PAIR_STEP_ALIGN = 22
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
 # the rocprofv3 --pmc runs summarised in profiles/ (English and Mandarin HBM traffic summaries).
-MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 19.2e6, "ctc_lattice": 80.5e6, "ctc_gradient": 73.3e6},
-                    (2, "f32"): {"ctc_softmax": 1232.5e6, "ctc_lattice": 13.9e6, "ctc_gradient": 53.8e6}}
+MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 8.2e6, "ctc_lattice": 62.9e6, "ctc_gradient": 73.4e6},
+                    (2, "f32"): {"ctc_softmax": 1223.2e6, "ctc_lattice": 13.9e6, "ctc_gradient": 53.9e6}}
 
 
 def kernel_bytes(batch, elem, mode="grad"):
