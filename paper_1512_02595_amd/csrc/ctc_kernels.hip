@@ -504,17 +504,6 @@ __device__ __forceinline__ double lse2(double a, double b)
     const float d = static_cast<float>(a - b);
     return hi + static_cast<double>(fast_log2(1.0f + fast_exp2(-fabsf(d))));
 }
-__device__ __forceinline__ double lse3(double a, double b, double c)
-{
-    const double hi = fmax(fmax(a, b), c);
-    const float da = static_cast<float>(a - hi), db = static_cast<float>(b - hi),
-                dc = static_cast<float>(c - hi);
-    // one of the three differences is 0; the other two are the median and the minimum
-    const float mid = __builtin_amdgcn_fmed3f(da, db, dc);
-    const float mn = fminf(fminf(da, db), dc);
-    return hi + static_cast<double>(fast_log2(1.0f + fast_exp2(mid) + fast_exp2(mn)));
-}
-
 // Lane i receives the value of lane i-1 (DPP wave_shr:1).  The shift writes nothing into lane 0,
 // which therefore keeps what `into` held there: initialised once to log 0 and passed back in at
 // every step, it needs no refill (two moves per step otherwise).
@@ -1041,7 +1030,8 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                               const double* __restrict__ alpha, const double* __restrict__ beta,
                               const double* __restrict__ logp, const int* __restrict__ chain_err,
                               float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
-                              int rows_per_group)
+                              int rows_per_group, const float* __restrict__ emit_blank,
+                              const float* __restrict__ emit_label)
 {
     extern __shared__ int g_lds[];
     int* s_lab = g_lds;
@@ -1075,6 +1065,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     struct RowData {
         double a[kAhead], b[kAhead];
         float l2, x0;
+        float e[kAhead], eb;              // sparse form: emissions of the label positions and of blank
     };
     auto request = [&](int t, RowData& d) {
         if (t >= tend || t >= m.Tb || !runs) return;
@@ -1090,6 +1081,15 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         d.l2 = lse[static_cast<size_t>(b) * Tt + t];
         if (!kSparse && lane < A) d.x0 = load_elem(x + (static_cast<size_t>(t) * B + b) * A, lane);
+        if (kSparse) {
+            const float* er = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.e_pitch;
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int j = u * 64 + lane;
+                if (j < L) d.e[u] = er[j];
+            }
+            d.eb = emit_blank[kBlankSlack + m.f_off + t];
+        }
     };
 
     for (int t = t0 + wave; t < tend; t += 4) {
@@ -1103,6 +1103,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
             continue;
         }
         const T* xrow = x + row_off;
+        const float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.e_pitch;   // sparse form only
         // Mass share of every label state; the blank states share what is left of 1.
         float zl = 0.0f;
 #pragma unroll
@@ -1161,15 +1162,22 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                     for (int i = 0; i < 8; ++i) o += (i0 + i < count) ? g[i] : 0.0f;
                 }
                 const int c = s_lab[j];
-                if (kSparse)
-                    store_elem(grow, c, fast_exp2(fmaf(load_elem(xrow, c), kLog2e, -l2)) - o);
-                else
+                if (kSparse) {
+                    // y of a label's symbol is 2^(its emission), which the softmax launch gathered
+                    // next to its neighbours': no scattered read of the activations.
+                    const int u = j >> 6;
+                    float e = 0.0f;
+#pragma unroll
+                    for (int k = 0; k < kAhead; ++k) e = (u == k) ? cur.e[k] : e;
+                    if (u >= kAhead) e = erow[j];
+                    store_elem(grow, c, fast_exp2(e) - o);
+                } else {
                     occ[c] = o;
+                }
             }
         }
         if (kSparse) {
-            if (lane == 0)
-                store_elem(grow, blank, fast_exp2(fmaf(load_elem(xrow, blank), kLog2e, -l2)) - zb);
+            if (lane == 0) store_elem(grow, blank, fast_exp2(cur.eb) - zb);
         } else {
             if (lane == 0) occ[blank] = zb;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1491,7 +1499,9 @@ int launch_gradient(const Launch& p, void* stream)
 #define CTC_LAUNCH_GRADIENT(TYPE, SPARSE)                                                          \
     hipLaunchKernelGGL((ctc_gradient_rows_kernel<TYPE, SPARSE>), grid, block, lds, s,               \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,     \
-                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank, Lmax, rows)
+                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank, Lmax, rows,       \
+                       reinterpret_cast<const float*>(p.ws + p.lay.emit_blank),                                       \
+                       reinterpret_cast<const float*>(p.ws + p.lay.emit_label))
     return checked_launch([&] {
         if (f32 && sparse) CTC_LAUNCH_GRADIENT(float, true);
         else if (f32) CTC_LAUNCH_GRADIENT(float, false);
