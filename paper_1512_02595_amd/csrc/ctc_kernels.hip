@@ -568,7 +568,7 @@ struct HaloLds {
 // read).  No barrier; the wavefronts run skewed.  A wavefront waits for data only on lower
 // ones and for space only on higher ones, wavefront 0 needs no data and the last one no space,
 // so every wait ends; a poll budget bounds them regardless and raises chain_err when spent.
-template <bool kBackward, Sync kSync, bool kStream, Mode kMode>
+template <bool kBackward, Sync kSync, Mode kMode>
 __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
@@ -711,10 +711,6 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             *op = static_cast<unsigned char>(choice);
         } else if (kMode == Mode::kLoss) {
             // nothing is kept
-        } else if (kStream) {
-            // Too much lattice to stay in the caches until the gradient kernel reads it:
-            // streaming stores (measured 15 % faster on both kernels for the 512-utterance batch).
-            __builtin_nontemporal_store(kBackward ? i_label : v_label, reinterpret_cast<double*>(op));
         } else {
             *reinterpret_cast<double*>(op) = kBackward ? i_label : v_label;
         }
@@ -846,7 +842,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     }
 }
 
-template <Sync kSync, bool kStream, Mode kMode>
+template <Sync kSync, Mode kMode>
 __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
@@ -882,9 +878,9 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         }
     }
     if (kMode != Mode::kGrad || blockIdx.y == 0)
-        run_chain<false, kSync, kStream, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+        run_chain<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
     else
-        run_chain<true, kSync, kStream, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+        run_chain<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
 }
 
 // grid = (utterances whose lattice runs, 2) for Mode::kGrad: y = 0 forward, y = 1 backward;
@@ -892,7 +888,7 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
 // receives the predecessor choices, or unused).
 // blockDim.x = 64 * (most wavefronts any utterance of the batch uses).
 // Variant for batches whose labels all fit one wavefront: no exchange at all.
-template <bool kStream, Mode kMode>
+template <Mode kMode>
 __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
                            const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -901,12 +897,12 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
                            double* __restrict__ logp, float* __restrict__ costs,
                            int* __restrict__ chain_err, double* __restrict__ sink)
 {
-    lattice_body<Sync::kNone, kStream, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kNone, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                               costs, chain_err, sink, nullptr);
 }
 
 // Multi-wavefront chains with the halo exchange.
-template <bool kStream, Mode kMode>
+template <Mode kMode>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -916,7 +912,7 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ HaloLds halo_lds;
-    lattice_body<Sync::kHalo, kStream, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kHalo, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                               costs, chain_err, sink, &halo_lds);
 }
 
@@ -932,7 +928,7 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
                                 int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ double xch[2][16];
-    lattice_body<Sync::kBarrier, false, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kBarrier, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                                costs, chain_err, sink, &xch[0][0]);
 }
 
@@ -1422,23 +1418,18 @@ int launch_lattice(const Launch& p, void* stream)
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
     const dim3 grid(p.n_run, p.mode == Mode::kGrad ? 2 : 1), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
-    // Stream the lattice past the caches when it is too large to still be there for the gradient.
-    const bool stream_out = p.mode == Mode::kGrad &&
-                            static_cast<size_t>(p.lay.ab_doubles) * 16 > (static_cast<size_t>(192) << 20);
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
     hipLaunchKernelGGL(KERNEL, grid, block, 0, s, meta, order, labels, emit_blank, emit_label,     \
                        alpha, beta, logp, p.costs, chain_err, sink)
     return checked_launch([&] {
         if (p.max_waves == 1) {
-            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<false, Mode::kLoss>));
-            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<false, Mode::kBest>));
-            else if (stream_out) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<true, Mode::kGrad>));
-            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<false, Mode::kGrad>));
+            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<Mode::kLoss>));
+            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<Mode::kBest>));
+            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<Mode::kGrad>));
         } else if (!p.needs_barrier) {
-            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<false, Mode::kLoss>));
-            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<false, Mode::kBest>));
-            else if (stream_out) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<true, Mode::kGrad>));
-            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel<false, Mode::kGrad>));
+            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<Mode::kLoss>));
+            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<Mode::kBest>));
+            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel<Mode::kGrad>));
         } else {
             if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kLoss>);
             else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kBest>);
