@@ -186,46 +186,64 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
                      int Tt, int B, int A, int blank, int max_label, int poll_budget, bool crowded)
 {
     __shared__ long long weight[kMaxDeviceMetaB];     // T_b x wavefronts; -1: does not run
+    __shared__ int repeats[kMaxDeviceMetaB];          // adjacent equal symbols; kBadLabel added for a bad symbol
     __shared__ int s_bad;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int kBadLabel = 1 << 20;
+    const int tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
-    for (int i = tid; i < B; i += kPlanThreads) order[i] = -1;
+    int* const s_len = reinterpret_cast<int*>(weight);       // label lengths, until the weights are written
+    for (int i = tid; i < B; i += kPlanThreads) {
+        order[i] = -1;
+        repeats[i] = 0;
+        s_len[i] = label_lengths[i];
+    }
     __syncthreads();
-    for (int b = wave; b < B; b += kPlanThreads / 64) {
-        const int L = label_lengths[b], Tb = input_lengths[b];
-        bool bad = L < 0 || L > max_label || Tb < 0 || Tb > Tt;
-        const int* lab = labels + static_cast<size_t>(b) * max_label;
-        int repeats = 0;
-        if (!bad) {
-            for (int j = lane; j < L; j += 64) {
-                const int c = lab[j];
-                bad = bad || c < 0 || c >= A || c == blank;
-                if (j > 0 && c == lab[j - 1]) ++repeats;
+    // Every entry of the padded label matrix on its own, eight reads per thread in flight.
+    const int cells = B * max_label;
+    for (int i0 = tid; i0 < cells; i0 += 8 * kPlanThreads) {
+        int c[8], before[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kPlanThreads;
+            c[u] = (i < cells) ? labels[i] : 0;
+            before[u] = (i < cells && i > 0) ? labels[i - 1] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kPlanThreads;
+            if (i >= cells) continue;
+            const int b = i / max_label, j = i - b * max_label;
+            const int L = s_len[b];
+            if (j < L && L <= max_label) {
+                int add = (c[u] < 0 || c[u] >= A || c[u] == blank) ? kBadLabel : 0;
+                if (j > 0 && c[u] == before[u]) ++add;
+                if (add) atomicAdd(&repeats[b], add);
             }
         }
-        bad = __any(bad);
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) repeats += __shfl_xor(repeats, o, 64);
-        const bool runs = !bad && Tb > 0 && Tb >= L + repeats;
+    }
+    __syncthreads();
+    for (int b = tid; b < B; b += kPlanThreads) {
+        const int L = label_lengths[b], Tb = input_lengths[b];
+        const int rep = repeats[b];
+        const bool bad = L < 0 || L > max_label || Tb < 0 || Tb > Tt || rep >= kBadLabel;
+        const bool runs = !bad && Tb > 0 && Tb >= L + rep;
         const WavePlan wp = plan_waves(bad ? 0 : L, crowded);
-        if (lane == 0) {
-            Utt m;
-            m.Tb = bad ? 0 : Tb;
-            m.L = bad ? 0 : L;
-            m.lab_off = b * max_label;
-            m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0);
-            m.f_off = b * Tt;
-            m.waves = wp.waves;
-            m.halo = wp.halo;
-            m.poll_budget = poll_budget;
-            m.e_direct = A <= kDirectMaxA ? 1 : 0;
-            m.e_pitch = m.e_direct ? A : m.L;
-            m.e_off = static_cast<int64_t>(b) * Tt * (m.e_direct ? A : max_label);
-            m.ab_off = static_cast<int64_t>(b) * Tt * (max_label + 1);
-            meta[b] = m;
-            weight[b] = runs ? static_cast<long long>(Tb) * wp.waves : -1;
-            if (bad) s_bad = 1;
-        }
+        Utt m;
+        m.Tb = bad ? 0 : Tb;
+        m.L = bad ? 0 : L;
+        m.lab_off = b * max_label;
+        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0);
+        m.f_off = b * Tt;
+        m.waves = wp.waves;
+        m.halo = wp.halo;
+        m.poll_budget = poll_budget;
+        m.e_direct = A <= kDirectMaxA ? 1 : 0;
+        m.e_pitch = m.e_direct ? A : m.L;
+        m.e_off = static_cast<int64_t>(b) * Tt * (m.e_direct ? A : max_label);
+        m.ab_off = static_cast<int64_t>(b) * Tt * (max_label + 1);
+        meta[b] = m;
+        weight[b] = runs ? static_cast<long long>(Tb) * wp.waves : -1;
+        if (bad) s_bad = 1;
     }
     __syncthreads();
     if (tid == 0) *status = s_bad ? CTC_STATUS_INVALID_VALUE : CTC_STATUS_SUCCESS;
