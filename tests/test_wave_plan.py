@@ -1,0 +1,77 @@
+"""The wavefront plan of the lattice kernels, checked on the CPU for every label length.
+
+plan_waves (paper_1512_02595_amd/csrc/ctc_internal.h) is plain C++ shared by the host launcher and the
+device-side planner; here it is compiled into a small host program and its invariants are checked:
+the kernels index lanes and LDS by them, so a plan outside them would read or write out of bounds.
+"""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+PROGRAM = r"""
+#include <cstdio>
+#include "ctc_internal.h"
+int main()
+{
+    for (int crowded = 0; crowded < 2; ++crowded)
+        for (int L = 0; L <= CTC_MAX_LABEL_LENGTH; ++L) {
+            const ctc::WavePlan p = ctc::plan_waves(L, crowded != 0);
+            std::printf("%d %d %d %d %d\n", crowded, L, p.waves, p.halo, p.barrier ? 1 : 0);
+        }
+    std::printf("chunk %d slack %d %d\n", ctc::kChunk, ctc::kBlankSlack, ctc::kLabelSlack);
+    return 0;
+}
+"""
+
+
+@pytest.fixture(scope="module")
+def plans(tmp_path_factory):
+    d = tmp_path_factory.mktemp("plan")
+    src, exe = d / "plan.cpp", d / "plan"
+    src.write_text(PROGRAM)
+    subprocess.run(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "include"),
+                    "-I", os.path.join(ROOT, "paper_1512_02595_amd", "csrc"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines()
+    rows = [tuple(int(v) for v in line.split()) for line in out if not line.startswith("chunk")]
+    consts = [line for line in out if line.startswith("chunk")][0].split()
+    return rows, {"chunk": int(consts[1]), "blank_slack": int(consts[3]), "label_slack": int(consts[4])}
+
+
+def test_every_label_length_has_a_plan_the_kernels_can_run(plans):
+    rows, c = plans
+    assert len(rows) == 2 * 1024
+    for crowded, L, waves, halo, barrier in rows:
+        pairs = L + 1
+        assert 1 <= waves <= 16, (L, waves)
+        if barrier:
+            # 64 pairs per wavefront, one barrier per step: every pair needs a lane
+            assert halo == 0 and waves * 64 >= pairs, (L, waves)
+            continue
+        if waves == 1:
+            assert halo == 0 and pairs <= 64, (L, waves, halo)
+            continue
+        # halo exchange: hand-overs fall on chunk boundaries, the lanes handed up are exact lanes,
+        # the exchange buffer holds two halves of 32 entries, and every pair has an exact lane
+        assert halo % c["chunk"] == 0 and c["chunk"] <= halo <= 32, (L, waves, halo)
+        assert halo <= 64 - halo
+        assert waves * (64 - halo) + halo >= pairs, (L, waves, halo)
+        # and no wavefront is idle: one fewer would not hold the pairs with this halo
+        assert (waves - 1) * (64 - halo) + halo < pairs or waves == 2, (L, waves, halo)
+
+
+def test_plans_only_switch_to_the_barrier_kernel_when_no_halo_fits(plans):
+    rows, _ = plans
+    for crowded, L, waves, halo, barrier in rows:
+        if barrier:
+            assert 16 * 56 + 8 < L + 1, L
+
+
+def test_emission_margins_cover_the_prefetch(plans):
+    """The lattice kernel requests emissions up to 3 * chunk - 1 rows past an utterance's block."""
+    _, c = plans
+    assert c["label_slack"] >= (3 * c["chunk"] - 1) * 1024
+    assert c["blank_slack"] >= 3 * c["chunk"] - 1 + c["chunk"] - 1
