@@ -260,6 +260,9 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         }
     }
     for (int i = n_run; i < c.B; ++i) order[i] = -1;
+    // The one-barrier-per-step kernel only has the log-domain recursion.
+    if (needs_barrier)
+        for (int b = 0; b < c.B; ++b) meta[b].flags |= kUttLogDomain;
     // Heaviest chains first, so the longest recursion does not start last.
     std::stable_sort(order, order + n_run, [&](int a, int b) {
         const int64_t wa = static_cast<int64_t>(meta[a].Tb) * meta[a].waves;

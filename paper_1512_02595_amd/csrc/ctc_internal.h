@@ -84,6 +84,11 @@ CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length, bool crowded = fals
 
 constexpr int kUttRuns = 1;
 constexpr int kUttInvalid = 2;
+// Set by the softmax launch when some emission of the utterance is too improbable for the
+// linear-domain recursion (below 2^kLinearMinLog2): its chains then run in the log domain.
+// (Also set for every utterance of a launch that uses the one-barrier-per-step kernel.)
+constexpr int kUttLogDomain = 4;
+constexpr float kLinearMinLog2 = -100.0f;
 // Lattice wavefronts of one launch beyond which chains are planned for total work: two per SIMD
 // of the 256 compute units.
 constexpr int kCrowdedWaves = 2 * 4 * 256;
@@ -111,9 +116,12 @@ struct Layout {
     size_t sink = 0;      // 256 bytes that lanes with nothing to store may scribble on
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
     size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits
-    size_t emit_blank = 0; // float[64 + sum Tb + 64]  log2 emission of blank per frame, slack both sides
-    size_t emit_label = 0; // float[slack + sum Tb*L + slack]  log2 emission of each label position;
-                           // the first float of the front slack holds the log-0 constant
+    size_t emit_blank = 0; // float[slack + sum Tb + slack]  emission of blank per frame: the probability y, or
+                           // log2 y (negative) where y < 2^kLinearMinLog2 (plain log2 y in launches for
+                           // the most probable alignment)
+    size_t emit_label = 0; // float[slack + sum Tb*L + slack]  emission of each label position, same coding;
+                           // the first two floats of the front slack hold the constants that lanes
+                           // without a label state read: probability 0 and log 0
     size_t alpha = 0;     // double[sum Tb*(L+1)]   label states only
     size_t beta = 0;      // double[sum Tb*(L+1)]
     size_t total = 0;

@@ -183,7 +183,8 @@ __global__ __launch_bounds__(kPlanThreads)
 void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ label_lengths,
                      const int* __restrict__ input_lengths, Utt* __restrict__ meta,
                      int* __restrict__ order, int* __restrict__ status,
-                     int Tt, int B, int A, int blank, int max_label, int poll_budget, bool crowded)
+                     int Tt, int B, int A, int blank, int max_label, int poll_budget, bool crowded,
+                     bool log_domain)
 {
     __shared__ long long weight[kMaxDeviceMetaB];     // T_b x wavefronts; -1: does not run
     __shared__ int repeats[kMaxDeviceMetaB];          // adjacent equal symbols; kBadLabel added for a bad symbol
@@ -232,7 +233,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         m.Tb = bad ? 0 : Tb;
         m.L = bad ? 0 : L;
         m.lab_off = b * max_label;
-        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0);
+        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) | (log_domain ? kUttLogDomain : 0);
         m.f_off = b * Tt;
         m.waves = wp.waves;
         m.halo = wp.halo;
@@ -271,7 +272,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
 // The gradient kernels write each state's mass share to its slot and let the first occurrence
 // add up the run in slot order, so a symbol's occupancy has one writer and a fixed order of
 // summation.  Also here: costs of utterances without a lattice, the per-utterance error
-// flags, the log-0 constant of the emission array.
+// flags, the two constants of the emission array.
 constexpr int kLinkSlotMask = 0x3FF, kLinkCountShift = 12;
 static_assert(CTC_MAX_LABEL_LENGTH <= kLinkSlotMask, "slot and count fields hold 10 bits");
 
@@ -279,9 +280,11 @@ struct SetupArgs {
     int* links;
     float* costs;
     int* chain_err;
-    float* log0;          // the float that lattice lanes without a label state read as their emission
+    float* log0;          // two floats that lattice lanes without a label state read as their emission:
+                          // [0] probability 0 (linear-domain chains), [1] log 0 (log-domain chains)
     int* host_flag;       // pinned host word: receives flag_value once the upload has been consumed
     int flag_value;
+    bool plain_logs;      // emissions are stored as log2 probabilities throughout (most probable alignment)
 };
 
 __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* __restrict__ labels,
@@ -307,7 +310,8 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
     if (tid == 0) {
         sa.chain_err[b] = 0;
         if (b == 0) {
-            sa.log0[0] = static_cast<float>(kNeg);
+            sa.log0[0] = 0.0f;
+            sa.log0[1] = static_cast<float>(kNeg);
             // This launch follows the upload kernel on the stream, so the host may now reuse
             // the pinned image.
             if (sa.host_flag)
@@ -317,6 +321,27 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
         if (m.flags & kUttInvalid) sa.costs[b] = __uint_as_float(0x7FC00000u);
         else if (!(m.flags & kUttRuns)) sa.costs[b] = (m.Tb == 0 && m.L == 0) ? 0.0f : __builtin_inff();
     }
+}
+
+// ---- emission coding -------------------------------------------------------------------------
+// The recursions run on probabilities (linear domain, see run_chain_linear) unless some
+// emission of the utterance is too small for that; an emission is therefore stored as the
+// probability y = 2^lp itself, or, where lp < kLinearMinLog2, as lp (a negative float, which
+// no probability is).  A lane that stores such a value raises the utterance's kUttLogDomain
+// flag, and its chains then take log2 of the stored probabilities instead.
+// (The most probable alignment has no sums to speed up: its launches store plain logarithms.)
+__device__ __forceinline__ float encode_emission(float lp, bool& small, bool plain_logs)
+{
+    if (plain_logs) return lp;
+    if (lp >= kLinearMinLog2) return fast_exp2(lp);
+    small = true;
+    return lp;
+}
+__device__ __forceinline__ float emission_log2(float v) { return v > 0.0f ? fast_log2(v) : v; }
+__device__ __forceinline__ float emission_probability(float v) { return fmaxf(v, 0.0f); }
+__device__ __forceinline__ void raise_log_domain(Utt* meta, int b, bool small)
+{
+    if (small) atomicOr(&meta[b].flags, kUttLogDomain);
 }
 
 // ---- softmax statistics + emission gather --------------------------------------------------
@@ -330,7 +355,7 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
-                        const Utt* __restrict__ meta,
+                        Utt* __restrict__ meta,
                         const int* __restrict__ labels, float* __restrict__ lse,
                         float* __restrict__ emit_blank, float* __restrict__ emit_label,
                         const SetupArgs sa, int Tt, int B, int A, int blank)
@@ -363,12 +388,14 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
     if (grads)
         for (int k = threadIdx.x; k < A; k += kRowThreads)
             store_elem(grow, k, fast_exp2(fmaf(load_elem(row, k), kLog2e, -l2)));
+    bool small = false;
     if (threadIdx.x == 0)
-        emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
+        emit_blank[kBlankSlack + m.f_off + t] = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = threadIdx.x; j < m.L; j += kRowThreads)
-        erow[j] = fmaf(load_elem(row, lab[j]), kLog2e, -l2);
+        erow[j] = encode_emission(fmaf(load_elem(row, lab[j]), kLog2e, -l2), small, sa.plain_logs);
+    raise_log_domain(meta, b, small);
 }
 
 // Wide alphabets, 16-byte aligned rows of at most 8192 symbols: the row is read once with
@@ -378,7 +405,7 @@ constexpr int kWideMaxA = 8192;
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
-                             const Utt* __restrict__ meta,
+                             Utt* __restrict__ meta,
                              const int* __restrict__ labels, float* __restrict__ lse,
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
                              const SetupArgs sa, int Tt, int B, int A, int blank)
@@ -437,11 +464,14 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
             Vec<T>::store(grow + static_cast<size_t>(idx) * N, y);
         }
     }
-    if (tid == 0) emit_blank[kBlankSlack + m.f_off + t] = fmaf(load_elem(row, blank), kLog2e, -l2);
+    bool small = false;
+    if (tid == 0)
+        emit_blank[kBlankSlack + m.f_off + t] = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = tid; j < m.L; j += kRowThreads)
-        erow[j] = fmaf(load_elem(row, lab[j]), kLog2e, -l2);
+        erow[j] = encode_emission(fmaf(load_elem(row, lab[j]), kLog2e, -l2), small, sa.plain_logs);
+    raise_log_domain(meta, b, small);
 }
 
 // Narrow alphabets: a workgroup takes kRows consecutive frames of one utterance, 256 / kRows
@@ -451,7 +481,7 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
 // does the setup role.
 template <typename T, int kRows>
 __global__ __launch_bounds__(kRowThreads)
-void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ meta,
+void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
                              const int* __restrict__ labels, float* __restrict__ lse,
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
                              const SetupArgs sa, int Tt, int B, int A, int blank)
@@ -494,24 +524,72 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, const Utt* __restrict__ me
         for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
         sum = (kPerRow == 16) ? row16_sum(sum) : wave_sum(sum);
         const float l2 = mx + fast_log2(sum);
-        for (int k = q; k < A; k += kPerRow) lrow[k] = fmaf(lrow[k], kLog2e, -l2);
+        // (coded as emissions; `unused` because what counts is which of them get stored below)
+        bool unused = false;
+        for (int k = q; k < A; k += kPerRow) lrow[k] = encode_emission(fmaf(lrow[k], kLog2e, -l2), unused, sa.plain_logs);
         if (q == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
     }
     if (!(m.flags & kUttRuns)) return;
     __syncthreads();
     const int rows = min(kRows, m.Tb - t0);
-    if (tid < rows) emit_blank[kBlankSlack + m.f_off + t0 + tid] = lp[tid * A + blank];
+    bool small = false;
+    if (tid < rows) {
+        const float e = lp[tid * A + blank];
+        emit_blank[kBlankSlack + m.f_off + t0 + tid] = e;
+        small = !sa.plain_logs && e < 0.0f;
+    }
     if (m.e_direct) {
         // Small alphabet: the rows themselves are the emission block (row pitch A).
         float* out = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * A;
-        for (int i = tid; i < rows * A; i += kRowThreads) out[i] = lp[i];
+        for (int i = tid; i < rows * A; i += kRowThreads) {
+            const float e = lp[i];
+            out[i] = e;
+            small = small || (!sa.plain_logs && e < 0.0f);
+        }
+        raise_log_domain(meta, b, small);
         return;
     }
     float* ebase = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * m.L;
     for (int j = tid; j < m.L; j += kRowThreads) {
         const int c = (j == tid) ? c_first : lab[j];
-        for (int rr = 0; rr < rows; ++rr) ebase[static_cast<size_t>(rr) * m.L + j] = lp[rr * A + c];
+        for (int rr = 0; rr < rows; ++rr) {
+            const float e = lp[rr * A + c];
+            ebase[static_cast<size_t>(rr) * m.L + j] = e;
+            small = small || (!sa.plain_logs && e < 0.0f);
+        }
     }
+    raise_log_domain(meta, b, small);
+}
+
+// ---- lattice storage -------------------------------------------------------------------------
+// What the recursions leave for the gradient, per label state and frame, and for the mass p per
+// utterance: a number m * 2^e as one 8-byte word,
+//   low  dword: e, int32
+//   high dword: the high dword of the fp64 m (sign, exponent, top 20 mantissa bits)
+// so that a linear-domain chain stores (frame, value in that frame) as they stand, with no
+// arithmetic on the way out.  Twenty mantissa bits bound the relative error of a state's share
+// alpha * beta / p by 2^-19, which is 2e-6 of a gradient entry at most.  Exponents stay above
+// -2^30 so that the sum of two cannot wrap.
+__device__ __forceinline__ double pack_state(double in_frame, int frame)
+{
+    return __hiloint2double(__double2hiint(in_frame), frame);
+}
+// From a base-2 logarithm (log-domain chains): m = 2^fraction in [1, 2), e = floor.
+__device__ __forceinline__ double pack_log2(double w)
+{
+    const double whole = floor(w);
+    const double m = static_cast<double>(fast_exp2(static_cast<float>(w - whole)));
+    // log 0 (and anything as small) is stored as the number 0; so is the reciprocal of a p that small
+    return (w > -1.0e9 && w < 1.0e9) ? pack_state(m, static_cast<int>(whole)) : 0.0;
+}
+// alpha * beta * (1 / p) from three packed words.  (The exponent in the low dword reads as the
+// last mantissa bits: a relative 2^-20 at most, and a stored zero reads as less than 2^-1040.)
+__device__ __forceinline__ float mass_share(double a, double b, float inverse_p_mantissa, int inverse_p_exponent)
+{
+    // m_a < 2^(kChunk + 2): 2^1000 m_a cannot overflow, and a share that needed more than that
+    // is of values that had been rounded away in their frames anyway.
+    const int e = min(__double2loint(a) + __double2loint(b) + inverse_p_exponent, 1000);
+    return static_cast<float>(__builtin_amdgcn_ldexp(a, e) * b) * inverse_p_mantissa;
 }
 
 // ---- lattice recursions ------------------------------------------------------------------
@@ -545,6 +623,7 @@ constexpr int kFromSame = 0, kFromBlank = 1 << 2, kFromPrevLabel = 2 << 2, kBlan
 // LDS of the halo exchange: per wavefront w, what w hands to w+1.
 struct HaloLds {
     double2 data[16][kHaloEntries];
+    int frame[16][kHaloEntries];      // linear-domain chains: the frame exponent that goes with each entry
     int ready[16];                    // last generation wavefront w has published
     int done[16];                     // last generation wavefront w has taken from w-1
     // Cost-only chains: the last wavefront to finish writes the cost (or NaN if any gave up).
@@ -587,7 +666,7 @@ struct HaloLds {
 // ones and for space only on higher ones, wavefront 0 needs no data and the last one no space,
 // so every wait ends; a poll budget bounds them regardless and raises chain_err when spent.
 template <bool kBackward, Sync kSync, Mode kMode>
-__device__ __forceinline__ void run_chain(const Utt m, const int u, const int* __restrict__ labels,
+__device__ __forceinline__ void run_chain_log(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
                                           void* __restrict__ out, double* __restrict__ logp,
@@ -595,6 +674,8 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
                                           double* __restrict__ sink, void* lds)
 {
     static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
+    // Launches for the most probable alignment store plain logarithms, the others coded emissions.
+    constexpr bool kCoded = kMode != Mode::kBest;
     const int L = m.L, Tb = m.Tb, P = L + 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
@@ -614,7 +695,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     // state reads a constant log 0 and stays there.
     const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch +
                                       (m.e_direct ? lab[li] : li)
-                                : emit_label;
+                                : emit_label + 1;
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
@@ -724,13 +805,13 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
 
     auto finish_step = [&](float eb, float el) {
         v_blank = i_blank + static_cast<double>(eb);
-        v_label = i_label + static_cast<double>(el);
+        v_label = i_label + static_cast<double>(kCoded ? emission_log2(el) : el);
         if (kMode == Mode::kBest) {
             *op = static_cast<unsigned char>(choice);
         } else if (kMode == Mode::kLoss) {
             // nothing is kept
         } else {
-            *reinterpret_cast<double*>(op) = kBackward ? i_label : v_label;
+            *reinterpret_cast<double*>(op) = pack_log2(kBackward ? i_label : v_label);
         }
         op += ostride;
     };
@@ -772,12 +853,12 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
 
     // step 0: every lane starts from the exact state of its pair, halo lanes included
     {
-        const float ebv = *bp;
-        const float el = *ep;
+        const float ebv = kCoded ? emission_log2(*bp) : *bp;
+        const float el = kCoded ? emission_log2(*ep) : *ep;
         v_blank = i_blank + static_cast<double>(readlane(ebv, 0));
         v_label = i_label + static_cast<double>(el);
         // (the predecessor choices of frame 0 are never looked at: nothing is written for it)
-        if (kMode == Mode::kGrad) *reinterpret_cast<double*>(op) = kBackward ? i_label : v_label;
+        if (kMode == Mode::kGrad) *reinterpret_cast<double*>(op) = pack_log2(kBackward ? i_label : v_label);
         op += ostride;
     }
 
@@ -795,7 +876,8 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
     // inside the instruction cache that two compute units share.
     // Whole chunks run without looking at the step number; only the last, short chunk of a
     // chain checks every step against the end.
-    auto run = [&](const float (&el)[kChunk], const float eb, int s0) {
+    auto run = [&](const float (&el)[kChunk], const float eb_coded, int s0) {
+        const float eb = kCoded ? emission_log2(eb_coded) : eb_coded;
         if (s0 + kChunk <= Tb) {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i) advance(s0 + i, readlane(eb, i), el[i]);
@@ -832,7 +914,7 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
                 costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
             } else {
                 const double lp = lse2(v_blank, prev);
-                logp[u] = lp;
+                logp[u] = pack_log2(-lp);          // 1 / p
                 const float cost = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
                 if (kSync == Sync::kHalo && kMode == Mode::kLoss) hl->cost = cost;
                 else costs[u] = cost;
@@ -854,6 +936,266 @@ __device__ __forceinline__ void run_chain(const Utt m, const int u, const int* _
             const int lost = __hip_atomic_load(&hl->gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             const float cost = hl->cost;
             costs[u] = lost ? __uint_as_float(0x7FC00000u) : cost;
+        }
+    } else if (kSync == Sync::kHalo && lost && lane == 0) {
+        chain_err[u] = 1;
+    }
+}
+
+// The same chain on probabilities instead of their logarithms: a step is then two fused
+// multiply-adds, an addition and two multiplications per pair, a third of the instructions of the
+// log-domain step and no transcendentals.  What makes it safe is an exponent per lane:
+//   true value = (v_blank, v_label) * 2^frame
+// with fp64 values and an int32 `frame` that is renewed after every chunk of kChunk steps:
+//   frame = largest binary exponent among this pair and the kChunk pairs below it.
+// Mass moves up by at most one pair per step, so until the next renewal everything that can
+// reach the pair is at most 2^(kChunk+1) in its frame (no overflow), and its own mass cannot
+// shrink by more than kChunk emissions, each at least 2^kLinearMinLog2, that is 800 of fp64's
+// 1022 binary orders of magnitude (utterances with smaller emissions run the log-domain chain).
+// Only what lies more than about 2^-1000 below the largest of its nine-pair window is rounded
+// away.  The value shifted in from the pair below is brought into this lane's frame by `scale`
+// = 2^(frame below - frame here), constant between renewals and folded into the multiply-adds.
+//
+// Storage (Mode::kGrad): the label state's value and its frame at every step, in one word
+// (pack_state).  The gradient kernels do not know which kind of chain wrote the lattice.
+constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real one, far from int32's ends
+
+template <bool kBackward, Sync kSync, Mode kMode>
+__device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
+                                                 const float* __restrict__ emit_blank,
+                                                 const float* __restrict__ emit_label,
+                                                 void* __restrict__ out, double* __restrict__ logp,
+                                                 float* __restrict__ costs, int* __restrict__ chain_err,
+                                                 double* __restrict__ sink, void* lds)
+{
+    static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
+    static_assert(kSync != Sync::kBarrier, "the barrier kernel runs the log-domain chain");
+    static_assert(kMode != Mode::kBest, "the maximum recursion runs in the log domain");
+    const int L = m.L, Tb = m.Tb, P = L + 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
+    const int j = wave * (64 - halo) + lane;             // pair of this lane (see run_chain_log)
+    const int* lab = labels + m.lab_off;
+    const bool has_label = j >= 0 && j < L;
+    const bool active = (wave == 0 || lane >= halo) && j <= L;
+    const int li = kBackward ? (L - 1 - j) : j;
+    const bool skip_ok = has_label && j >= 1 && lab[li] != lab[kBackward ? (li + 1) : (li - 1)];
+
+    const int f0 = kBackward ? (Tb - 1) : 0;
+    const int fdir = kBackward ? -1 : 1;
+    // A lane without a label state reads a constant probability 0 and stays there.
+    const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch +
+                                      (m.e_direct ? lab[li] : li)
+                                : emit_label;
+    const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
+    const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    const bool stores = kMode == Mode::kGrad && active && has_label;
+    double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * P + li : sink;
+    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * P : 0;
+
+    HaloLds* const hl = static_cast<HaloLds*>(lds);
+    const int last_wave = m.waves - 1;
+    int budget = m.poll_budget;
+    bool lost = false;
+    const int chunks_per_hand_over = halo / kChunk;
+    int until_hand_over = chunks_per_hand_over;
+    int generation = 0;
+    int half = 0;
+    const int wr_slot = lane >= 64 - halo ? lane - (64 - halo) : 0;
+    const int rd_slot = lane < halo ? lane : 0;
+    double2* const wr_base = (kSync == Sync::kHalo) ? &hl->data[wave][wr_slot] : nullptr;
+    const double2* const rd_base = (kSync == Sync::kHalo) ? &hl->data[wave > 0 ? wave - 1 : 0][rd_slot] : nullptr;
+    int* const wr_frame = (kSync == Sync::kHalo) ? &hl->frame[wave][wr_slot] : nullptr;
+    const int* const rd_frame = (kSync == Sync::kHalo) ? &hl->frame[wave > 0 ? wave - 1 : 0][rd_slot] : nullptr;
+    int* const my_ready = &hl->ready[wave];
+    int* const my_done = &hl->done[wave];
+    int* const up_done = &hl->done[wave < 15 ? wave + 1 : 15];
+    int* const low_ready = &hl->ready[wave > 0 ? wave - 1 : 0];
+
+    double i_blank = (j == 0) ? 1.0 : 0.0;
+    double i_label = (j == 0 && has_label) ? 1.0 : 0.0;
+    double v_blank, v_label;
+    int frame = 0;
+    double scale = 1.0;                                  // 2^(frame of the pair below - frame)
+    double skip_scale = skip_ok ? 1.0 : 0.0;             // the same where the label may be entered from that pair's label
+
+    auto counter = [&](int* p) {
+        return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto uniform = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+    int done_seen = 0;
+    // The exchange protocol of run_chain_log; an entry carries the pair's frame as well.
+    auto hand_over = [&]() {
+        ++generation;
+        half ^= 32;
+        if (wave < last_wave) {
+            int seen = uniform(done_seen);
+            if (__builtin_expect(seen < generation - 2, 0)) {
+                while (seen < generation - 2 && budget > 0) {
+                    --budget;
+                    seen = uniform(counter(up_done));
+                }
+                lost = lost || seen < generation - 2;
+            }
+            if (lane >= 64 - halo) {
+                wr_base[half] = make_double2(v_blank, v_label);
+                wr_frame[half] = frame;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 63) __hip_atomic_store(my_ready, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            done_seen = counter(up_done);
+        }
+        if (wave > 0) {
+            int ready = counter(low_ready);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            double2 v = rd_base[half];
+            int vf = rd_frame[half];
+            ready = uniform(ready);
+            if (__builtin_expect(ready < generation, 0)) {
+                while (ready < generation && budget > 0) {
+                    --budget;
+                    ready = counter(low_ready);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    v = rd_base[half];
+                    vf = rd_frame[half];
+                    ready = uniform(ready);
+                }
+                lost = lost || ready < generation;
+            }
+            if (lane < halo) {
+                v_blank = v.x;
+                v_label = v.y;
+                frame = vf;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 0) __hip_atomic_store(my_done, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    };
+
+    // Label value of pair j-1 after the last step, in that pair's frame (0 for pair 0: the shift
+    // leaves lane 0 what it had).
+    int prev_lo = 0, prev_hi = 0;
+    auto from_prev_pair = [&](double mine) { return shift_up(mine, prev_lo, prev_hi); };
+    auto shift_up_int = [](int v) { return __builtin_amdgcn_update_dpp(kNoExponent, v, 0x138, 0xf, 0xf, false); };
+
+    // New frames after a chunk.  (A pair whose window holds no mass yet gets kNoExponent: its
+    // values are zero and stay zero whatever the exponent.)
+    auto renew_frames = [&]() {
+        const double top = fmax(v_blank, v_label);
+        const int mine = (top > 0.0) ? frame + __builtin_amdgcn_frexp_exp(top) : kNoExponent;
+        int window = mine;
+#pragma unroll
+        for (int k = 0; k < kChunk; ++k) window = max(mine, shift_up_int(window));
+        const int rise = frame - window;
+        v_blank = __builtin_amdgcn_ldexp(v_blank, rise);
+        v_label = __builtin_amdgcn_ldexp(v_label, rise);
+        frame = window;
+        // 2^1023 is the largest factor there is; a pair that far below its neighbour has been
+        // rounded away already.
+        const int below = min(max(shift_up_int(window) - window, -1100), 1023);
+        scale = __builtin_amdgcn_ldexp(1.0, below);
+        skip_scale = skip_ok ? scale : 0.0;
+    };
+
+    auto finish_step = [&](float eb, float el) {
+        v_blank = i_blank * static_cast<double>(eb);
+        v_label = i_label * static_cast<double>(el);
+        if (kMode == Mode::kGrad) *op = pack_state(kBackward ? i_label : v_label, frame);
+        op += ostride;
+    };
+    auto end_chunk = [&]() {
+        if (kSync == Sync::kHalo) {
+            if (--until_hand_over == 0) {
+                hand_over();
+                until_hand_over = chunks_per_hand_over;
+            }
+        }
+        renew_frames();
+    };
+    auto advance = [&](float eb, float el) {
+        // The blank state sums its own value and the label of the pair before; the label state
+        // its own value, the old blank and, where the skip is allowed, that label too.
+        const double prev = from_prev_pair(v_label);
+        i_blank = __builtin_fma(prev, scale, v_blank);
+        i_label = v_label + __builtin_fma(prev, skip_scale, v_blank);
+        finish_step(eb, el);
+    };
+    auto readlane = [](float v, int l) {
+        return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
+    };
+
+    // step 0
+    {
+        const float ebv = *bp;
+        const float el = *ep;
+        v_blank = i_blank * static_cast<double>(readlane(ebv, 0));
+        v_label = i_label * static_cast<double>(el);
+        if (kMode == Mode::kGrad) *op = pack_state(kBackward ? i_label : v_label, frame);
+        op += ostride;
+    }
+
+    // Emissions of steps 1..: two register sets, one in use, one being filled (as run_chain_log).
+    float el_a[kChunk], el_b[kChunk], eb_a, eb_b;
+    auto fetch = [&](float (&el)[kChunk], float& eb, int s0) {
+        eb = bp[fdir * s0];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            ep += estride;
+            el[i] = *ep;
+        }
+    };
+    auto run = [&](const float (&el)[kChunk], const float eb, int s0) {
+        if (s0 + kChunk <= Tb) {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i) advance(readlane(eb, i), el[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i)
+                if (s0 + i < Tb) advance(readlane(eb, i), el[i]);
+        }
+    };
+    fetch(el_a, eb_a, 1);
+    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
+        fetch(el_b, eb_b, s0 + kChunk);
+        run(el_a, eb_a, s0);
+        end_chunk();
+        fetch(el_a, eb_a, s0 + 2 * kChunk);
+        if (s0 + kChunk < Tb) {
+            run(el_b, eb_b, s0 + kChunk);
+            end_chunk();
+        }
+    }
+
+    if (!kBackward) {
+        // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1), from the lane of pair L (exact, as is the
+        // lane below it: see run_chain_log).
+        const double from_below = from_prev_pair(v_label) * scale;
+        if (active && j == L) {
+            // p = mantissa * 2^exponent, mantissa in [0.5, 1)
+            const double p = v_blank + from_below;
+            const double mantissa = __builtin_amdgcn_frexp_mant(p);
+            const int exponent = frame + __builtin_amdgcn_frexp_exp(p);
+            const double l2 = static_cast<double>(exponent) +
+                              static_cast<double>(fast_log2(static_cast<float>(mantissa)));
+            logp[u] = (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0;     // 1 / p
+            const float cost = (p > 0.0) ? static_cast<float>(-l2 * kLn2) : __builtin_inff();
+            if (kSync == Sync::kHalo && kMode == Mode::kLoss) hl->cost = cost;
+            else costs[u] = cost;
+        }
+    }
+    if (kSync == Sync::kHalo && kMode == Mode::kLoss) {
+        // as in run_chain_log: the wavefront that finishes last writes the cost
+        if (lost && lane == 0) hl->gave_up = 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        int before = 0;
+        if (lane == 0)
+            before = __hip_atomic_fetch_add(&hl->finished, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        before = __builtin_amdgcn_readfirstlane(before);
+        if (before == m.waves - 1 && lane == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int any_lost = __hip_atomic_load(&hl->gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const float cost = hl->cost;
+            costs[u] = any_lost ? __uint_as_float(0x7FC00000u) : cost;
         }
     } else if (kSync == Sync::kHalo && lost && lane == 0) {
         chain_err[u] = 1;
@@ -895,10 +1237,23 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
             return;
         }
     }
-    if (kMode != Mode::kGrad || blockIdx.y == 0)
-        run_chain<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
-    else
-        run_chain<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+    const bool forward = kMode != Mode::kGrad || blockIdx.y == 0;
+    bool in_log_domain = true;                  // all the barrier kernel has, and what the maximum recursion uses
+    if constexpr (kSync != Sync::kBarrier && kMode != Mode::kBest) {
+        in_log_domain = (m.flags & kUttLogDomain) != 0;
+        if (!in_log_domain) {
+            if (forward)
+                run_chain_linear<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+            else
+                run_chain_linear<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+        }
+    }
+    if (in_log_domain) {
+        if (forward)
+            run_chain_log<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+        else
+            run_chain_log<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+    }
 }
 
 // grid = (utterances whose lattice runs, 2) for Mode::kGrad: y = 0 forward, y = 1 backward;
@@ -1016,7 +1371,7 @@ void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __r
 }
 
 // ---- gradient ------------------------------------------------------------------------------
-//   gamma_t(s) = 2^(alpha_t(s) + beta_t(s) - log2 p)        mass share of state s
+//   gamma_t(s) = alpha_t(s) * beta_t(s) / p                 mass share of state s (mass_share)
 //   grad[k]    = y_t(k) - sum_{s: symbol(s) = k} gamma_t(s)
 // Only the label states' gamma are computed from the stored lattice; the blank column gets
 // 1 - (sum over label states), which is the blank states' share because the shares of all
@@ -1066,7 +1421,9 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         __syncthreads();
     }
     const size_t pitch = static_cast<size_t>(P);
-    const double lp = runs ? logp[b] : 0.0;
+    const double packed_inverse_p = runs ? logp[b] : 0.0;
+    const float inverse_p = static_cast<float>(packed_inverse_p);
+    const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
     const double* const abase = alpha + m.ab_off;
     const double* const bbase = beta + m.ab_off;
@@ -1124,7 +1481,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         for (int u = 0; u < kAhead; ++u) {
             const int j = u * 64 + lane;
             if (j < L) {
-                const float gl = fast_exp2(static_cast<float>(cur.a[u] + cur.b[u] - lp));
+                const float gl = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
                 g_label[s_lnk[j] & kLinkSlotMask] = gl;
                 zl += gl;
             }
@@ -1146,7 +1503,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                 for (int u = 0; u < kAhead; ++u) {
                     const int j = j0 + u * 64 + lane;
                     if (j < L) {
-                        const float gl = fast_exp2(static_cast<float>(a[u] + bb[u] - lp));
+                        const float gl = mass_share(a[u], bb[u], inverse_p, inverse_p_exponent);
                         g_label[s_lnk[j] & kLinkSlotMask] = gl;
                         zl += gl;
                     }
@@ -1177,21 +1534,21 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                 }
                 const int c = s_lab[j];
                 if (kSparse) {
-                    // y of a label's symbol is 2^(its emission), which the softmax launch gathered
+                    // y of a label's symbol is its emission, which the softmax launch gathered
                     // next to its neighbours': no scattered read of the activations.
                     const int u = j >> 6;
                     float e = 0.0f;
 #pragma unroll
                     for (int k = 0; k < kAhead; ++k) e = (u == k) ? cur.e[k] : e;
                     if (u >= kAhead) e = erow[j];
-                    store_elem(grow, c, fast_exp2(e) - o);
+                    store_elem(grow, c, emission_probability(e) - o);
                 } else {
                     occ[c] = o;
                 }
             }
         }
         if (kSparse) {
-            if (lane == 0) store_elem(grow, blank, fast_exp2(cur.eb) - zb);
+            if (lane == 0) store_elem(grow, blank, emission_probability(cur.eb) - zb);
         } else {
             if (lane == 0) occ[blank] = zb;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1257,7 +1614,9 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         __syncthreads();
     }
     const size_t pitch = static_cast<size_t>(P);
-    const double lp = runs ? logp[b] : 0.0;
+    const double packed_inverse_p = runs ? logp[b] : 0.0;
+    const float inverse_p = static_cast<float>(packed_inverse_p);
+    const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
     const double* const abase = alpha + m.ab_off;
     const double* const bbase = beta + m.ab_off;
@@ -1287,13 +1646,13 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         for (int u = 0; u < kAhead; ++u) {
             const int j = u * 64 + lane;
             if (j < L) {
-                const float gl = fast_exp2(static_cast<float>(a[u] + bb[u] - lp));
+                const float gl = mass_share(a[u], bb[u], inverse_p, inverse_p_exponent);
                 g_slot[s_slot[j]] = gl;
                 zl += gl;
             }
         }
         for (int j = kAhead * 64 + lane; j < L; j += 64) {
-            const float gl = fast_exp2(static_cast<float>(arow[j] + brow[j] - lp));
+            const float gl = mass_share(arow[j], brow[j], inverse_p, inverse_p_exponent);
             g_slot[s_slot[j]] = gl;
             zl += gl;
         }
@@ -1357,20 +1716,21 @@ int launch_plan(const Launch& p, void* stream)
         hipLaunchKernelGGL(ctc_plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(stream),
                            p.labels, p.dev_label_lengths, p.dev_input_lengths,
                            reinterpret_cast<Utt*>(p.ws + p.lay.meta), reinterpret_cast<int*>(p.ws + p.lay.order),
-                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label, p.poll_budget, p.crowded);
+                           p.dev_status, p.T, p.B, p.A, p.blank, p.max_label, p.poll_budget, p.crowded,
+                           p.needs_barrier);
     });
 }
 
 int launch_softmax(const Launch& p, void* stream)
 {
-    auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
+    auto* meta = reinterpret_cast<Utt*>(p.ws + p.lay.meta);
     const int* labels = p.labels;
     auto* lse = reinterpret_cast<float*>(p.ws + p.lay.lse);
     auto* emit_blank = reinterpret_cast<float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
     const SetupArgs sa{reinterpret_cast<int*>(p.ws + p.lay.links), p.costs,
                        reinterpret_cast<int*>(p.ws + p.lay.chain_err), emit_label,
-                       p.host_flag, p.host_flag_value};
+                       p.host_flag, p.host_flag_value, p.mode == Mode::kBest};
     const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;

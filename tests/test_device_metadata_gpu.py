@@ -15,7 +15,7 @@ from paper_1512_02595_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-def both_paths(batch, dtype=ctc.DTYPE_F32, max_label=None):
+def both_paths(batch, dtype=ctc.DTYPE_F32, max_label=None, same_kernels=True):
     print(f"device-metadata case {batch.name} seed={batch.seed} T={batch.T} B={batch.B} A={batch.A}", flush=True)
     max_label = int(batch.label_lengths.max()) if max_label is None else max_label
     dm = harness.DeviceMetaBatch(batch.T, batch.B, batch.A, max_label, batch.blank, dtype)
@@ -25,8 +25,15 @@ def both_paths(batch, dtype=ctc.DTYPE_F32, max_label=None):
     status, costs, grads = dm.results()
     ref_costs, ref_grads = harness.run_batch(batch, dtype)
     assert status == ctc.STATUS_SUCCESS
-    assert np.array_equal(costs, ref_costs, equal_nan=True)
-    assert np.array_equal(grads, ref_grads)
+    if same_kernels:
+        assert np.array_equal(costs, ref_costs, equal_nan=True)
+        assert np.array_equal(grads, ref_grads)
+    else:
+        # a different recursion kernel: the same numbers up to rounding
+        assert np.array_equal(np.isfinite(costs), np.isfinite(ref_costs))
+        ok = np.isfinite(ref_costs)
+        assert np.abs(costs[ok] - ref_costs[ok]).max() <= 1e-5 * max(np.abs(ref_costs[ok]).max(), 1e-2)
+        assert np.abs(grads - ref_grads).max() <= 2e-5
     return dm, costs, grads
 
 
@@ -54,7 +61,9 @@ def test_matches_the_host_metadata_call_on_other_shapes(maker):
 def test_bounds_far_above_the_actual_labels():
     """A label bound that only the barrier kernel serves, on a batch of short labels; and a bound that makes
     the launch as wide as sixteen wavefronts while the labels need one or two."""
-    both_paths(wl.make_random(31, T=60, B=3, A=5, max_label=20, min_input=30), max_label=ctc.MAX_LABEL_LENGTH)
+    # (the barrier kernel recurs on logarithms, the host call's kernel for short labels on probabilities)
+    both_paths(wl.make_random(31, T=60, B=3, A=5, max_label=20, min_input=30), max_label=ctc.MAX_LABEL_LENGTH,
+               same_kernels=False)
     both_paths(wl.make_random(32, T=150, B=5, A=6, max_label=100, min_input=120, feasible_only=True), max_label=900)
 
 
