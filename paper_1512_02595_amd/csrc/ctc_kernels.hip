@@ -584,12 +584,17 @@ __device__ __forceinline__ double pack_log2(double w)
 }
 // alpha * beta * (1 / p) from three packed words.  (The exponent in the low dword reads as the
 // last mantissa bits: a relative 2^-20 at most, and a stored zero reads as less than 2^-1040.)
+// Either of alpha and beta may lie a thousand binary orders below the top of its own frame
+// while their product is a share of order one, so the exponent that the three words add up to
+// is spread over both factors before they are multiplied.  m_a, m_b < 2^(kChunk + 2) in their
+// frames, hence 2^1000 of either cannot overflow; a share that needed more is of values that
+// had been rounded away in their frames.
 __device__ __forceinline__ float mass_share(double a, double b, float inverse_p_mantissa, int inverse_p_exponent)
 {
-    // m_a < 2^(kChunk + 2): 2^1000 m_a cannot overflow, and a share that needed more than that
-    // is of values that had been rounded away in their frames anyway.
-    const int e = min(__double2loint(a) + __double2loint(b) + inverse_p_exponent, 1000);
-    return static_cast<float>(__builtin_amdgcn_ldexp(a, e) * b) * inverse_p_mantissa;
+    const int e = min(__double2loint(a) + __double2loint(b) + inverse_p_exponent, 2000);
+    const int half = e >> 1;
+    return static_cast<float>(__builtin_amdgcn_ldexp(a, half) * __builtin_amdgcn_ldexp(b, e - half)) *
+           inverse_p_mantissa;
 }
 
 // ---- lattice recursions ------------------------------------------------------------------

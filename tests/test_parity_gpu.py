@@ -124,6 +124,37 @@ def test_worst_case_spread_of_random_logits():
     check(wl.make_random(78, T=600, B=4, A=29, max_label=170, min_input=550, sigma=6.0, feasible_only=True))
 
 
+def test_emissions_too_small_for_the_linear_domain():
+    """Logit spreads of hundreds of nats: emissions below 2^-100 send an utterance's recursions to the
+    log domain.  First every utterance (single- and multi-wavefront labels), then a launch in which one
+    utterance of several has one such frame."""
+    check(wl.make_random(81, T=120, B=6, A=7, max_label=40, min_input=90, sigma=60.0, feasible_only=True))
+    check(wl.make_random(82, T=260, B=4, A=5, max_label=200, min_input=250, sigma=45.0, feasible_only=True))
+    check(wl.make_random(83, T=30, B=3, A=900, max_label=12, min_input=20, sigma=40.0, feasible_only=True))
+    batch = wl.make_random(84, T=90, B=5, A=29, max_label=30, min_input=70, sigma=2.0, feasible_only=True)
+    lab = batch.labels_of(2)
+    assert len(lab) > 0
+    batch.logits[11, 2, lab[0]] = -300.0                # one label symbol at e^-300 in one frame of utterance 2
+    check(batch)
+
+
+def test_steep_fronts_just_inside_the_linear_domain():
+    """Every label emission near 2^-90 (blank 62 nats above the symbols), labels of up to 200 symbols:
+    neighbouring lattice states differ by ninety binary orders of magnitude at the fronts, close to
+    the most that the linear-domain recursion's nine-pair exponent window is built for."""
+    rng = np.random.default_rng(85)
+    T, B, A = 500, 4, 4
+    lab_len = np.array([200, 150, 63, 64])
+    labs = [rng.integers(1, A, size=n) for n in lab_len]
+    x = rng.standard_normal((T, B, A)).astype(np.float32)
+    x[:, :, 0] += 62.0
+    batch = wl.CTCBatch(name="steep", T=T, B=B, A=A, blank=0, logits=x,
+                        flat_labels=np.concatenate(labs).astype(np.int32),
+                        label_lengths=lab_len.astype(np.int32),
+                        input_lengths=np.array([500, 480, 200, 450], dtype=np.int32))
+    check(batch)
+
+
 def test_single_symbol_alphabet_long_repeats():
     """Every label position repeats its predecessor: each needs a blank in between."""
     check(wl.make_random(79, T=500, B=3, A=2, max_label=240, min_input=490, blank=0, sigma=3.0,
