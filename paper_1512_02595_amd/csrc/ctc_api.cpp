@@ -43,7 +43,7 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.frames = frames;
     l.ab_doubles = ab;
     size_t off = 0;
-    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 48 B each: stays 8-byte aligned
+    l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 64 B each: stays 8-byte aligned
     l.order = off;  off += static_cast<size_t>(B) * sizeof(int32_t);
     l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
     l.upload_bytes = off;
@@ -80,8 +80,8 @@ ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
         emit += Tb * (A <= kDirectMaxA ? A : L);
         frames += Tb;
         // per-utterance byte offsets inside the kernels are 32-bit
-        if (Tb * (L + 1) * 8 > INT32_MAX) too_long = true;
-        ab += Tb * (L + 1);
+        if (Tb * lattice_pitch(L) * 8 > INT32_MAX) too_long = true;
+        ab += Tb * lattice_pitch(L);
     }
     if (too_long) return CTC_STATUS_UNSUPPORTED;
     if (sumL > INT32_MAX || frames > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
@@ -98,8 +98,8 @@ ctc_status_t make_layout_bounds(int T, int B, int A, int max_label, ctc_dtype_t 
     if (dtype != CTC_DTYPE_F32 && dtype != CTC_DTYPE_BF16) return CTC_STATUS_INVALID_VALUE;
     if (max_label > CTC_MAX_LABEL_LENGTH || B > kMaxDeviceMetaB) return CTC_STATUS_UNSUPPORTED;
     const int64_t Tl = T, Bl = B, Ll = max_label;
-    if (Tl * (Ll + 1) * 8 > INT32_MAX || Bl * Ll > INT32_MAX || Bl * Tl > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
-    carve(T, B, Bl * Ll, Bl * Tl * (A <= kDirectMaxA ? A : Ll), Bl * Tl, Bl * Tl * (Ll + 1), lay);
+    if (Tl * lattice_pitch(Ll) * 8 > INT32_MAX || Bl * Ll > INT32_MAX || Bl * Tl > INT32_MAX) return CTC_STATUS_UNSUPPORTED;
+    carve(T, B, Bl * Ll, Bl * Tl * (A <= kDirectMaxA ? A : Ll), Bl * Tl, Bl * Tl * lattice_pitch(Ll), lay);
     return CTC_STATUS_SUCCESS;
 }
 
@@ -215,7 +215,10 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
 
     // Would the launch, planned for latency, put more than two wavefronts on every SIMD?
     int64_t latency_waves = 0;
-    for (int b = 0; b < c.B; ++b) latency_waves += plan_waves(c.label_lengths[b]).waves;
+    for (int b = 0; b < c.B; ++b) {
+        const int L = c.label_lengths[b];
+        latency_waves += two_pairs_per_lane(L, false) ? plan_waves2(L).waves : plan_waves(L).waves;
+    }
     const bool crowded = latency_waves * (c.mode == Mode::kGrad ? 2 : 1) > kCrowdedWaves;
 
     int64_t lab_off = 0, e_off = 0, ab_off = 0, f_off = 0;
@@ -238,11 +241,14 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.Tb = Tb;
         m.L = L;
         m.lab_off = static_cast<int32_t>(lab_off);
-        m.flags = runs ? kUttRuns : 0;
+        m.flags = (runs ? kUttRuns : 0) | (two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0);
         m.f_off = static_cast<int32_t>(f_off);
         const WavePlan wp = plan_waves(L, crowded);
         m.waves = wp.waves;
         m.halo = wp.halo;
+        const WavePlan wp2 = plan_waves2(L, crowded);
+        m.waves2 = wp2.waves;
+        m.halo2 = wp2.halo;
         m.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
         m.e_off = e_off;
         m.ab_off = ab_off;
@@ -251,10 +257,10 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         lab_off += L;
         e_off += static_cast<int64_t>(Tb) * (c.A <= kDirectMaxA ? c.A : L);
         f_off += Tb;
-        ab_off += static_cast<int64_t>(Tb) * (L + 1);
+        ab_off += static_cast<int64_t>(Tb) * lattice_pitch(L);
         if (runs) {
             order[n_run++] = b;
-            max_waves = std::max(max_waves, wp.waves);
+            max_waves = std::max(max_waves, std::max(wp.waves, wp2.waves));
             needs_barrier = needs_barrier || wp.barrier;
             max_frames = std::max(max_frames, Tb);
         }
@@ -265,8 +271,8 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         for (int b = 0; b < c.B; ++b) meta[b].flags |= kUttLogDomain;
     // Heaviest chains first, so the longest recursion does not start last.
     std::stable_sort(order, order + n_run, [&](int a, int b) {
-        const int64_t wa = static_cast<int64_t>(meta[a].Tb) * meta[a].waves;
-        const int64_t wb = static_cast<int64_t>(meta[b].Tb) * meta[b].waves;
+        const int64_t wa = static_cast<int64_t>(meta[a].Tb) * ((meta[a].flags & kUttTwoPairs) ? meta[a].waves2 : meta[a].waves);
+        const int64_t wb = static_cast<int64_t>(meta[b].Tb) * ((meta[b].flags & kUttTwoPairs) ? meta[b].waves2 : meta[b].waves);
         return wa > wb;
     });
 
@@ -413,8 +419,11 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.dtype = dtype;
     p.n_run = B;                       // one lattice workgroup per utterance; those that do not run leave at once
     p.max_waves = 1;
-    p.crowded = static_cast<int64_t>(B) * plan_waves(max_label).waves * (grads ? 2 : 1) > 2 * kCrowdedWaves;
-    for (int L = 0; L <= max_label; ++L) p.max_waves = std::max(p.max_waves, plan_waves(L, p.crowded).waves);
+    p.crowded = static_cast<int64_t>(B) * (two_pairs_per_lane(max_label, false) ? plan_waves2(max_label).waves
+                                                                                : plan_waves(max_label).waves) *
+                    (grads ? 2 : 1) > 2 * kCrowdedWaves;
+    for (int L = 0; L <= max_label; ++L)
+        p.max_waves = std::max(p.max_waves, std::max(plan_waves(L, p.crowded).waves, plan_waves2(L, p.crowded).waves));
     p.max_frames = T;
     p.max_label = max_label;
     p.needs_barrier = plan_waves(max_label).barrier;

@@ -17,18 +17,21 @@ struct Utt {
     int32_t flags;     // bit 0: the lattice runs (Tb > 0 and an alignment exists);
                        // bit 1: lengths or labels failed the device-side checks (cost NaN)
     int32_t f_off;     // frames of all earlier utterances: offset of its blank emissions [Tb]
-    int32_t waves;     // wavefronts its lattice chains use
+    int32_t waves;     // wavefronts its lattice chains use when a lane owns one state pair (log-domain
+                       // chains, and linear-domain chains of at most 64 pairs)
     int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
     int32_t poll_budget; // LDS polls a wavefront of its chains may spend waiting on a neighbour before it gives up
     int64_t e_off;     // offset (floats) of its label emissions, [Tb][e_pitch]
-    int64_t ab_off;    // offset (doubles) of its alpha/beta blocks [Tb][L+1]
+    int64_t ab_off;    // offset (8-byte words) of its alpha/beta blocks [Tb][lattice_pitch(L)]
     int32_t e_pitch;   // floats per frame of its emission block: L (one gathered emission per label
                        // position) or, for alphabets of at most kDirectMaxA symbols, A (the frame's
                        // whole row of log2 probabilities, indexed by symbol)
     int32_t e_direct;  // 1: the block holds whole rows and a label state reads column label[i];
                        // 0: it holds gathered emissions and the state reads column i
+    int32_t waves2;    // the same plan for linear-domain chains of more than 64 pairs, whose lanes own
+    int32_t halo2;     // two neighbouring pairs each (plan_waves2)
 };
-static_assert(sizeof(Utt) == 56, "Utt is copied word by word and read with scalar loads: keep it 8-byte sized");
+static_assert(sizeof(Utt) == 64, "Utt is copied word by word and read with scalar loads: keep it 8-byte sized");
 
 // Alphabets up to this size skip the emission gather: a frame's normalised row is as small as
 // the gathered emissions would be (at most two cache lines), and every lattice lane finds its
@@ -82,12 +85,55 @@ CTC_HOST_DEVICE inline WavePlan plan_waves(int label_length, bool crowded = fals
     return best;
 }
 
+// The same for chains whose lanes own two neighbouring state pairs each (linear domain, more than
+// 64 pairs).  A wavefront then covers 128 pairs, an error at lane 0 needs two steps per lane to
+// move up, so a halo of h lanes lasts 2h steps: h is a multiple of 4 (hand-overs on chunk
+// boundaries), at most 16 (the exchange buffer).  Sixteen wavefronts hold any supported label.
+// Measured on gfx950: about 150 clocks per step with one wavefront per SIMD, 600 per hand-over.
+CTC_HOST_DEVICE inline WavePlan plan_waves2(int label_length, bool crowded = false)
+{
+    const int lanes = (label_length + 2) / 2;          // ceil((L + 1) / 2)
+    if (lanes <= 64) return {1, 0, false};
+    WavePlan best{16, 4, false};
+    float best_cost = 1e30f;
+    for (int w = 2; w <= 16; ++w) {
+        // w * (64 - halo) + halo >= lanes
+        int halo = (64 * w - lanes) / (w - 1);
+        if (halo > 16) halo = 16;
+        halo -= halo % 4;
+        if (halo < 4) continue;
+        const int per_simd = (w + 3) / 4;
+        const float cost = crowded ? w * (110.0f + 300.0f / halo)
+                                   : ((per_simd == 1) ? 150.0f : per_simd * 110.0f) + 300.0f / halo + 4.0f * w;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = {w, halo, false};
+        }
+    }
+    return best;
+}
+
+// Which of the two plans a linear-domain chain uses.  Measured on gfx950: a step of a two-pair
+// lane takes about 180 clocks against 120 for a one-pair lane, and a hand-over 560, so while a
+// label's one-pair plan keeps to one wavefront per SIMD (at most 4) it is the faster one; beyond
+// that, and in crowded launches, where wavefront-steps count and not one chain's latency, the
+// two-pair plan with half the wavefronts wins.
+CTC_HOST_DEVICE inline bool two_pairs_per_lane(int label_length, bool crowded)
+{
+    if (label_length + 1 <= 64) return false;
+    const WavePlan one = plan_waves(label_length, crowded);
+    return crowded || one.barrier || one.waves > 4;
+}
+
 constexpr int kUttRuns = 1;
 constexpr int kUttInvalid = 2;
 // Set by the softmax launch when some emission of the utterance is too improbable for the
 // linear-domain recursion (below 2^kLinearMinLog2): its chains then run in the log domain.
 // (Also set for every utterance of a launch that uses the one-barrier-per-step kernel.)
 constexpr int kUttLogDomain = 4;
+// Linear-domain chains of this utterance give two neighbouring state pairs to every lane
+// (plan_waves2) instead of one (plan_waves): see two_pairs_per_lane.
+constexpr int kUttTwoPairs = 8;
 constexpr float kLinearMinLog2 = -100.0f;
 // Lattice wavefronts of one launch beyond which chains are planned for total work: two per SIMD
 // of the 256 compute units.
@@ -106,6 +152,9 @@ constexpr int kOverFetchRows = 3 * kChunk;
 constexpr int kBlankSlack = kOverFetchRows + kChunk;                          // floats, each side
 constexpr int kLabelSlack = kOverFetchRows * (CTC_MAX_LABEL_LENGTH + 1);      // floats, each side
 
+// Row pitch (8-byte words) of an utterance's lattice blocks: column 1 + i holds label state i.
+CTC_HOST_DEVICE inline int64_t lattice_pitch(int64_t L) { return L + 2; }
+
 // Byte offsets of the workspace regions, all multiples of 256.
 struct Layout {
     size_t meta = 0;      // Utt[B]
@@ -122,8 +171,8 @@ struct Layout {
     size_t emit_label = 0; // float[slack + sum Tb*L + slack]  emission of each label position, same coding;
                            // the first two floats of the front slack hold the constants that lanes
                            // without a label state read: probability 0 and log 0
-    size_t alpha = 0;     // double[sum Tb*(L+1)]   label states only
-    size_t beta = 0;      // double[sum Tb*(L+1)]
+    size_t alpha = 0;     // 8-byte words [sum Tb*(L+2)]: label states only, one unused column on either side
+    size_t beta = 0;      // of a frame's row (lattice_pitch), so that a lane may store two neighbours at once
     size_t total = 0;
     size_t upload_bytes = 0;   // meta..labels are contiguous: the image the host prepares per call
     int64_t sumL = 0;

@@ -175,7 +175,7 @@ void ctc_upload_kernel(const int* __restrict__ host_image, int* __restrict__ ws,
 // otherwise.  Per utterance: range checks, the count of adjacent repeats (an alignment exists
 // iff T_b >= L + repeats), the wavefront plan, and the offsets of its blocks, which are laid
 // out with the strides of the largest utterance the caller allows (labels [B][max_label],
-// emissions b * T * max_label, lattice b * T * (max_label + 1), frames b * T).  Then the run
+// emissions b * T * max_label, lattice b * T * lattice_pitch(max_label), frames b * T).  Then the run
 // order: heaviest chains first (rank by T_b x wavefronts, ties by index), -1 for the rest.
 constexpr int kPlanThreads = 1024;
 
@@ -233,17 +233,21 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         m.Tb = bad ? 0 : Tb;
         m.L = bad ? 0 : L;
         m.lab_off = b * max_label;
-        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) | (log_domain ? kUttLogDomain : 0);
+        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) | (log_domain ? kUttLogDomain : 0) |
+                  (!bad && two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0);
         m.f_off = b * Tt;
         m.waves = wp.waves;
         m.halo = wp.halo;
+        const WavePlan wp2 = plan_waves2(bad ? 0 : L, crowded);
+        m.waves2 = wp2.waves;
+        m.halo2 = wp2.halo;
         m.poll_budget = poll_budget;
         m.e_direct = A <= kDirectMaxA ? 1 : 0;
         m.e_pitch = m.e_direct ? A : m.L;
         m.e_off = static_cast<int64_t>(b) * Tt * (m.e_direct ? A : max_label);
-        m.ab_off = static_cast<int64_t>(b) * Tt * (max_label + 1);
+        m.ab_off = static_cast<int64_t>(b) * Tt * lattice_pitch(max_label);
         meta[b] = m;
-        weight[b] = runs ? static_cast<long long>(Tb) * wp.waves : -1;
+        weight[b] = runs ? static_cast<long long>(Tb) * ((m.flags & kUttTwoPairs) ? wp2.waves : wp.waves) : -1;
         if (bad) s_bad = 1;
     }
     __syncthreads();
@@ -648,8 +652,8 @@ struct HaloLds {
 // excludes its own frame's emission, and that is what gets stored, so that
 // log alpha + log beta is the log mass of alignments through a state.
 //
-// Storage: only the label states are written, alpha_row[i] = alpha(2i+1), beta_row[i] =
-// beta(2i+1), row pitch L+1 doubles.  The blank states are needed by the recursion but not by
+// Storage: only the label states are written, alpha_row[1 + i] = alpha(2i+1), beta_row[1 + i] =
+// beta(2i+1), row pitch L+2 words (lattice_pitch; the first and the last column stay unused).  The blank states are needed by the recursion but not by
 // the gradient, which takes the blank's occupancy as 1 minus that of all label states
 // (sum_s alpha_t(s) beta_t(s) = p at every frame).
 //
@@ -704,17 +708,18 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
-    // Output: only the label state of each pair is kept (row pitch L+1 doubles, column = label
+    // Output: only the label state of each pair is kept (row pitch L+2 words, column = 1 + label
     // index, in both directions); the gradient gets the blank's share as the complement.
     // Lanes that store nothing write to a sink instead.
     // With Mode::kBest the same block holds one byte per pair and frame instead (row pitch
     // L+1 bytes, column = pair), pair L included: its blank state has a choice to record.
     constexpr int64_t kOutBytes = (kMode == Mode::kBest) ? 1 : 8;
+    const int64_t out_pitch = (kMode == Mode::kBest) ? P : lattice_pitch(L);
     const bool stores = (kMode == Mode::kBest) ? active : (active && has_label);
     char* op = stores ? static_cast<char*>(out) +
-                            (m.ab_off + static_cast<int64_t>(f0) * P + (kMode == Mode::kBest ? j : li)) * kOutBytes
+                            (m.ab_off + static_cast<int64_t>(f0) * out_pitch + (kMode == Mode::kBest ? j : li + 1)) * kOutBytes
                       : reinterpret_cast<char*>(sink);
-    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * P * kOutBytes : 0;
+    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * out_pitch * kOutBytes : 0;
     int choice = 0;
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
@@ -995,8 +1000,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
     const bool stores = kMode == Mode::kGrad && active && has_label;
-    double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * P + li : sink;
-    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * P : 0;
+    double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * lattice_pitch(L) + li + 1 : sink;
+    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * lattice_pitch(L) : 0;
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
@@ -1207,6 +1212,281 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     }
 }
 
+// Linear-domain chains of more than 64 pairs: a lane owns two neighbouring pairs, A = 2q and
+// B = 2q + 1 (q = wave * (64 - halo) + lane), so a wavefront covers 128 pairs and most labels need
+// one or two wavefronts instead of two to four.  Pair A takes the label of pair B of the lane
+// below (one DPP shift and `scale`, as in run_chain_linear), pair B the label of pair A of its own
+// lane: the two recursions of a lane are independent within a step and fill each other's issue
+// gaps.  Both pairs share the lane's frame; mass moves up half a lane per step, so the window
+// of a renewal is this lane and the kChunk / 2 lanes below it, and a halo of h lanes stays exact
+// for 2h steps (hand-over every 2h steps: h is a multiple of 4).
+// The two label states of a lane are neighbours in the lattice row and go out in one 16-byte
+// store; where pair B has no label state (the lane of the last pair) its half falls on one of
+// the row's two unused columns.
+constexpr int kHalo2Lanes = 16;           // most halo lanes plan_waves2 asks for
+
+struct Halo2Lds {
+    double2 data[16][2][kHalo2Lanes][2];  // [wavefront][generation parity][halo lane][pair]: (blank, label)
+    int frame[16][2][kHalo2Lanes];
+    int ready[16];
+    int done[16];
+    int finished;                     // cost-only chains, as in HaloLds
+    int gave_up;
+    float cost;
+};
+
+struct alignas(8) LabelStatePair { double lo, hi; };   // two neighbouring columns of a lattice row
+
+template <bool kBackward, Mode kMode>
+__device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, const int* __restrict__ labels,
+                                                  const float* __restrict__ emit_blank,
+                                                  const float* __restrict__ emit_label,
+                                                  void* __restrict__ out, double* __restrict__ logp,
+                                                  float* __restrict__ costs, int* __restrict__ chain_err,
+                                                  double* __restrict__ sink, void* lds)
+{
+    static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
+    static_assert(kMode != Mode::kBest, "the maximum recursion runs in the log domain");
+    const int L = m.L, Tb = m.Tb;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int halo = m.halo2, waves = m.waves2;
+    const int q = wave * (64 - halo) + lane;
+    const int ja = 2 * q, jb = 2 * q + 1;                // the lane's pairs, in the chain's own order
+    const int* lab = labels + m.lab_off;
+    const bool has_a = ja < L, has_b = jb < L;           // label states (pair L has a blank state only)
+    const bool active = (wave == 0 || lane >= halo) && ja <= L;
+    const int lia = kBackward ? (L - 1 - ja) : ja;       // label index of pair A's label state
+    const int lib = kBackward ? (lia - 1) : (lia + 1);
+    const int back = kBackward ? 1 : -1;                 // label index of the pair before = index + back
+    const bool skip_a = has_a && ja >= 1 && lab[lia] != lab[lia + back];
+    const bool skip_b = has_b && lab[lib] != lab[lib + back];
+
+    const int f0 = kBackward ? (Tb - 1) : 0;
+    const int fdir = kBackward ? -1 : 1;
+    const float* const rows = emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch;
+    // A pair without a label state reads a constant probability 0 and stays there.
+    const float* epa = has_a ? rows + (m.e_direct ? lab[lia] : lia) : emit_label;
+    const float* epb = has_b ? rows + (m.e_direct ? lab[lib] : lib) : emit_label;
+    const int64_t stride_a = has_a ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
+    const int64_t stride_b = has_b ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
+    const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    // Output: label state i sits in column 1 + i; the lane's two are columns 1 + min(lia, lib) and
+    // the next one.  (has_a false: nothing of this lane is kept.)
+    const bool stores = kMode == Mode::kGrad && active && has_a;
+    const int pitch = static_cast<int>(lattice_pitch(L));
+    double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * pitch + 1 + (kBackward ? lib : lia)
+                        : sink;
+    const int64_t ostride = stores ? static_cast<int64_t>(fdir) * pitch : 0;
+
+    Halo2Lds* const hl = static_cast<Halo2Lds*>(lds);
+    const int last_wave = waves - 1;
+    int budget = m.poll_budget;
+    bool lost = false;
+    const int chunks_per_hand_over = 2 * halo / kChunk;
+    int until_hand_over = chunks_per_hand_over;
+    int generation = 0;
+    int parity = 0;
+    const int wr_slot = (halo > 0 && lane >= 64 - halo) ? lane - (64 - halo) : 0;
+    const int rd_slot = lane < halo ? lane : 0;
+    const int below = wave > 0 ? wave - 1 : 0;
+    int* const my_ready = &hl->ready[wave];
+    int* const my_done = &hl->done[wave];
+    int* const up_done = &hl->done[wave < 15 ? wave + 1 : 15];
+    int* const low_ready = &hl->ready[below];
+
+    double ia_blank = (ja == 0) ? 1.0 : 0.0, ia_label = (ja == 0 && has_a) ? 1.0 : 0.0;
+    double ib_blank = 0.0, ib_label = 0.0;
+    double va_blank, va_label, vb_blank, vb_label;
+    int frame = 0;
+    double scale = 1.0;                                  // 2^(frame of the lane below - frame)
+    double skip_a_scale = skip_a ? 1.0 : 0.0;
+    const double skip_b_one = skip_b ? 1.0 : 0.0;
+
+    auto counter = [&](int* p) {
+        return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto uniform = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+    int done_seen = 0;
+    // The exchange protocol of run_chain_log; an entry carries both pairs of a lane and its frame.
+    auto hand_over = [&]() {
+        ++generation;
+        parity ^= 1;
+        if (wave < last_wave) {
+            int seen = uniform(done_seen);
+            if (__builtin_expect(seen < generation - 2, 0)) {
+                while (seen < generation - 2 && budget > 0) {
+                    --budget;
+                    seen = uniform(counter(up_done));
+                }
+                lost = lost || seen < generation - 2;
+            }
+            if (lane >= 64 - halo) {
+                hl->data[wave][parity][wr_slot][0] = make_double2(va_blank, va_label);
+                hl->data[wave][parity][wr_slot][1] = make_double2(vb_blank, vb_label);
+                hl->frame[wave][parity][wr_slot] = frame;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 63) __hip_atomic_store(my_ready, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            done_seen = counter(up_done);
+        }
+        if (wave > 0) {
+            int ready = counter(low_ready);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            double2 a = hl->data[below][parity][rd_slot][0];
+            double2 b = hl->data[below][parity][rd_slot][1];
+            int vf = hl->frame[below][parity][rd_slot];
+            ready = uniform(ready);
+            if (__builtin_expect(ready < generation, 0)) {
+                while (ready < generation && budget > 0) {
+                    --budget;
+                    ready = counter(low_ready);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    a = hl->data[below][parity][rd_slot][0];
+                    b = hl->data[below][parity][rd_slot][1];
+                    vf = hl->frame[below][parity][rd_slot];
+                    ready = uniform(ready);
+                }
+                lost = lost || ready < generation;
+            }
+            if (lane < halo) {
+                va_blank = a.x;
+                va_label = a.y;
+                vb_blank = b.x;
+                vb_label = b.y;
+                frame = vf;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 0) __hip_atomic_store(my_done, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    };
+
+    int prev_lo = 0, prev_hi = 0;
+    auto from_lane_below = [&](double mine) { return shift_up(mine, prev_lo, prev_hi); };
+    auto shift_up_int = [](int v) { return __builtin_amdgcn_update_dpp(kNoExponent, v, 0x138, 0xf, 0xf, false); };
+
+    auto renew_frames = [&]() {
+        const double top = fmax(fmax(va_blank, va_label), fmax(vb_blank, vb_label));
+        const int mine = (top > 0.0) ? frame + __builtin_amdgcn_frexp_exp(top) : kNoExponent;
+        int window = mine;
+#pragma unroll
+        for (int k = 0; k < kChunk / 2; ++k) window = max(mine, shift_up_int(window));
+        const int rise = frame - window;
+        va_blank = __builtin_amdgcn_ldexp(va_blank, rise);
+        va_label = __builtin_amdgcn_ldexp(va_label, rise);
+        vb_blank = __builtin_amdgcn_ldexp(vb_blank, rise);
+        vb_label = __builtin_amdgcn_ldexp(vb_label, rise);
+        frame = window;
+        const int down = min(max(shift_up_int(window) - window, -1100), 1023);
+        scale = __builtin_amdgcn_ldexp(1.0, down);
+        skip_a_scale = skip_a ? scale : 0.0;
+    };
+
+    auto store = [&]() {
+        if (kMode == Mode::kGrad) {
+            const double a = pack_state(kBackward ? ia_label : va_label, frame);
+            const double b = pack_state(kBackward ? ib_label : vb_label, frame);
+            *reinterpret_cast<LabelStatePair*>(op) = kBackward ? LabelStatePair{b, a} : LabelStatePair{a, b};
+        }
+        op += ostride;
+    };
+    auto finish_step = [&](float eb, float ela, float elb) {
+        const double ebd = static_cast<double>(eb);
+        va_blank = ia_blank * ebd;
+        va_label = ia_label * static_cast<double>(ela);
+        vb_blank = ib_blank * ebd;
+        vb_label = ib_label * static_cast<double>(elb);
+        store();
+    };
+    auto end_chunk = [&]() {
+        if (--until_hand_over == 0) {
+            hand_over();
+            until_hand_over = chunks_per_hand_over;
+        }
+        renew_frames();
+    };
+    auto advance = [&](float eb, float ela, float elb) {
+        const double prev = from_lane_below(vb_label);
+        ia_blank = __builtin_fma(prev, scale, va_blank);
+        ia_label = va_label + __builtin_fma(prev, skip_a_scale, va_blank);
+        ib_blank = vb_blank + va_label;
+        ib_label = vb_label + __builtin_fma(va_label, skip_b_one, vb_blank);
+        finish_step(eb, ela, elb);
+    };
+    auto readlane = [](float v, int l) {
+        return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
+    };
+
+    // step 0
+    finish_step(readlane(*bp, 0), *epa, *epb);
+
+    float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk], eb_a, eb_b;
+    auto fetch = [&](float (&ela)[kChunk], float (&elb)[kChunk], float& eb, int s0) {
+        eb = bp[fdir * s0];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            epa += stride_a;
+            epb += stride_b;
+            ela[i] = *epa;
+            elb[i] = *epb;
+        }
+    };
+    auto run = [&](const float (&ela)[kChunk], const float (&elb)[kChunk], const float eb, int s0) {
+        if (s0 + kChunk <= Tb) {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i) advance(readlane(eb, i), ela[i], elb[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i)
+                if (s0 + i < Tb) advance(readlane(eb, i), ela[i], elb[i]);
+        }
+    };
+    fetch(ela_a, elb_a, eb_a, 1);
+    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
+        fetch(ela_b, elb_b, eb_b, s0 + kChunk);
+        run(ela_a, elb_a, eb_a, s0);
+        end_chunk();
+        fetch(ela_a, elb_a, eb_a, s0 + 2 * kChunk);
+        if (s0 + kChunk < Tb) {
+            run(ela_b, elb_b, eb_b, s0 + kChunk);
+            end_chunk();
+        }
+    }
+
+    if (!kBackward) {
+        // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L - 1.
+        // L even: pair L is this lane's A, pair L - 1 the B of the lane below; L odd: pair L is B.
+        const double from_below = from_lane_below(vb_label) * scale;
+        if (active && (ja == L || jb == L)) {
+            const double p = (ja == L) ? va_blank + from_below : vb_blank + va_label;
+            const double mantissa = __builtin_amdgcn_frexp_mant(p);         // [0.5, 1)
+            const int exponent = frame + __builtin_amdgcn_frexp_exp(p);
+            const double l2 = static_cast<double>(exponent) +
+                              static_cast<double>(fast_log2(static_cast<float>(mantissa)));
+            logp[u] = (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0;     // 1 / p
+            const float cost = (p > 0.0) ? static_cast<float>(-l2 * kLn2) : __builtin_inff();
+            if (kMode == Mode::kLoss) hl->cost = cost;
+            else costs[u] = cost;
+        }
+    }
+    if (kMode == Mode::kLoss) {
+        // as in run_chain_log: the wavefront that finishes last writes the cost
+        if (lost && lane == 0) hl->gave_up = 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        int before = 0;
+        if (lane == 0)
+            before = __hip_atomic_fetch_add(&hl->finished, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        before = __builtin_amdgcn_readfirstlane(before);
+        if (before == waves - 1 && lane == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int any_lost = __hip_atomic_load(&hl->gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const float cost = hl->cost;
+            costs[u] = any_lost ? __uint_as_float(0x7FC00000u) : cost;
+        }
+    } else if (lost && lane == 0) {
+        chain_err[u] = 1;
+    }
+}
+
 template <Sync kSync, Mode kMode>
 __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
@@ -1220,16 +1500,29 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
     const int u = order[blockIdx.x];
     if (u < 0) return;                  // device-planned batches launch one workgroup per utterance, running or not
     const Utt m = meta[u];
-    const bool idle = static_cast<int>(threadIdx.x >> 6) >= m.waves;
+    // Which recursion: the barrier kernel and the maximum recursion have the log domain only;
+    // otherwise the flag that the softmax launch may have raised decides.  A linear-domain chain
+    // gives one pair or two to a lane as the launcher planned it (two_pairs_per_lane).
+    const bool in_log_domain = kSync == Sync::kBarrier || kMode == Mode::kBest || (m.flags & kUttLogDomain) != 0;
+    const bool two_pairs = kSync == Sync::kHalo && !in_log_domain && (m.flags & kUttTwoPairs) != 0;
+    const int waves = two_pairs ? m.waves2 : m.waves;
+    const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves;
     if (kSync == Sync::kHalo) {
-        HaloLds* hl = static_cast<HaloLds*>(lds);
+        // the counters of the exchange buffer in use
+        int* ready = two_pairs ? static_cast<Halo2Lds*>(lds)->ready : static_cast<HaloLds*>(lds)->ready;
+        int* done = two_pairs ? static_cast<Halo2Lds*>(lds)->done : static_cast<HaloLds*>(lds)->done;
         if (threadIdx.x < 16) {
-            hl->ready[threadIdx.x] = 0;
-            hl->done[threadIdx.x] = 0;
+            ready[threadIdx.x] = 0;
+            done[threadIdx.x] = 0;
         }
         if (threadIdx.x == 0) {
-            hl->finished = 0;
-            hl->gave_up = 0;
+            if (two_pairs) {
+                static_cast<Halo2Lds*>(lds)->finished = 0;
+                static_cast<Halo2Lds*>(lds)->gave_up = 0;
+            } else {
+                static_cast<HaloLds*>(lds)->finished = 0;
+                static_cast<HaloLds*>(lds)->gave_up = 0;
+            }
         }
         __syncthreads();
         if (idle) return;
@@ -1243,22 +1536,28 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         }
     }
     const bool forward = kMode != Mode::kGrad || blockIdx.y == 0;
-    bool in_log_domain = true;                  // all the barrier kernel has, and what the maximum recursion uses
     if constexpr (kSync != Sync::kBarrier && kMode != Mode::kBest) {
-        in_log_domain = (m.flags & kUttLogDomain) != 0;
+        if (two_pairs) {
+            if constexpr (kSync == Sync::kHalo) {
+                if (forward)
+                    run_chain_linear2<false, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+                else
+                    run_chain_linear2<true, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+            }
+            return;
+        }
         if (!in_log_domain) {
             if (forward)
                 run_chain_linear<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
             else
                 run_chain_linear<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+            return;
         }
     }
-    if (in_log_domain) {
-        if (forward)
-            run_chain_log<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
-        else
-            run_chain_log<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
-    }
+    if (forward)
+        run_chain_log<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+    else
+        run_chain_log<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
 }
 
 // grid = (utterances whose lattice runs, 2) for Mode::kGrad: y = 0 forward, y = 1 backward;
@@ -1289,7 +1588,7 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         double* __restrict__ logp, float* __restrict__ costs,
                         int* __restrict__ chain_err, double* __restrict__ sink)
 {
-    __shared__ HaloLds halo_lds;
+    __shared__ union { HaloLds one; Halo2Lds two; } halo_lds;      // one pair per lane, or two
     lattice_body<Sync::kHalo, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                               costs, chain_err, sink, &halo_lds);
 }
@@ -1417,7 +1716,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const Utt m = meta[b];
     if (t0 == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
     const bool runs = (m.flags & kUttRuns) != 0;
-    const int L = m.L, P = L + 1;
+    const int L = m.L;
     if (runs && t0 < m.Tb) {
         for (int j = tid; j < L; j += kRowThreads) {
             s_lab[j] = labels[m.lab_off + j];
@@ -1425,13 +1724,13 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         __syncthreads();
     }
-    const size_t pitch = static_cast<size_t>(P);
+    const size_t pitch = static_cast<size_t>(lattice_pitch(L));
     const double packed_inverse_p = runs ? logp[b] : 0.0;
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
-    const double* const abase = alpha + m.ab_off;
-    const double* const bbase = beta + m.ab_off;
+    const double* const abase = alpha + m.ab_off + 1;      // label state i sits in column 1 + i
+    const double* const bbase = beta + m.ab_off + 1;
 
     // What a row needs from memory, requested in one go before any of it is used, so that a
     // row costs one memory latency: the lattice values of the first kAhead * 64 label states
@@ -1600,7 +1899,7 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const Utt m = meta[b];
     if (t0 == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
     const bool runs = (m.flags & kUttRuns) != 0;
-    const int L = m.L, P = L + 1;
+    const int L = m.L;
     if (runs && t0 < m.Tb) {
         if (tid < 64) {
             s_start[tid] = 0;
@@ -1618,13 +1917,13 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         __syncthreads();
     }
-    const size_t pitch = static_cast<size_t>(P);
+    const size_t pitch = static_cast<size_t>(lattice_pitch(L));
     const double packed_inverse_p = runs ? logp[b] : 0.0;
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
-    const double* const abase = alpha + m.ab_off;
-    const double* const bbase = beta + m.ab_off;
+    const double* const abase = alpha + m.ab_off + 1;      // label state i sits in column 1 + i
+    const double* const bbase = beta + m.ab_off + 1;
     for (int t = t0 + wave; t < tend; t += 4) {
         const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
         T* grow = grads + row_off;

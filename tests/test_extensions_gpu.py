@@ -209,10 +209,11 @@ def test_best_path_repeats_bitwise_and_leaves_the_other_calls_intact():
 def test_a_lost_wavefront_exchange_is_reported_as_nan_cost():
     """With a poll budget of zero every wait between the wavefronts of a long label gives up at once:
     all kernels still run to their end, and the utterances concerned report NaN in all three calls,
-    while labels that fit one wavefront are unaffected."""
+    while labels that fit one wavefront are unaffected.  (The label of 400 symbols takes the recursion
+    whose lanes own two state pairs each, those of 120 and 150 the one-pair recursion.)"""
     rng = np.random.default_rng(51)
-    T, A = 160, 7
-    lengths = np.asarray([150, 40, 150, 10, 120, 63], dtype=np.int32)
+    T, A = 420, 7
+    lengths = np.asarray([150, 40, 400, 10, 120, 63], dtype=np.int32)
     # labels without adjacent repeats, so that every utterance has an alignment
     labs = [(1 + np.cumsum(rng.integers(1, A - 1, size=n)) % (A - 1)).astype(np.int32) for n in lengths]
     batch = wl.CTCBatch(name="lost-exchange", T=T, B=len(lengths), A=A, blank=0,

@@ -21,6 +21,8 @@ int main()
         for (int L = 0; L <= CTC_MAX_LABEL_LENGTH; ++L) {
             const ctc::WavePlan p = ctc::plan_waves(L, crowded != 0);
             std::printf("%d %d %d %d %d\n", crowded, L, p.waves, p.halo, p.barrier ? 1 : 0);
+            const ctc::WavePlan p2 = ctc::plan_waves2(L, crowded != 0);
+            std::printf("two %d %d %d %d %d\n", crowded, L, p2.waves, p2.halo, p2.barrier ? 1 : 0);
         }
     std::printf("chunk %d slack %d %d\n", ctc::kChunk, ctc::kBlankSlack, ctc::kLabelSlack);
     return 0;
@@ -36,9 +38,11 @@ def plans(tmp_path_factory):
     subprocess.run(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "include"),
                     "-I", os.path.join(ROOT, "paper_1512_02595_amd", "csrc"), str(src), "-o", str(exe)], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines()
-    rows = [tuple(int(v) for v in line.split()) for line in out if not line.startswith("chunk")]
+    rows = [tuple(int(v) for v in line.split()) for line in out if line[0].isdigit()]
+    rows2 = [tuple(int(v) for v in line.split()[1:]) for line in out if line.startswith("two")]
     consts = [line for line in out if line.startswith("chunk")][0].split()
-    return rows, {"chunk": int(consts[1]), "blank_slack": int(consts[3]), "label_slack": int(consts[4])}
+    return rows, {"chunk": int(consts[1]), "blank_slack": int(consts[3]), "label_slack": int(consts[4]),
+                  "two_pairs": rows2}
 
 
 def test_every_label_length_has_a_plan_the_kernels_can_run(plans):
@@ -61,6 +65,22 @@ def test_every_label_length_has_a_plan_the_kernels_can_run(plans):
         assert waves * (64 - halo) + halo >= pairs, (L, waves, halo)
         # and no wavefront is idle: one fewer would not hold the pairs with this halo
         assert (waves - 1) * (64 - halo) + halo < pairs or waves == 2, (L, waves, halo)
+
+
+def test_every_label_length_has_a_two_pairs_per_lane_plan(plans):
+    """plan_waves2: lanes own two neighbouring pairs; a halo of h lanes lasts 2h steps."""
+    _, c = plans
+    rows = c["two_pairs"]
+    assert len(rows) == 2 * 1024
+    for crowded, L, waves, halo, barrier in rows:
+        lanes = (L + 2) // 2                        # ceil((L + 1) / 2) lanes hold the L + 1 pairs
+        assert not barrier and 1 <= waves <= 16, (L, waves)
+        if waves == 1:
+            assert halo == 0 and lanes <= 64, (L, halo)
+            continue
+        # hand-overs every 2 * halo steps fall on chunk boundaries; the exchange buffer holds 16 lanes
+        assert (2 * halo) % c["chunk"] == 0 and 4 <= halo <= 16, (L, waves, halo)
+        assert waves * (64 - halo) + halo >= lanes, (L, waves, halo)
 
 
 def test_plans_only_switch_to_the_barrier_kernel_when_no_halo_fits(plans):
