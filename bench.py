@@ -28,17 +28,24 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # One non-packed, non-fused VALU operation per lane per clock: 256 CUs x 64 lanes x 2.4 GHz.
 # (The published 157.3 TFLOP/s fp32 vector figure counts 2 for packing and 2 for FMA on top.)
 ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
-# Lane-operations of one step of one (blank, label) state pair in one direction:
-# 4 transcendentals (two exp2, two log2) at quarter rate (= 16) + 25 plain operations.
+# Algorithmic lane-operations of one step of one (blank, label) state pair in one direction, priced
+# for the log-space recursion that defines the path: two two-term log-sum-exps = 4 transcendentals
+# (two exp2, two log2) at quarter rate (= 16) + 25 plain operations.  The kernel itself recurs on
+# probabilities with a per-lane exponent and issues about a third of that (see LANE_OPS_EXECUTED),
+# so `achieved` is the rate at which the defined work gets done, not the ALU's busy rate.
 LANE_OPS_PER_PAIR_STEP = 41
+# What the linear-domain kernel executes per pair-step: 2 fused multiply-adds, 1 addition,
+# 2 multiplications, 2 conversions of emissions, 2 DPP moves, 1 pack, 1 address, and about 3 for
+# the renewal of the exponents every 8 steps.
+LANE_OPS_EXECUTED = 14
 # The max recursion of the alignment has no transcendentals: compares, selects, two fp64 adds.
 LANE_OPS_PER_PAIR_STEP_ALIGN = 22
 
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
 # the rocprofv3 --pmc runs summarised in profiles/ (English and Mandarin HBM traffic summaries).
-MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 8.2e6, "ctc_lattice": 62.9e6, "ctc_gradient": 73.4e6},
-                    (2, "f32"): {"ctc_softmax": 1223.2e6, "ctc_lattice": 13.9e6, "ctc_gradient": 53.9e6}}
+MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 8.2e6, "ctc_lattice": 63.3e6, "ctc_gradient": 73.8e6},
+                    (2, "f32"): {"ctc_softmax": 1223.6e6, "ctc_lattice": 14.1e6, "ctc_gradient": 26.2e6}}
 
 
 def kernel_bytes(batch, elem, mode="grad"):
@@ -234,7 +241,9 @@ def main():
         roofline = {"kernel": dom_name, "bound": "alu", "achieved": round(achieved, 4),
                     "peak": round(ALU_PEAK_TOPS, 2), "unit": "TFLOP/s",
                     "frac": round(achieved / ALU_PEAK_TOPS, 5), "traffic": traffic,
-                    "note": "flop = one non-packed VALU lane-operation; transcendental = 4"}
+                    "note": "flop = one non-packed VALU lane-operation of the log-space recursion that defines "
+                            "the path (transcendental = 4, 41 per pair-step); the kernel recurs on probabilities "
+                            "and executes about %d per pair-step" % LANE_OPS_EXECUTED}
     else:
         achieved = kernels[dom_name]["GBps"]
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -252,7 +261,7 @@ def main():
         "ms_per_step_cache_warm": round(warm_ms, 5),
         "rotating_bytes": int(sum(d.x.numel() * d.x.element_size() * 2 + d.ws_bytes for d in dbs)),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64 lattice state, f32 transcendentals, %s activations" % args.dtype,
+        "dtype": "f64 lattice state (probabilities with a per-lane exponent), %s activations" % args.dtype,
         "data": "synthetic",
         "config": {"workload": "config[%d] %s: B=%d A=%d T=%d, %d rotating minibatches"
                    % (args.config, batches[0].name, B, batches[0].A, batches[0].T, len(batches)),
