@@ -629,7 +629,7 @@ enum class Sync { kNone, kHalo, kBarrier };
 // blank state: 0 = stayed, 1 = came from the label of the pair before.
 constexpr int kFromSame = 0, kFromBlank = 1 << 2, kFromPrevLabel = 2 << 2, kBlankFromPrevLabel = 1;
 
-// LDS of the halo exchange: per wavefront w, what w hands to w+1.
+// LDS of the halo exchange of the chains with one pair per lane: per wavefront w, what w hands to w+1.
 struct HaloLds {
     double2 data[16][kHaloEntries];
     int frame[16][kHaloEntries];      // linear-domain chains: the frame exponent that goes with each entry
@@ -970,6 +970,8 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
 // (pack_state).  The gradient kernels do not know which kind of chain wrote the lattice.
 constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real one, far from int32's ends
 
+constexpr int kRing = 4;                  // hand-overs a boundary's buffer holds (two pairs per lane)
+
 template <bool kBackward, Sync kSync, Mode kMode>
 __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
                                                  const float* __restrict__ emit_blank,
@@ -981,7 +983,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
     static_assert(kSync != Sync::kBarrier, "the barrier kernel runs the log-domain chain");
     static_assert(kMode != Mode::kBest, "the maximum recursion runs in the log domain");
-    const int L = m.L, Tb = m.Tb, P = L + 1;
+    const int L = m.L, Tb = m.Tb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
     const int j = wave * (64 - halo) + lane;             // pair of this lane (see run_chain_log)
@@ -1226,10 +1228,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
 constexpr int kHalo2Lanes = 16;           // most halo lanes plan_waves2 asks for
 
 struct Halo2Lds {
-    double2 data[16][2][kHalo2Lanes][2];  // [wavefront][generation parity][halo lane][pair]: (blank, label)
-    int frame[16][2][kHalo2Lanes];
-    int ready[16];
-    int done[16];
+    double2 data[16][kRing][kHalo2Lanes][2];  // [wavefront][hand-over mod kRing][halo lane][pair]: (blank, label)
+    int2 tag[16][kRing][kHalo2Lanes];         // (the lane's frame, number of the hand-over)
     int finished;                     // cost-only chains, as in HaloLds
     int gave_up;
     float cost;
@@ -1285,14 +1285,9 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     const int chunks_per_hand_over = 2 * halo / kChunk;
     int until_hand_over = chunks_per_hand_over;
     int generation = 0;
-    int parity = 0;
     const int wr_slot = (halo > 0 && lane >= 64 - halo) ? lane - (64 - halo) : 0;
     const int rd_slot = lane < halo ? lane : 0;
-    const int below = wave > 0 ? wave - 1 : 0;
-    int* const my_ready = &hl->ready[wave];
-    int* const my_done = &hl->done[wave];
-    int* const up_done = &hl->done[wave < 15 ? wave + 1 : 15];
-    int* const low_ready = &hl->ready[below];
+    const int below = wave > 0 ? wave - 1 : 0, above = wave < 15 ? wave + 1 : 15;
 
     double ia_blank = (ja == 0) ? 1.0 : 0.0, ia_label = (ja == 0 && has_a) ? 1.0 : 0.0;
     double ib_blank = 0.0, ib_label = 0.0;
@@ -1302,49 +1297,50 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     double skip_a_scale = skip_a ? 1.0 : 0.0;
     const double skip_b_one = skip_b ? 1.0 : 0.0;
 
-    auto counter = [&](int* p) {
-        return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    };
     auto uniform = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
-    int done_seen = 0;
-    // The exchange protocol of run_chain_log; an entry carries both pairs of a lane and its frame.
+    auto generation_of = [&](const int2* tag) {
+        return __hip_atomic_load(&tag->y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto read_tag = [&](const int2* tag) {
+        const unsigned long long w = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(tag),
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return make_int2(static_cast<int>(w), static_cast<int>(w >> 32));
+    };
+    auto write_tag = [&](int2* tag, int frame_of_lane, int number) {
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(tag),
+                           (static_cast<unsigned long long>(static_cast<unsigned>(number)) << 32) |
+                               static_cast<unsigned>(frame_of_lane),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    int above_seen = 0;
+    // Hand-over g: first take the halo lanes' exact state from the wavefront below, then pass the
+    // top `halo` lanes up.  An entry is a lane's four values and, in a last word, its frame and
+    // the number g; LDS operations of a wavefront complete in order, so a reader that finds g in
+    // the last word finds the values of hand-over g in the others.  A boundary's buffer holds
+    // kRing hand-overs.  Before it overwrites the one that held hand-over g - kRing, a wavefront
+    // makes sure that the one above has taken that: a wavefront publishes g only after its own
+    // reads of g (the last one, which has nothing to hand up, publishes a bare number), so what
+    // it has published says how far it has read; that reading was requested at the previous
+    // hand-over.  (With one pair per lane this form was 4 % slower than two counters and two
+    // buffers; with two pairs per lane in a crowded launch it is 9 % faster.)
     auto hand_over = [&]() {
         ++generation;
-        parity ^= 1;
-        if (wave < last_wave) {
-            int seen = uniform(done_seen);
-            if (__builtin_expect(seen < generation - 2, 0)) {
-                while (seen < generation - 2 && budget > 0) {
-                    --budget;
-                    seen = uniform(counter(up_done));
-                }
-                lost = lost || seen < generation - 2;
-            }
-            if (lane >= 64 - halo) {
-                hl->data[wave][parity][wr_slot][0] = make_double2(va_blank, va_label);
-                hl->data[wave][parity][wr_slot][1] = make_double2(vb_blank, vb_label);
-                hl->frame[wave][parity][wr_slot] = frame;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            if (lane == 63) __hip_atomic_store(my_ready, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            done_seen = counter(up_done);
-        }
+        const int half = generation & (kRing - 1);
         if (wave > 0) {
-            int ready = counter(low_ready);
+            const int2* const tag = &hl->tag[below][half][rd_slot];
+            const double2* const data = &hl->data[below][half][rd_slot][0];
+            int2 t = read_tag(tag);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            double2 a = hl->data[below][parity][rd_slot][0];
-            double2 b = hl->data[below][parity][rd_slot][1];
-            int vf = hl->frame[below][parity][rd_slot];
-            ready = uniform(ready);
+            double2 a = data[0], b = data[1];
+            int ready = uniform(t.y);
             if (__builtin_expect(ready < generation, 0)) {
                 while (ready < generation && budget > 0) {
                     --budget;
-                    ready = counter(low_ready);
+                    t = read_tag(tag);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    a = hl->data[below][parity][rd_slot][0];
-                    b = hl->data[below][parity][rd_slot][1];
-                    vf = hl->frame[below][parity][rd_slot];
-                    ready = uniform(ready);
+                    a = data[0];
+                    b = data[1];
+                    ready = uniform(t.y);
                 }
                 lost = lost || ready < generation;
             }
@@ -1353,10 +1349,28 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
                 va_label = a.y;
                 vb_blank = b.x;
                 vb_label = b.y;
-                frame = vf;
+                frame = t.x;
             }
+        }
+        if (wave < last_wave) {
+            int seen = uniform(above_seen);
+            if (__builtin_expect(seen < generation - kRing, 0)) {
+                while (seen < generation - kRing && budget > 0) {
+                    --budget;
+                    seen = uniform(generation_of(&hl->tag[above][half][0]));
+                }
+                lost = lost || seen < generation - kRing;
+            }
+            if (lane >= 64 - halo) {
+                hl->data[wave][half][wr_slot][0] = make_double2(va_blank, va_label);
+                hl->data[wave][half][wr_slot][1] = make_double2(vb_blank, vb_label);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                write_tag(&hl->tag[wave][half][wr_slot], frame, generation);
+            }
+            above_seen = generation_of(&hl->tag[above][(half + 1) & (kRing - 1)][0]);
+        } else if (wave > 0) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            if (lane == 0) __hip_atomic_store(my_done, generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (lane == 0) write_tag(&hl->tag[wave][half][0], 0, generation);
         }
     };
 
@@ -1447,7 +1461,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         end_chunk();
         fetch(ela_a, elb_a, eb_a, s0 + 2 * kChunk);
         if (s0 + kChunk < Tb) {
-            run(ela_b, elb_b, eb_b, s0 + kChunk);
+                run(ela_b, elb_b, eb_b, s0 + kChunk);
             end_chunk();
         }
     }
@@ -1508,20 +1522,24 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
     const int waves = two_pairs ? m.waves2 : m.waves;
     const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves;
     if (kSync == Sync::kHalo) {
-        // the counters of the exchange buffer in use
-        int* ready = two_pairs ? static_cast<Halo2Lds*>(lds)->ready : static_cast<HaloLds*>(lds)->ready;
-        int* done = two_pairs ? static_cast<Halo2Lds*>(lds)->done : static_cast<HaloLds*>(lds)->done;
-        if (threadIdx.x < 16) {
-            ready[threadIdx.x] = 0;
-            done[threadIdx.x] = 0;
-        }
-        if (threadIdx.x == 0) {
-            if (two_pairs) {
-                static_cast<Halo2Lds*>(lds)->finished = 0;
-                static_cast<Halo2Lds*>(lds)->gave_up = 0;
-            } else {
-                static_cast<HaloLds*>(lds)->finished = 0;
-                static_cast<HaloLds*>(lds)->gave_up = 0;
+        // the exchange buffer in use starts with every counter and hand-over number at zero
+        if (two_pairs) {
+            Halo2Lds* hl = static_cast<Halo2Lds*>(lds);
+            int* tags = reinterpret_cast<int*>(&hl->tag[0][0][0]);
+            for (int i = threadIdx.x; i < 16 * kRing * kHalo2Lanes * 2; i += blockDim.x) tags[i] = 0;
+            if (threadIdx.x == 0) {
+                hl->finished = 0;
+                hl->gave_up = 0;
+            }
+        } else {
+            HaloLds* hl = static_cast<HaloLds*>(lds);
+            if (threadIdx.x < 16) {
+                hl->ready[threadIdx.x] = 0;
+                hl->done[threadIdx.x] = 0;
+            }
+            if (threadIdx.x == 0) {
+                hl->finished = 0;
+                hl->gave_up = 0;
             }
         }
         __syncthreads();
