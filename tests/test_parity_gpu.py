@@ -277,22 +277,32 @@ def test_device_side_errors_are_reported_as_status():
     assert st == ctc.STATUS_INVALID_VALUE
 
 
-def test_every_wavefront_plan_boundary():
-    """Label lengths on both sides of every change of the wavefront plan (1 to 16 wavefronts with halos of
-    8 to 32 pairs, then the barrier kernel), all three calls: the exchange between wavefronts is exercised in
-    every configuration the planner can produce."""
-    rng = np.random.default_rng(77)
-    A = 6
-    lengths = sorted({62, 63, 64, 65, 95, 96, 97, 119, 120, 121, 159, 160, 161, 183, 184, 199, 200, 201, 231, 232, 233,
-                      271, 272, 287, 288, 327, 328, 343, 344, 399, 400, 455, 456, 511, 512, 567, 568, 623, 624,
-                      679, 680, 735, 736, 791, 792, 847, 848, 895, 896, 902, 903, 904, 960, 1023})
-    T = 1040
+def plan_boundary_batch(lengths, seed, A=6, T=1040):
+    rng = np.random.default_rng(seed)
     labs = [(1 + np.cumsum(rng.integers(1, A - 1, size=n)) % (A - 1)).astype(np.int32) for n in lengths]
     t_b = np.asarray([min(T, max(n + 3, int(n * rng.uniform(1.0, 1.3)) + 2)) for n in lengths], dtype=np.int32)
-    batch = wl.CTCBatch(name="plan-boundaries", T=T, B=len(lengths), A=A, blank=0,
-                        logits=(rng.standard_normal((T, len(lengths), A)) * 2.0).astype(np.float32),
-                        flat_labels=np.concatenate(labs), label_lengths=np.asarray(lengths, dtype=np.int32),
-                        input_lengths=t_b, seed=77)
+    return wl.CTCBatch(name="plan-boundaries", T=T, B=len(lengths), A=A, blank=0,
+                       logits=(rng.standard_normal((T, len(lengths), A)) * 2.0).astype(np.float32),
+                       flat_labels=np.concatenate(labs), label_lengths=np.asarray(lengths, dtype=np.int32),
+                       input_lengths=t_b, seed=seed)
+
+
+@pytest.mark.parametrize("lengths", [
+    # one pair per lane while that takes at most 4 wavefronts (halos of 8 to 32 pairs), two pairs per lane
+    # beyond (2 to 9 wavefronts, halos of 4 to 16 lanes); the best path always has one pair per lane
+    # (up to 16 wavefronts)
+    sorted({62, 63, 64, 65, 95, 96, 97, 119, 120, 121, 159, 160, 161, 183, 184, 199, 200, 201, 231, 232, 233,
+            234, 235, 236, 237, 238, 239, 240, 253, 254, 255, 256, 271, 272, 287, 288, 327, 328, 343, 344, 345,
+            346, 399, 400, 431, 432, 433, 455, 456, 511, 512, 519, 520, 521, 567, 568, 607, 608, 609, 623, 624,
+            679, 680, 695, 696, 697, 735, 736, 783, 784, 785, 791, 792, 847, 848, 871, 872, 873, 895, 896,
+            902, 903}),
+    # labels for which no halo is left with one pair per lane: the launch uses the barrier kernel
+    [100, 903, 904, 960, 1023],
+])
+def test_every_wavefront_plan_boundary(lengths):
+    """Label lengths on both sides of every change of the wavefront plans, all three calls: the exchange
+    between wavefronts is exercised in every configuration the planners can produce."""
+    batch = plan_boundary_batch(lengths, 77)
     costs, grads, _, _ = check(batch)
     assert np.isfinite(costs).all()
     # the cost-only call and the best path run the same chains in their own modes
@@ -307,6 +317,26 @@ def test_every_wavefront_plan_boundary():
     same = sum(np.array_equal(states[b], ref_a[b]) for b in range(batch.B))
     print(f"  best path: {same}/{batch.B} alignments identical to the oracle's", flush=True)
     assert same >= 0.9 * batch.B
+
+
+def test_two_pairs_per_lane_in_a_crowded_launch():
+    """Seven hundred utterances whose labels need two wavefronts with one pair per lane: the launcher plans
+    such a launch for total work, which gives two pairs to every lane (one wavefront for up to 127 symbols,
+    two beyond)."""
+    rng = np.random.default_rng(88)
+    B, T, A = 700, 150, 5
+    lengths = rng.integers(64, 141, size=B)
+    labs = [(1 + np.cumsum(rng.integers(1, A - 1, size=n)) % (A - 1)).astype(np.int32) for n in lengths]
+    batch = wl.CTCBatch(name="crowded", T=T, B=B, A=A, blank=0,
+                        logits=(rng.standard_normal((T, B, A)) * 2.0).astype(np.float32),
+                        flat_labels=np.concatenate(labs), label_lengths=lengths.astype(np.int32),
+                        input_lengths=np.minimum(T, lengths + rng.integers(1, 12, size=B)).astype(np.int32), seed=88)
+    costs, _, _, _ = check(batch)
+    assert np.isfinite(costs).all()
+    db = harness.DeviceBatch(batch)
+    db.run_loss()
+    loss_only, _ = db.results()
+    assert np.abs(loss_only - costs).max() <= 1e-5 * np.abs(costs).max()      # (the cost-only launch is not crowded)
 
 
 def test_many_random_shapes():
