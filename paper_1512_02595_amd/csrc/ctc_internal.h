@@ -25,7 +25,7 @@ struct Utt {
     int64_t ab_off;    // offset (8-byte words) of its alpha/beta blocks [Tb][lattice_pitch(L)]
     int32_t e_pitch;   // floats per frame of its emission block: L (one gathered emission per label
                        // position) or, for alphabets of at most kDirectMaxA symbols, A (the frame's
-                       // whole row of log2 probabilities, indexed by symbol)
+                       // whole normalised row, indexed by symbol)
     int32_t e_direct;  // 1: the block holds whole rows and a label state reads column label[i];
                        // 0: it holds gathered emissions and the state reads column i
     int32_t waves2;    // the same plan for linear-domain chains of more than 64 pairs, whose lanes own

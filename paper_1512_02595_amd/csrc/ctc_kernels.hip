@@ -6,23 +6,26 @@
 //             (or plan: the same records built on the GPU from device-resident lengths and labels)
 //   setup     per utterance: label positions grouped by symbol (the appendix's one-off
 //             key-value sort, done by counting), degenerate costs; rides in the softmax launch
-//   softmax   per frame row: log2-sum-exp2 of the scaled logits, and the log2 emissions of
-//             blank and of every label position, gathered once so that the recursions read
-//             them coalesced
+//   softmax   per frame row: log2-sum-exp2 of the scaled logits, and the emissions (softmax
+//             outputs) of blank and of every label position, gathered once so that the
+//             recursions read them coalesced
 //   lattice   alpha and beta recursions, both in one launch on different workgroups
 //             (cost only: alpha alone; alignment: the max recursion with recorded choices)
 //   gradient  softmax minus the normalised per-symbol occupancy; zero fill of padding
 //             (alignment: the backtrace instead)
 //
-// All lattice quantities are base-2 logarithms: v_exp_f32 / v_log_f32 are base 2, so the
-// recursion carries no scaling multiplies.  log(0) is represented by kNeg, a large finite
-// negative number, which keeps every operation NaN-free: adding emissions to it leaves it
-// unchanged, and 2^(kNeg - anything finite) is exactly 0.
-//
-// alpha and beta are carried and stored in fp64.  Their magnitude grows with the number of
-// frames (thousands of bits for a 15 s utterance) while the gradient needs
-// alpha + beta - log p to about 1e-5 absolute, which fp32 cannot hold at that magnitude.
-// Only the bounded differences that enter exp2/log2 are narrowed to fp32.
+// The recursions run on probabilities, each lane's values in fp64 with an int32 exponent of
+// the lane's own (its "frame") that is renewed every kChunk steps: no transcendentals and a
+// third of the instructions of the log-space form (run_chain_linear, run_chain_linear2).
+// alpha and beta span thousands of binary orders of magnitude over a 15 s utterance, and the
+// states that carry the mass lie a thousand orders below the largest of their frame, so the
+// exponent has to be per lane; fp64 then leaves room for the kChunk steps between renewals.
+// Utterances with an emission below 2^kLinearMinLog2 (found by the softmax launch), launches
+// of the barrier kernel and the maximum recursion use the log-space form instead
+// (run_chain_log): base-2 logarithms in fp64 (v_exp_f32 / v_log_f32 are base 2, so no scaling
+// multiplies; only the bounded differences that enter them are narrowed to fp32), log(0) a
+// large finite negative number, which keeps every operation NaN-free.
+// Either way the lattice is stored as (value, exponent) words, see pack_state.
 
 #include <hip/hip_runtime.h>
 
@@ -479,7 +482,7 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
 }
 
 // Narrow alphabets: a workgroup takes kRows consecutive frames of one utterance, 256 / kRows
-// threads per row.  The normalised log2 probabilities of those rows are kept in LDS
+// threads per row.  The normalised rows (as coded emissions) are kept in LDS
 // (kRows * A floats, dynamic), from where the emissions of all label positions are gathered
 // with the label symbols held in registers.  grid (ceil(T / kRows) + 1, B), the extra column
 // does the setup role.
