@@ -1945,7 +1945,32 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const int tend = min(t0 + rows_per_group, Tt);
     const double* const abase = alpha + m.ab_off + 1;      // label state i sits in column 1 + i
     const double* const bbase = beta + m.ab_off + 1;
-    for (int t = t0 + wave; t < tend; t += 4) {
+    // What a row needs from memory: the lattice words of its first kAhead * 64 label states
+    // (longer labels read the rest in line), its log-sum-exp and its activations.  A row's
+    // values are requested while the row before it is still being summed up out of LDS: by then
+    // the registers are free again (the shares are in LDS), so the overlap costs none.
+    struct RowData {
+        double a[kAhead], b[kAhead];
+        float l2, x0;
+    };
+    auto request = [&](int t, RowData& d) {
+        const double* arow = abase + static_cast<size_t>(t) * pitch;
+        const double* brow = bbase + static_cast<size_t>(t) * pitch;
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int j = u * 64 + lane;
+            if (j < L) {
+                d.a[u] = arow[j];
+                d.b[u] = brow[j];
+            }
+        }
+        d.l2 = lse[static_cast<size_t>(b) * Tt + t];
+        d.x0 = (lane < A) ? load_elem(x + (static_cast<size_t>(t) * B + b) * A, lane) : 0.0f;
+    };
+    RowData cur = {};
+    const int t_first = t0 + wave;
+    if (runs && t_first < tend && t_first < m.Tb) request(t_first, cur);
+    for (int t = t_first; t < tend; t += 4) {
         const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
         T* grow = grads + row_off;
         if (t >= m.Tb || !runs) {
@@ -1954,24 +1979,12 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         const double* arow = abase + static_cast<size_t>(t) * pitch;
         const double* brow = bbase + static_cast<size_t>(t) * pitch;
-        // everything the row needs from memory is requested before the first use
-        double a[kAhead], bb[kAhead];
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const int j = u * 64 + lane;
-            if (j < L) {
-                a[u] = arow[j];
-                bb[u] = brow[j];
-            }
-        }
-        const float l2 = lse[static_cast<size_t>(b) * Tt + t];
-        const float x0 = (lane < A) ? load_elem(x + row_off, lane) : 0.0f;
         float zl = 0.0f;
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             const int j = u * 64 + lane;
             if (j < L) {
-                const float gl = mass_share(a[u], bb[u], inverse_p, inverse_p_exponent);
+                const float gl = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
                 g_slot[s_slot[j]] = gl;
                 zl += gl;
             }
@@ -1981,6 +1994,8 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
             g_slot[s_slot[j]] = gl;
             zl += gl;
         }
+        const float l2 = cur.l2, x0 = cur.x0;
+        if (t + 4 < tend && t + 4 < m.Tb) request(t + 4, cur);
         const float zb = 1.0f - wave_sum(zl);      // the blank states share what is left of 1
         // LDS operations of one wavefront complete in program order; the fence only keeps the
         // compiler from moving them across.
