@@ -22,7 +22,8 @@ int main()
             const ctc::WavePlan p = ctc::plan_waves(L, crowded != 0);
             std::printf("%d %d %d %d %d\n", crowded, L, p.waves, p.halo, p.barrier ? 1 : 0);
             const ctc::WavePlan p2 = ctc::plan_waves2(L, crowded != 0);
-            std::printf("two %d %d %d %d %d\n", crowded, L, p2.waves, p2.halo, p2.barrier ? 1 : 0);
+            std::printf("two %d %d %d %d %d %d\n", crowded, L, p2.waves, p2.halo, p2.barrier ? 1 : 0,
+                        ctc::two_pairs_per_lane(L, crowded != 0) ? 1 : 0);
         }
     std::printf("chunk %d slack %d %d\n", ctc::kChunk, ctc::kBlankSlack, ctc::kLabelSlack);
     return 0;
@@ -72,7 +73,7 @@ def test_every_label_length_has_a_two_pairs_per_lane_plan(plans):
     _, c = plans
     rows = c["two_pairs"]
     assert len(rows) == 2 * 1024
-    for crowded, L, waves, halo, barrier in rows:
+    for crowded, L, waves, halo, barrier, chosen in rows:
         lanes = (L + 2) // 2                        # ceil((L + 1) / 2) lanes hold the L + 1 pairs
         assert not barrier and 1 <= waves <= 16, (L, waves)
         if waves == 1:
@@ -81,6 +82,21 @@ def test_every_label_length_has_a_two_pairs_per_lane_plan(plans):
         # hand-overs every 2 * halo steps fall on chunk boundaries; the exchange buffer holds 16 lanes
         assert (2 * halo) % c["chunk"] == 0 and 4 <= halo <= 16, (L, waves, halo)
         assert waves * (64 - halo) + halo >= lanes, (L, waves, halo)
+
+
+def test_choice_between_one_and_two_pairs_per_lane(plans):
+    """Two pairs per lane only for labels of more than 64 pairs; always when the one-pair plan would put
+    several wavefronts on a SIMD or has no halo left, and always in crowded launches."""
+    rows, c = plans
+    one = {(crowded, L): (waves, barrier) for crowded, L, waves, halo, barrier in rows}
+    for crowded, L, waves2, halo2, _, chosen in c["two_pairs"]:
+        waves1, barrier1 = one[(crowded, L)]
+        if L + 1 <= 64:
+            assert not chosen, L
+        else:
+            assert bool(chosen) == bool(crowded or barrier1 or waves1 > 4), (crowded, L, waves1, chosen)
+        if chosen:
+            assert waves2 <= waves1, (crowded, L, waves1, waves2)
 
 
 def test_plans_only_switch_to_the_barrier_kernel_when_no_halo_fits(plans):
