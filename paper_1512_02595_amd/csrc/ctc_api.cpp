@@ -241,7 +241,8 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.Tb = Tb;
         m.L = L;
         m.lab_off = static_cast<int32_t>(lab_off);
-        m.flags = (runs ? kUttRuns : 0) | (two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0);
+        m.flags = (runs ? kUttRuns : 0) | (two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0) |
+                  (Tb > kLinearMaxFrames ? kUttLogDomain : 0);
         m.f_off = static_cast<int32_t>(f_off);
         const WavePlan wp = plan_waves(L, crowded);
         m.waves = wp.waves;

@@ -135,6 +135,9 @@ constexpr int kUttLogDomain = 4;
 // (plan_waves2) instead of one (plan_waves): see two_pairs_per_lane.
 constexpr int kUttTwoPairs = 8;
 constexpr float kLinearMinLog2 = -100.0f;
+// Utterances of more frames than this run the log domain whatever their emissions: the lanes'
+// exponents, which fall by up to 100 per frame, must stay clear of kNoExponent and of int32's end.
+constexpr int kLinearMaxFrames = 1 << 21;
 // Lattice wavefronts of one launch beyond which chains are planned for total work: two per SIMD
 // of the 256 compute units.
 constexpr int kCrowdedWaves = 2 * 4 * 256;

@@ -236,7 +236,8 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         m.Tb = bad ? 0 : Tb;
         m.L = bad ? 0 : L;
         m.lab_off = b * max_label;
-        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) | (log_domain ? kUttLogDomain : 0) |
+        m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) |
+                  ((log_domain || Tb > kLinearMaxFrames) ? kUttLogDomain : 0) |
                   (!bad && two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0);
         m.f_off = b * Tt;
         m.waves = wp.waves;

@@ -161,6 +161,20 @@ def test_single_symbol_alphabet_long_repeats():
                          feasible_only=True))
 
 
+def test_two_million_frames():
+    """Utterances as long as the linear-domain recursion takes (2^21 frames; the lanes' exponents go down to
+    minus several millions) and one frame longer, which the launcher sends to the log domain."""
+    rng = np.random.default_rng(91)
+    T, B, A = (1 << 21) + 1, 2, 3
+    x = rng.standard_normal((T, B, A)).astype(np.float32)
+    labs = [rng.integers(1, A, size=5), rng.integers(1, A, size=70)]
+    batch = wl.CTCBatch(name="two-million-frames", T=T, B=B, A=A, blank=0, logits=x,
+                        flat_labels=np.concatenate(labs).astype(np.int32),
+                        label_lengths=np.array([5, 70], dtype=np.int32),
+                        input_lengths=np.array([T, T - 1], dtype=np.int32), seed=91)
+    check(batch)
+
+
 def test_degenerate_lengths():
     """Empty labels, zero frames, single frames, the feasibility boundary."""
     rng = np.random.default_rng(0)
