@@ -53,6 +53,8 @@ def test_matches_the_host_metadata_call_bitwise_and_the_oracle():
     lambda: wl.make_random(2, T=40, B=9, A=9, max_label=30),                                   # infeasible pairs
     lambda: wl.make_random(4, T=300, B=7, A=5, max_label=290, min_input=250, feasible_only=True),  # several wavefronts
     lambda: wl.make_random(17, T=50, B=4, A=29, max_label=0),                                  # empty labels
+    lambda: wl.make_random(81, T=120, B=6, A=7, max_label=40, min_input=90, sigma=60.0, feasible_only=True),  # emissions below the linear range
+    lambda: wl.make_random(6, T=420, B=3, A=4, max_label=400, min_input=410, feasible_only=True),  # two pairs per lane
 ])
 def test_matches_the_host_metadata_call_on_other_shapes(maker):
     both_paths(maker())
