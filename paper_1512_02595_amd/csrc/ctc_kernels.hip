@@ -130,6 +130,19 @@ __device__ __forceinline__ float row16_max(float v)
     v = fmaxf(v, dpp_permute<0x140>(v));
     return v;
 }
+// The same over groups of 4 neighbouring lanes.
+__device__ __forceinline__ float quad_sum(float v)
+{
+    v += dpp_permute<0xB1>(v);
+    v += dpp_permute<0x4E>(v);
+    return v;
+}
+__device__ __forceinline__ float quad_max(float v)
+{
+    v = fmaxf(v, dpp_permute<0xB1>(v));
+    v = fmaxf(v, dpp_permute<0x4E>(v));
+    return v;
+}
 // Whole wavefront (all 64 lanes active); the four row results are combined in a fixed order.
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -494,8 +507,8 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
                              float* __restrict__ emit_blank, float* __restrict__ emit_label,
                              const SetupArgs sa, int Tt, int B, int A, int blank)
 {
-    constexpr int kPerRow = kRowThreads / kRows;          // threads per row: a 16-lane row or a wavefront
-    static_assert(kPerRow == 16 || kPerRow == 64, "row reductions exist for 16 and 64 lanes");
+    constexpr int kPerRow = kRowThreads / kRows;          // threads per row: a quad, a 16-lane row or a wavefront
+    static_assert(kPerRow == 4 || kPerRow == 16 || kPerRow == 64, "row reductions exist for 4, 16 and 64 lanes");
     extern __shared__ float lp[];                          // [kRows][A]
     __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
     const int b = blockIdx.y, tid = threadIdx.x;
@@ -526,11 +539,11 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
                 mx = fmaxf(mx, v[u]);
             }
         }
-        mx = (kPerRow == 16) ? row16_max(mx) : wave_max(mx);
+        mx = (kPerRow == 4) ? quad_max(mx) : (kPerRow == 16) ? row16_max(mx) : wave_max(mx);
         mx *= kLog2e;
         float sum = 0.0f;
         for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
-        sum = (kPerRow == 16) ? row16_sum(sum) : wave_sum(sum);
+        sum = (kPerRow == 4) ? quad_sum(sum) : (kPerRow == 16) ? row16_sum(sum) : wave_sum(sum);
         const float l2 = mx + fast_log2(sum);
         // (coded as emissions; `unused` because what counts is which of them get stored below)
         bool unused = false;
@@ -2076,7 +2089,20 @@ int launch_softmax(const Launch& p, void* stream)
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;
     return checked_launch([&] {
-        if (p.A <= 512) {
+        if (p.A <= kDirectMaxA) {
+            // the smallest alphabets: 64 frames per workgroup, four lanes per frame, so that a
+            // workgroup has several kilobytes under way
+            const dim3 grid((p.T + 63) / 64 + 1, p.B);
+            const size_t lds = static_cast<size_t>(64) * p.A * sizeof(float);
+            if (f32)
+                hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 64>), grid, block, lds, s,
+                                   static_cast<const float*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 64>), grid, block, lds, s,
+                                   static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
+                                   emit_label, sa, p.T, p.B, p.A, p.blank);
+        } else if (p.A <= 512) {
             const dim3 grid((p.T + 15) / 16 + 1, p.B);
             const size_t lds = static_cast<size_t>(16) * p.A * sizeof(float);
             if (f32)
