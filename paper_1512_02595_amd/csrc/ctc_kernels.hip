@@ -143,6 +143,12 @@ __device__ __forceinline__ float quad_max(float v)
     v = fmaxf(v, dpp_permute<0x4E>(v));
     return v;
 }
+__device__ __forceinline__ int quad_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);
+    return v;
+}
 // Whole wavefront (all 64 lanes active); the four row results are combined in a fixed order.
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -306,28 +312,44 @@ struct SetupArgs {
     int* host_flag;       // pinned host word: receives flag_value once the upload has been consumed
     int flag_value;
     bool plain_logs;      // emissions are stored as log2 probabilities throughout (most probable alignment)
+    int parts;            // workgroups per utterance that share the setup role (grid columns beyond the rows)
 };
 
+// The grouping compares every pair of label positions; it is spread over `parts` workgroups per
+// utterance (64 positions each at a time) and four lanes per position, each lane walking a quarter
+// of the label, so that a label of 500 symbols costs 125 steps per lane instead of 1000.
+constexpr int kSetupLabelSlots = CTC_MAX_LABEL_LENGTH + 5;     // the label and a quarter's padding
+
 __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* __restrict__ labels,
-                                           const SetupArgs sa, int* s_lab)
+                                           const SetupArgs sa, int* s_lab, const int part, const int parts)
 {
     const int tid = threadIdx.x;
     const int* lab = labels + m.lab_off;
-    for (int j = tid; j < m.L; j += kRowThreads) s_lab[j] = lab[j];
+    const int quarter_length = (m.L + 3) / 4;
+    // padding: a symbol that is neither smaller than nor equal to any real one
+    for (int j = tid; j < 4 * quarter_length; j += kRowThreads) s_lab[j] = (j < m.L) ? lab[j] : 0x7FFFFFFF;
     __syncthreads();
-    for (int j = tid; j < m.L; j += kRowThreads) {
+    const int quarter = tid & 3;
+    const int* const mine = s_lab + quarter * quarter_length;
+    const int first_i = quarter * quarter_length;
+    for (int j = part * 64 + (tid >> 2); j < m.L; j += parts * 64) {
         const int c = s_lab[j];
-        // Independent iterations keep the LDS reads (one broadcast each) in flight.
+        // Independent iterations keep the LDS reads in flight.
         int below = 0, before = 0, count = 0;
-        for (int i = 0; i < m.L; ++i) {
-            const int ci = s_lab[i];
+        for (int i = 0; i < quarter_length; ++i) {
+            const int ci = mine[i];
             below += ci < c;
             count += ci == c;
-            before += (ci == c) & (i < j);
+            before += (ci == c) & (first_i + i < j);
         }
-        sa.links[m.lab_off + j] = (below + before) | (count << kLinkCountShift) |
-                                  (before == 0 ? static_cast<int>(0x80000000u) : 0);
+        below = quad_sum(below);
+        count = quad_sum(count);
+        before = quad_sum(before);
+        if (quarter == 0)
+            sa.links[m.lab_off + j] = (below + before) | (count << kLinkCountShift) |
+                                      (before == 0 ? static_cast<int>(0x80000000u) : 0);
     }
+    if (part != 0) return;
     if (tid == 0) {
         sa.chain_err[b] = 0;
         if (b == 0) {
@@ -382,10 +404,10 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
                         const SetupArgs sa, int Tt, int B, int A, int blank)
 {
     __shared__ float red[8];
-    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
+    __shared__ int s_lab[kSetupLabelSlots];
     const int t = blockIdx.x, b = blockIdx.y;
     const Utt m = meta[b];
-    if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
+    if (t == Tt) { setup_role(m, b, labels, sa, s_lab, 0, 1); return; }
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
     T* grow = grads + row_off;
     const bool runs = (m.flags & kUttRuns) != 0;
@@ -434,11 +456,11 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
     constexpr int N = Vec<T>::N;
     constexpr int kVecs = kWideMaxA / (N * kRowThreads);      // vectors per thread
     __shared__ float red[8];
-    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
+    __shared__ int s_lab[kSetupLabelSlots];
     // Utterance fastest: consecutive workgroups take consecutive rows of the tensor.
     const int t = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
     const Utt m = meta[b];
-    if (t == Tt) { setup_role(m, b, labels, sa, s_lab); return; }
+    if (t == Tt) { setup_role(m, b, labels, sa, s_lab, 0, 1); return; }
     const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
     T* grow = grads + row_off;
     const int nvec = A / N;
@@ -510,10 +532,13 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
     constexpr int kPerRow = kRowThreads / kRows;          // threads per row: a quad, a 16-lane row or a wavefront
     static_assert(kPerRow == 4 || kPerRow == 16 || kPerRow == 64, "row reductions exist for 4, 16 and 64 lanes");
     extern __shared__ float lp[];                          // [kRows][A]
-    __shared__ int s_lab[CTC_MAX_LABEL_LENGTH + 1];
+    __shared__ int s_lab[kSetupLabelSlots];
     const int b = blockIdx.y, tid = threadIdx.x;
     const Utt m = meta[b];
-    if (blockIdx.x == gridDim.x - 1) { setup_role(m, b, labels, sa, s_lab); return; }
+    if (blockIdx.x >= gridDim.x - sa.parts) {
+        setup_role(m, b, labels, sa, s_lab, static_cast<int>(blockIdx.x - (gridDim.x - sa.parts)), sa.parts);
+        return;
+    }
     const int t0 = blockIdx.x * kRows;
     if (t0 >= m.Tb) return;
     const int r = tid / kPerRow, q = tid % kPerRow, t = t0 + r;
@@ -2084,7 +2109,10 @@ int launch_softmax(const Launch& p, void* stream)
     auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
     const SetupArgs sa{reinterpret_cast<int*>(p.ws + p.lay.links), p.costs,
                        reinterpret_cast<int*>(p.ws + p.lay.chain_err), emit_label,
-                       p.host_flag, p.host_flag_value, p.mode == Mode::kBest};
+                       p.host_flag, p.host_flag_value, p.mode == Mode::kBest,
+                       // few utterances: spread each one's grouping over several workgroups (its
+                       // latency counts); many: one workgroup each keeps the chip busy already
+                       p.B >= 256 ? 1 : std::max(1, (p.max_label + 63) / 64)};
     const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;
@@ -2092,7 +2120,7 @@ int launch_softmax(const Launch& p, void* stream)
         if (p.A <= kDirectMaxA) {
             // the smallest alphabets: 64 frames per workgroup, four lanes per frame, so that a
             // workgroup has several kilobytes under way
-            const dim3 grid((p.T + 63) / 64 + 1, p.B);
+            const dim3 grid((p.T + 63) / 64 + sa.parts, p.B);
             const size_t lds = static_cast<size_t>(64) * p.A * sizeof(float);
             if (f32)
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 64>), grid, block, lds, s,
@@ -2103,7 +2131,7 @@ int launch_softmax(const Launch& p, void* stream)
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
                                    emit_label, sa, p.T, p.B, p.A, p.blank);
         } else if (p.A <= 512) {
-            const dim3 grid((p.T + 15) / 16 + 1, p.B);
+            const dim3 grid((p.T + 15) / 16 + sa.parts, p.B);
             const size_t lds = static_cast<size_t>(16) * p.A * sizeof(float);
             if (f32)
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 16>), grid, block, lds, s,
@@ -2114,7 +2142,7 @@ int launch_softmax(const Launch& p, void* stream)
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
                                    emit_label, sa, p.T, p.B, p.A, p.blank);
         } else if (p.A <= kRowsMaxA) {
-            const dim3 grid((p.T + 3) / 4 + 1, p.B);
+            const dim3 grid((p.T + 3) / 4 + sa.parts, p.B);
             const size_t lds = static_cast<size_t>(4) * p.A * sizeof(float);
             if (f32)
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<float, 4>), grid, block, lds, s,
