@@ -163,6 +163,25 @@ __device__ __forceinline__ float wave_max(float v)
                  fmaxf(__int_as_float(__builtin_amdgcn_readlane(r, 32)), __int_as_float(__builtin_amdgcn_readlane(r, 48))));
 }
 
+// Inclusive running sum over the 64 lanes of a wavefront (all active): lane i receives
+// v_0 + ... + v_i, added up in a fixed order.  Four shifted additions within each row of 16
+// lanes, then the last lane of a row is added to the rows above it (row_bcast).
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ float dpp_or_zero(float v)     // lanes without a source lane, or outside the rows, get 0
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, kRowMask, 0xf, false));
+}
+__device__ __forceinline__ float wave_running_sum(float v)
+{
+    v += dpp_or_zero<0x111, 0xf>(v);      // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);      // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);      // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);      // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);      // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xc>(v);      // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // `slot` is 4 floats of LDS private to this reduction.
 __device__ __forceinline__ float block_sum(float v, float* slot)
 {
@@ -1936,9 +1955,13 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
 }
 
 // Alphabets of at most 64 symbols (the English one has 29): lane k of a row's wavefront is
-// symbol k.  It adds up the run of slots of its symbol (start and length per symbol are put
-// into LDS once per workgroup) and writes grad[k] = y_k - occupancy_k straight away: no scan
-// over the label for first occurrences and no occupancy array per row.
+// symbol k.  The shares, which sit in slot order (the positions of a symbol next to each other),
+// are turned into running sums with wavefront scans; a symbol's occupancy is then the
+// difference of the entries at the two ends of its run (start and length per symbol are put
+// into LDS once per workgroup), the blank's is 1 minus the total, and lane k writes
+// grad[k] = y_k - occupancy_k straight away: no loop over a run, no scan over the label for first
+// occurrences, no occupancy array per row.  The order of the additions is fixed, so results
+// repeat bitwise.
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
@@ -1997,6 +2020,7 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         const double* brow = bbase + static_cast<size_t>(t) * pitch;
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
+            if (u * 64 >= L) break;                      // (the same for every lane)
             const int j = u * 64 + lane;
             if (j < L) {
                 d.a[u] = arow[j];
@@ -2018,40 +2042,35 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         const double* arow = abase + static_cast<size_t>(t) * pitch;
         const double* brow = bbase + static_cast<size_t>(t) * pitch;
-        float zl = 0.0f;
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
+            if (u * 64 >= L) break;                      // (the same for every lane)
             const int j = u * 64 + lane;
-            if (j < L) {
-                const float gl = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
-                g_slot[s_slot[j]] = gl;
-                zl += gl;
-            }
+            if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
         }
-        for (int j = kAhead * 64 + lane; j < L; j += 64) {
-            const float gl = mass_share(arow[j], brow[j], inverse_p, inverse_p_exponent);
-            g_slot[s_slot[j]] = gl;
-            zl += gl;
-        }
+        for (int j = kAhead * 64 + lane; j < L; j += 64)
+            g_slot[s_slot[j]] = mass_share(arow[j], brow[j], inverse_p, inverse_p_exponent);
         const float l2 = cur.l2, x0 = cur.x0;
         if (t + 4 < tend && t + 4 < m.Tb) request(t + 4, cur);
-        const float zb = 1.0f - wave_sum(zl);      // the blank states share what is left of 1
-        // LDS operations of one wavefront complete in program order; the fence only keeps the
+        // LDS operations of one wavefront complete in program order; the fences only keep the
         // compiler from moving them across.
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        float o = 0.0f;
+        // The shares now sit in slot order, the positions of a symbol next to each other: turn
+        // them into running sums (64 slots at a time, the total so far carried along), so that
+        // a symbol's occupancy is the difference of two entries and the blank's 1 minus the last.
+        float carried = 0.0f;
+        for (int base = 0; base < L; base += 64) {
+            const int slot = base + lane;
+            const float sum = wave_running_sum(slot < L ? g_slot[slot] : 0.0f) + carried;
+            if (slot < L) g_slot[slot] = sum;
+            carried = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sum), 63));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         if (lane < A) {
             const int first = s_start[lane], count = s_count[lane];
-            // Eight independent reads at a time; slots past the run add an exact zero, so the
-            // order of summation is the run's own (positions ascending).
-            for (int i0 = 0; i0 < count; i0 += 8) {
-                float g[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) g[i] = g_slot[min(first + i0 + i, L - 1)];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) o += (i0 + i < count) ? g[i] : 0.0f;
-            }
-            if (lane == blank) o = zb;
+            float o = 0.0f;
+            if (count > 0) o = g_slot[first + count - 1] - (first > 0 ? g_slot[first - 1] : 0.0f);
+            if (lane == blank) o = 1.0f - carried;       // the blank states share what is left of 1
             store_elem(grow, lane, fast_exp2(fmaf(x0, kLog2e, -l2)) - o);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
