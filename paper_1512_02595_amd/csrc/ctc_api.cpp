@@ -34,6 +34,20 @@ inline bool record(int err)
 }  // namespace
 
 namespace {
+// Compute units of the current device (asked once per device).
+int compute_units()
+{
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 // Region offsets from the batch totals (label symbols, label emissions, frames, lattice pairs).
 void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab, Layout* lay)
 {
@@ -44,7 +58,7 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.ab_doubles = ab;
     size_t off = 0;
     l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 64 B each: stays 8-byte aligned
-    l.order = off;  off += static_cast<size_t>(B) * sizeof(int32_t);
+    l.order = off;  off += static_cast<size_t>(B) * 2 * sizeof(int32_t);
     l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
     l.upload_bytes = off;
     off = align_up(off);
@@ -266,16 +280,27 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
             max_frames = std::max(max_frames, Tb);
         }
     }
-    for (int i = n_run; i < c.B; ++i) order[i] = -1;
     // The one-barrier-per-step kernel only has the log-domain recursion.
     if (needs_barrier)
         for (int b = 0; b < c.B; ++b) meta[b].flags |= kUttLogDomain;
-    // Heaviest chains first, so the longest recursion does not start last.
-    std::stable_sort(order, order + n_run, [&](int a, int b) {
-        const int64_t wa = static_cast<int64_t>(meta[a].Tb) * ((meta[a].flags & kUttTwoPairs) ? meta[a].waves2 : meta[a].waves);
-        const int64_t wb = static_cast<int64_t>(meta[b].Tb) * ((meta[b].flags & kUttTwoPairs) ? meta[b].waves2 : meta[b].waves);
-        return wa > wb;
+    // Heaviest chains first, so the longest recursion does not start last; launches of more
+    // chains than compute units are ordered for the SIMDs' loads (order_chains).
+    auto chain_waves = [&](int b) {
+        const bool two = (meta[b].flags & (kUttTwoPairs | kUttLogDomain)) == kUttTwoPairs && c.mode != Mode::kBest;
+        return two ? meta[b].waves2 : meta[b].waves;
+    };
+    std::vector<int32_t> running(order, order + n_run);
+    std::stable_sort(running.begin(), running.end(), [&](int a, int b) {
+        return static_cast<int64_t>(meta[a].Tb) * chain_waves(a) > static_cast<int64_t>(meta[b].Tb) * chain_waves(b);
     });
+    std::vector<int32_t> run_frames(static_cast<size_t>(n_run)), run_waves(static_cast<size_t>(n_run));
+    for (int i = 0; i < n_run; ++i) {
+        run_frames[i] = meta[running[i]].Tb;
+        run_waves[i] = chain_waves(running[i]);
+    }
+    const int dirs = c.mode == Mode::kGrad ? 2 : 1;
+    order_chains(running.data(), run_frames.data(), run_waves.data(), n_run, dirs, compute_units(), order);
+    for (int i = n_run * dirs; i < 2 * c.B; ++i) order[i] = -1;
 
     if (c.ws_bytes < lay.total) return CTC_STATUS_WORKSPACE_TOO_SMALL;
 
@@ -283,6 +308,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->T = c.T; out->B = c.B; out->A = c.A; out->blank = c.blank;
     out->dtype = c.dtype;
     out->n_run = n_run;
+    out->n_chains = n_run * dirs;
     out->max_waves = max_waves;
     out->max_frames = max_frames;
     out->max_label = max_label;
@@ -418,7 +444,8 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.mode = grads ? Mode::kGrad : Mode::kLoss;
     p.T = T; p.B = B; p.A = A; p.blank = blank;
     p.dtype = dtype;
-    p.n_run = B;                       // one lattice workgroup per utterance; those that do not run leave at once
+    p.n_run = B;                       // a lattice workgroup per utterance and direction; those that do not run leave at once
+    p.n_chains = B * (grads ? 2 : 1);
     p.max_waves = 1;
     p.crowded = static_cast<int64_t>(B) * (two_pairs_per_lane(max_label, false) ? plan_waves2(max_label).waves
                                                                                 : plan_waves(max_label).waves) *

@@ -225,17 +225,21 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
                      const int* __restrict__ input_lengths, Utt* __restrict__ meta,
                      int* __restrict__ order, int* __restrict__ status,
                      int Tt, int B, int A, int blank, int max_label, int poll_budget, bool crowded,
-                     bool log_domain)
+                     bool log_domain, int dirs)
 {
     __shared__ long long weight[kMaxDeviceMetaB];     // T_b x wavefronts; -1: does not run
     __shared__ int repeats[kMaxDeviceMetaB];          // adjacent equal symbols; kBadLabel added for a bad symbol
-    __shared__ int s_bad;
+    __shared__ int s_bad, s_running;
     constexpr int kBadLabel = 1 << 20;
     const int tid = threadIdx.x;
-    if (tid == 0) s_bad = 0;
+    if (tid == 0) {
+        s_bad = 0;
+        s_running = 0;
+    }
     int* const s_len = reinterpret_cast<int*>(weight);       // label lengths, until the weights are written
     for (int i = tid; i < B; i += kPlanThreads) {
-        order[i] = -1;
+        order[2 * i] = -1;
+        order[2 * i + 1] = -1;
         repeats[i] = 0;
         s_len[i] = label_lengths[i];
     }
@@ -291,6 +295,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         meta[b] = m;
         weight[b] = runs ? static_cast<long long>(Tb) * ((m.flags & kUttTwoPairs) ? wp2.waves : wp.waves) : -1;
         if (bad) s_bad = 1;
+        if (runs) atomicAdd(&s_running, 1);
     }
     __syncthreads();
     if (tid == 0) *status = s_bad ? CTC_STATUS_INVALID_VALUE : CTC_STATUS_SUCCESS;
@@ -302,7 +307,11 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
             const long long wj = weight[j];
             rank += (wj > wi) || (wj == wi && j < i);
         }
-        order[rank] = i;
+        // Heaviest first, in blocks of kChainBlock utterances: a block's forward chains, then its
+        // backward chains (order_chains; the device planner does not balance the SIMDs' loads
+        // beyond that).
+        const int first = rank - rank % kChainBlock, in_block = min(kChainBlock, s_running - first);
+        for (int d = 0; d < dirs; ++d) order[first * dirs + d * in_block + rank % kChainBlock] = 2 * i + d;
     }
 }
 
@@ -1572,8 +1581,10 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
                                              int* __restrict__ chain_err, double* __restrict__ sink,
                                              void* lds)
 {
-    const int u = order[blockIdx.x];
-    if (u < 0) return;                  // device-planned batches launch one workgroup per utterance, running or not
+    const int chain = order[blockIdx.x];           // utterance * 2 + direction
+    if (chain < 0) return;              // device-planned batches launch a workgroup per utterance and direction, running or not
+    const int u = chain >> 1;
+    const bool forward = kMode != Mode::kGrad || (chain & 1) == 0;
     const Utt m = meta[u];
     // Which recursion: the barrier kernel and the maximum recursion have the log domain only;
     // otherwise the flag that the softmax launch may have raised decides.  A linear-domain chain
@@ -1609,12 +1620,11 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         if (idle) {
             // Nothing to compute, but keep meeting the barriers of the working wavefronts:
             // one per recursion step, plus the forward chain's final exchange.
-            const int barriers = (m.Tb - 1) + (blockIdx.y == 0 ? 1 : 0);
+            const int barriers = (m.Tb - 1) + (forward ? 1 : 0);
             for (int i = 0; i < barriers; ++i) __syncthreads();
             return;
         }
     }
-    const bool forward = kMode != Mode::kGrad || blockIdx.y == 0;
     if constexpr (kSync != Sync::kBarrier && kMode != Mode::kBest) {
         if (two_pairs) {
             if constexpr (kSync == Sync::kHalo) {
@@ -1639,9 +1649,9 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         run_chain_log<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
 }
 
-// grid = (utterances whose lattice runs, 2) for Mode::kGrad: y = 0 forward, y = 1 backward;
-// (utterances, 1) for the other modes, which only run forward (`alpha` is then the block that
-// receives the predecessor choices, or unused).
+// grid = one workgroup per entry of `order` (utterance * 2 + direction: 0 forward, 1 backward; only
+// Mode::kGrad has backward chains; in the other modes `alpha` is the block that receives the
+// predecessor choices, or unused).
 // blockDim.x = 64 * (most wavefronts any utterance of the batch uses).
 // Variant for batches whose labels all fit one wavefront: no exchange at all.
 template <Mode kMode>
@@ -2115,7 +2125,7 @@ int launch_plan(const Launch& p, void* stream)
                            p.labels, p.dev_label_lengths, p.dev_input_lengths,
                            reinterpret_cast<Utt*>(p.ws + p.lay.meta), reinterpret_cast<int*>(p.ws + p.lay.order),
                            p.dev_status, p.T, p.B, p.A, p.blank, p.max_label, p.poll_budget, p.crowded,
-                           p.needs_barrier);
+                           p.needs_barrier, p.mode == Mode::kGrad ? 2 : 1);
     });
 }
 
@@ -2208,7 +2218,7 @@ int launch_lattice(const Launch& p, void* stream)
     auto* beta = reinterpret_cast<double*>(p.ws + p.lay.beta);
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
-    const dim3 grid(p.n_run, p.mode == Mode::kGrad ? 2 : 1), block(64 * p.max_waves);
+    const dim3 grid(p.n_chains), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
     hipLaunchKernelGGL(KERNEL, grid, block, 0, s, meta, order, labels, emit_blank, emit_label,     \
