@@ -756,7 +756,7 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     // Launches for the most probable alignment store plain logarithms, the others coded emissions.
     constexpr bool kCoded = kMode != Mode::kBest;
     const int L = m.L, Tb = m.Tb, P = L + 1;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: in a scalar register)
     const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
     const int j = wave * (64 - halo) + lane;
     const int* lab = labels + m.lab_off;
@@ -1054,7 +1054,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     static_assert(kSync != Sync::kBarrier, "the barrier kernel runs the log-domain chain");
     static_assert(kMode != Mode::kBest, "the maximum recursion runs in the log domain");
     const int L = m.L, Tb = m.Tb;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: in a scalar register)
     const int halo = (kSync == Sync::kHalo) ? m.halo : 0;
     const int j = wave * (64 - halo) + lane;             // pair of this lane (see run_chain_log)
     const int* lab = labels + m.lab_off;
@@ -1318,7 +1318,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
     static_assert(kMode != Mode::kBest, "the maximum recursion runs in the log domain");
     const int L = m.L, Tb = m.Tb;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: in a scalar register)
     const int halo = m.halo2, waves = m.waves2;
     const int q = wave * (64 - halo) + lane;
     const int ja = 2 * q, jb = 2 * q + 1;                // the lane's pairs, in the chain's own order
@@ -2025,33 +2025,41 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         double a[kAhead], b[kAhead];
         float l2, x0;
     };
-    auto request = [&](int t, RowData& d) {
-        const double* arow = abase + static_cast<size_t>(t) * pitch;
-        const double* brow = bbase + static_cast<size_t>(t) * pitch;
+    // Row addresses are kept as running pointers of this wavefront's rows (t_first, t_first + 4,
+    // ...): the products t x pitch and (t x B + b) x A are formed once, not per row.
+    const int t_first = t0 + wave;
+    const double* next_a = abase + static_cast<size_t>(t_first) * pitch + lane;       // of the row to request next
+    const double* next_b = bbase + static_cast<size_t>(t_first) * pitch + lane;
+    const float* next_lse = lse + static_cast<size_t>(b) * Tt + t_first;
+    const size_t row_step = static_cast<size_t>(4) * B * A;
+    const T* next_x = x + (static_cast<size_t>(t_first) * B + b) * A;
+    T* grow = grads + (static_cast<size_t>(t_first) * B + b) * A;                     // of the row being written
+    auto request = [&](RowData& d) {
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             if (u * 64 >= L) break;                      // (the same for every lane)
-            const int j = u * 64 + lane;
-            if (j < L) {
-                d.a[u] = arow[j];
-                d.b[u] = brow[j];
+            if (u * 64 + lane < L) {
+                d.a[u] = next_a[u * 64];
+                d.b[u] = next_b[u * 64];
             }
         }
-        d.l2 = lse[static_cast<size_t>(b) * Tt + t];
-        d.x0 = (lane < A) ? load_elem(x + (static_cast<size_t>(t) * B + b) * A, lane) : 0.0f;
+        d.l2 = *next_lse;
+        d.x0 = (lane < A) ? load_elem(next_x, lane) : 0.0f;
+    };
+    auto advance_request = [&]() {
+        next_a += 4 * pitch;
+        next_b += 4 * pitch;
+        next_lse += 4;
+        next_x += row_step;
     };
     RowData cur = {};
-    const int t_first = t0 + wave;
-    if (runs && t_first < tend && t_first < m.Tb) request(t_first, cur);
-    for (int t = t_first; t < tend; t += 4) {
-        const size_t row_off = (static_cast<size_t>(t) * B + b) * A;
-        T* grow = grads + row_off;
+    if (runs && t_first < tend && t_first < m.Tb) request(cur);
+    for (int t = t_first; t < tend; t += 4, grow += row_step) {
         if (t >= m.Tb || !runs) {
             if (lane < A) store_elem(grow, lane, 0.0f);
             continue;
         }
-        const double* arow = abase + static_cast<size_t>(t) * pitch;
-        const double* brow = bbase + static_cast<size_t>(t) * pitch;
+        const double* arow = next_a, * brow = next_b;     // this row's, past its first kAhead * 64 states
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             if (u * 64 >= L) break;                      // (the same for every lane)
@@ -2059,9 +2067,10 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
             if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
         }
         for (int j = kAhead * 64 + lane; j < L; j += 64)
-            g_slot[s_slot[j]] = mass_share(arow[j], brow[j], inverse_p, inverse_p_exponent);
+            g_slot[s_slot[j]] = mass_share(arow[j - lane], brow[j - lane], inverse_p, inverse_p_exponent);
         const float l2 = cur.l2, x0 = cur.x0;
-        if (t + 4 < tend && t + 4 < m.Tb) request(t + 4, cur);
+        advance_request();
+        if (t + 4 < tend && t + 4 < m.Tb) request(cur);
         // LDS operations of one wavefront complete in program order; the fences only keep the
         // compiler from moving them across.
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
