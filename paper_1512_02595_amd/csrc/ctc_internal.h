@@ -9,6 +9,10 @@
 
 #include "ctc_mi355x.h"
 
+#ifndef CTC_STREAMING_MB
+#define CTC_STREAMING_MB 128
+#endif
+
 namespace ctc {
 
 // Per-utterance record, identical on host and device (48 bytes).
@@ -205,6 +209,10 @@ inline void order_chains(const int32_t* utt, const int32_t* frames, const int32_
     }
 }
 
+// Lattice size (alpha and beta together) beyond which the gradient kernel reads it with loads
+// that leave no copy in the caches.  Measured on gfx950: 0.4 GB (512 utterances) 141 -> 104 us with
+// such loads, 53 MB (64 utterances) 14.9 -> 15.7 us.
+constexpr size_t kStreamingLatticeBytes = size_t(CTC_STREAMING_MB) << 20;
 constexpr int kDefaultPollBudget = 1 << 22;   // enough for seconds of waiting: only a stuck neighbour exhausts it
 constexpr int kMaxBatch = 65535;         // utterances index the second grid dimension of the row kernels
 constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ranks in LDS

@@ -1972,7 +1972,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
 // grad[k] = y_k - occupancy_k straight away: no loop over a run, no scan over the label for first
 // occurrences, no occupancy array per row.  The order of the additions is fixed, so results
 // repeat bitwise.
-template <typename T>
+template <typename T, bool kStreaming>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
                                 const Utt* __restrict__ meta, const int* __restrict__ labels,
@@ -2034,13 +2034,16 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const size_t row_step = static_cast<size_t>(4) * B * A;
     const T* next_x = x + (static_cast<size_t>(t_first) * B + b) * A;
     T* grow = grads + (static_cast<size_t>(t_first) * B + b) * A;                     // of the row being written
+    // A lattice larger than the caches is read once and never again: such launches use loads that
+    // leave no copy behind (kStreaming), which keeps the caches for the rest.
+    auto lattice_word = [&](const double* p) { return kStreaming ? __builtin_nontemporal_load(p) : *p; };
     auto request = [&](RowData& d) {
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             if (u * 64 >= L) break;                      // (the same for every lane)
             if (u * 64 + lane < L) {
-                d.a[u] = next_a[u * 64];
-                d.b[u] = next_b[u * 64];
+                d.a[u] = lattice_word(next_a + u * 64);
+                d.b[u] = lattice_word(next_b + u * 64);
             }
         }
         d.l2 = *next_lse;
@@ -2067,7 +2070,8 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
             if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
         }
         for (int j = kAhead * 64 + lane; j < L; j += 64)
-            g_slot[s_slot[j]] = mass_share(arow[j - lane], brow[j - lane], inverse_p, inverse_p_exponent);
+            g_slot[s_slot[j]] = mass_share(lattice_word(arow + (j - lane)), lattice_word(brow + (j - lane)),
+                                           inverse_p, inverse_p_exponent);
         const float l2 = cur.l2, x0 = cur.x0;
         advance_request();
         if (t + 4 < tend && t + 4 < m.Tb) request(cur);
@@ -2284,19 +2288,21 @@ int launch_gradient(const Launch& p, void* stream)
     const dim3 grid((p.T + rows - 1) / rows, p.B);
     const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + (sparse ? 0 : p.A))) * 4;
     if (p.A <= 64) {
+        // Both lattice blocks together against what the caches hold (kStreamingLatticeBytes).
+        const bool streaming = 2 * p.lay.ab_doubles * sizeof(double) > kStreamingLatticeBytes;
         const size_t nlds = (static_cast<size_t>(Lmax) + 128 + 4 * (static_cast<size_t>(Lmax) + 1)) * 4;
+#define CTC_LAUNCH_NARROW(TYPE, STREAMING)                                                          \
+    hipLaunchKernelGGL((ctc_gradient_narrow_kernel<TYPE, STREAMING>), grid, block, nlds, s,         \
+                       static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,    \
+                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,   \
+                       Lmax, rows)
         return checked_launch([&] {
-            if (f32)
-                hipLaunchKernelGGL(ctc_gradient_narrow_kernel<float>, grid, block, nlds, s,
-                                   static_cast<const float*>(p.x), static_cast<float*>(p.grads), meta, labels,
-                                   links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,
-                                   Lmax, rows);
-            else
-                hipLaunchKernelGGL(ctc_gradient_narrow_kernel<bf16_t>, grid, block, nlds, s,
-                                   static_cast<const bf16_t*>(p.x), static_cast<bf16_t*>(p.grads), meta, labels,
-                                   links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,
-                                   Lmax, rows);
+            if (f32 && streaming) CTC_LAUNCH_NARROW(float, true);
+            else if (f32) CTC_LAUNCH_NARROW(float, false);
+            else if (streaming) CTC_LAUNCH_NARROW(bf16_t, true);
+            else CTC_LAUNCH_NARROW(bf16_t, false);
         });
+#undef CTC_LAUNCH_NARROW
     }
 #define CTC_LAUNCH_GRADIENT(TYPE, SPARSE)                                                          \
     hipLaunchKernelGGL((ctc_gradient_rows_kernel<TYPE, SPARSE>), grid, block, lds, s,               \
