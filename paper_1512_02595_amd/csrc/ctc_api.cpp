@@ -267,8 +267,8 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
         m.e_off = e_off;
         m.ab_off = ab_off;
-        m.e_direct = c.A <= kDirectMaxA ? 1 : 0;
-        m.e_pitch = m.e_direct ? c.A : L;
+        m.e_direct = emission_layout(c.A);
+        m.e_pitch = m.e_direct == kEmitSymbolMajor ? Tb : L;
         lab_off += L;
         e_off += static_cast<int64_t>(Tb) * (c.A <= kDirectMaxA ? c.A : L);
         f_off += Tb;

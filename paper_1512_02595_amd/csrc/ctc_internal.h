@@ -27,21 +27,19 @@ struct Utt {
                        // chains, and linear-domain chains of at most 64 pairs)
     int32_t halo;      // lanes per wavefront that recompute the wavefront below (0: none)
     int32_t poll_budget; // LDS polls a wavefront of its chains may spend waiting on a neighbour before it gives up
-    int64_t e_off;     // offset (floats) of its label emissions, [Tb][e_pitch]
+    int64_t e_off;     // offset (floats) of its label emissions
     int64_t ab_off;    // offset (8-byte words) of its alpha/beta blocks [Tb][lattice_pitch(L)]
-    int32_t e_pitch;   // floats per frame of its emission block: L (one gathered emission per label
-                       // position) or, for alphabets of at most kDirectMaxA symbols, A (the frame's
-                       // whole normalised row, indexed by symbol)
-    int32_t e_direct;  // 1: the block holds whole rows and a label state reads column label[i];
-                       // 0: it holds gathered emissions and the state reads column i
+    int32_t e_pitch;   // row pitch (floats) of its emission block: L (a frame's gathered emissions, one
+                       // per label position) or the frames of a symbol's row (symbol-major block)
+    int32_t e_direct;  // layout of the emission block: kEmitGathered or kEmitSymbolMajor (emission_layout)
     int32_t waves2;    // the same plan for linear-domain chains of more than 64 pairs, whose lanes own
     int32_t halo2;     // two neighbouring pairs each (plan_waves2)
 };
 static_assert(sizeof(Utt) == 64, "Utt is copied word by word and read with scalar loads: keep it 8-byte sized");
 
 // Alphabets up to this size skip the emission gather: a frame's normalised row is as small as
-// the gathered emissions would be (at most two cache lines), and every lattice lane finds its
-// symbol's column in it.
+// the gathered emissions would be, and the rows themselves, transposed, are the emission block
+// (emission_layout).
 constexpr int kDirectMaxA = 64;
 
 #if defined(__HIPCC__)
@@ -130,6 +128,17 @@ CTC_HOST_DEVICE inline bool two_pairs_per_lane(int label_length, bool crowded)
     const WavePlan one = plan_waves(label_length, crowded);
     return crowded || one.barrier || one.waves > 4;
 }
+
+// How a launch's label emissions are laid out (Utt::e_direct).
+//   kEmitGathered:    [frame][label position], L floats per frame (alphabets above kDirectMaxA)
+//   kEmitSymbolMajor: [symbol][frame]: the normalised rows themselves, transposed, so that a
+//                     symbol's frames lie side by side and a lane fetches the frames of a chunk
+//                     in two 16-byte loads instead of eight loads a row apart
+// Measured on gfx950 against the rows as they are ([frame][symbol]): English minibatch, lattice
+// launch 60.4 -> 58.4 us; long utterances (two wavefronts of a chain on one SIMD, instruction
+// issue the limit) 203 -> 168 us.
+constexpr int kEmitGathered = 0, kEmitSymbolMajor = 1;
+CTC_HOST_DEVICE inline int emission_layout(int A) { return A <= kDirectMaxA ? kEmitSymbolMajor : kEmitGathered; }
 
 constexpr int kUttRuns = 1;
 constexpr int kUttInvalid = 2;

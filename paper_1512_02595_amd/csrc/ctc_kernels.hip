@@ -288,8 +288,8 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         m.waves2 = wp2.waves;
         m.halo2 = wp2.halo;
         m.poll_budget = poll_budget;
-        m.e_direct = A <= kDirectMaxA ? 1 : 0;
-        m.e_pitch = m.e_direct ? A : m.L;
+        m.e_direct = emission_layout(A);
+        m.e_pitch = m.e_direct == kEmitSymbolMajor ? Tt : m.L;
         m.e_off = static_cast<int64_t>(b) * Tt * (m.e_direct ? A : max_label);
         m.ab_off = static_cast<int64_t>(b) * Tt * lattice_pitch(max_label);
         meta[b] = m;
@@ -331,12 +331,20 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
 constexpr int kLinkSlotMask = 0x3FF, kLinkCountShift = 12;
 static_assert(CTC_MAX_LABEL_LENGTH <= kLinkSlotMask, "slot and count fields hold 10 bits");
 
+// Constants that lanes without a label state read as their emission, at the start of the
+// emission array (inside its slack): 20 floats of probability 0, then 20 of log 0.  Such a lane
+// points at entry 8 of its 20: a fetch reads the 8 floats before it or the 8 after it
+// (fetch_frames), the first step the entry itself.
+constexpr int kEmissionConstantRun = 20;
+constexpr int kZeroEmission = 8, kLogZeroEmission = kEmissionConstantRun + 8, kEmissionConstants = 2 * kEmissionConstantRun;
+static_assert(kChunk <= 8 && kEmissionConstants <= kLabelSlack, "constants sit inside the front slack");
+
 struct SetupArgs {
     int* links;
     float* costs;
     int* chain_err;
-    float* log0;          // two floats that lattice lanes without a label state read as their emission:
-                          // [0] probability 0 (linear-domain chains), [1] log 0 (log-domain chains)
+    float* log0;          // kEmissionConstants floats that lattice lanes without a label state read as their
+                          // emission: probability 0 (linear-domain chains) and log 0 (log-domain chains)
     int* host_flag;       // pinned host word: receives flag_value once the upload has been consumed
     int flag_value;
     bool plain_logs;      // emissions are stored as log2 probabilities throughout (most probable alignment)
@@ -381,8 +389,7 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
     if (tid == 0) {
         sa.chain_err[b] = 0;
         if (b == 0) {
-            sa.log0[0] = 0.0f;
-            sa.log0[1] = static_cast<float>(kNeg);
+            for (int i = 0; i < kEmissionConstants; ++i) sa.log0[i] = (i < kEmissionConstantRun) ? 0.0f : static_cast<float>(kNeg);
             // This launch follows the upload kernel on the stream, so the host may now reuse
             // the pinned image.
             if (sa.host_flag)
@@ -612,14 +619,18 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
         emit_blank[kBlankSlack + m.f_off + t0 + tid] = e;
         small = !sa.plain_logs && e < 0.0f;
     }
-    if (m.e_direct) {
-        // Small alphabet: the rows themselves are the emission block (row pitch A).
-        float* out = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t0) * A;
-        for (int i = tid; i < rows * A; i += kRowThreads) {
-            const float e = lp[i];
-            out[i] = e;
-            small = small || (!sa.plain_logs && e < 0.0f);
-        }
+    if (m.e_direct == kEmitSymbolMajor) {
+        // Small alphabet: the normalised rows themselves are the emission block, stored symbol-major
+        // (a symbol's frames side by side, e_pitch floats per symbol: fetch_frames).  A wavefront
+        // writes up to 64 frames of one symbol at a time.
+        float* out = emit_label + kLabelSlack + m.e_off + t0;
+        const int rr = tid & 63;
+        if (rr < rows)
+            for (int a = tid >> 6; a < A; a += kRowThreads / 64) {
+                const float e = lp[rr * A + a];
+                out[static_cast<size_t>(a) * m.e_pitch + rr] = e;
+                small = small || (!sa.plain_logs && e < 0.0f);
+            }
         raise_log_domain(meta, b, small);
         return;
     }
@@ -697,6 +708,25 @@ enum class Sync { kNone, kHalo, kBarrier };
 // number of states the walk moves down.  Bits 2..3, the label state: 0 = stayed, 1 = came from
 // the pair's blank, 2 = came from the label of the pair before (skipping the blank).  Bit 0, the
 // blank state: 0 = stayed, 1 = came from the label of the pair before.
+// The next kChunk frames of one symbol out of a transposed emission block (symbol-major: a
+// symbol's frames lie side by side), in the order the chain takes them, in two 16-byte loads
+// instead of kChunk loads a row apart.  `p` points at the frame of the step before the first one
+// wanted and moves on by `advance` floats (kChunk in the chain's direction; 0 for a lane
+// without a label state, which keeps reading its constants).
+struct __attribute__((packed, aligned(4))) Float4 { float v[4]; };
+static_assert(kChunk == 8, "fetch_frames loads two Float4");
+template <bool kBackward>
+__device__ __forceinline__ void fetch_frames(const float*& p, int advance, float (&el)[kChunk])
+{
+    const Float4 lo = *reinterpret_cast<const Float4*>(kBackward ? p - 8 : p + 1);
+    const Float4 hi = *reinterpret_cast<const Float4*>(kBackward ? p - 4 : p + 5);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        el[i] = kBackward ? hi.v[3 - i] : lo.v[i];
+        el[4 + i] = kBackward ? lo.v[3 - i] : hi.v[i];
+    }
+    p += advance;
+}
 constexpr int kFromSame = 0, kFromBlank = 1 << 2, kFromPrevLabel = 2 << 2, kBlankFromPrevLabel = 1;
 
 // LDS of the halo exchange of the chains with one pair per lane: per wavefront w, what w hands to w+1.
@@ -744,7 +774,7 @@ struct HaloLds {
 // read).  No barrier; the wavefronts run skewed.  A wavefront waits for data only on lower
 // ones and for space only on higher ones, wavefront 0 needs no data and the last one no space,
 // so every wait ends; a poll budget bounds them regardless and raises chain_err when spent.
-template <bool kBackward, Sync kSync, Mode kMode>
+template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
@@ -772,10 +802,16 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     const int fdir = kBackward ? -1 : 1;
     // Label emissions: a per-lane pointer that moves one row per step.  A lane without a label
     // state reads a constant log 0 and stays there.
-    const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch +
-                                      (m.e_direct ? lab[li] : li)
-                                : emit_label + 1;
+    // (In a symbol-major block the pointer moves one float per step: emission_layout.  The layout
+    // is the launch's, a template parameter: a test at run time would join two paths with
+    // different numbers of loads under way, and the waits after the join would be the
+    // cautious ones.)
+    constexpr bool direct = kSymbolMajor;
+    const float* ep = !has_label ? emit_label + kLogZeroEmission
+                      : direct   ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(lab[li]) * m.e_pitch + f0
+                                 : emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch + li;
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
+    const int eadvance = has_label ? fdir * kChunk : 0;
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
     // Output: only the label state of each pair is kept (row pitch L+2 words, column = 1 + label
@@ -946,6 +982,10 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     float el_a[kChunk], el_b[kChunk], eb_a, eb_b;
     auto fetch = [&](float (&el)[kChunk], float& eb, int s0) {
         eb = bp[fdir * s0];
+        if (direct) {
+            fetch_frames<kBackward>(ep, eadvance, el);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             ep += estride;
@@ -1042,7 +1082,7 @@ constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real 
 
 constexpr int kRing = 4;                  // hand-overs a boundary's buffer holds (two pairs per lane)
 
-template <bool kBackward, Sync kSync, Mode kMode>
+template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
                                                  const float* __restrict__ emit_blank,
                                                  const float* __restrict__ emit_label,
@@ -1066,10 +1106,12 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     const int f0 = kBackward ? (Tb - 1) : 0;
     const int fdir = kBackward ? -1 : 1;
     // A lane without a label state reads a constant probability 0 and stays there.
-    const float* ep = has_label ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch +
-                                      (m.e_direct ? lab[li] : li)
-                                : emit_label;
+    constexpr bool direct = kSymbolMajor;                // see run_chain_log
+    const float* ep = !has_label ? emit_label + kZeroEmission
+                      : direct   ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(lab[li]) * m.e_pitch + f0
+                                 : emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch + li;
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
+    const int eadvance = has_label ? fdir * kChunk : 0;
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
     const bool stores = kMode == Mode::kGrad && active && has_label;
     double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * lattice_pitch(L) + li + 1 : sink;
@@ -1220,6 +1262,10 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     float el_a[kChunk], el_b[kChunk], eb_a, eb_b;
     auto fetch = [&](float (&el)[kChunk], float& eb, int s0) {
         eb = bp[fdir * s0];
+        if (direct) {
+            fetch_frames<kBackward>(ep, eadvance, el);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             ep += estride;
@@ -1307,7 +1353,7 @@ struct Halo2Lds {
 
 struct alignas(8) LabelStatePair { double lo, hi; };   // two neighbouring columns of a lattice row
 
-template <bool kBackward, Mode kMode>
+template <bool kBackward, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, const int* __restrict__ labels,
                                                   const float* __restrict__ emit_blank,
                                                   const float* __restrict__ emit_label,
@@ -1333,10 +1379,12 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
 
     const int f0 = kBackward ? (Tb - 1) : 0;
     const int fdir = kBackward ? -1 : 1;
-    const float* const rows = emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch;
+    constexpr bool direct = kSymbolMajor;                // see run_chain_log
+    const float* const rows = emit_label + kLabelSlack + m.e_off + (direct ? f0 : static_cast<int64_t>(f0) * m.e_pitch);
     // A pair without a label state reads a constant probability 0 and stays there.
-    const float* epa = has_a ? rows + (m.e_direct ? lab[lia] : lia) : emit_label;
-    const float* epb = has_b ? rows + (m.e_direct ? lab[lib] : lib) : emit_label;
+    const float* epa = has_a ? rows + (direct ? static_cast<int64_t>(lab[lia]) * m.e_pitch : lia) : emit_label + kZeroEmission;
+    const float* epb = has_b ? rows + (direct ? static_cast<int64_t>(lab[lib]) * m.e_pitch : lib) : emit_label + kZeroEmission;
+    const int advance_a = has_a ? fdir * kChunk : 0, advance_b = has_b ? fdir * kChunk : 0;
     const int64_t stride_a = has_a ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     const int64_t stride_b = has_b ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
@@ -1506,6 +1554,11 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk], eb_a, eb_b;
     auto fetch = [&](float (&ela)[kChunk], float (&elb)[kChunk], float& eb, int s0) {
         eb = bp[fdir * s0];
+        if (direct) {
+            fetch_frames<kBackward>(epa, advance_a, ela);
+            fetch_frames<kBackward>(epb, advance_b, elb);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             epa += stride_a;
@@ -1571,7 +1624,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     }
 }
 
-template <Sync kSync, Mode kMode>
+template <Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
@@ -1629,24 +1682,24 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         if (two_pairs) {
             if constexpr (kSync == Sync::kHalo) {
                 if (forward)
-                    run_chain_linear2<false, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+                    run_chain_linear2<false, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
                 else
-                    run_chain_linear2<true, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+                    run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
             }
             return;
         }
         if (!in_log_domain) {
             if (forward)
-                run_chain_linear<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+                run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
             else
-                run_chain_linear<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+                run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
             return;
         }
     }
     if (forward)
-        run_chain_log<false, kSync, kMode>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+        run_chain_log<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
     else
-        run_chain_log<true, kSync, Mode::kGrad>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+        run_chain_log<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
 }
 
 // grid = one workgroup per entry of `order` (utterance * 2 + direction: 0 forward, 1 backward; only
@@ -1654,7 +1707,7 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
 // predecessor choices, or unused).
 // blockDim.x = 64 * (most wavefronts any utterance of the batch uses).
 // Variant for batches whose labels all fit one wavefront: no exchange at all.
-template <Mode kMode>
+template <Mode kMode, bool kSymbolMajor>
 __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
                            const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -1663,12 +1716,12 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
                            double* __restrict__ logp, float* __restrict__ costs,
                            int* __restrict__ chain_err, double* __restrict__ sink)
 {
-    lattice_body<Sync::kNone, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                               costs, chain_err, sink, nullptr);
 }
 
 // Multi-wavefront chains with the halo exchange.
-template <Mode kMode>
+template <Mode kMode, bool kSymbolMajor>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -1678,13 +1731,13 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ union { HaloLds one; Halo2Lds two; } halo_lds;      // one pair per lane, or two
-    lattice_body<Sync::kHalo, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                               costs, chain_err, sink, &halo_lds);
 }
 
 // Labels too long to leave room for a halo (more than 16 * 63 pairs): 64 pairs per wavefront
 // and one barrier per step.
-template <Mode kMode>
+template <Mode kMode, bool kSymbolMajor>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restrict__ order,
                                 const int* __restrict__ labels, const float* __restrict__ emit_blank,
@@ -1694,7 +1747,7 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
                                 int* __restrict__ chain_err, double* __restrict__ sink)
 {
     __shared__ double xch[2][16];
-    lattice_body<Sync::kBarrier, kMode>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
                                                costs, chain_err, sink, &xch[0][0]);
 }
 
@@ -2236,21 +2289,26 @@ int launch_lattice(const Launch& p, void* stream)
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
     hipLaunchKernelGGL(KERNEL, grid, block, 0, s, meta, order, labels, emit_blank, emit_label,     \
                        alpha, beta, logp, p.costs, chain_err, sink)
+    // The emission layout is the launch's (emission_layout), and a template parameter of the kernels.
+    const bool symbol_major = emission_layout(p.A) == kEmitSymbolMajor;
+#define CTC_LAUNCH_LATTICE_MODE(KERNEL, MODE)                                                       \
+    do {                                                                                           \
+        if (symbol_major) CTC_LAUNCH_LATTICE((KERNEL<MODE, true>));                                \
+        else CTC_LAUNCH_LATTICE((KERNEL<MODE, false>));                                            \
+    } while (0)
+#define CTC_LAUNCH_LATTICE_KERNEL(KERNEL)                                                           \
+    do {                                                                                           \
+        if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE_MODE(KERNEL, Mode::kLoss);                   \
+        else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE_MODE(KERNEL, Mode::kBest);              \
+        else CTC_LAUNCH_LATTICE_MODE(KERNEL, Mode::kGrad);                                         \
+    } while (0)
     return checked_launch([&] {
-        if (p.max_waves == 1) {
-            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<Mode::kLoss>));
-            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<Mode::kBest>));
-            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel_w1<Mode::kGrad>));
-        } else if (!p.needs_barrier) {
-            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<Mode::kLoss>));
-            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE((ctc_lattice_kernel<Mode::kBest>));
-            else CTC_LAUNCH_LATTICE((ctc_lattice_kernel<Mode::kGrad>));
-        } else {
-            if (p.mode == Mode::kLoss) CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kLoss>);
-            else if (p.mode == Mode::kBest) CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kBest>);
-            else CTC_LAUNCH_LATTICE(ctc_lattice_kernel_barrier<Mode::kGrad>);
-        }
+        if (p.max_waves == 1) CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel_w1);
+        else if (!p.needs_barrier) CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel);
+        else CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel_barrier);
     });
+#undef CTC_LAUNCH_LATTICE_KERNEL
+#undef CTC_LAUNCH_LATTICE_MODE
 #undef CTC_LAUNCH_LATTICE
 }
 
