@@ -227,11 +227,12 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     int32_t* order = reinterpret_cast<int32_t*>(image + lay.order);
     int32_t* labels = reinterpret_cast<int32_t*>(image + lay.labels);
 
+    const bool symbol_major = emission_layout(c.A) == kEmitSymbolMajor;
     // Would the launch, planned for latency, put more than two wavefronts on every SIMD?
     int64_t latency_waves = 0;
     for (int b = 0; b < c.B; ++b) {
         const int L = c.label_lengths[b];
-        latency_waves += two_pairs_per_lane(L, false) ? plan_waves2(L).waves : plan_waves(L).waves;
+        latency_waves += two_pairs_per_lane(L, false, symbol_major) ? plan_waves2(L).waves : plan_waves(L).waves;
     }
     const bool crowded = latency_waves * (c.mode == Mode::kGrad ? 2 : 1) > kCrowdedWaves;
 
@@ -255,7 +256,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.Tb = Tb;
         m.L = L;
         m.lab_off = static_cast<int32_t>(lab_off);
-        m.flags = (runs ? kUttRuns : 0) | (two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0) |
+        m.flags = (runs ? kUttRuns : 0) | (two_pairs_per_lane(L, crowded, symbol_major) ? kUttTwoPairs : 0) |
                   (Tb > kLinearMaxFrames ? kUttLogDomain : 0);
         m.f_off = static_cast<int32_t>(f_off);
         const WavePlan wp = plan_waves(L, crowded);
@@ -447,7 +448,8 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.n_run = B;                       // a lattice workgroup per utterance and direction; those that do not run leave at once
     p.n_chains = B * (grads ? 2 : 1);
     p.max_waves = 1;
-    p.crowded = static_cast<int64_t>(B) * (two_pairs_per_lane(max_label, false) ? plan_waves2(max_label).waves
+    const bool symbol_major = emission_layout(A) == kEmitSymbolMajor;
+    p.crowded = static_cast<int64_t>(B) * (two_pairs_per_lane(max_label, false, symbol_major) ? plan_waves2(max_label).waves
                                                                                 : plan_waves(max_label).waves) *
                     (grads ? 2 : 1) > 2 * kCrowdedWaves;
     for (int L = 0; L <= max_label; ++L)

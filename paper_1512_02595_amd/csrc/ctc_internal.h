@@ -48,6 +48,8 @@ constexpr int kDirectMaxA = 64;
 #define CTC_HOST_DEVICE
 #endif
 
+constexpr int kChunkSteps = 8;        // = kChunk (below): steps between two possible hand-overs
+
 // How the L+1 state pairs of a chain are spread over wavefronts.
 struct WavePlan {
     int waves;
@@ -121,12 +123,16 @@ CTC_HOST_DEVICE inline WavePlan plan_waves2(int label_length, bool crowded = fal
 // lane takes about 180 clocks against 120 for a one-pair lane, and a hand-over 560, so while a
 // label's one-pair plan keeps to one wavefront per SIMD (at most 4) it is the faster one; beyond
 // that, and in crowded launches, where wavefront-steps count and not one chain's latency, the
-// two-pair plan with half the wavefronts wins.
-CTC_HOST_DEVICE inline bool two_pairs_per_lane(int label_length, bool crowded)
+// two-pair plan with half the wavefronts wins.  Where the emission block is symbol-major
+// (emission_layout) a two-pair lane's fetches are cheap, and the two-pair plan also wins against
+// a one-pair plan that hands over every chunk (halo 8): 64 utterances of 600 frames, lattice
+// launch for labels of 215 symbols 52.1 -> 46.5 us, of 230 symbols 52.9 -> 50.1 us; up to 207
+// symbols (halo 16 or more) the one-pair plan stays ahead by up to 4 us.
+CTC_HOST_DEVICE inline bool two_pairs_per_lane(int label_length, bool crowded, bool symbol_major = false)
 {
     if (label_length + 1 <= 64) return false;
     const WavePlan one = plan_waves(label_length, crowded);
-    return crowded || one.barrier || one.waves > 4;
+    return crowded || one.barrier || one.waves > 4 || (symbol_major && one.halo < 2 * kChunkSteps);
 }
 
 // How a launch's label emissions are laid out (Utt::e_direct).
@@ -231,7 +237,7 @@ constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ra
 // has requested steps up to s0 + 3*kChunk - 1: at most 3*kChunk - 1 rows past either end of
 // an utterance's block (past the end going forward, before the start going backward).  These
 // margins keep such reads inside the workspace; the values read there are never used.
-constexpr int kChunk = 8;             // steps whose emissions are fetched together (plan_waves: halo % 8 == 0)
+constexpr int kChunk = kChunkSteps;   // steps whose emissions are fetched together (plan_waves: halo % 8 == 0)
 constexpr int kOverFetchRows = 3 * kChunk;
 constexpr int kBlankSlack = kOverFetchRows + kChunk;                          // floats, each side
 constexpr int kLabelSlack = kOverFetchRows * (CTC_MAX_LABEL_LENGTH + 1);      // floats, each side

@@ -280,7 +280,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         m.lab_off = b * max_label;
         m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) |
                   ((log_domain || Tb > kLinearMaxFrames) ? kUttLogDomain : 0) |
-                  (!bad && two_pairs_per_lane(L, crowded) ? kUttTwoPairs : 0);
+                  (!bad && two_pairs_per_lane(L, crowded, emission_layout(A) == kEmitSymbolMajor) ? kUttTwoPairs : 0);
         m.f_off = b * Tt;
         m.waves = wp.waves;
         m.halo = wp.halo;

@@ -24,6 +24,7 @@ int main()
             const ctc::WavePlan p2 = ctc::plan_waves2(L, crowded != 0);
             std::printf("two %d %d %d %d %d %d\n", crowded, L, p2.waves, p2.halo, p2.barrier ? 1 : 0,
                         ctc::two_pairs_per_lane(L, crowded != 0) ? 1 : 0);
+            std::printf("sym %d %d %d\n", crowded, L, ctc::two_pairs_per_lane(L, crowded != 0, true) ? 1 : 0);
         }
     std::printf("chunk %d slack %d %d\n", ctc::kChunk, ctc::kBlankSlack, ctc::kLabelSlack);
     return 0;
@@ -42,7 +43,8 @@ def plans(tmp_path_factory):
     rows = [tuple(int(v) for v in line.split()) for line in out if line[0].isdigit()]
     rows2 = [tuple(int(v) for v in line.split()[1:]) for line in out if line.startswith("two")]
     consts = [line for line in out if line.startswith("chunk")][0].split()
-    return rows, {"chunk": int(consts[1]), "blank_slack": int(consts[3]), "label_slack": int(consts[4]),
+    sym = {tuple(int(v) for v in line.split()[1:3]): int(line.split()[3]) for line in out if line.startswith("sym")}
+    return rows, {"symbol_major": sym, "chunk": int(consts[1]), "blank_slack": int(consts[3]), "label_slack": int(consts[4]),
                   "two_pairs": rows2}
 
 
@@ -97,6 +99,12 @@ def test_choice_between_one_and_two_pairs_per_lane(plans):
             assert bool(chosen) == bool(crowded or barrier1 or waves1 > 4), (crowded, L, waves1, chosen)
         if chosen:
             assert waves2 <= waves1, (crowded, L, waves1, waves2)
+    # symbol-major emission block: also where the one-pair plan would hand over every chunk
+    halo1 = {(crowded, L): halo for crowded, L, waves, halo, barrier in rows}
+    for crowded, L, waves2, halo2, _, chosen in c["two_pairs"]:
+        expect = bool(chosen) or (L + 1 > 64 and halo1[(crowded, L)] < 2 * c["chunk"])
+        assert bool(c["symbol_major"][(crowded, L)]) == expect, (crowded, L)
+    assert not c["symbol_major"][(0, 207)] and c["symbol_major"][(0, 208)] and c["symbol_major"][(0, 231)]
 
 
 def test_plans_only_switch_to_the_barrier_kernel_when_no_halo_fits(plans):
