@@ -44,7 +44,7 @@ LANE_OPS_PER_PAIR_STEP_ALIGN = 22
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
 # the rocprofv3 --pmc runs summarised in profiles/ (English and Mandarin HBM traffic summaries).
-MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 8.2e6, "ctc_lattice": 63.3e6, "ctc_gradient": 73.8e6},
+MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 8.5e6, "ctc_lattice": 62.8e6, "ctc_gradient": 73.8e6},
                     (2, "f32"): {"ctc_softmax": 1223.6e6, "ctc_lattice": 14.1e6, "ctc_gradient": 26.2e6}}
 
 
