@@ -302,10 +302,12 @@ def plan_boundary_batch(lengths, seed, A=6, T=1040):
 
 
 @pytest.mark.parametrize("lengths", [
-    # one pair per lane while that takes at most 4 wavefronts (halos of 8 to 32 pairs), two pairs per lane
-    # beyond (2 to 9 wavefronts, halos of 4 to 16 lanes); the best path always has one pair per lane
-    # (up to 16 wavefronts)
-    sorted({62, 63, 64, 65, 95, 96, 97, 119, 120, 121, 159, 160, 161, 183, 184, 199, 200, 201, 231, 232, 233,
+    # one pair per lane while that takes at most 4 wavefronts with halos of 16 to 32 pairs (up to 207
+    # symbols: the alphabet is small, so the emission block is symbol-major), two pairs per lane beyond
+    # (2 to 9 wavefronts, halos of 4 to 16 lanes); the best path always has one pair per lane (up to 16
+    # wavefronts)
+    sorted({62, 63, 64, 65, 95, 96, 97, 119, 120, 121, 159, 160, 161, 183, 184, 199, 200, 201, 206, 207, 208,
+            209, 215, 216, 223, 224, 225, 231, 232, 233,
             234, 235, 236, 237, 238, 239, 240, 253, 254, 255, 256, 271, 272, 287, 288, 327, 328, 343, 344, 345,
             346, 399, 400, 431, 432, 433, 455, 456, 511, 512, 519, 520, 521, 567, 568, 607, 608, 609, 623, 624,
             679, 680, 695, 696, 697, 735, 736, 783, 784, 785, 791, 792, 847, 848, 871, 872, 873, 895, 896,
