@@ -91,6 +91,29 @@ def test_random_shapes(seed, kw):
     check(wl.make_random(seed, **kw))
 
 
+@pytest.mark.parametrize("A", [63, 64, 65, 66])
+def test_both_sides_of_the_emission_layouts(A):
+    """Alphabets of up to 64 symbols keep the normalised rows, symbol-major, as the emission block; wider ones
+    gather an emission per label position.  Same lengths on both sides of the switch, labels from one to three
+    wavefronts wide (one and two state pairs per lane), utterances shorter than one fetch of eight frames
+    included, fp32 and bf16."""
+    rng = np.random.default_rng(640 + A)
+    lengths = [0, 1, 3, 7, 30, 63, 64, 100, 150, 207, 208, 230, 260]
+    frames = [1, 2, 5, 9, 40, 80, 70, 130, 170, 230, 215, 300, 300]
+    T = max(frames)
+    labs = []
+    for n in lengths:                       # no adjacent repeats: every label fits its utterance
+        lab = 1 + (np.cumsum(rng.integers(1, A - 2, size=n)) % (A - 1))
+        labs.append(lab.astype(np.int32))
+    batch = wl.CTCBatch(name="layouts", T=T, B=len(lengths), A=A, blank=0,
+                        logits=(rng.standard_normal((T, len(lengths), A)) * 2.0).astype(np.float32),
+                        flat_labels=np.concatenate(labs), label_lengths=np.asarray(lengths, dtype=np.int32),
+                        input_lengths=np.asarray(frames, dtype=np.int32), seed=640 + A)
+    costs, _, _, _ = check(batch)
+    assert np.isfinite(costs).all()
+    check(batch, ctc.DTYPE_BF16)
+
+
 def test_random_shapes_bf16():
     check(wl.make_random(9, T=50, B=6, A=29, max_label=20, sigma=2.0, feasible_only=True), ctc.DTYPE_BF16)
     check(wl.make_random(10, T=30, B=3, A=1001, max_label=10), ctc.DTYPE_BF16)
