@@ -259,9 +259,9 @@ struct Layout {
     size_t emit_blank = 0; // float[slack + sum Tb + slack]  emission of blank per frame: the probability y, or
                            // log2 y (negative) where y < 2^kLinearMinLog2 (plain log2 y in launches for
                            // the most probable alignment)
-    size_t emit_label = 0; // float[slack + sum Tb*L + slack]  emission of each label position, same coding;
-                           // the first two floats of the front slack hold the constants that lanes
-                           // without a label state read: probability 0 and log 0
+    size_t emit_label = 0; // float[slack + sum Tb*L + slack]  emission of each label position, same coding
+                           // (sum Tb*A for small alphabets: emission_layout); the front slack starts with
+                           // the constants that lanes without a label state read: probability 0 and log 0
     size_t alpha = 0;     // 8-byte words [sum Tb*(L+2)]: label states only, one unused column on either side
     size_t beta = 0;      // of a frame's row (lattice_pitch), so that a lane may store two neighbours at once
     size_t total = 0;

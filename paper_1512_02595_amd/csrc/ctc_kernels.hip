@@ -8,8 +8,9 @@
 //             key-value sort, done by counting), degenerate costs; rides in the softmax launch
 //   softmax   per frame row: log2-sum-exp2 of the scaled logits, and the emissions (softmax
 //             outputs) of blank and of every label position, gathered once so that the
-//             recursions read them coalesced
-//   lattice   alpha and beta recursions, both in one launch on different workgroups
+//             recursions read them coalesced (small alphabets: the normalised rows themselves,
+//             stored symbol-major)
+//   lattice   alpha and beta recursions, both in one launch, a workgroup per utterance and direction
 //             (cost only: alpha alone; alignment: the max recursion with recorded choices)
 //   gradient  softmax minus the normalised per-symbol occupancy; zero fill of padding
 //             (alignment: the backtrace instead)
