@@ -1,8 +1,11 @@
 """GPU tests of ctc_loss_and_grad_device: lengths and labels on the device, nothing read from the host.
 
-Its results must be bitwise those of the host-metadata call (same kernels, other block offsets)
-and so within the oracle's tolerances; invalid entries are reported through the device status
-word; and the call can be recorded into a HIP graph and replayed on new buffer contents.
+Every shape is compared with the CPU oracle, element by element, to the tolerances of the
+host-metadata call (costs 1e-4 relative, gradients 1e-4 absolute; bf16: 2e-2 and 1e-2), and with
+the host-metadata call itself: bitwise where both calls plan the same chains, within rounding
+where the bounds make the device call plan otherwise.  Invalid entries are reported through the
+device status word; and the call can be recorded into a HIP graph and replayed on new buffer
+contents.
 """
 import numpy as np
 import pytest
@@ -25,6 +28,23 @@ def both_paths(batch, dtype=ctc.DTYPE_F32, max_label=None, same_kernels=True):
     status, costs, grads = dm.results()
     ref_costs, ref_grads = harness.run_batch(batch, dtype)
     assert status == ctc.STATUS_SUCCESS
+    # against the oracle, as the host-metadata call is checked
+    logits = batch.logits if dtype == ctc.DTYPE_F32 else wl.to_bf16_grid(batch.logits)
+    orc_c, orc_g = orc.ctc_loss_and_grad(logits, batch.flat_labels, batch.label_lengths, batch.input_lengths,
+                                         batch.blank)
+    rtol, atol = (1e-4, 1e-4) if dtype == ctc.DTYPE_F32 else (2e-2, 1e-2)
+    inf = np.isinf(orc_c)
+    assert np.array_equal(np.isinf(costs) & (costs > 0), inf) and not np.isnan(costs).any()
+    err_c = np.abs(costs[~inf] - orc_c[~inf]) / np.maximum(np.abs(orc_c[~inf]), 1e-2)
+    err_g = np.abs(grads - orc_g).max()
+    print(f"  against the oracle: max cost rel err {err_c.max() if err_c.size else 0.0:.3e}  "
+          f"max grad abs err {err_g:.3e}", flush=True)
+    assert err_c.size == 0 or err_c.max() <= rtol
+    assert err_g <= atol
+    for b in range(batch.B):
+        assert not grads[batch.input_lengths[b]:, b, :].any()
+        if inf[b]:
+            assert not grads[:, b, :].any()
     if same_kernels:
         assert np.array_equal(costs, ref_costs, equal_nan=True)
         assert np.array_equal(grads, ref_grads)
@@ -39,11 +59,7 @@ def both_paths(batch, dtype=ctc.DTYPE_F32, max_label=None, same_kernels=True):
 
 def test_matches_the_host_metadata_call_bitwise_and_the_oracle():
     batch = wl.make_config(0)
-    _, costs, grads = both_paths(batch, max_label=40)           # bound larger than any label
-    ref_c, ref_g = orc.ctc_loss_and_grad(batch.logits, batch.flat_labels, batch.label_lengths,
-                                         batch.input_lengths, batch.blank)
-    assert np.abs(costs - ref_c).max() <= 1e-4 * np.abs(ref_c).max()
-    assert np.abs(grads - ref_g).max() <= 1e-4
+    both_paths(batch, max_label=40)           # bound larger than any label
 
 
 @pytest.mark.parametrize("maker", [

@@ -14,34 +14,7 @@ from paper_1512_02595_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-COST_RTOL, GRAD_ATOL = 1e-4, 1e-4
-BF16_COST_RTOL, BF16_GRAD_ATOL = 2e-2, 1e-2
-
-
-def check(batch, dtype=ctc.DTYPE_F32, nthreads=0):
-    print(f"case {batch.name} seed={batch.seed} T={batch.T} B={batch.B} A={batch.A} dtype={dtype}", flush=True)
-    logits = batch.logits if dtype == ctc.DTYPE_F32 else wl.to_bf16_grid(batch.logits)
-    ref_c, ref_g = orc.ctc_loss_and_grad(logits, batch.flat_labels, batch.label_lengths,
-                                         batch.input_lengths, batch.blank, nthreads=nthreads)
-    costs, grads = harness.run_batch(batch, dtype)
-    rtol, atol = (COST_RTOL, GRAD_ATOL) if dtype == ctc.DTYPE_F32 else (BF16_COST_RTOL, BF16_GRAD_ATOL)
-    inf = np.isinf(ref_c)
-    assert np.array_equal(np.isinf(costs) & (costs > 0), inf), (costs, ref_c)
-    fin = ~inf
-    err_c = np.abs(costs[fin] - ref_c[fin]) / np.maximum(np.abs(ref_c[fin]), 1e-2)
-    assert not np.isnan(costs).any()
-    assert err_c.size == 0 or err_c.max() <= rtol, f"cost rel err {err_c.max()}"
-    assert not np.isnan(grads).any()
-    err_g = np.abs(grads - ref_g).max()
-    print(f"  max cost rel err {err_c.max() if err_c.size else 0.0:.3e}  max grad abs err {err_g:.3e}"
-          f"  (cost range {np.min(ref_c[fin]) if fin.any() else 0:.1f}..{np.max(ref_c[fin]) if fin.any() else 0:.1f} nats)",
-          flush=True)
-    assert err_g <= atol, f"grad abs err {err_g}"
-    for b in range(batch.B):                       # padding rows are exact zeros
-        assert not grads[batch.input_lengths[b]:, b, :].any()
-        if inf[b]:
-            assert not grads[:, b, :].any()
-    return costs, grads, float(err_c.max()) if err_c.size else 0.0, float(err_g)
+from parity_checks import BF16_COST_RTOL, BF16_GRAD_ATOL, COST_RTOL, GRAD_ATOL, check, check_best  # noqa: F401
 
 
 def test_tiny_config():
@@ -349,13 +322,11 @@ def test_every_wavefront_plan_boundary(lengths):
     db.run_loss()
     loss_only, _ = db.results()
     assert np.array_equal(loss_only, costs)
-    db.run_best_path()
-    scores, states = db.best_path_results()
-    ref_s, ref_a = orc.ctc_best_path(batch.logits, batch.flat_labels, batch.label_lengths, batch.input_lengths, 0)
-    assert np.abs(scores - ref_s).max() <= 1e-4 * np.abs(ref_s).max()
-    same = sum(np.array_equal(states[b], ref_a[b]) for b in range(batch.B))
-    print(f"  best path: {same}/{batch.B} alignments identical to the oracle's", flush=True)
-    assert same >= 0.9 * batch.B
+    # The most probable alignment runs the same chains in its own mode (one pair per lane, up to 16
+    # wavefronts): every utterance's score against the oracle's with a tolerance of its own, and every
+    # returned walk validated (legal, ends where it must, its own float64 probability equal to the best
+    # score), whether or not it is the oracle's; how many are identical is asserted separately.
+    check_best(batch, min_same=0.9)
 
 
 def test_two_pairs_per_lane_in_a_crowded_launch():
