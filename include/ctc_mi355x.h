@@ -17,10 +17,25 @@
  * or (device).  The library allocates no device memory: every buffer, including
  * the scratch workspace, belongs to the caller (Section 4.3 motivates keeping
  * allocation off the training step).  All device work is enqueued on the given
- * stream and the calls return without waiting for it; host arrays are consumed
- * before the call returns.  The only memory the library itself holds is a small ring of
- * pinned host buffers per device (the per-call metadata image the first kernel reads), created
- * on first use and kept until the process ends; ctc_loss_and_grad_device does without it.
+ * stream and the calls return without waiting for it (never: see below); host
+ * arrays are consumed before the call returns.
+ *
+ * State the library keeps, process-wide, behind one mutex (calls from several
+ * threads are serialised while they prepare and enqueue, a few microseconds):
+ *   - Per device, pinned host memory for the per-call metadata image that the
+ *     first kernel of a host-metadata call reads: 8 slots of 256 KiB, allocated
+ *     in one piece by the first call on that device and kept until the process
+ *     ends.  A slot is free again once the call's second kernel has run.  No
+ *     later call allocates, with two exceptions that each happen once: a batch
+ *     whose image (72 bytes per utterance + 4 per label symbol) exceeds a slot
+ *     gets a pool of larger slots, and a caller with more calls in flight than
+ *     there are slots (it enqueues that far ahead of the GPU) gets a pool of
+ *     twice as many.  The host never waits for a slot.  Pools stop growing at
+ *     256 MiB per device; a call that then finds every slot in flight returns
+ *     CTC_STATUS_NOT_READY immediately, with nothing enqueued.
+ *     ctc_loss_and_grad_device uses none of this.
+ *   - The poll budget of ctc_debug_set_poll_budget, and the calling thread's
+ *     last HIP error code.
  */
 #ifndef CTC_MI355X_H
 #define CTC_MI355X_H
@@ -37,9 +52,17 @@ typedef enum {
     CTC_STATUS_INVALID_VALUE = 1,       /* null pointer, size or id out of range, overlapping buffers */
     CTC_STATUS_WORKSPACE_TOO_SMALL = 2, /* workspace_bytes below what ctc_workspace_size reports */
     CTC_STATUS_HIP_ERROR = 3,           /* a HIP runtime call failed; see ctc_last_hip_error */
-    CTC_STATUS_UNSUPPORTED = 4          /* a size beyond what the kernels index: a label longer than
+    CTC_STATUS_UNSUPPORTED = 4,         /* a size beyond what the kernels index: a label longer than
                                            CTC_MAX_LABEL_LENGTH, more than 65535 utterances, ... */
+    CTC_STATUS_NOT_READY = 5            /* host-metadata calls only: so many earlier calls are still in
+                                           flight that their metadata images fill the pinned memory the
+                                           library may hold (256 MiB per device); nothing was enqueued:
+                                           synchronise the stream, or call again later */
 } ctc_status_t;
+
+/* The HIP stream type, declared as hip_runtime_api.h declares it so that this header needs no
+ * HIP include (repeating an identical typedef is allowed in C11 and C++). */
+typedef struct ihipStream_t *hipStream_t;
 
 /* Element type of activations AND gradients.  Arithmetic is always fp32/fp64 inside. */
 typedef enum {
@@ -103,8 +126,7 @@ ctc_status_t ctc_workspace_size(int T, int B, int A,
  *                 feature); the backward recursion and the gradient pass are then left out.
  *   workspace     (device) 256-byte aligned scratch of at least ctc_workspace_size bytes;
  *                 contents on entry are irrelevant, contents on exit are unspecified
- *   stream        a hipStream_t (passed as void* so that this header needs no HIP
- *                 include); NULL is the default stream
+ *   stream        the stream all work is enqueued on; NULL is the default stream
  *
  * Errors are reported by status only; nothing is printed or thrown.  On an error
  * found during validation nothing has been enqueued.  Results are bitwise
@@ -120,7 +142,7 @@ ctc_status_t ctc_loss_and_grad(const void *activations,
                                float *costs,
                                void *grads,
                                void *workspace, size_t workspace_bytes,
-                               void *stream);
+                               hipStream_t stream);
 
 /*
  * Same computation as ctc_loss_and_grad, but brackets each kernel with HIP events
@@ -141,7 +163,7 @@ ctc_status_t ctc_profile_kernels(const void *activations,
                                  float *costs,
                                  void *grads,
                                  void *workspace, size_t workspace_bytes,
-                                 void *stream,
+                                 hipStream_t stream,
                                  float *kernel_ms);
 
 /*
@@ -157,7 +179,8 @@ ctc_status_t ctc_profile_kernels(const void *activations,
  * for the largest utterance they allow:
  *
  *   labels            (device) [B, max_label_length] int32, one padded row per utterance;
- *                     only the first label_lengths[b] entries of row b are read
+ *                     every entry is read, but only the first label_lengths[b] of row b are
+ *                     looked at: the padding may hold anything
  *   label_lengths     (device) [B]
  *   input_lengths     (device) [B]
  *   max_label_length  0..CTC_MAX_LABEL_LENGTH; B is limited to 4096
@@ -170,7 +193,11 @@ ctc_status_t ctc_profile_kernels(const void *activations,
  *   workspace         at least ctc_workspace_size_device bytes (larger than the exact-size
  *                     query of the host-metadata calls: T x B x (max_label_length + 1) lattice pairs)
  *   grads             may be NULL (costs only), as for ctc_loss_and_grad
- *   everything else as for ctc_loss_and_grad; results are bitwise the same as its results.
+ *   everything else as for ctc_loss_and_grad.  Results are the same numbers up to rounding:
+ *                     bitwise those of ctc_loss_and_grad where both calls plan an utterance's chains
+ *                     alike, which they do unless the bounds (B x max_label_length) make this call
+ *                     plan its launch for total work, or use the one-barrier-per-step kernel, where
+ *                     the actual labels would not.
  *
  * The return value covers what the host can check (pointers, T, B, A, blank, dtype, bounds,
  * workspace size, launch errors).
@@ -189,7 +216,7 @@ ctc_status_t ctc_loss_and_grad_device(const void *activations,
                                       void *grads,
                                       int32_t *status_out,
                                       void *workspace, size_t workspace_bytes,
-                                      void *stream);
+                                      hipStream_t stream);
 
 /*
  * Most probable alignment of each utterance (Section 5.1, "Dataset Construction": the
@@ -223,7 +250,7 @@ ctc_status_t ctc_best_path(const void *activations,
                            float *scores,
                            int32_t *alignment,
                            void *workspace, size_t workspace_bytes,
-                           void *stream);
+                           hipStream_t stream);
 
 /* ctc_best_path with per-launch device times, as ctc_profile_kernels:
  * kernel_ms (host) [CTC_NUM_KERNELS] = softmax, lattice (max recursion), backtrace. */
@@ -236,7 +263,7 @@ ctc_status_t ctc_profile_best_path(const void *activations,
                                    float *scores,
                                    int32_t *alignment,
                                    void *workspace, size_t workspace_bytes,
-                                   void *stream,
+                                   hipStream_t stream,
                                    float *kernel_ms);
 
 /* Prefix of the name under which launch `index` (0..CTC_KERNEL_BACKTRACE) appears in a profiler
@@ -258,6 +285,11 @@ int ctc_last_hip_error(void);
  * end.  Negative values restore the default.  Applies to calls made afterwards, process-wide.
  */
 void ctc_debug_set_poll_budget(int polls);
+
+/* Diagnostics: how many times the library has allocated pinned host memory so far in this
+ * process (all devices).  1 after the first host-metadata call on one device, and still 1 after
+ * any number of further calls that keep within 8 in flight and 256 KiB of metadata. */
+long ctc_debug_staging_allocations(void);
 
 #ifdef __cplusplus
 }

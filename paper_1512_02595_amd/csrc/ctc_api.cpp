@@ -10,7 +10,6 @@
 #include <atomic>
 #include <cstring>
 #include <mutex>
-#include <thread>
 #include <vector>
 
 #include "ctc_internal.h"
@@ -122,70 +121,120 @@ namespace {
 // Pinned host buffers for the per-call metadata image.  The upload kernel reads the image
 // straight from host memory, so a slot may be rewritten only after that kernel has run: the
 // launch that follows it on the stream stores the slot's generation number into a pinned flag
-// word, which the host checks before it reuses the slot (no event, so no marker packet sits
-// between two kernels of a call).  One ring per device, created on first use, kept for the
-// life of the process.
-constexpr int kStagingSlots = 8;
+// word in front of the image, which the host checks before it reuses the slot (no event, so no
+// marker packet sits between two kernels of a call).
+//
+// All slots of a device come from one allocation, made at the first call on that device
+// (kInitialSlots slots of at least kMinSlotBytes each), so that no later call allocates -- the
+// point of Section 4.3.  The host never waits for a slot: when every slot is still in flight
+// (the caller has enqueued that many calls ahead of the GPU), or when a batch's image outgrows
+// the slots, a further pool with twice the slots, or larger ones, is allocated and used from
+// then on (earlier pools are left to drain and are kept, so their total is below the last
+// pool's size); pools of one device stop growing at kMaxStagingBytes, and a call that finds
+// every slot in flight then returns CTC_STATUS_NOT_READY at once.
+constexpr int kInitialSlots = 8;
+constexpr size_t kMinSlotBytes = size_t(256) << 10;
+constexpr size_t kMaxStagingBytes = size_t(256) << 20;
 constexpr size_t kFlagBytes = 64;            // the flag word sits in front of the image
 
 struct StagingSlot {
     char* host = nullptr;                    // kFlagBytes of flag, then the image
-    size_t capacity = 0;                     // of the image part
     int generation = 0;                      // value the device stores once the image is free
     bool in_flight = false;
     int* flag() const { return reinterpret_cast<int*>(host); }
     char* image() const { return host + kFlagBytes; }
+    // Has the device released the image?  (A plain read of pinned memory; never waits.)
+    bool released() const { return *static_cast<volatile int*>(flag()) == generation; }
 };
 
-struct StagingRing {
-    int device = -1;
+struct StagingPool {
+    char* base = nullptr;
+    size_t slot_bytes = 0;                   // of the image part of each slot
+    std::vector<StagingSlot> slots;
     int next = 0;
-    StagingSlot slots[kStagingSlots];
+};
+
+struct DeviceStaging {
+    int device = -1;
+    size_t total_bytes = 0;
+    std::vector<StagingPool*> pools;         // the last one serves new calls
+    std::atomic<long> allocations{0};
 };
 
 std::mutex g_staging_mutex;
-std::vector<StagingRing*> g_staging_rings;
+std::vector<DeviceStaging*> g_staging;
 
-// Returns a slot of at least `bytes`, or nullptr on a HIP error.  Caller holds g_staging_mutex.
-StagingSlot* acquire_slot(size_t bytes)
+DeviceStaging* staging_of(int dev)
+{
+    for (DeviceStaging* d : g_staging)
+        if (d->device == dev) return d;
+    DeviceStaging* d = new DeviceStaging();
+    d->device = dev;
+    g_staging.push_back(d);
+    return d;
+}
+
+// A new pool of `slots` slots of `slot_bytes` each.  nullptr: past the cap (status_out =
+// NOT_READY) or the allocation failed (HIP_ERROR).
+StagingPool* add_pool(DeviceStaging* d, int slots, size_t slot_bytes, ctc_status_t* status_out)
+{
+    const size_t stride = kFlagBytes + slot_bytes;
+    const size_t bytes = stride * static_cast<size_t>(slots);
+    if (d->total_bytes + bytes > kMaxStagingBytes) {
+        *status_out = CTC_STATUS_NOT_READY;
+        return nullptr;
+    }
+    void* mem = nullptr;
+    if (!record(hipHostMalloc(&mem, bytes, hipHostMallocDefault))) {
+        *status_out = CTC_STATUS_HIP_ERROR;
+        return nullptr;
+    }
+    StagingPool* pool = new StagingPool();
+    pool->base = static_cast<char*>(mem);
+    pool->slot_bytes = slot_bytes;
+    pool->slots.resize(static_cast<size_t>(slots));
+    for (int i = 0; i < slots; ++i) {
+        pool->slots[static_cast<size_t>(i)].host = pool->base + stride * static_cast<size_t>(i);
+        *pool->slots[static_cast<size_t>(i)].flag() = 0;
+    }
+    d->pools.push_back(pool);
+    d->total_bytes += bytes;
+    d->allocations.fetch_add(1, std::memory_order_relaxed);
+    return pool;
+}
+
+// Returns a free slot of at least `bytes`, or nullptr with the status to return.  Never waits.
+// Caller holds g_staging_mutex.
+StagingSlot* acquire_slot(size_t bytes, ctc_status_t* status_out)
 {
     int dev = 0;
-    if (!record(hipGetDevice(&dev))) return nullptr;
-    StagingRing* ring = nullptr;
-    for (StagingRing* r : g_staging_rings)
-        if (r->device == dev) ring = r;
-    if (!ring) {
-        ring = new StagingRing();
-        ring->device = dev;
-        g_staging_rings.push_back(ring);
+    if (!record(hipGetDevice(&dev))) {
+        *status_out = CTC_STATUS_HIP_ERROR;
+        return nullptr;
     }
-    StagingSlot& slot = ring->slots[ring->next];
-    ring->next = (ring->next + 1) % kStagingSlots;
-    if (slot.in_flight) {
-        // Seven calls have been enqueued since this slot was used: normally long done.
-        volatile int* flag = slot.flag();
-        for (long spins = 0; *flag != slot.generation; ++spins) {
-            if (spins > (1L << 26)) {        // minutes: the stream is stuck or was destroyed
-                g_last_hip_error = static_cast<int>(hipErrorNotReady);
-                return nullptr;
+    DeviceStaging* d = staging_of(dev);
+    const size_t want = std::max(kMinSlotBytes, (2 * bytes + 65535) / 65536 * 65536 - kFlagBytes);
+    StagingPool* pool = d->pools.empty() ? nullptr : d->pools.back();
+    if (pool && bytes <= pool->slot_bytes) {
+        const int n = static_cast<int>(pool->slots.size());
+        for (int k = 0; k < n; ++k) {
+            StagingSlot& slot = pool->slots[static_cast<size_t>((pool->next + k) % n)];
+            if (slot.in_flight && slot.released()) slot.in_flight = false;
+            if (!slot.in_flight) {
+                pool->next = (pool->next + k + 1) % n;
+                return &slot;
             }
-            std::this_thread::yield();
         }
-        slot.in_flight = false;
+        // every slot is in flight: the caller runs that far ahead of the GPU
+        pool = add_pool(d, 2 * n, pool->slot_bytes, status_out);
+    } else if (pool) {
+        pool = add_pool(d, static_cast<int>(pool->slots.size()), want, status_out);     // a larger image than any before
+    } else {
+        pool = add_pool(d, kInitialSlots, want, status_out);
     }
-    if (slot.capacity < bytes) {
-        if (slot.host) (void)hipHostFree(slot.host);
-        slot.host = nullptr;
-        slot.capacity = 0;
-        const size_t want = (bytes + 65535) / 65536 * 65536;
-        void* mem = nullptr;
-        if (!record(hipHostMalloc(&mem, want + kFlagBytes, hipHostMallocDefault))) return nullptr;
-        slot.host = static_cast<char*>(mem);
-        slot.capacity = want;
-        *slot.flag() = 0;
-        slot.generation = 0;
-    }
-    return &slot;
+    if (!pool) return nullptr;
+    pool->next = 1;
+    return &pool->slots[0];
 }
 
 struct Call {
@@ -340,6 +389,22 @@ ctc_status_t precheck(const Call& c)
     return CTC_STATUS_SUCCESS;
 }
 
+// HIP events of a profiled call, destroyed however the call ends.
+struct Events {
+    hipEvent_t ev[CTC_NUM_KERNELS + 3] = {};
+    bool create()
+    {
+        for (auto& e : ev)
+            if (!record(hipEventCreate(&e))) return false;
+        return true;
+    }
+    ~Events()
+    {
+        for (auto& e : ev)
+            if (e) (void)hipEventDestroy(e);
+    }
+};
+
 ctc_status_t run(const Call& c, float* kernel_ms)
 {
     ctc_status_t st = precheck(c);
@@ -349,8 +414,11 @@ ctc_status_t run(const Call& c, float* kernel_ms)
     if (st != CTC_STATUS_SUCCESS) return st;
 
     hipStream_t s = static_cast<hipStream_t>(c.stream);
+    // Events 0..CTC_NUM_KERNELS bracket the launches; the last two are recorded back to back
+    // and give what an interval with nothing in it reads, which is taken off every interval.
+    Events events;
+    hipEvent_t* const ev = events.ev;
     Launch p;
-    StagingSlot* slot = nullptr;
     {
         // The image is validated while it is written; on an error nothing has been enqueued and
         // the slot simply stays free.
@@ -369,32 +437,33 @@ ctc_status_t run(const Call& c, float* kernel_ms)
             st = prepare(c, lay, &p, scratch.data());
             return st != CTC_STATUS_SUCCESS ? st : CTC_STATUS_HIP_ERROR;
         }
-        slot = acquire_slot(lay.upload_bytes);
-        if (!slot) return CTC_STATUS_HIP_ERROR;
+        StagingSlot* const slot = acquire_slot(lay.upload_bytes, &st);
+        if (!slot) return st;
         st = prepare(c, lay, &p, slot->image());
         if (st != CTC_STATUS_SUCCESS) return st;
+        if (kernel_ms && !events.create()) return CTC_STATUS_HIP_ERROR;
         slot->generation += 1;
         p.host_flag = slot->flag();
         p.host_flag_value = slot->generation;
+        // The upload launch's own time is not reported separately: it is a few microseconds and
+        // overlaps the tail of whatever ran before on the stream.
         if (!record(launch_setup(p, c.stream))) return CTC_STATUS_HIP_ERROR;
+        // The softmax launch, which follows, is the one that releases the image.  Should it fail to
+        // go out, nothing would ever release the slot while the upload kernel may still be reading
+        // it: wait for the stream (an error path) and leave the slot free.
+        if ((kernel_ms && !record(hipEventRecord(ev[0], s))) || !record(launch_softmax(p, c.stream))) {
+            (void)hipStreamSynchronize(s);
+            return CTC_STATUS_HIP_ERROR;
+        }
         slot->in_flight = true;
     }
+    if (kernel_ms && !record(hipEventRecord(ev[1], s))) return CTC_STATUS_HIP_ERROR;
 
-    // Events 0..CTC_NUM_KERNELS bracket the launches; the last two are recorded back to back
-    // and give what an interval with nothing in it reads, which is taken off every interval.
-    hipEvent_t ev[CTC_NUM_KERNELS + 3] = {};
-    if (kernel_ms) {
-        for (auto& e : ev)
-            if (!record(hipEventCreate(&e))) return CTC_STATUS_HIP_ERROR;
-        if (!record(hipEventRecord(ev[0], s))) return CTC_STATUS_HIP_ERROR;
-    }
-    // The upload launch has gone out above (its own time is not reported separately: it is a few
-    // microseconds and overlaps the tail of whatever ran before on the stream).
     // Cost-only calls end with the lattice launch.
     int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {
         launch_softmax, launch_lattice,
         c.mode == Mode::kGrad ? launch_gradient : (c.mode == Mode::kLoss ? nullptr : launch_backtrace)};
-    for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
+    for (int i = 1; i < CTC_NUM_KERNELS; ++i) {
         if (stages[i] && !record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
         if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
     }
@@ -409,7 +478,6 @@ ctc_status_t run(const Call& c, float* kernel_ms)
             if (!record(hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]))) return CTC_STATUS_HIP_ERROR;
             kernel_ms[i] = stages[i] ? std::max(kernel_ms[i] - empty, 0.0f) : 0.0f;
         }
-        for (auto& e : ev) (void)hipEventDestroy(e);
     }
     return CTC_STATUS_SUCCESS;
 }
@@ -497,7 +565,7 @@ ctc_status_t ctc_loss_and_grad_device(const void* activations, const int32_t* la
                                       const int32_t* label_lengths, const int32_t* input_lengths,
                                       int max_label_length, int T, int B, int A, int blank,
                                       ctc_dtype_t dtype, float* costs, void* grads, int32_t* status_out,
-                                      void* workspace, size_t workspace_bytes, void* stream)
+                                      void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     return ctc::run_device(activations, labels, label_lengths, input_lengths, max_label_length, T, B, A,
                            blank, dtype, costs, grads, status_out, workspace, workspace_bytes, stream);
@@ -517,7 +585,7 @@ ctc_status_t ctc_workspace_size(int T, int B, int A, const int32_t* label_length
 ctc_status_t ctc_loss_and_grad(const void* activations, const int32_t* flat_labels,
                                const int32_t* label_lengths, const int32_t* input_lengths,
                                int T, int B, int A, int blank, ctc_dtype_t dtype, float* costs,
-                               void* grads, void* workspace, size_t workspace_bytes, void* stream)
+                               void* grads, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     ctc::Call c{grads ? ctc::Mode::kGrad : ctc::Mode::kLoss, activations, flat_labels, label_lengths,
                 input_lengths, T, B, A, blank, dtype, costs, grads, nullptr, workspace, workspace_bytes, stream};
@@ -527,7 +595,7 @@ ctc_status_t ctc_loss_and_grad(const void* activations, const int32_t* flat_labe
 ctc_status_t ctc_profile_kernels(const void* activations, const int32_t* flat_labels,
                                  const int32_t* label_lengths, const int32_t* input_lengths,
                                  int T, int B, int A, int blank, ctc_dtype_t dtype, float* costs,
-                                 void* grads, void* workspace, size_t workspace_bytes, void* stream,
+                                 void* grads, void* workspace, size_t workspace_bytes, hipStream_t stream,
                                  float* kernel_ms)
 {
     if (!kernel_ms) return CTC_STATUS_INVALID_VALUE;
@@ -539,7 +607,7 @@ ctc_status_t ctc_profile_kernels(const void* activations, const int32_t* flat_la
 ctc_status_t ctc_best_path(const void* activations, const int32_t* flat_labels,
                            const int32_t* label_lengths, const int32_t* input_lengths,
                            int T, int B, int A, int blank, ctc_dtype_t dtype, float* scores,
-                           int32_t* alignment, void* workspace, size_t workspace_bytes, void* stream)
+                           int32_t* alignment, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     ctc::Call c{ctc::Mode::kBest, activations, flat_labels, label_lengths, input_lengths, T, B, A, blank,
                 dtype, scores, nullptr, alignment, workspace, workspace_bytes, stream};
@@ -550,7 +618,7 @@ ctc_status_t ctc_profile_best_path(const void* activations, const int32_t* flat_
                                    const int32_t* label_lengths, const int32_t* input_lengths,
                                    int T, int B, int A, int blank, ctc_dtype_t dtype, float* scores,
                                    int32_t* alignment, void* workspace, size_t workspace_bytes,
-                                   void* stream, float* kernel_ms)
+                                   hipStream_t stream, float* kernel_ms)
 {
     if (!kernel_ms) return CTC_STATUS_INVALID_VALUE;
     ctc::Call c{ctc::Mode::kBest, activations, flat_labels, label_lengths, input_lengths, T, B, A, blank,
@@ -577,11 +645,20 @@ const char* ctc_status_string(ctc_status_t status)
         case CTC_STATUS_WORKSPACE_TOO_SMALL: return "workspace too small";
         case CTC_STATUS_HIP_ERROR: return "HIP runtime error";
         case CTC_STATUS_UNSUPPORTED: return "unsupported size";
+        case CTC_STATUS_NOT_READY: return "too many calls in flight";
         default: return "unknown status";
     }
 }
 
 int ctc_last_hip_error(void) { return ctc::g_last_hip_error; }
+
+long ctc_debug_staging_allocations(void)
+{
+    std::lock_guard<std::mutex> lock(ctc::g_staging_mutex);
+    long n = 0;
+    for (const ctc::DeviceStaging* d : ctc::g_staging) n += d->allocations.load(std::memory_order_relaxed);
+    return n;
+}
 
 void ctc_debug_set_poll_budget(int polls)
 {

@@ -2248,7 +2248,9 @@ int launch_softmax(const Launch& p, void* stream)
                 hipLaunchKernelGGL((ctc_softmax_rows_kernel<bf16_t, 4>), grid, block, lds, s,
                                    static_cast<const bf16_t*>(p.x), meta, labels, lse, emit_blank,
                                    emit_label, sa, p.T, p.B, p.A, p.blank);
-        } else if (vector_ok(p) && p.A <= kWideMaxA) {
+        } else if (vector_ok(p) && p.A <= kWideMaxA && p.T + 1 <= kMaxBatch) {
+            // (frames index the second grid dimension here, which ends at 65535; longer tensors take
+            // the scalar kernel below, whose second dimension is the utterance)
             const dim3 grid(p.B, p.T + 1);
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_wide_kernel<float>, grid, block, 0, s,

@@ -19,6 +19,7 @@ STATUS_INVALID_VALUE = 1
 STATUS_WORKSPACE_TOO_SMALL = 2
 STATUS_HIP_ERROR = 3
 STATUS_UNSUPPORTED = 4
+STATUS_NOT_READY = 5
 
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
@@ -31,7 +32,8 @@ KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
            "ctc_workspace_size_device", "ctc_loss_and_grad_device",
-           "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget")
+           "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget",
+           "ctc_debug_staging_allocations")
 
 _lib = None
 
@@ -77,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.ctc_last_hip_error.argtypes = []
     lib.ctc_debug_set_poll_budget.restype = None
     lib.ctc_debug_set_poll_budget.argtypes = [ci]
+    lib.ctc_debug_staging_allocations.restype = ctypes.c_long
+    lib.ctc_debug_staging_allocations.argtypes = []
     _lib = lib
     return lib
 
@@ -209,3 +213,8 @@ def loss_and_grad_device(*args, **kw) -> None:
 def debug_set_poll_budget(polls: int) -> None:
     """LDS polls a lattice wavefront may spend waiting on its neighbour (negative: default)."""
     load().ctc_debug_set_poll_budget(int(polls))
+
+
+def debug_staging_allocations() -> int:
+    """Pinned host allocations the library has made so far in this process."""
+    return int(load().ctc_debug_staging_allocations())

@@ -36,7 +36,9 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings_and_kernel_names(lib):
     assert ctc.status_string(ctc.STATUS_SUCCESS) == "success"
-    assert len({ctc.status_string(i) for i in range(5)}) == 5
+    assert len({ctc.status_string(i) for i in range(6)}) == 6
+    assert ctc.status_string(ctc.STATUS_NOT_READY) == "too many calls in flight"
+    assert ctc.debug_staging_allocations() >= 0        # (callable without a GPU; counts pinned allocations)
     names = [ctc.kernel_name(i) for i in range(ctc.NUM_KERNELS)]
     assert names == ["ctc_softmax", "ctc_lattice", "ctc_gradient"]
     assert ctc.kernel_name(ctc.KERNEL_BACKTRACE) == "ctc_backtrace"
