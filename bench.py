@@ -42,10 +42,49 @@ LANE_OPS_EXECUTED = 14
 LANE_OPS_PER_PAIR_STEP_ALIGN = 22
 
 
-# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from
-# the rocprofv3 --pmc runs summarised in profiles/ (English and Mandarin HBM traffic summaries).
-MEASURED_TRAFFIC = {(1, "f32"): {"ctc_softmax": 8.5e6, "ctc_lattice": 62.8e6, "ctc_gradient": 73.8e6},
-                    (2, "f32"): {"ctc_softmax": 1223.6e6, "ctc_lattice": 14.1e6, "ctc_gradient": 26.2e6}}
+# HBM bytes per launch as the counters saw them (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+# counter reads for a plain copy of known size): profiles/hbm_traffic.json, written from the rocprofv3 --pmc
+# runs whose summaries sit beside it.  Each entry names the sources it was measured on; a figure measured
+# on other sources than the ones in the tree is reported with "traffic_current": false.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+# What the paper reports for this computation (Section 4.2, Table "gpucpuctc"): seconds per epoch spent in
+# the CTC cost and gradient, on its CPU implementation and on its GPU implementation.  Other hardware, other
+# workload unit (an epoch of its corpora): context, not a baseline for `value`.
+PAPER_CONTEXT = {
+    "source": "Section 4.2, Table gpucpuctc: CTC time in seconds per epoch, 5-layer 3-RNN model",
+    "hardware": "NVIDIA Titan X GPUs (count for this run not stated; 8 per node, 8 or 16 typical) vs. the node's "
+                "two Intel CPUs (model not stated), fp32",
+    "english": {"cpu_ctc_s_per_epoch": 5888.12, "gpu_ctc_s_per_epoch": 203.56, "speedup": 28.9},
+    "mandarin": {"cpu_ctc_s_per_epoch": 1688.01, "gpu_ctc_s_per_epoch": 135.05, "speedup": 12.5},
+    "note": "with about 8 M utterances per English epoch (11,940 h at about 7 s each: an estimate, the paper gives "
+            "no count for this table) the GPU figure is roughly 39 k utterances/s over all its GPUs",
+}
+
+
+def source_digest():
+    """sha256 (first 16 hex digits) over the library's sources: ties a counter measurement to the code."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1512_02595_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(config, dtype, kernel):
+    """(bytes per launch, measured on the current sources?) from profiles/hbm_traffic.json, or (None, None)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None, None
+    entry = table.get("config%d/%s" % (config, dtype))
+    if not entry or kernel not in entry.get("kernels", {}):
+        return None, None
+    k = entry["kernels"][kernel]
+    return float(k["read_bytes"] + k["written_bytes"]), entry.get("source_digest") == source_digest()
 
 
 def kernel_bytes(batch, elem, mode="grad"):
@@ -230,24 +269,36 @@ def main():
     dom_name = names[dom]
     if args.profile_steps == 0:
         dom_name = None
-    traffic = MEASURED_TRAFFIC.get((args.config, args.dtype), {}).get(dom_name) if args.mode == "grad" else None
+    traffic, traffic_current = (measured_traffic(args.config, args.dtype, dom_name)
+                                if args.mode == "grad" and dom_name else (None, None))
     if dom_name is None:
         roofline = None
-    elif dom_name == "ctc_lattice":
-        directions = 2.0 if args.mode == "grad" else 1.0
-        lane_ops = LANE_OPS_PER_PAIR_STEP_ALIGN if args.mode == "align" else LANE_OPS_PER_PAIR_STEP
-        pair_steps = directions * float(np.mean([k[1] for k in kb]))
-        achieved = pair_steps * lane_ops / (kavg[dom] * 1e-3) / 1e12
-        roofline = {"kernel": dom_name, "bound": "alu", "achieved": round(achieved, 4),
-                    "peak": round(ALU_PEAK_TOPS, 2), "unit": "TFLOP/s",
-                    "frac": round(achieved / ALU_PEAK_TOPS, 5), "traffic": traffic,
-                    "note": "flop = one non-packed VALU lane-operation of the log-space recursion that defines "
-                            "the path (transcendental = 4, 41 per pair-step); the kernel recurs on probabilities "
-                            "and executes about %d per pair-step" % LANE_OPS_EXECUTED}
     else:
+        # The dominant kernel against the HBM roofline: its algorithmic bytes (kernel_bytes) over its
+        # measured duration.
         achieved = kernels[dom_name]["GBps"]
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic}
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
+                    "traffic_current": traffic_current}
+        if dom_name == "ctc_lattice":
+            # The recursion is a chain of dependent steps and moves few bytes: what limits it is the rate
+            # at which a wavefront issues the step's instructions.  For orientation, the same kernel
+            # against the vector ALUs, in lane-operations per second: the operations it executes, and
+            # the operations of the log-space recursion that defines the path (which it does not run).
+            directions = 2.0 if args.mode == "grad" else 1.0
+            priced = LANE_OPS_PER_PAIR_STEP_ALIGN if args.mode == "align" else LANE_OPS_PER_PAIR_STEP
+            executed = LANE_OPS_PER_PAIR_STEP_ALIGN if args.mode == "align" else LANE_OPS_EXECUTED
+            pair_steps = directions * float(np.mean([k[1] for k in kb]))
+            per_s = pair_steps / (kavg[dom] * 1e-3) / 1e12
+            roofline["alu_orientation"] = {
+                "peak_T_lane_ops_per_s": round(ALU_PEAK_TOPS, 2),
+                "executed_lane_ops_per_pair_step": executed,
+                "executed_frac_of_peak": round(per_s * executed / ALU_PEAK_TOPS, 5),
+                "log_space_lane_ops_per_pair_step": priced,
+                "log_space_equivalent_frac_of_peak": round(per_s * priced / ALU_PEAK_TOPS, 5),
+                "note": "peak = one non-packed, non-fused VALU operation per lane and clock (256 CUs x 64 lanes x "
+                        "2.4 GHz); the executed count is the linear-domain step's, the log-space count prices the "
+                        "defining recursion (a transcendental as 4)"}
 
     out = {
         "metric": {"grad": "ctc_loss_grad_utterances_per_s", "loss": "ctc_loss_only_utterances_per_s",
@@ -271,6 +322,7 @@ def main():
         "compulsory_bytes": int(compulsory),
         "kernels": kernels,
         "roofline": roofline,
+        "paper_context": PAPER_CONTEXT,
     }
 
     if not args.no_cpu_baseline:
