@@ -219,6 +219,39 @@ ctc_status_t ctc_loss_and_grad_device(const void *activations,
                                       hipStream_t stream);
 
 /*
+ * ctc_loss_and_grad_device without a workspace argument, for callers that cannot allocate device
+ * memory or have it allocated for them: code recorded into a HIP graph, tight serving loops,
+ * harnesses that forbid hipMalloc.  The workspace is an array of CTC_STATIC_WORKSPACE_BYTES that is
+ * part of the library's device code: every GPU the library runs on holds its own copy from the
+ * moment the library is loaded until the process ends.  The call allocates nothing (no hipMalloc,
+ * no hipHostMalloc, no pinned staging); on its first use on a device it looks up the array's
+ * address there, nothing more.
+ *
+ *   arguments, results and status_out as for ctc_loss_and_grad_device;
+ *   a batch shape whose ctc_workspace_size_device exceeds CTC_STATIC_WORKSPACE_BYTES is refused
+ *   with CTC_STATUS_WORKSPACE_TOO_SMALL before anything is enqueued (64 MiB hold, for instance,
+ *   16 utterances of 750 frames and up to 250 label symbols over a 29-symbol alphabet).
+ *
+ * All calls on one GPU share that GPU's array, whatever their streams: calls that overlap in time
+ * on one GPU race and give wrong results; calls on one stream, or otherwise ordered, are fine.  The
+ * array keeps the previous call's contents; nothing in it needs clearing between calls (every word
+ * a call reads it has written before).
+ */
+#define CTC_STATIC_WORKSPACE_BYTES (64u << 20)
+
+ctc_status_t ctc_loss_and_grad_device_static(const void *activations,
+                                             const int32_t *labels,
+                                             const int32_t *label_lengths,
+                                             const int32_t *input_lengths,
+                                             int max_label_length,
+                                             int T, int B, int A, int blank,
+                                             ctc_dtype_t dtype,
+                                             float *costs,
+                                             void *grads,
+                                             int32_t *status_out,
+                                             hipStream_t stream);
+
+/*
  * Most probable alignment of each utterance (Section 5.1, "Dataset Construction": the
  * alignment step of the segmentation pipeline),
  *

@@ -14,6 +14,11 @@
 
 #include "ctc_internal.h"
 
+// Workspace of ctc_loss_and_grad_device_static: device memory that belongs to the library's code
+// object, one copy per GPU, so that the entry point needs no allocation by anybody.  In host code
+// this name is only a handle for hipGetSymbolAddress; the kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[CTC_STATIC_WORKSPACE_BYTES];
+
 namespace ctc {
 
 namespace {
@@ -546,10 +551,49 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     return CTC_STATUS_SUCCESS;
 }
 
+// Address of `scratch` on the current device (each GPU holds its own copy at its own address):
+// asked once per device, with that device current, and kept.
+void* static_workspace()
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void* address[kMaxDevices] = {};
+    int dev = 0;
+    if (!record(hipGetDevice(&dev))) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        g_last_hip_error = static_cast<int>(hipErrorInvalidDevice);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!address[dev]) {
+        void* ptr = nullptr;
+        if (!record(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)))) return nullptr;
+        address[dev] = ptr;
+    }
+    return address[dev];
+}
+
 }  // namespace
 }  // namespace ctc
 
 extern "C" {
+
+ctc_status_t ctc_loss_and_grad_device_static(const void* activations, const int32_t* labels,
+                                             const int32_t* label_lengths, const int32_t* input_lengths,
+                                             int max_label_length, int T, int B, int A, int blank,
+                                             ctc_dtype_t dtype, float* costs, void* grads,
+                                             int32_t* status_out, hipStream_t stream)
+{
+    // Sizes first: a batch shape beyond the static workspace is refused before anything else happens.
+    ctc::Layout lay;
+    const ctc_status_t st = ctc::make_layout_bounds(T, B, A, max_label_length, dtype, &lay);
+    if (st != CTC_STATUS_SUCCESS) return st;
+    if (lay.total > CTC_STATIC_WORKSPACE_BYTES) return CTC_STATUS_WORKSPACE_TOO_SMALL;
+    void* const ws = ctc::static_workspace();
+    if (!ws) return CTC_STATUS_HIP_ERROR;
+    return ctc::run_device(activations, labels, label_lengths, input_lengths, max_label_length, T, B, A,
+                           blank, dtype, costs, grads, status_out, ws, CTC_STATIC_WORKSPACE_BYTES, stream);
+}
 
 ctc_status_t ctc_workspace_size_device(int T, int B, int A, int max_label_length, ctc_dtype_t dtype,
                                        size_t* bytes_out)

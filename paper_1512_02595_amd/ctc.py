@@ -31,7 +31,7 @@ KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
 
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
-           "ctc_workspace_size_device", "ctc_loss_and_grad_device",
+           "ctc_workspace_size_device", "ctc_loss_and_grad_device", "ctc_loss_and_grad_device_static",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget",
            "ctc_debug_staging_allocations")
 
@@ -71,6 +71,8 @@ def load() -> ctypes.CDLL:
     lib.ctc_loss_and_grad_device.restype = st
     lib.ctc_loss_and_grad_device.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp,
                                              ctypes.c_size_t, vp]
+    lib.ctc_loss_and_grad_device_static.restype = st
+    lib.ctc_loss_and_grad_device_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp]
     lib.ctc_kernel_name.restype = ctypes.c_char_p
     lib.ctc_kernel_name.argtypes = [ci]
     lib.ctc_status_string.restype = ctypes.c_char_p
@@ -201,6 +203,20 @@ def loss_and_grad_device_status(activations_ptr, labels_ptr, label_lengths_ptr, 
         ctypes.c_void_p(input_lengths_ptr), int(max_label_length), int(T), int(B), int(A), int(blank),
         int(dtype), ctypes.c_void_p(costs_ptr), ctypes.c_void_p(grads_ptr), ctypes.c_void_p(status_ptr),
         ctypes.c_void_p(workspace_ptr), ctypes.c_size_t(workspace_bytes), ctypes.c_void_p(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def loss_and_grad_device_static_status(activations_ptr, labels_ptr, label_lengths_ptr, input_lengths_ptr,
+                                       max_label_length, T, B, A, blank, dtype, costs_ptr, grads_ptr,
+                                       status_ptr, stream=0) -> int:
+    """Raw ctc_loss_and_grad_device_static: the device-metadata call on the library's own workspace."""
+    return int(load().ctc_loss_and_grad_device_static(
+        ctypes.c_void_p(activations_ptr), ctypes.c_void_p(labels_ptr), ctypes.c_void_p(label_lengths_ptr),
+        ctypes.c_void_p(input_lengths_ptr), int(max_label_length), int(T), int(B), int(A), int(blank),
+        int(dtype), ctypes.c_void_p(costs_ptr), ctypes.c_void_p(grads_ptr), ctypes.c_void_p(status_ptr),
+        ctypes.c_void_p(stream)))
 
 
 def loss_and_grad_device(*args, **kw) -> None:
