@@ -648,37 +648,62 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
 }
 
 // ---- lattice storage -------------------------------------------------------------------------
-// What the recursions leave for the gradient, per label state and frame, and for the mass p per
-// utterance: a number m * 2^e as one 8-byte word,
-//   low  dword: e, int32
-//   high dword: the high dword of the fp64 m (sign, exponent, top 20 mantissa bits)
-// so that a linear-domain chain stores (frame, value in that frame) as they stand, with no
-// arithmetic on the way out.  Twenty mantissa bits bound the relative error of a state's share
-// alpha * beta / p by 2^-19, which is 2e-6 of a gradient entry at most.  Exponents stay above
-// -2^30 so that the sum of two cannot wrap.
+// What the recursions leave for the gradient, per label state, frame and direction: a number
+// m * 2^e, as
+//   a value word (uint32): the high dword of the fp64 m (sign, exponent, top 20 mantissa bits),
+//                          one per state and frame, rows of lattice_pitch(L) words by frame;
+//   an exponent word (int32): e, one per state and exponent row.
+// A linear-domain chain stores its state in the lane's frame as it stands (no arithmetic on the
+// way out), and the frame changes only when a chunk ends: it writes one exponent row per chunk
+// (exponent_row), 4.5 bytes per state and frame in all.  A log-domain chain has a new exponent at
+// every step and writes one exponent row per step.  Both blocks of a direction are sized for the
+// latter (which chain runs is decided on the GPU, by the softmax launch): values in the first
+// half of the direction's region, exponents in the second.
+// Twenty mantissa bits bound the relative error of a state's share alpha * beta / p by 2^-19,
+// which is 2e-6 of a gradient entry at most.  Exponents stay above -2^30 so that the sum of two
+// cannot wrap.
+// The mass p of an utterance (its reciprocal) keeps both parts in one 8-byte word (pack_state).
 __device__ __forceinline__ double pack_state(double in_frame, int frame)
 {
     return __hiloint2double(__double2hiint(in_frame), frame);
 }
-// From a base-2 logarithm (log-domain chains): m = 2^fraction in [1, 2), e = floor.
-__device__ __forceinline__ double pack_log2(double w)
+// Exponent row of the state a chain reached at its step `step` (0 .. Tb-1; a forward chain's step
+// is the frame, a backward chain's Tb-1-frame).  Linear domain: the initial frame serves step 0 and
+// the first chunk (steps 1 .. kChunk), each later chunk has a row of its own.
+__device__ __forceinline__ int exponent_row(int step, bool log_domain)
+{
+    return log_domain ? step : (max(step - 1, 0) / kChunk);
+}
+// A base-2 logarithm (log-domain chains) as value and exponent: m = 2^fraction in [1, 2), e = floor.
+// log 0 (and anything as small) is stored as the number 0.
+__device__ __forceinline__ void split_log2(double w, uint32_t& value, int& exponent)
 {
     const double whole = floor(w);
     const double m = static_cast<double>(fast_exp2(static_cast<float>(w - whole)));
-    // log 0 (and anything as small) is stored as the number 0; so is the reciprocal of a p that small
-    return (w > -1.0e9 && w < 1.0e9) ? pack_state(m, static_cast<int>(whole)) : 0.0;
+    const bool real = w > -1.0e9 && w < 1.0e9;
+    value = real ? static_cast<uint32_t>(__double2hiint(m)) : 0u;
+    exponent = real ? static_cast<int>(whole) : 0;
 }
-// alpha * beta * (1 / p) from three packed words.  (The exponent in the low dword reads as the
-// last mantissa bits: a relative 2^-20 at most, and a stored zero reads as less than 2^-1040.)
-// Either of alpha and beta may lie a thousand binary orders below the top of its own frame
-// while their product is a share of order one, so the exponent that the three words add up to
+__device__ __forceinline__ double pack_log2(double w)          // the same as one word (1 / p)
+{
+    uint32_t value;
+    int exponent;
+    split_log2(w, value, exponent);
+    return __hiloint2double(static_cast<int>(value), exponent);
+}
+// alpha * beta * (1 / p) from the stored parts.  (The missing low dword of a value is a relative
+// 2^-20 at most.)  Either of alpha and beta may lie a thousand binary orders below the top of its
+// own frame while their product is a share of order one, so the exponent that the three add up to
 // is spread over both factors before they are multiplied.  m_a, m_b < 2^(kChunk + 2) in their
 // frames, hence 2^1000 of either cannot overflow; a share that needed more is of values that
 // had been rounded away in their frames.
-__device__ __forceinline__ float mass_share(double a, double b, float inverse_p_mantissa, int inverse_p_exponent)
+__device__ __forceinline__ float mass_share(uint32_t a_value, int a_exponent, uint32_t b_value, int b_exponent,
+                                            float inverse_p_mantissa, int inverse_p_exponent)
 {
-    const int e = min(__double2loint(a) + __double2loint(b) + inverse_p_exponent, 2000);
+    const int e = min(a_exponent + b_exponent + inverse_p_exponent, 2000);
     const int half = e >> 1;
+    const double a = __hiloint2double(static_cast<int>(a_value), 0);
+    const double b = __hiloint2double(static_cast<int>(b_value), 0);
     return static_cast<float>(__builtin_amdgcn_ldexp(a, half) * __builtin_amdgcn_ldexp(b, e - half)) *
            inverse_p_mantissa;
 }
@@ -779,9 +804,10 @@ template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const int* __restrict__ labels,
                                           const float* __restrict__ emit_blank,
                                           const float* __restrict__ emit_label,
-                                          void* __restrict__ out, double* __restrict__ logp,
+                                          uint32_t* __restrict__ out, int* __restrict__ out_exponents,
+                                          double* __restrict__ logp,
                                           float* __restrict__ costs, int* __restrict__ chain_err,
-                                          double* __restrict__ sink, void* lds)
+                                          uint32_t* __restrict__ sink, void* lds)
 {
     static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
     // Launches for the most probable alignment store plain logarithms, the others coded emissions.
@@ -816,18 +842,29 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
     // Output: only the label state of each pair is kept (row pitch L+2 words, column = 1 + label
-    // index, in both directions); the gradient gets the blank's share as the complement.
+    // index, in both directions; value rows by frame, exponent rows by step: one per step in the
+    // log domain); the gradient gets the blank's share as the complement.
     // Lanes that store nothing write to a sink instead.
-    // With Mode::kBest the same block holds one byte per pair and frame instead (row pitch
+    // With Mode::kBest the value block holds one byte per pair and frame instead (row pitch
     // L+1 bytes, column = pair), pair L included: its blank state has a choice to record.
-    constexpr int64_t kOutBytes = (kMode == Mode::kBest) ? 1 : 8;
+    constexpr int64_t kOutBytes = (kMode == Mode::kBest) ? 1 : 4;
     const int64_t out_pitch = (kMode == Mode::kBest) ? P : lattice_pitch(L);
     const bool stores = (kMode == Mode::kBest) ? active : (active && has_label);
-    char* op = stores ? static_cast<char*>(out) +
+    char* op = stores ? reinterpret_cast<char*>(out) +
                             (m.ab_off + static_cast<int64_t>(f0) * out_pitch + (kMode == Mode::kBest ? j : li + 1)) * kOutBytes
                       : reinterpret_cast<char*>(sink);
     const int64_t ostride = stores ? static_cast<int64_t>(fdir) * out_pitch * kOutBytes : 0;
+    int* xp = (stores && kMode == Mode::kGrad) ? out_exponents + m.ab_off + li + 1 : reinterpret_cast<int*>(sink);
+    const int64_t xstride = (stores && kMode == Mode::kGrad) ? out_pitch : 0;
     int choice = 0;
+    auto store_state = [&](double w) {
+        uint32_t value;
+        int exponent;
+        split_log2(w, value, exponent);
+        *reinterpret_cast<uint32_t*>(op) = value;
+        *xp = exponent;
+        xp += xstride;
+    };
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
@@ -928,7 +965,7 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
         } else if (kMode == Mode::kLoss) {
             // nothing is kept
         } else {
-            *reinterpret_cast<double*>(op) = pack_log2(kBackward ? i_label : v_label);
+            store_state(kBackward ? i_label : v_label);
         }
         op += ostride;
     };
@@ -975,7 +1012,7 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
         v_blank = i_blank + static_cast<double>(readlane(ebv, 0));
         v_label = i_label + static_cast<double>(el);
         // (the predecessor choices of frame 0 are never looked at: nothing is written for it)
-        if (kMode == Mode::kGrad) *reinterpret_cast<double*>(op) = pack_log2(kBackward ? i_label : v_label);
+        if (kMode == Mode::kGrad) store_state(kBackward ? i_label : v_label);
         op += ostride;
     }
 
@@ -1087,9 +1124,10 @@ template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
                                                  const float* __restrict__ emit_blank,
                                                  const float* __restrict__ emit_label,
-                                                 void* __restrict__ out, double* __restrict__ logp,
+                                                 uint32_t* __restrict__ out, int* __restrict__ out_exponents,
+                                                 double* __restrict__ logp,
                                                  float* __restrict__ costs, int* __restrict__ chain_err,
-                                                 double* __restrict__ sink, void* lds)
+                                                 uint32_t* __restrict__ sink, void* lds)
 {
     static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
     static_assert(kSync != Sync::kBarrier, "the barrier kernel runs the log-domain chain");
@@ -1114,9 +1152,13 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
     const int eadvance = has_label ? fdir * kChunk : 0;
     const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    // Values by frame, exponents by chunk (exponent_row): the lane's frame is what it is until the
+    // chunk ends.
     const bool stores = kMode == Mode::kGrad && active && has_label;
-    double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * lattice_pitch(L) + li + 1 : sink;
+    uint32_t* op = stores ? out + m.ab_off + static_cast<int64_t>(f0) * lattice_pitch(L) + li + 1 : sink;
     const int64_t ostride = stores ? static_cast<int64_t>(fdir) * lattice_pitch(L) : 0;
+    int* xp = stores ? out_exponents + m.ab_off + li + 1 : reinterpret_cast<int*>(sink);
+    const int64_t xstride = stores ? lattice_pitch(L) : 0;
 
     HaloLds* const hl = static_cast<HaloLds*>(lds);
     const int last_wave = m.waves - 1;
@@ -1225,7 +1267,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     auto finish_step = [&](float eb, float el) {
         v_blank = i_blank * static_cast<double>(eb);
         v_label = i_label * static_cast<double>(el);
-        if (kMode == Mode::kGrad) *op = pack_state(kBackward ? i_label : v_label, frame);
+        if (kMode == Mode::kGrad) *op = static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label));
         op += ostride;
     };
     auto end_chunk = [&]() {
@@ -1236,6 +1278,9 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
             }
         }
         renew_frames();
+        // the next chunk's exponent row
+        xp += xstride;
+        if (kMode == Mode::kGrad) *xp = frame;
     };
     auto advance = [&](float eb, float el) {
         // The blank state sums its own value and the label of the pair before; the label state
@@ -1255,7 +1300,10 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         const float el = *ep;
         v_blank = i_blank * static_cast<double>(readlane(ebv, 0));
         v_label = i_label * static_cast<double>(el);
-        if (kMode == Mode::kGrad) *op = pack_state(kBackward ? i_label : v_label, frame);
+        if (kMode == Mode::kGrad) {
+            *op = static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label));
+            *xp = frame;                                 // exponent row 0: step 0 and the first chunk
+        }
         op += ostride;
     }
 
@@ -1352,15 +1400,17 @@ struct Halo2Lds {
     float cost;
 };
 
-struct alignas(8) LabelStatePair { double lo, hi; };   // two neighbouring columns of a lattice row
+struct alignas(4) LabelStatePair { uint32_t lo, hi; };   // two neighbouring columns of a lattice row
+struct alignas(4) ExponentPair { int lo, hi; };
 
 template <bool kBackward, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, const int* __restrict__ labels,
                                                   const float* __restrict__ emit_blank,
                                                   const float* __restrict__ emit_label,
-                                                  void* __restrict__ out, double* __restrict__ logp,
+                                                  uint32_t* __restrict__ out, int* __restrict__ out_exponents,
+                                                  double* __restrict__ logp,
                                                   float* __restrict__ costs, int* __restrict__ chain_err,
-                                                  double* __restrict__ sink, void* lds)
+                                                  uint32_t* __restrict__ sink, void* lds)
 {
     static_assert(kMode == Mode::kGrad || !kBackward, "only the gradient needs the backward chain");
     static_assert(kMode != Mode::kBest, "the maximum recursion runs in the log domain");
@@ -1393,9 +1443,11 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     // the next one.  (has_a false: nothing of this lane is kept.)
     const bool stores = kMode == Mode::kGrad && active && has_a;
     const int pitch = static_cast<int>(lattice_pitch(L));
-    double* op = stores ? static_cast<double*>(out) + m.ab_off + static_cast<int64_t>(f0) * pitch + 1 + (kBackward ? lib : lia)
-                        : sink;
+    const int first_column = 1 + (kBackward ? lib : lia);
+    uint32_t* op = stores ? out + m.ab_off + static_cast<int64_t>(f0) * pitch + first_column : sink;
     const int64_t ostride = stores ? static_cast<int64_t>(fdir) * pitch : 0;
+    int* xp = stores ? out_exponents + m.ab_off + first_column : reinterpret_cast<int*>(sink);
+    const int64_t xstride = stores ? pitch : 0;
 
     Halo2Lds* const hl = static_cast<Halo2Lds*>(lds);
     const int last_wave = waves - 1;
@@ -1516,11 +1568,15 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
 
     auto store = [&]() {
         if (kMode == Mode::kGrad) {
-            const double a = pack_state(kBackward ? ia_label : va_label, frame);
-            const double b = pack_state(kBackward ? ib_label : vb_label, frame);
+            const uint32_t a = static_cast<uint32_t>(__double2hiint(kBackward ? ia_label : va_label));
+            const uint32_t b = static_cast<uint32_t>(__double2hiint(kBackward ? ib_label : vb_label));
             *reinterpret_cast<LabelStatePair*>(op) = kBackward ? LabelStatePair{b, a} : LabelStatePair{a, b};
         }
         op += ostride;
+    };
+    // both label states of the lane share its frame
+    auto store_frame = [&]() {
+        if (kMode == Mode::kGrad) *reinterpret_cast<ExponentPair*>(xp) = ExponentPair{frame, frame};
     };
     auto finish_step = [&](float eb, float ela, float elb) {
         const double ebd = static_cast<double>(eb);
@@ -1536,6 +1592,8 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             until_hand_over = chunks_per_hand_over;
         }
         renew_frames();
+        xp += xstride;                                   // the next chunk's exponent row
+        store_frame();
     };
     auto advance = [&](float eb, float ela, float elb) {
         const double prev = from_lane_below(vb_label);
@@ -1550,6 +1608,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     };
 
     // step 0
+    store_frame();                                       // exponent row 0: step 0 and the first chunk
     finish_step(readlane(*bp, 0), *epa, *epb);
 
     float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk], eb_a, eb_b;
@@ -1625,14 +1684,24 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     }
 }
 
+// Where the chains of a launch leave their states: value and exponent blocks of both directions
+// (see "lattice storage").  In the modes without a backward chain the forward value block receives
+// the predecessor choices (Mode::kBest) or nothing.
+struct LatticeOut {
+    uint32_t* alpha;
+    int* alpha_exponents;
+    uint32_t* beta;
+    int* beta_exponents;
+};
+
 template <Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
                                              const float* __restrict__ emit_label,
-                                             double* __restrict__ alpha, double* __restrict__ beta,
+                                             const LatticeOut lat,
                                              double* __restrict__ logp, float* __restrict__ costs,
-                                             int* __restrict__ chain_err, double* __restrict__ sink,
+                                             int* __restrict__ chain_err, uint32_t* __restrict__ sink,
                                              void* lds)
 {
     const int chain = order[blockIdx.x];           // utterance * 2 + direction
@@ -1683,24 +1752,24 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
         if (two_pairs) {
             if constexpr (kSync == Sync::kHalo) {
                 if (forward)
-                    run_chain_linear2<false, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+                    run_chain_linear2<false, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
                 else
-                    run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+                    run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
             }
             return;
         }
         if (!in_log_domain) {
             if (forward)
-                run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+                run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
             else
-                run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+                run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
             return;
         }
     }
     if (forward)
-        run_chain_log<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, alpha, logp, costs, chain_err, sink, lds);
+        run_chain_log<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
     else
-        run_chain_log<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, beta, logp, costs, chain_err, sink, lds);
+        run_chain_log<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
 }
 
 // grid = one workgroup per entry of `order` (utterance * 2 + direction: 0 forward, 1 backward; only
@@ -1713,11 +1782,11 @@ __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
                            const int* __restrict__ labels, const float* __restrict__ emit_blank,
                            const float* __restrict__ emit_label,
-                           double* __restrict__ alpha, double* __restrict__ beta,
+                           const LatticeOut lat,
                            double* __restrict__ logp, float* __restrict__ costs,
-                           int* __restrict__ chain_err, double* __restrict__ sink)
+                           int* __restrict__ chain_err, uint32_t* __restrict__ sink)
 {
-    lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
                                               costs, chain_err, sink, nullptr);
 }
 
@@ -1727,12 +1796,12 @@ __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
                         const float* __restrict__ emit_label,
-                        double* __restrict__ alpha, double* __restrict__ beta,
+                        const LatticeOut lat,
                         double* __restrict__ logp, float* __restrict__ costs,
-                        int* __restrict__ chain_err, double* __restrict__ sink)
+                        int* __restrict__ chain_err, uint32_t* __restrict__ sink)
 {
     __shared__ union { HaloLds one; Halo2Lds two; } halo_lds;      // one pair per lane, or two
-    lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
                                               costs, chain_err, sink, &halo_lds);
 }
 
@@ -1743,12 +1812,12 @@ __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restrict__ order,
                                 const int* __restrict__ labels, const float* __restrict__ emit_blank,
                                 const float* __restrict__ emit_label,
-                                double* __restrict__ alpha, double* __restrict__ beta,
+                                const LatticeOut lat,
                                 double* __restrict__ logp, float* __restrict__ costs,
-                                int* __restrict__ chain_err, double* __restrict__ sink)
+                                int* __restrict__ chain_err, uint32_t* __restrict__ sink)
 {
     __shared__ double xch[2][16];
-    lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, alpha, beta, logp,
+    lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
                                                costs, chain_err, sink, &xch[0][0]);
 }
 
@@ -1838,12 +1907,37 @@ void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __r
 
 constexpr int kAhead = 4;             // 64-state pieces of a row requested together
 
+// The stored lattice of one utterance as the gradient kernels read it: the label states of frame t
+// are one row of alpha values, one of beta values, and the exponent rows that the two chains wrote
+// for the steps at which they reached that frame (exponent_row: alpha's step is t, beta's Tb-1-t).
+struct LatticeRow {
+    const uint32_t* a;
+    const int* ea;
+    const uint32_t* b;
+    const int* eb;
+};
+struct LatticeRows {
+    const uint32_t* a;
+    const int* ea;
+    const uint32_t* b;
+    const int* eb;
+    size_t pitch;
+    int Tb;
+    bool log_domain;
+    __device__ __forceinline__ LatticeRow at(int t) const
+    {
+        const size_t values = static_cast<size_t>(t) * pitch;
+        return {a + values, ea + static_cast<size_t>(exponent_row(t, log_domain)) * pitch,
+                b + values, eb + static_cast<size_t>(exponent_row(Tb - 1 - t, log_domain)) * pitch};
+    }
+};
+
 template <typename T, bool kSparse>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                               const Utt* __restrict__ meta, const int* __restrict__ labels,
                               const int* __restrict__ links, const float* __restrict__ lse,
-                              const double* __restrict__ alpha, const double* __restrict__ beta,
+                              const LatticeOut lat,
                               const double* __restrict__ logp, const int* __restrict__ chain_err,
                               float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
                               int rows_per_group, const float* __restrict__ emit_blank,
@@ -1872,8 +1966,10 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
-    const double* const abase = alpha + m.ab_off + 1;      // label state i sits in column 1 + i
-    const double* const bbase = beta + m.ab_off + 1;
+    const bool log_domain = (m.flags & kUttLogDomain) != 0;  // decides where a row's exponents are (exponent_row)
+    const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
+                              lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
+                              pitch, m.Tb, log_domain};
 
     // What a row needs from memory, requested in one go before any of it is used, so that a
     // row costs one memory latency: the lattice values of the first kAhead * 64 label states
@@ -1881,20 +1977,22 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     // 64 activations.  (Requesting the next row during the current one was measured slower:
     // the extra registers cost more wavefronts per SIMD than the overlap gains.)
     struct RowData {
-        double a[kAhead], b[kAhead];
+        uint32_t a[kAhead], b[kAhead];
+        int ea[kAhead], eb_[kAhead];
         float l2, x0;
         float e[kAhead], eb;              // sparse form: emissions of the label positions and of blank
     };
     auto request = [&](int t, RowData& d) {
         if (t >= tend || t >= m.Tb || !runs) return;
-        const double* arow = abase + static_cast<size_t>(t) * pitch;
-        const double* brow = bbase + static_cast<size_t>(t) * pitch;
+        const LatticeRow row = rows_of.at(t);
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             const int j = u * 64 + lane;
             if (j < L) {
-                d.a[u] = arow[j];
-                d.b[u] = brow[j];
+                d.a[u] = row.a[j];
+                d.b[u] = row.b[j];
+                d.ea[u] = row.ea[j];
+                d.eb_[u] = row.eb[j];
             }
         }
         d.l2 = lse[static_cast<size_t>(b) * Tt + t];
@@ -1928,29 +2026,31 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
         for (int u = 0; u < kAhead; ++u) {
             const int j = u * 64 + lane;
             if (j < L) {
-                const float gl = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
+                const float gl = mass_share(cur.a[u], cur.ea[u], cur.b[u], cur.eb_[u], inverse_p, inverse_p_exponent);
                 g_label[s_lnk[j] & kLinkSlotMask] = gl;
                 zl += gl;
             }
         }
         if (L > kAhead * 64) {
-            const double* arow = abase + static_cast<size_t>(t) * pitch;
-            const double* brow = bbase + static_cast<size_t>(t) * pitch;
+            const LatticeRow row = rows_of.at(t);
             for (int j0 = kAhead * 64; j0 < L; j0 += kAhead * 64) {
-                double a[kAhead], bb[kAhead];
+                uint32_t a[kAhead], bb[kAhead];
+                int ea[kAhead], eb[kAhead];
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
                     const int j = j0 + u * 64 + lane;
                     if (j < L) {
-                        a[u] = arow[j];
-                        bb[u] = brow[j];
+                        a[u] = row.a[j];
+                        bb[u] = row.b[j];
+                        ea[u] = row.ea[j];
+                        eb[u] = row.eb[j];
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
                     const int j = j0 + u * 64 + lane;
                     if (j < L) {
-                        const float gl = mass_share(a[u], bb[u], inverse_p, inverse_p_exponent);
+                        const float gl = mass_share(a[u], ea[u], bb[u], eb[u], inverse_p, inverse_p_exponent);
                         g_label[s_lnk[j] & kLinkSlotMask] = gl;
                         zl += gl;
                     }
@@ -2031,7 +2131,7 @@ __global__ __launch_bounds__(kRowThreads)
 void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
                                 const Utt* __restrict__ meta, const int* __restrict__ labels,
                                 const int* __restrict__ links, const float* __restrict__ lse,
-                                const double* __restrict__ alpha, const double* __restrict__ beta,
+                                const LatticeOut lat,
                                 const double* __restrict__ logp, const int* __restrict__ chain_err,
                                 float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
                                 int rows_per_group)
@@ -2069,66 +2169,72 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
-    const double* const abase = alpha + m.ab_off + 1;      // label state i sits in column 1 + i
-    const double* const bbase = beta + m.ab_off + 1;
+    const bool log_domain = (m.flags & kUttLogDomain) != 0;  // decides where a row's exponents are (exponent_row)
+    const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
+                              lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
+                              pitch, m.Tb, log_domain};
     // What a row needs from memory: the lattice words of its first kAhead * 64 label states
     // (longer labels read the rest in line), its log-sum-exp and its activations.  A row's
     // values are requested while the row before it is still being summed up out of LDS: by then
     // the registers are free again (the shares are in LDS), so the overlap costs none.
     struct RowData {
-        double a[kAhead], b[kAhead];
+        uint32_t a[kAhead], b[kAhead];
+        int ea[kAhead], eb[kAhead];
         float l2, x0;
     };
     // Row addresses are kept as running pointers of this wavefront's rows (t_first, t_first + 4,
-    // ...): the products t x pitch and (t x B + b) x A are formed once, not per row.
+    // ...): the product (t x B + b) x A is formed once, not per row.
     const int t_first = t0 + wave;
-    const double* next_a = abase + static_cast<size_t>(t_first) * pitch + lane;       // of the row to request next
-    const double* next_b = bbase + static_cast<size_t>(t_first) * pitch + lane;
     const float* next_lse = lse + static_cast<size_t>(b) * Tt + t_first;
     const size_t row_step = static_cast<size_t>(4) * B * A;
     const T* next_x = x + (static_cast<size_t>(t_first) * B + b) * A;
     T* grow = grads + (static_cast<size_t>(t_first) * B + b) * A;                     // of the row being written
-    // A lattice larger than the caches is read once and never again: such launches use loads that
-    // leave no copy behind (kStreaming), which keeps the caches for the rest.
-    auto lattice_word = [&](const double* p) { return kStreaming ? __builtin_nontemporal_load(p) : *p; };
-    auto request = [&](RowData& d) {
+    // A lattice larger than the caches is read once and never again: such launches read the values
+    // with loads that leave no copy behind (kStreaming), which keeps the caches for the rest (the
+    // exponent rows among it: eight frames share one).
+    auto value_word = [&](const uint32_t* p) { return kStreaming ? __builtin_nontemporal_load(p) : *p; };
+    auto request = [&](int t, RowData& d) {
+        const LatticeRow row = rows_of.at(t);
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             if (u * 64 >= L) break;                      // (the same for every lane)
-            if (u * 64 + lane < L) {
-                d.a[u] = lattice_word(next_a + u * 64);
-                d.b[u] = lattice_word(next_b + u * 64);
+            const int j = u * 64 + lane;
+            if (j < L) {
+                d.a[u] = value_word(row.a + j);
+                d.b[u] = value_word(row.b + j);
+                d.ea[u] = row.ea[j];
+                d.eb[u] = row.eb[j];
             }
         }
         d.l2 = *next_lse;
         d.x0 = (lane < A) ? load_elem(next_x, lane) : 0.0f;
     };
     auto advance_request = [&]() {
-        next_a += 4 * pitch;
-        next_b += 4 * pitch;
         next_lse += 4;
         next_x += row_step;
     };
     RowData cur = {};
-    if (runs && t_first < tend && t_first < m.Tb) request(cur);
+    if (runs && t_first < tend && t_first < m.Tb) request(t_first, cur);
     for (int t = t_first; t < tend; t += 4, grow += row_step) {
         if (t >= m.Tb || !runs) {
             if (lane < A) store_elem(grow, lane, 0.0f);
             continue;
         }
-        const double* arow = next_a, * brow = next_b;     // this row's, past its first kAhead * 64 states
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             if (u * 64 >= L) break;                      // (the same for every lane)
             const int j = u * 64 + lane;
-            if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.b[u], inverse_p, inverse_p_exponent);
+            if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.ea[u], cur.b[u], cur.eb[u], inverse_p, inverse_p_exponent);
         }
-        for (int j = kAhead * 64 + lane; j < L; j += 64)
-            g_slot[s_slot[j]] = mass_share(lattice_word(arow + (j - lane)), lattice_word(brow + (j - lane)),
-                                           inverse_p, inverse_p_exponent);
+        if (L > kAhead * 64) {
+            const LatticeRow row = rows_of.at(t);         // this row's states past the first kAhead * 64
+            for (int j = kAhead * 64 + lane; j < L; j += 64)
+                g_slot[s_slot[j]] = mass_share(value_word(row.a + j), row.ea[j], value_word(row.b + j), row.eb[j],
+                                               inverse_p, inverse_p_exponent);
+        }
         const float l2 = cur.l2, x0 = cur.x0;
         advance_request();
-        if (t + 4 < tend && t + 4 < m.Tb) request(cur);
+        if (t + 4 < tend && t + 4 < m.Tb) request(t + 4, cur);
         // LDS operations of one wavefront complete in program order; the fences only keep the
         // compiler from moving them across.
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -2173,6 +2279,14 @@ bool vector_ok(const Launch& p)
     return p.A % n == 0 && reinterpret_cast<uintptr_t>(p.x) % 16 == 0 &&
            reinterpret_cast<uintptr_t>(p.grads) % 16 == 0;
 }
+}
+
+// Values in the first half of a direction's region, exponents in the second.
+static LatticeOut lattice_blocks(const Launch& p)
+{
+    auto* alpha = reinterpret_cast<uint32_t*>(p.ws + p.lay.alpha);
+    auto* beta = reinterpret_cast<uint32_t*>(p.ws + p.lay.beta);
+    return {alpha, reinterpret_cast<int*>(alpha + p.lay.ab_doubles), beta, reinterpret_cast<int*>(beta + p.lay.ab_doubles)};
 }
 
 int launch_setup(const Launch& p, void* stream)
@@ -2282,16 +2396,15 @@ int launch_lattice(const Launch& p, void* stream)
     const int* labels = p.labels;
     auto* emit_blank = reinterpret_cast<const float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<const float*>(p.ws + p.lay.emit_label);
-    auto* sink = reinterpret_cast<double*>(p.ws + p.lay.sink);
-    auto* alpha = reinterpret_cast<double*>(p.ws + p.lay.alpha);
-    auto* beta = reinterpret_cast<double*>(p.ws + p.lay.beta);
+    auto* sink = reinterpret_cast<uint32_t*>(p.ws + p.lay.sink);
+    const LatticeOut lat = lattice_blocks(p);
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
     const dim3 grid(p.n_chains), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
     hipLaunchKernelGGL(KERNEL, grid, block, 0, s, meta, order, labels, emit_blank, emit_label,     \
-                       alpha, beta, logp, p.costs, chain_err, sink)
+                       lat, logp, p.costs, chain_err, sink)
     // The emission layout is the launch's (emission_layout), and a template parameter of the kernels.
     const bool symbol_major = emission_layout(p.A) == kEmitSymbolMajor;
 #define CTC_LAUNCH_LATTICE_MODE(KERNEL, MODE)                                                       \
@@ -2333,8 +2446,7 @@ int launch_gradient(const Launch& p, void* stream)
     const int* labels = p.labels;
     auto* links = reinterpret_cast<const int*>(p.ws + p.lay.links);
     auto* lse = reinterpret_cast<const float*>(p.ws + p.lay.lse);
-    auto* alpha = reinterpret_cast<const double*>(p.ws + p.lay.alpha);
-    auto* beta = reinterpret_cast<const double*>(p.ws + p.lay.beta);
+    const LatticeOut lat = lattice_blocks(p);
     auto* logp = reinterpret_cast<const double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<const int*>(p.ws + p.lay.chain_err);
     const dim3 block(kRowThreads);
@@ -2350,12 +2462,12 @@ int launch_gradient(const Launch& p, void* stream)
     const size_t lds = (2 * static_cast<size_t>(Lmax) + 4 * (static_cast<size_t>(Lmax) + 1 + (sparse ? 0 : p.A))) * 4;
     if (p.A <= 64) {
         // Both lattice blocks together against what the caches hold (kStreamingLatticeBytes).
-        const bool streaming = 2 * p.lay.ab_doubles * sizeof(double) > kStreamingLatticeBytes;
+        const bool streaming = 2 * p.lay.ab_doubles * sizeof(uint32_t) > kStreamingLatticeBytes;
         const size_t nlds = (static_cast<size_t>(Lmax) + 128 + 4 * (static_cast<size_t>(Lmax) + 1)) * 4;
 #define CTC_LAUNCH_NARROW(TYPE, STREAMING)                                                          \
     hipLaunchKernelGGL((ctc_gradient_narrow_kernel<TYPE, STREAMING>), grid, block, nlds, s,         \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,    \
-                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,   \
+                       links, lse, lat, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,           \
                        Lmax, rows)
         return checked_launch([&] {
             if (f32 && streaming) CTC_LAUNCH_NARROW(float, true);
@@ -2368,7 +2480,7 @@ int launch_gradient(const Launch& p, void* stream)
 #define CTC_LAUNCH_GRADIENT(TYPE, SPARSE)                                                          \
     hipLaunchKernelGGL((ctc_gradient_rows_kernel<TYPE, SPARSE>), grid, block, lds, s,               \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,     \
-                       links, lse, alpha, beta, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank, Lmax, rows,       \
+                       links, lse, lat, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank, Lmax, rows,               \
                        reinterpret_cast<const float*>(p.ws + p.lay.emit_blank),                                       \
                        reinterpret_cast<const float*>(p.ws + p.lay.emit_label))
     return checked_launch([&] {
