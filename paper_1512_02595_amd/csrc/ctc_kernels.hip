@@ -755,17 +755,41 @@ __device__ __forceinline__ void fetch_frames(const float*& p, int advance, float
 }
 constexpr int kFromSame = 0, kFromBlank = 1 << 2, kFromPrevLabel = 2 << 2, kBlankFromPrevLabel = 1;
 
-// LDS of the halo exchange of the chains with one pair per lane: per wavefront w, what w hands to w+1.
-struct HaloLds {
-    double2 data[16][kHaloEntries];
-    int frame[16][kHaloEntries];      // linear-domain chains: the frame exponent that goes with each entry
-    int ready[16];                    // last generation wavefront w has published
-    int done[16];                     // last generation wavefront w has taken from w-1
+// LDS of a chain's workgroup (dynamic, sized by the launch for its widest chain): a header, then
+// one block per wavefront that holds what that wavefront hands to the one above it.
+struct HaloHeader {
     // Cost-only chains: the last wavefront to finish writes the cost (or NaN if any gave up).
     int finished;                     // wavefronts that have reached the end of the chain
     int gave_up;
     float cost;
+    int unused;
 };
+// Chains with one pair per lane.
+struct HaloWave {
+    double2 data[kHaloEntries];
+    int frame[kHaloEntries];          // linear-domain chains: the frame exponent that goes with each entry
+    int ready;                        // last generation this wavefront has published
+    int done;                         // last generation this wavefront has taken from the one below
+    int unused[2];
+};
+
+// Chains with two pairs per lane (run_chain_linear2).
+constexpr int kRing = 4;                  // hand-overs a boundary's buffer holds
+constexpr int kHalo2Lanes = 16;           // most halo lanes plan_waves2 asks for
+struct Halo2Wave {
+    double2 data[kRing][kHalo2Lanes][2];      // [hand-over mod kRing][halo lane][pair]: (blank, label)
+    int2 tag[kRing][kHalo2Lanes];             // (the lane's frame, number of the hand-over)
+};
+constexpr size_t kHaloWaveBytes = sizeof(HaloWave) > sizeof(Halo2Wave) ? sizeof(HaloWave) : sizeof(Halo2Wave);
+static_assert(sizeof(HaloHeader) % 16 == 0 && kHaloWaveBytes % 16 == 0, "the blocks hold 16-byte entries");
+// Bytes of dynamic LDS of a lattice launch whose workgroups have `waves` wavefronts.
+constexpr size_t halo_lds_bytes(int waves) { return sizeof(HaloHeader) + static_cast<size_t>(waves) * kHaloWaveBytes; }
+template <typename Wave>
+__device__ __forceinline__ Wave* halo_wave(void* lds, int wave)
+{
+    return reinterpret_cast<Wave*>(static_cast<char*>(lds) + sizeof(HaloHeader) + static_cast<size_t>(wave) * kHaloWaveBytes);
+}
+
 
 // One chain = one direction of one utterance.  A lane owns the pair
 //   forward : (blank state 2j,       label j        = state 2j+1)
@@ -866,8 +890,11 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
         xp += xstride;
     };
 
-    HaloLds* const hl = static_cast<HaloLds*>(lds);
+    HaloHeader* const hl = static_cast<HaloHeader*>(lds);
     const int last_wave = m.waves - 1;
+    HaloWave* const mine_lds = halo_wave<HaloWave>(lds, wave);
+    HaloWave* const below_lds = halo_wave<HaloWave>(lds, wave > 0 ? wave - 1 : 0);
+    HaloWave* const above_lds = halo_wave<HaloWave>(lds, wave < last_wave ? wave + 1 : wave);
     int budget = m.poll_budget;                          // polls left before this wavefront gives up waiting
     bool lost = false;                                   // it did give up: what it computed since is not to be trusted
     // Hand-overs fall on chunk boundaries (the halo is a multiple of kChunk), so the step
@@ -879,13 +906,13 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     // (halo <= 32), so a producer may run one hand-over ahead of its consumer.
     int half = 0;                                        // entry offset of the half in use: 0 or 32
     double2* const wr_base = (kSync == Sync::kHalo)
-        ? &hl->data[wave][lane >= 64 - halo ? lane - (64 - halo) : 0] : nullptr;
+        ? &mine_lds->data[lane >= 64 - halo ? lane - (64 - halo) : 0] : nullptr;
     const double2* const rd_base = (kSync == Sync::kHalo)
-        ? &hl->data[wave > 0 ? wave - 1 : 0][lane < halo ? lane : 0] : nullptr;
-    int* const my_ready = &hl->ready[wave];
-    int* const my_done = &hl->done[wave];
-    int* const up_done = &hl->done[wave < 15 ? wave + 1 : 15];
-    int* const low_ready = &hl->ready[wave > 0 ? wave - 1 : 0];
+        ? &below_lds->data[lane < halo ? lane : 0] : nullptr;
+    int* const my_ready = &mine_lds->ready;
+    int* const my_done = &mine_lds->done;
+    int* const up_done = &above_lds->done;
+    int* const low_ready = &below_lds->ready;
 
     double i_blank = (j == 0) ? 0.0 : kNeg;
     double i_label = (j == 0 && has_label) ? 0.0 : kNeg;
@@ -1118,8 +1145,6 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
 // (pack_state).  The gradient kernels do not know which kind of chain wrote the lattice.
 constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real one, far from int32's ends
 
-constexpr int kRing = 4;                  // hand-overs a boundary's buffer holds (two pairs per lane)
-
 template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
                                                  const float* __restrict__ emit_blank,
@@ -1160,8 +1185,11 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     int* xp = stores ? out_exponents + m.ab_off + li + 1 : reinterpret_cast<int*>(sink);
     const int64_t xstride = stores ? lattice_pitch(L) : 0;
 
-    HaloLds* const hl = static_cast<HaloLds*>(lds);
+    HaloHeader* const hl = static_cast<HaloHeader*>(lds);
     const int last_wave = m.waves - 1;
+    HaloWave* const mine_lds = halo_wave<HaloWave>(lds, wave);
+    HaloWave* const below_lds = halo_wave<HaloWave>(lds, wave > 0 ? wave - 1 : 0);
+    HaloWave* const above_lds = halo_wave<HaloWave>(lds, wave < last_wave ? wave + 1 : wave);
     int budget = m.poll_budget;
     bool lost = false;
     const int chunks_per_hand_over = halo / kChunk;
@@ -1170,14 +1198,14 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     int half = 0;
     const int wr_slot = lane >= 64 - halo ? lane - (64 - halo) : 0;
     const int rd_slot = lane < halo ? lane : 0;
-    double2* const wr_base = (kSync == Sync::kHalo) ? &hl->data[wave][wr_slot] : nullptr;
-    const double2* const rd_base = (kSync == Sync::kHalo) ? &hl->data[wave > 0 ? wave - 1 : 0][rd_slot] : nullptr;
-    int* const wr_frame = (kSync == Sync::kHalo) ? &hl->frame[wave][wr_slot] : nullptr;
-    const int* const rd_frame = (kSync == Sync::kHalo) ? &hl->frame[wave > 0 ? wave - 1 : 0][rd_slot] : nullptr;
-    int* const my_ready = &hl->ready[wave];
-    int* const my_done = &hl->done[wave];
-    int* const up_done = &hl->done[wave < 15 ? wave + 1 : 15];
-    int* const low_ready = &hl->ready[wave > 0 ? wave - 1 : 0];
+    double2* const wr_base = (kSync == Sync::kHalo) ? &mine_lds->data[wr_slot] : nullptr;
+    const double2* const rd_base = (kSync == Sync::kHalo) ? &below_lds->data[rd_slot] : nullptr;
+    int* const wr_frame = (kSync == Sync::kHalo) ? &mine_lds->frame[wr_slot] : nullptr;
+    const int* const rd_frame = (kSync == Sync::kHalo) ? &below_lds->frame[rd_slot] : nullptr;
+    int* const my_ready = &mine_lds->ready;
+    int* const my_done = &mine_lds->done;
+    int* const up_done = &above_lds->done;
+    int* const low_ready = &below_lds->ready;
 
     double i_blank = (j == 0) ? 1.0 : 0.0;
     double i_label = (j == 0 && has_label) ? 1.0 : 0.0;
@@ -1390,16 +1418,6 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
 // The two label states of a lane are neighbours in the lattice row and go out in one 16-byte
 // store; where pair B has no label state (the lane of the last pair) its half falls on one of
 // the row's two unused columns.
-constexpr int kHalo2Lanes = 16;           // most halo lanes plan_waves2 asks for
-
-struct Halo2Lds {
-    double2 data[16][kRing][kHalo2Lanes][2];  // [wavefront][hand-over mod kRing][halo lane][pair]: (blank, label)
-    int2 tag[16][kRing][kHalo2Lanes];         // (the lane's frame, number of the hand-over)
-    int finished;                     // cost-only chains, as in HaloLds
-    int gave_up;
-    float cost;
-};
-
 struct alignas(4) LabelStatePair { uint32_t lo, hi; };   // two neighbouring columns of a lattice row
 struct alignas(4) ExponentPair { int lo, hi; };
 
@@ -1449,7 +1467,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     int* xp = stores ? out_exponents + m.ab_off + first_column : reinterpret_cast<int*>(sink);
     const int64_t xstride = stores ? pitch : 0;
 
-    Halo2Lds* const hl = static_cast<Halo2Lds*>(lds);
+    HaloHeader* const hl = static_cast<HaloHeader*>(lds);
     const int last_wave = waves - 1;
     int budget = m.poll_budget;
     bool lost = false;
@@ -1458,7 +1476,9 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     int generation = 0;
     const int wr_slot = (halo > 0 && lane >= 64 - halo) ? lane - (64 - halo) : 0;
     const int rd_slot = lane < halo ? lane : 0;
-    const int below = wave > 0 ? wave - 1 : 0, above = wave < 15 ? wave + 1 : 15;
+    Halo2Wave* const mine_lds = halo_wave<Halo2Wave>(lds, wave);
+    Halo2Wave* const below_lds = halo_wave<Halo2Wave>(lds, wave > 0 ? wave - 1 : 0);
+    Halo2Wave* const above_lds = halo_wave<Halo2Wave>(lds, wave < last_wave ? wave + 1 : wave);
 
     double ia_blank = (ja == 0) ? 1.0 : 0.0, ia_label = (ja == 0 && has_a) ? 1.0 : 0.0;
     double ib_blank = 0.0, ib_label = 0.0;
@@ -1498,8 +1518,8 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         ++generation;
         const int half = generation & (kRing - 1);
         if (wave > 0) {
-            const int2* const tag = &hl->tag[below][half][rd_slot];
-            const double2* const data = &hl->data[below][half][rd_slot][0];
+            const int2* const tag = &below_lds->tag[half][rd_slot];
+            const double2* const data = &below_lds->data[half][rd_slot][0];
             int2 t = read_tag(tag);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             double2 a = data[0], b = data[1];
@@ -1528,20 +1548,20 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             if (__builtin_expect(seen < generation - kRing, 0)) {
                 while (seen < generation - kRing && budget > 0) {
                     --budget;
-                    seen = uniform(generation_of(&hl->tag[above][half][0]));
+                    seen = uniform(generation_of(&above_lds->tag[half][0]));
                 }
                 lost = lost || seen < generation - kRing;
             }
             if (lane >= 64 - halo) {
-                hl->data[wave][half][wr_slot][0] = make_double2(va_blank, va_label);
-                hl->data[wave][half][wr_slot][1] = make_double2(vb_blank, vb_label);
+                mine_lds->data[half][wr_slot][0] = make_double2(va_blank, va_label);
+                mine_lds->data[half][wr_slot][1] = make_double2(vb_blank, vb_label);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                write_tag(&hl->tag[wave][half][wr_slot], frame, generation);
+                write_tag(&mine_lds->tag[half][wr_slot], frame, generation);
             }
-            above_seen = generation_of(&hl->tag[above][(half + 1) & (kRing - 1)][0]);
+            above_seen = generation_of(&above_lds->tag[(half + 1) & (kRing - 1)][0]);
         } else if (wave > 0) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            if (lane == 0) write_tag(&hl->tag[wave][half][0], 0, generation);
+            if (lane == 0) write_tag(&mine_lds->tag[half][0], 0, generation);
         }
     };
 
@@ -1718,24 +1738,19 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
     const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves;
     if (kSync == Sync::kHalo) {
         // the exchange buffer in use starts with every counter and hand-over number at zero
+        // (every wavefront of the workgroup clears its own block, whether it takes part or not)
+        HaloHeader* hl = static_cast<HaloHeader*>(lds);
         if (two_pairs) {
-            Halo2Lds* hl = static_cast<Halo2Lds*>(lds);
-            int* tags = reinterpret_cast<int*>(&hl->tag[0][0][0]);
-            for (int i = threadIdx.x; i < 16 * kRing * kHalo2Lanes * 2; i += blockDim.x) tags[i] = 0;
-            if (threadIdx.x == 0) {
-                hl->finished = 0;
-                hl->gave_up = 0;
-            }
-        } else {
-            HaloLds* hl = static_cast<HaloLds*>(lds);
-            if (threadIdx.x < 16) {
-                hl->ready[threadIdx.x] = 0;
-                hl->done[threadIdx.x] = 0;
-            }
-            if (threadIdx.x == 0) {
-                hl->finished = 0;
-                hl->gave_up = 0;
-            }
+            int* tags = reinterpret_cast<int*>(&halo_wave<Halo2Wave>(lds, threadIdx.x >> 6)->tag[0][0]);
+            for (int i = threadIdx.x & 63; i < kRing * kHalo2Lanes * 2; i += 64) tags[i] = 0;
+        } else if ((threadIdx.x & 63) == 0) {
+            HaloWave* w = halo_wave<HaloWave>(lds, threadIdx.x >> 6);
+            w->ready = 0;
+            w->done = 0;
+        }
+        if (threadIdx.x == 0) {
+            hl->finished = 0;
+            hl->gave_up = 0;
         }
         __syncthreads();
         if (idle) return;
@@ -1800,9 +1815,9 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         double* __restrict__ logp, float* __restrict__ costs,
                         int* __restrict__ chain_err, uint32_t* __restrict__ sink)
 {
-    __shared__ union { HaloLds one; Halo2Lds two; } halo_lds;      // one pair per lane, or two
+    extern __shared__ double2 halo_lds[];                    // halo_lds_bytes(wavefronts of the workgroup)
     lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
-                                              costs, chain_err, sink, &halo_lds);
+                                              costs, chain_err, sink, halo_lds);
 }
 
 // Labels too long to leave room for a halo (more than 16 * 63 pairs): 64 pairs per wavefront
@@ -2401,9 +2416,10 @@ int launch_lattice(const Launch& p, void* stream)
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
     const dim3 grid(p.n_chains), block(64 * p.max_waves);
+    const size_t lds_bytes = (p.max_waves > 1 && !p.needs_barrier) ? halo_lds_bytes(p.max_waves) : 0;
     auto s = static_cast<hipStream_t>(stream);
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
-    hipLaunchKernelGGL(KERNEL, grid, block, 0, s, meta, order, labels, emit_blank, emit_label,     \
+    hipLaunchKernelGGL(KERNEL, grid, block, lds_bytes, s, meta, order, labels, emit_blank, emit_label,     \
                        lat, logp, p.costs, chain_err, sink)
     // The emission layout is the launch's (emission_layout), and a template parameter of the kernels.
     const bool symbol_major = emission_layout(p.A) == kEmitSymbolMajor;
