@@ -141,6 +141,9 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct minibatches rotated through")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap", type=int, default=-1,
+                    help="0: write the whole gradient in a launch of its own even where the lattice launch has idle "
+                         "compute units; 1..100: ctc_debug_set_overlap; default: the library's setting")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (reference for HBM counters)")
     args = ap.parse_args()
@@ -172,6 +175,8 @@ def main():
                           "copy_GBps_read_plus_write": round(2 * n / (ms * 1e-3) / 1e9, 1)}), flush=True)
         return
     ctc.load()
+    if args.overlap >= 0:
+        ctc.debug_set_overlap(args.overlap)
     dtype = ctc.DTYPE_F32 if args.dtype == "f32" else ctc.DTYPE_BF16
     elem = 4 if dtype == ctc.DTYPE_F32 else 2
 

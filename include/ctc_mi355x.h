@@ -319,6 +319,18 @@ int ctc_last_hip_error(void);
  */
 void ctc_debug_set_poll_budget(int polls);
 
+/*
+ * Diagnostics.  Where a call's recursions leave compute units idle (fewer chains than three
+ * quarters of the compute units, alphabets of at most 64 symbols), the gradient rows of the
+ * utterances whose chains end early are written inside the recursions' launch, as soon as both
+ * chains of an utterance have ended, and the gradient launch that follows only writes the rest.
+ * `percent`: 0 switches that off for calls made afterwards, process-wide (for measurements of the
+ * two forms side by side); 1..100 sets the share of the launch's expected duration within which an
+ * utterance's chains must end for its rows to be written that way; negative restores the default.
+ * Results are bitwise the same whatever the setting.
+ */
+void ctc_debug_set_overlap(int percent);
+
 /* Diagnostics: how many times the library has allocated pinned host memory so far in this
  * process (all devices).  1 after the first host-metadata call on one device, and still 1 after
  * any number of further calls that keep within 8 in flight and 256 KiB of metadata. */

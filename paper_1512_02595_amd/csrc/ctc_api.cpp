@@ -25,6 +25,10 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 std::atomic<int> g_poll_budget{kDefaultPollBudget};
+// Gradient rows inside the lattice launch where it has idle compute units: 0 = never; otherwise the
+// percentage of the launch's expected duration up to which an utterance's chains must end for its rows
+// to be written by the launch's workers (the rest are written by the gradient launch that follows).
+std::atomic<int> g_overlap{kWorkerSharePercent};
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -64,12 +68,16 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.meta = off;   off += static_cast<size_t>(B) * sizeof(Utt);            // 64 B each: stays 8-byte aligned
     l.order = off;  off += static_cast<size_t>(B) * 2 * sizeof(int32_t);
     l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
+    l.tasks = off;  off += (static_cast<size_t>(B) * 6 + 1 + kXcds + 1) * sizeof(int32_t);
     l.upload_bytes = off;
     off = align_up(off);
     l.links = off;  off = align_up(off + static_cast<size_t>(sumL) * sizeof(int32_t));
     l.logp = off;   off = align_up(off + static_cast<size_t>(B) * sizeof(double));
     l.sink = off;   off = align_up(off + 256);
     l.chain_err = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
+    l.done = off;   off = align_up(off + static_cast<size_t>(B) * kDoneStride * sizeof(int32_t));
+    l.where = off;  off = align_up(off + static_cast<size_t>(B) * 2 * sizeof(int32_t));
+    l.leftover = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.lse = off;    off = align_up(off + static_cast<size_t>(B) * T * sizeof(float));
     l.emit_blank = off;
     off = align_up(off + (static_cast<size_t>(frames) + 2 * kBlankSlack) * sizeof(float));
@@ -357,6 +365,60 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     order_chains(running.data(), run_frames.data(), run_waves.data(), n_run, dirs, compute_units(), order);
     for (int i = n_run * dirs; i < 2 * c.B; ++i) order[i] = -1;
 
+    // Gradient rows inside the lattice launch (kTaskRows), where the launch leaves at least a quarter
+    // of the compute units without a chain.  (Narrow alphabets only: the workers run the gradient
+    // of ctc_gradient_narrow_kernel.)
+    const int n_cu = compute_units();
+    int32_t* const task_die = reinterpret_cast<int32_t*>(image + lay.tasks);     // [kXcds + 1]
+    int32_t* const task_prefix = task_die + kXcds + 1;                           // [2B + 1]
+    int32_t* const task_info = task_prefix + 2 * c.B + 1;                        // [2B]
+    int32_t* const task_first = task_info + 2 * c.B;                             // [2B]
+    int n_entries = 0, n_tasks = 0;
+    const int share_percent = g_overlap.load(std::memory_order_relaxed);
+    if (share_percent > 0 && c.mode == Mode::kGrad && c.A <= kDirectMaxA && !needs_barrier &&
+        n_run > 0 && 2 * c.B <= kMaxTaskEntries && n_cu % kXcds == 0 && n_run * dirs + n_cu / 4 <= n_cu) {
+        // The die of an utterance's chains: workgroup i runs on die i mod kXcds (order_chains puts an
+        // utterance's two chains a multiple of kXcds entries apart).
+        std::vector<int> die_of(static_cast<size_t>(c.B), 0);
+        for (int i = 0; i < n_run * dirs; ++i)
+            if ((order[i] & 1) == 0) die_of[static_cast<size_t>(order[i] >> 1)] = i % kXcds;
+        // Chains end in the order of their frames, those that exchange between wavefronts a little later.
+        auto ends_at = [&](int b) { return meta[b].Tb * (chain_waves(b) > 1 ? 5 : 4); };
+        std::vector<int32_t> ending(running);
+        std::stable_sort(ending.begin(), ending.end(), [&](int a, int b) { return ends_at(a) < ends_at(b); });
+        const int last_end = ends_at(ending.back());
+        const int blocks = (c.T + kTaskRows - 1) / kTaskRows;
+        auto data_blocks = [&](int b) { return (meta[b].flags & kUttRuns) ? (meta[b].Tb + kTaskRows - 1) / kTaskRows : 0; };
+        auto add = [&](int info, int first, int count) {
+            if (count <= 0) return;
+            task_prefix[n_entries] = n_tasks;
+            task_info[n_entries] = info;
+            task_first[n_entries] = first;
+            ++n_entries;
+            n_tasks += count;
+        };
+        for (int die = 0; die < kXcds; ++die) {
+            task_die[die] = n_entries;
+            // what needs no lattice first (shared out over the dies by utterance number) ...
+            for (int b = die; b < c.B; b += kXcds) add(b | (kTaskRowsLog2 << kTaskRowsShift), data_blocks(b), blocks - data_blocks(b));
+            // ... then the die's utterances as their chains end; the last ones of the launch in small
+            // tasks, so that what is left when the last chain ends is spread over all the workers
+            // ... then the die's utterances as their chains end.  Those that end last are not worth waiting
+            // for inside the launch (what is left when the last chain ends is too little work for the
+            // workers' wavefronts to hide their memory latencies behind): the gradient launch takes them.
+            for (int b : ending) {
+                if (die_of[static_cast<size_t>(b)] != die) continue;
+                if (static_cast<int64_t>(ends_at(b)) * 100 > static_cast<int64_t>(last_end) * share_percent) {
+                    meta[b].flags |= kUttGradientLater;
+                    continue;
+                }
+                add(b | kTaskWaits | (kTaskRowsLog2 << kTaskRowsShift), 0, data_blocks(b));
+            }
+        }
+        task_die[kXcds] = n_entries;
+        task_prefix[n_entries] = n_tasks;
+    }
+
     if (c.ws_bytes < lay.total) return CTC_STATUS_WORKSPACE_TOO_SMALL;
 
     out->mode = c.mode;
@@ -380,6 +442,9 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->dev_status = nullptr;
     out->poll_budget = g_poll_budget.load(std::memory_order_relaxed);
     out->crowded = crowded;
+    out->n_tasks = n_tasks;
+    out->n_task_entries = n_entries;
+    out->n_cu = n_cu;
     out->lay = lay;
     return CTC_STATUS_SUCCESS;
 }
@@ -465,6 +530,8 @@ ctc_status_t run(const Call& c, float* kernel_ms)
     if (kernel_ms && !record(hipEventRecord(ev[1], s))) return CTC_STATUS_HIP_ERROR;
 
     // Cost-only calls end with the lattice launch.
+    // (Where the lattice launch carries the gradient rows itself, Launch::n_tasks, the gradient launch only
+    // looks for utterances that the workers had to leave to it.)
     int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {
         launch_softmax, launch_lattice,
         c.mode == Mode::kGrad ? launch_gradient : (c.mode == Mode::kLoss ? nullptr : launch_backtrace)};
@@ -543,6 +610,9 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.dev_input_lengths = input_lengths;
     p.dev_status = status;
     p.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
+    p.n_tasks = 0;                     // the queue of an overlapped launch is prepared on the host
+    p.n_task_entries = 0;
+    p.n_cu = 0;
     p.lay = lay;
     int (*const stages[4])(const Launch&, void*) = {
         launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : nullptr};
@@ -702,6 +772,11 @@ long ctc_debug_staging_allocations(void)
     long n = 0;
     for (const ctc::DeviceStaging* d : ctc::g_staging) n += d->allocations.load(std::memory_order_relaxed);
     return n;
+}
+
+void ctc_debug_set_overlap(int percent)
+{
+    ctc::g_overlap.store(percent < 0 ? ctc::kWorkerSharePercent : std::min(percent, 100), std::memory_order_relaxed);
 }
 
 void ctc_debug_set_poll_budget(int polls)

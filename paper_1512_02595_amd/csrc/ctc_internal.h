@@ -155,6 +155,9 @@ constexpr int kUttLogDomain = 4;
 // Linear-domain chains of this utterance give two neighbouring state pairs to every lane
 // (plan_waves2) instead of one (plan_waves): see two_pairs_per_lane.
 constexpr int kUttTwoPairs = 8;
+// Overlapped launches (kTaskRows): the utterance's gradient rows are written by the gradient launch,
+// not by the lattice launch's workers.
+constexpr int kUttGradientLater = 16;
 constexpr float kLinearMinLog2 = -100.0f;
 // Utterances of more frames than this run the log domain whatever their emissions: the lanes'
 // exponents, which fall by up to 100 per frame, must stay clear of kNoExponent and of int32's end.
@@ -228,6 +231,34 @@ inline void order_chains(const int32_t* utt, const int32_t* frames, const int32_
 // that leave no copy in the caches.  Measured on gfx950: 0.4 GB (512 utterances) 141 -> 104 us with
 // such loads, 53 MB (64 utterances) 14.9 -> 15.7 us.
 constexpr size_t kStreamingLatticeBytes = size_t(CTC_STREAMING_MB) << 20;
+
+// Gradient rows inside the lattice launch.  A launch with fewer chains than compute units leaves
+// the rest of the chip idle for as long as the longest chain runs, while the gradient of an
+// utterance could start the moment both of its chains have ended.  Such launches therefore carry
+// extra workgroups after the chains' ("workers") whose wavefronts share out a list of tasks: a task
+// is kTaskRows consecutive frames of one utterance.  The list holds first the tasks that need no
+// lattice (zero fill of padding frames and of utterances without an alignment), then the frames
+// of the utterances in the order in which their chains are expected to end; a wavefront whose
+// next task belongs to an utterance whose chains are still running waits for that utterance's
+// counter (bounded polling).  Chains are launched first, so they are resident before any worker:
+// a worker only ever waits for work that is running.
+// A worker reads an utterance's lattice out of the L2 of the die (XCD) that its chains ran on, so
+// the list has a section per die, for the workers of that die.
+// The list as the host prepares it (part of the metadata image): `entries` runs of tasks,
+//   die[d]      first entry of die d's section (die[kXcds] = entries)
+//   prefix[e]   number of tasks before entry e (prefix[entries] = all tasks)
+//   info[e]     utterance (low 16 bits); log2 of the rows per task; kTaskWaits if its chains must have ended
+//   first[e]    first block (of that many rows) of the run
+constexpr int kTaskRowsLog2 = 3, kTaskRows = 1 << kTaskRowsLog2;
+constexpr int kWorkerSharePercent = 80;     // utterances whose chains end in the last fifth of the launch are left to the gradient launch
+constexpr int kTaskRowsShift = 16;
+constexpr int kTaskWaits = 1 << 30;
+constexpr int kMaxTaskEntries = 256;        // two runs per utterance: overlapped launches have at most 128 utterances
+constexpr int kWorkerWavesPerCu = 16;       // worker wavefronts per idle compute unit (the chains' register budget allows 4 per SIMD)
+constexpr int kDoneStride = 64;             // ints between two utterances' counters: each in a 256-byte block of its own, so that
+                                            // the waiting for one utterance does not hit the memory channel of the others
+constexpr int kWherePolls = 256;            // polls before a worker stops asking where an utterance's chains run (they start within microseconds)
+constexpr int kWorkerPollBudget = 1 << 22;  // polls (each followed by a short sleep) before a worker gives an utterance up
 constexpr int kDefaultPollBudget = 1 << 22;   // enough for seconds of waiting: only a stuck neighbour exhausts it
 constexpr int kMaxBatch = 65535;         // utterances index the second grid dimension of the row kernels
 constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ranks in LDS
@@ -251,10 +282,14 @@ struct Layout {
     size_t order = 0;     // int32[2B]    the lattice launch's chains, one per workgroup: utterance * 2 + direction
                           //              (0 forward, 1 backward), -1 for a workgroup without one (order_chains)
     size_t labels = 0;    // int32[sumL]
+    size_t tasks = 0;     // int32[9 + 3 * 2B + 1]  the workers' tasks: die[9], prefix[2B + 1], info[2B], first[2B] (see kTaskRows)
     size_t links = 0;     // int32[sumL]  grouping of the label positions by symbol (slot, count, first)
     size_t logp = 0;      // double[B]    log2 of the alignment mass
     size_t sink = 0;      // 256 bytes that lanes with nothing to store may scribble on
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
+    size_t done = 0;      // int32[B * kDoneStride]  wavefronts of the utterance's chains that have ended (overlapped launches)
+    size_t where = 0;     // int32[2B]    1 + the die each chain's workgroup runs on
+    size_t leftover = 0;  // int32[B]     utterances whose rows a worker had to leave to the gradient launch
     size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits
     size_t emit_blank = 0; // float[slack + sum Tb + slack]  emission of blank per frame: the probability y, or
                            // log2 y (negative) where y < 2^kLinearMinLog2 (plain log2 y in launches for
@@ -315,6 +350,10 @@ struct Launch {
     int32_t* dev_status;
     int poll_budget;          // copied into every Utt record
     bool crowded;             // plan the chains for total work rather than latency (device planner)
+    // Gradient rows inside the lattice launch (kTaskRows): 0 tasks = a gradient launch of its own.
+    int n_tasks;
+    int n_task_entries;
+    int n_cu;                 // compute units of the device
     Layout lay;
 };
 

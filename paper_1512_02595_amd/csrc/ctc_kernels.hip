@@ -344,6 +344,9 @@ struct SetupArgs {
     int* links;
     float* costs;
     int* chain_err;
+    int* done;            // per utterance: wavefronts of its chains that have ended (overlapped launches)
+    int* where;           // per chain: the die it runs on
+    int* leftover;        // per utterance: rows left to the gradient launch
     float* log0;          // kEmissionConstants floats that lattice lanes without a label state read as their
                           // emission: probability 0 (linear-domain chains) and log 0 (log-domain chains)
     int* host_flag;       // pinned host word: receives flag_value once the upload has been consumed
@@ -389,6 +392,10 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
     if (part != 0) return;
     if (tid == 0) {
         sa.chain_err[b] = 0;
+        sa.done[b * kDoneStride] = 0;
+        sa.where[2 * b] = 0;
+        sa.where[2 * b + 1] = 0;
+        sa.leftover[b] = (m.flags & kUttGradientLater) ? 1 : 0;
         if (b == 0) {
             for (int i = 0; i < kEmissionConstants; ++i) sa.log0[i] = (i < kEmissionConstantRun) ? 0.0f : static_cast<float>(kNeg);
             // This launch follows the upload kernel on the stream, so the host may now reuse
@@ -667,6 +674,19 @@ __device__ __forceinline__ double pack_state(double in_frame, int frame)
 {
     return __hiloint2double(__double2hiint(in_frame), frame);
 }
+// Loads of what a chain has left for the gradient.  The gradient launch reads plainly.  A worker
+// of the lattice launch (gradient_worker) reads while other chains still run: its loads carry
+// device scope, so that the compute unit's own cache, which may hold a line from before the chain
+// wrote it, is passed by and the L2 answers, which chain and worker share (see gradient_worker).
+template <bool kCoherent, typename W>
+__device__ __forceinline__ W lattice_load(const W* p)
+{
+    if (kCoherent) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+template <typename W>
+__device__ __forceinline__ void lattice_store(W* p, W v) { *p = v; }
+
 // Exponent row of the state a chain reached at its step `step` (0 .. Tb-1; a forward chain's step
 // is the frame, a backward chain's Tb-1-frame).  Linear domain: the initial frame serves step 0 and
 // the first chunk (steps 1 .. kChunk), each later chunk has a row of its own.
@@ -885,8 +905,8 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
         uint32_t value;
         int exponent;
         split_log2(w, value, exponent);
-        *reinterpret_cast<uint32_t*>(op) = value;
-        *xp = exponent;
+        lattice_store(reinterpret_cast<uint32_t*>(op), value);
+        lattice_store(xp, exponent);
         xp += xstride;
     };
 
@@ -1099,7 +1119,7 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
                 costs[u] = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
             } else {
                 const double lp = lse2(v_blank, prev);
-                logp[u] = pack_log2(-lp);          // 1 / p
+                lattice_store(&logp[u], pack_log2(-lp));          // 1 / p
                 const float cost = (lp < -1.0e29) ? __builtin_inff() : static_cast<float>(-lp * kLn2);
                 if (kSync == Sync::kHalo && kMode == Mode::kLoss) hl->cost = cost;
                 else costs[u] = cost;
@@ -1123,7 +1143,7 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
             costs[u] = lost ? __uint_as_float(0x7FC00000u) : cost;
         }
     } else if (kSync == Sync::kHalo && lost && lane == 0) {
-        chain_err[u] = 1;
+        lattice_store(&chain_err[u], 1);
     }
 }
 
@@ -1295,7 +1315,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     auto finish_step = [&](float eb, float el) {
         v_blank = i_blank * static_cast<double>(eb);
         v_label = i_label * static_cast<double>(el);
-        if (kMode == Mode::kGrad) *op = static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label));
+        if (kMode == Mode::kGrad) lattice_store(op, static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label)));
         op += ostride;
     };
     auto end_chunk = [&]() {
@@ -1308,7 +1328,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         renew_frames();
         // the next chunk's exponent row
         xp += xstride;
-        if (kMode == Mode::kGrad) *xp = frame;
+        if (kMode == Mode::kGrad) lattice_store(xp, frame);
     };
     auto advance = [&](float eb, float el) {
         // The blank state sums its own value and the label of the pair before; the label state
@@ -1329,8 +1349,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         v_blank = i_blank * static_cast<double>(readlane(ebv, 0));
         v_label = i_label * static_cast<double>(el);
         if (kMode == Mode::kGrad) {
-            *op = static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label));
-            *xp = frame;                                 // exponent row 0: step 0 and the first chunk
+            lattice_store(op, static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label)));
+            lattice_store(xp, frame);                    // exponent row 0: step 0 and the first chunk
         }
         op += ostride;
     }
@@ -1382,7 +1402,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
             const int exponent = frame + __builtin_amdgcn_frexp_exp(p);
             const double l2 = static_cast<double>(exponent) +
                               static_cast<double>(fast_log2(static_cast<float>(mantissa)));
-            logp[u] = (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0;     // 1 / p
+            lattice_store(&logp[u], (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0);     // 1 / p
             const float cost = (p > 0.0) ? static_cast<float>(-l2 * kLn2) : __builtin_inff();
             if (kSync == Sync::kHalo && kMode == Mode::kLoss) hl->cost = cost;
             else costs[u] = cost;
@@ -1403,7 +1423,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
             costs[u] = any_lost ? __uint_as_float(0x7FC00000u) : cost;
         }
     } else if (kSync == Sync::kHalo && lost && lane == 0) {
-        chain_err[u] = 1;
+        lattice_store(&chain_err[u], 1);
     }
 }
 
@@ -1590,13 +1610,17 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         if (kMode == Mode::kGrad) {
             const uint32_t a = static_cast<uint32_t>(__double2hiint(kBackward ? ia_label : va_label));
             const uint32_t b = static_cast<uint32_t>(__double2hiint(kBackward ? ib_label : vb_label));
-            *reinterpret_cast<LabelStatePair*>(op) = kBackward ? LabelStatePair{b, a} : LabelStatePair{a, b};
+            // (one 8-byte word: b's value in the upper half when a's column comes first)
+            lattice_store(reinterpret_cast<unsigned long long*>(op),
+                          kBackward ? (static_cast<unsigned long long>(a) << 32) | b : (static_cast<unsigned long long>(b) << 32) | a);
         }
         op += ostride;
     };
     // both label states of the lane share its frame
     auto store_frame = [&]() {
-        if (kMode == Mode::kGrad) *reinterpret_cast<ExponentPair*>(xp) = ExponentPair{frame, frame};
+        if (kMode == Mode::kGrad)
+            lattice_store(reinterpret_cast<unsigned long long*>(xp),
+                          (static_cast<unsigned long long>(static_cast<unsigned>(frame)) << 32) | static_cast<unsigned>(frame));
     };
     auto finish_step = [&](float eb, float ela, float elb) {
         const double ebd = static_cast<double>(eb);
@@ -1679,7 +1703,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             const int exponent = frame + __builtin_amdgcn_frexp_exp(p);
             const double l2 = static_cast<double>(exponent) +
                               static_cast<double>(fast_log2(static_cast<float>(mantissa)));
-            logp[u] = (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0;     // 1 / p
+            lattice_store(&logp[u], (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0);     // 1 / p
             const float cost = (p > 0.0) ? static_cast<float>(-l2 * kLn2) : __builtin_inff();
             if (kMode == Mode::kLoss) hl->cost = cost;
             else costs[u] = cost;
@@ -1700,7 +1724,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             costs[u] = any_lost ? __uint_as_float(0x7FC00000u) : cost;
         }
     } else if (lost && lane == 0) {
-        chain_err[u] = 1;
+        lattice_store(&chain_err[u], 1);
     }
 }
 
@@ -1714,8 +1738,9 @@ struct LatticeOut {
     int* beta_exponents;
 };
 
+// Returns the utterance whose chain this wavefront has run to its end, -1 if it ran none.
 template <Sync kSync, Mode kMode, bool kSymbolMajor>
-__device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
+__device__ __forceinline__ int lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
                                              const float* __restrict__ emit_label,
@@ -1725,7 +1750,7 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
                                              void* lds)
 {
     const int chain = order[blockIdx.x];           // utterance * 2 + direction
-    if (chain < 0) return;              // device-planned batches launch a workgroup per utterance and direction, running or not
+    if (chain < 0) return -1;           // device-planned batches launch a workgroup per utterance and direction, running or not
     const int u = chain >> 1;
     const bool forward = kMode != Mode::kGrad || (chain & 1) == 0;
     const Utt m = meta[u];
@@ -1753,14 +1778,14 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
             hl->gave_up = 0;
         }
         __syncthreads();
-        if (idle) return;
+        if (idle) return -1;
     } else if (kSync == Sync::kBarrier) {
         if (idle) {
             // Nothing to compute, but keep meeting the barriers of the working wavefronts:
             // one per recursion step, plus the forward chain's final exchange.
             const int barriers = (m.Tb - 1) + (forward ? 1 : 0);
             for (int i = 0; i < barriers; ++i) __syncthreads();
-            return;
+            return -1;
         }
     }
     if constexpr (kSync != Sync::kBarrier && kMode != Mode::kBest) {
@@ -1771,20 +1796,370 @@ __device__ __forceinline__ void lattice_body(const Utt* __restrict__ meta, const
                 else
                     run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
             }
-            return;
+            return u;
         }
         if (!in_log_domain) {
             if (forward)
                 run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
             else
                 run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
-            return;
+            return u;
         }
     }
     if (forward)
         run_chain_log<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
     else
         run_chain_log<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
+    return u;
+}
+
+// ---- gradient rows of narrow alphabets (shared by the gradient kernel and the lattice launch's workers) ----
+constexpr int kAhead = 4;             // 64-state pieces of a row requested together
+
+// The stored lattice of one utterance as the gradient kernels read it: the label states of frame t
+// are one row of alpha values, one of beta values, and the exponent rows that the two chains wrote
+// for the steps at which they reached that frame (exponent_row: alpha's step is t, beta's Tb-1-t).
+struct LatticeRow {
+    const uint32_t* a;
+    const int* ea;
+    const uint32_t* b;
+    const int* eb;
+};
+struct LatticeRows {
+    const uint32_t* a;
+    const int* ea;
+    const uint32_t* b;
+    const int* eb;
+    size_t pitch;
+    int Tb;
+    bool log_domain;
+    __device__ __forceinline__ LatticeRow at(int t) const
+    {
+        const size_t values = static_cast<size_t>(t) * pitch;
+        return {a + values, ea + static_cast<size_t>(exponent_row(t, log_domain)) * pitch,
+                b + values, eb + static_cast<size_t>(exponent_row(Tb - 1 - t, log_domain)) * pitch};
+    }
+};
+
+// The rows t_first, t_first + t_step, ... (below tend) of utterance b, by one wavefront: lane k is
+// symbol k (alphabets of at most 64 symbols).  s_slot, s_start, s_count: the grouping of the label's
+// positions as ctc_gradient_narrow_kernel describes it, in LDS; g_slot: L + 1 floats of LDS of this
+// wavefront's own.
+template <typename T, bool kStreaming, bool kCoherent>
+__device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T* __restrict__ grads, const Utt m,
+                                                     const int b, const LatticeOut lat,
+                                                     const float* __restrict__ lse, const double* __restrict__ logp,
+                                                     const int Tt, const int B, const int A, const int blank,
+                                                     const int t_first, const int t_step, const int tend,
+                                                     const int* s_slot, const int* s_start, const int* s_count,
+                                                     float* g_slot)
+{
+    const int lane = threadIdx.x & 63;
+    const bool runs = (m.flags & kUttRuns) != 0;
+    const int L = m.L;
+    const size_t pitch = static_cast<size_t>(lattice_pitch(L));
+    const double packed_inverse_p = runs ? lattice_load<kCoherent>(&logp[b]) : 0.0;
+    const float inverse_p = static_cast<float>(packed_inverse_p);
+    const int inverse_p_exponent = __double2loint(packed_inverse_p);
+    const bool log_domain = (m.flags & kUttLogDomain) != 0;  // decides where a row's exponents are (exponent_row)
+    const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
+                              lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
+                              pitch, m.Tb, log_domain};
+    // What a row needs from memory: the lattice words of its first kAhead * 64 label states
+    // (longer labels read the rest in line), its log-sum-exp and its activations.  A row's
+    // values are requested while the row before it is still being summed up out of LDS: by then
+    // the registers are free again (the shares are in LDS), so the overlap costs none.
+    struct RowData {
+        uint32_t a[kAhead], b[kAhead];
+        int ea[kAhead], eb[kAhead];
+        float l2, x0;
+    };
+    // Row addresses are kept as running pointers of this wavefront's rows (t_first, t_first + t_step,
+    // ...): the product (t x B + b) x A is formed once, not per row.
+    const float* next_lse = lse + static_cast<size_t>(b) * Tt + t_first;
+    const size_t row_step = static_cast<size_t>(t_step) * B * A;
+    const T* next_x = x + (static_cast<size_t>(t_first) * B + b) * A;
+    T* grow = grads + (static_cast<size_t>(t_first) * B + b) * A;                     // of the row being written
+    // A lattice larger than the caches is read once and never again: such launches read the values
+    // with loads that leave no copy behind (kStreaming), which keeps the caches for the rest (the
+    // exponent rows among it: eight frames share one).
+    auto value_word = [&](const uint32_t* p) {
+        return kCoherent ? lattice_load<true>(p) : (kStreaming ? __builtin_nontemporal_load(p) : *p);
+    };
+    auto exponent_word = [&](const int* p) { return lattice_load<kCoherent>(p); };
+    auto request = [&](int t, RowData& d) {
+        const LatticeRow row = rows_of.at(t);
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            if (u * 64 >= L) break;                      // (the same for every lane)
+            const int j = u * 64 + lane;
+            if (j < L) {
+                d.a[u] = value_word(row.a + j);
+                d.b[u] = value_word(row.b + j);
+                d.ea[u] = exponent_word(row.ea + j);
+                d.eb[u] = exponent_word(row.eb + j);
+            }
+        }
+        d.l2 = *next_lse;
+        d.x0 = (lane < A) ? load_elem(next_x, lane) : 0.0f;
+    };
+    auto advance_request = [&]() {
+        next_lse += t_step;
+        next_x += row_step;
+    };
+    RowData cur = {};
+    if (runs && t_first < tend && t_first < m.Tb) request(t_first, cur);
+    for (int t = t_first; t < tend; t += t_step, grow += row_step) {
+        if (t >= m.Tb || !runs) {
+            if (lane < A) store_elem(grow, lane, 0.0f);
+            continue;
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            if (u * 64 >= L) break;                      // (the same for every lane)
+            const int j = u * 64 + lane;
+            if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.ea[u], cur.b[u], cur.eb[u], inverse_p, inverse_p_exponent);
+        }
+        if (L > kAhead * 64) {
+            const LatticeRow row = rows_of.at(t);         // this row's states past the first kAhead * 64
+            for (int j = kAhead * 64 + lane; j < L; j += 64)
+                g_slot[s_slot[j]] = mass_share(value_word(row.a + j), exponent_word(row.ea + j), value_word(row.b + j), exponent_word(row.eb + j),
+                                               inverse_p, inverse_p_exponent);
+        }
+        const float l2 = cur.l2, x0 = cur.x0;
+        advance_request();
+        if (t + t_step < tend && t + t_step < m.Tb) request(t + t_step, cur);
+        // LDS operations of one wavefront complete in program order; the fences only keep the
+        // compiler from moving them across.
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // The shares now sit in slot order, the positions of a symbol next to each other: turn
+        // them into running sums (64 slots at a time, the total so far carried along), so that
+        // a symbol's occupancy is the difference of two entries and the blank's 1 minus the last.
+        float carried = 0.0f;
+        for (int base = 0; base < L; base += 64) {
+            const int slot = base + lane;
+            const float sum = wave_running_sum(slot < L ? g_slot[slot] : 0.0f) + carried;
+            if (slot < L) g_slot[slot] = sum;
+            carried = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sum), 63));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (lane < A) {
+            const int first = s_start[lane], count = s_count[lane];
+            float o = 0.0f;
+            if (count > 0) o = g_slot[first + count - 1] - (first > 0 ? g_slot[first - 1] : 0.0f);
+            if (lane == blank) o = 1.0f - carried;       // the blank states share what is left of 1
+            store_elem(grow, lane, fast_exp2(fmaf(x0, kLog2e, -l2)) - o);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+}
+
+// ---- gradient rows inside the lattice launch (kTaskRows in the launcher's header) ----------------
+// What the workgroups after the chains' get besides the chains' arguments.
+struct WorkerArgs {
+    const void* x;            // activations and gradient tensor, of type `dtype`
+    void* grads;
+    const int* links;
+    const float* lse;
+    const int* tasks;         // the list of tasks: die[kXcds + 1], prefix[2B + 1], info[2B], first[2B]
+    int* done;                // per utterance: wavefronts of its chains that have ended
+    int* where;               // per chain: 1 + the die its workgroup runs on
+    int* leftover;            // per utterance: set if a worker had to leave its rows to the gradient launch
+    int n_tasks;              // 0: the launch has no workers
+    int n_entries;
+    int n_chains;
+    int n_cu;
+    int rounds;               // the launch has rounds x n_cu workgroups; the first n_chains of every round do not work
+    int worker_waves;         // wavefronts of a working workgroup that have a piece of LDS to work in
+    int T, B, A, blank, Lmax;
+    int dtype;
+    int lds_ints;             // ints of dynamic LDS of the launch's workgroups
+};
+
+// The die (XCD) this wavefront runs on: each has an L2 of its own.
+__device__ __forceinline__ int this_xcd() { return static_cast<int>(__builtin_amdgcn_s_getreg(63508) & 15u); }   // XCC_ID, 32 bits
+
+// How a chain hands its lattice to the workers without a device-wide cache write-back (which,
+// with the matching invalidation on the workers' side, was measured to lengthen the running chains
+// by half): the L2 of a die is the point at which all its compute units agree, a chain's stores are
+// complete once that L2 has them, and workgroups are dealt to the dies in turn, so that the workers
+// of a die can be given the utterances whose chains ran there.  A chain's first wavefront publishes
+// the die it finds itself on; a worker that finds itself on another die than both chains of an
+// utterance does not touch it and marks the utterance for the gradient launch that follows.
+__device__ __forceinline__ void chain_started(const WorkerArgs& wk, int chain)
+{
+    if (wk.n_tasks > 0 && threadIdx.x == 0)
+        __hip_atomic_store(&wk.where[chain], this_xcd() + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// A chain's wavefront has ended: once all its stores have completed (the L2 has them), the
+// utterance's counter moves.
+__device__ __forceinline__ void chain_ended(const WorkerArgs& wk, int u)
+{
+    if (wk.n_tasks == 0 || u < 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // (waits for the stores; no cache operation)
+    __builtin_amdgcn_s_waitcnt(0);
+    if ((threadIdx.x & 63) == 0)
+        __hip_atomic_fetch_add(&wk.done[u * kDoneStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A workgroup after the chains'.  Its wavefronts work on their own: the tasks are dealt out in
+// turn over all working wavefronts of the launch (wavefront w takes tasks w, w + W, w + 2W, ...:
+// no shared counter, whose traffic was measured to slow the chains severalfold), so that the
+// tasks of the utterances that end last are spread over all of them.  For each task a wavefront
+// waits if the utterance still has chains running, stages the grouping of the utterance's label
+// in its own piece of LDS and writes the task's rows.  `lds` holds lds_ints ints: the list's table
+// for the workgroup, then a piece per wavefront.
+template <typename T>
+__device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* __restrict__ meta,
+                                                const int* __restrict__ labels, const LatticeOut lat,
+                                                const double* __restrict__ logp, const int* __restrict__ chain_err,
+                                                float* __restrict__ costs, int* lds, const int lds_ints,
+                                                const bool one_wave_chains)
+{
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int E = wk.n_entries, Lmax = wk.Lmax;
+    int* const s_die = lds;                       // [kXcds + 1]
+    int* const s_prefix = s_die + kXcds + 1;      // [E + 1]
+    int* const s_info = s_prefix + E + 1;         // [E]
+    int* const s_first = s_info + E;              // [E]
+    const int* const prefix_in = wk.tasks + kXcds + 1;
+    const int* const info_in = prefix_in + 2 * wk.B + 1;
+    const int* const first_in = info_in + 2 * wk.B;
+    for (int i = threadIdx.x; i <= kXcds; i += blockDim.x) s_die[i] = wk.tasks[i];
+    for (int i = threadIdx.x; i <= E; i += blockDim.x) s_prefix[i] = prefix_in[i];
+    for (int i = threadIdx.x; i < E; i += blockDim.x) {
+        s_info[i] = info_in[i];
+        s_first[i] = first_in[i];
+    }
+    __syncthreads();                              // the only barrier, before any wavefront waits for anything
+    const int table = kXcds + 1 + 3 * E + 1, piece = 2 * Lmax + 129;
+    if (wave >= wk.worker_waves || table + (wave + 1) * piece > lds_ints) return;
+    int* const s_slot = lds + table + wave * piece;   // [Lmax]  as in ctc_gradient_narrow_kernel
+    int* const s_start = s_slot + Lmax;               // [64]
+    int* const s_count = s_start + 64;                // [64]
+    float* const g_slot = reinterpret_cast<float*>(s_count + 64);   // [Lmax + 1]
+    const T* const x = static_cast<const T*>(wk.x);
+    T* const grads = static_cast<T*>(wk.grads);
+
+    // This workgroup's die as the dispatcher deals them out (workgroup i to die i mod kXcds; n_cu is a
+    // multiple of kXcds), its rank among the working workgroups of that die, and their number: of the
+    // places n_chains .. n_cu - 1 of a round, those congruent to the die.
+    const int round = static_cast<int>(blockIdx.x) / wk.n_cu, place = static_cast<int>(blockIdx.x) % wk.n_cu;
+    const int die = place % kXcds;
+    const int first_place = wk.n_chains + (die - wk.n_chains % kXcds + kXcds) % kXcds;
+    const int per_round = (wk.n_cu - first_place + kXcds - 1) / kXcds;
+    const int group = round * per_round + (place - first_place) / kXcds;
+    const int stride = wk.rounds * per_round * wk.worker_waves;
+    // the die's section of the list
+    const int e_first = s_die[die], e_end = s_die[die + 1];
+    const int ticket_first = s_prefix[e_first], ticket_end = s_prefix[e_end];
+    const int xcd = this_xcd();
+    int ready = -1;                               // the utterance whose chains this wavefront last found ended, here
+    int staged = -1;                              // the utterance whose label grouping sits in this wavefront's LDS
+    for (int ticket = ticket_first + wave * wk.rounds * per_round + group; ticket < ticket_end; ticket += stride) {
+        // the run of tasks the ticket falls into
+        int e = e_first;
+        for (int i0 = e_first; i0 < e_end; i0 += 64) {
+            const int i = i0 + lane;
+            e += __popcll(__ballot(i < e_end && s_prefix[i + 1] <= ticket));
+        }
+        const int info = s_info[e];
+        const int b = info & 0xFFFF, rows_log2 = (info >> kTaskRowsShift) & 15;
+        const int t0 = (s_first[e] + ticket - s_prefix[e]) << rows_log2;
+        const int tend = min(t0 + (1 << rows_log2), wk.T);
+        const Utt m = meta[b];
+        const bool runs = (m.flags & kUttRuns) != 0;
+        if (runs && t0 < m.Tb) {
+            if ((info & kTaskWaits) && b != ready) {
+                // Which die do the utterance's chains run on?  They publish it as they start, at most
+                // microseconds after this wavefront did.  Only if it is this die can the counter and the
+                // lattice be read here (the L2 they sit in is this die's); otherwise, or if the answer
+                // does not come (another die's store need not become visible here), the utterance is
+                // left to the gradient launch.
+                auto published = [&]() {
+                    int here = 0;
+                    if (lane == 0) {
+                        const int f = __hip_atomic_load(&wk.where[2 * b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const int r = __hip_atomic_load(&wk.where[2 * b + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        here = (f == 0 || r == 0) ? 0 : ((f == xcd + 1 && r == xcd + 1) ? 1 : 2);
+                    }
+                    return __builtin_amdgcn_readfirstlane(here);
+                };
+                int here = published();
+                for (int polls = kWherePolls; here == 0 && polls > 0; --polls) {
+                    __builtin_amdgcn_s_sleep(24);
+                    here = published();
+                }
+                if (here != 1) {
+                    if (lane == 0) wk.leftover[b] = 1;
+                    continue;
+                }
+                // both chains of the utterance, every wavefront of them (as lattice_body counts them)
+                const bool two_pairs = !one_wave_chains && (m.flags & (kUttLogDomain | kUttTwoPairs)) == kUttTwoPairs;
+                const int expected = 2 * (two_pairs ? m.waves2 : m.waves);
+                // (one lane asks; a sleep of some hundred nanoseconds between two questions)
+                int budget = kWorkerPollBudget;
+                auto ended_now = [&]() {
+                    int v = 0;
+                    if (lane == 0) v = __hip_atomic_load(&wk.done[b * kDoneStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    return __builtin_amdgcn_readfirstlane(v);
+                };
+                int ended = ended_now();
+                while (ended < expected && budget > 0) {
+                    __builtin_amdgcn_s_sleep(24);
+                    --budget;
+                    ended = ended_now();
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");    // (orders the loads below after the counter's)
+                if (ended < expected) {
+                    // (chains that never end: nothing of this task can be computed)
+                    if (lane == 0) costs[b] = __uint_as_float(0x7FC00000u);
+                    continue;
+                }
+                ready = b;
+            }
+            if (t0 == 0 && lane == 0 && lattice_load<true>(&chain_err[b]) != 0)
+                costs[b] = __uint_as_float(0x7FC00000u);
+            // the grouping of the label's positions, for this wavefront
+            if (b != staged) {
+            staged = b;
+            s_start[lane] = 0;
+            s_count[lane] = 0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            for (int j = lane; j < m.L; j += 64) {
+                const int link = wk.links[m.lab_off + j];
+                s_slot[j] = link & kLinkSlotMask;
+                if (link < 0) {
+                    const int c = labels[m.lab_off + j];
+                    s_start[c] = link & kLinkSlotMask;
+                    s_count[c] = (link >> kLinkCountShift) & kLinkSlotMask;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            }
+        }
+        narrow_gradient_rows<T, false, true>(x, grads, m, b, lat, wk.lse, logp, wk.T, wk.B, wk.A, wk.blank, t0, 1, tend,
+                                       s_slot, s_start, s_count, g_slot);
+    }
+}
+
+// Workgroups beyond the chains' are workers -- unless they would share a compute unit with a chain:
+// the dispatcher hands workgroup i to compute unit i mod n_cu (see order_chains), a chain's
+// wavefront needs its SIMD to itself, so the workgroups that would land there leave at once.
+__device__ __forceinline__ bool is_worker(const WorkerArgs& wk)
+{
+    return wk.n_tasks > 0 && static_cast<int>(blockIdx.x) >= wk.n_chains;
+}
+__device__ __forceinline__ void run_worker(const WorkerArgs& wk, const Utt* __restrict__ meta,
+                                           const int* __restrict__ labels, const LatticeOut lat,
+                                           const double* __restrict__ logp, const int* __restrict__ chain_err,
+                                           float* __restrict__ costs, int* lds, bool one_wave_chains)
+{
+    if (static_cast<int>(blockIdx.x % static_cast<unsigned>(wk.n_cu)) < wk.n_chains) return;
+    if (wk.dtype == CTC_DTYPE_F32)
+        gradient_worker<float>(wk, meta, labels, lat, logp, chain_err, costs, lds, wk.lds_ints, one_wave_chains);
+    else
+        gradient_worker<bf16_t>(wk, meta, labels, lat, logp, chain_err, costs, lds, wk.lds_ints, one_wave_chains);
 }
 
 // grid = one workgroup per entry of `order` (utterance * 2 + direction: 0 forward, 1 backward; only
@@ -1799,10 +2174,19 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
                            const float* __restrict__ emit_label,
                            const LatticeOut lat,
                            double* __restrict__ logp, float* __restrict__ costs,
-                           int* __restrict__ chain_err, uint32_t* __restrict__ sink)
+                           int* __restrict__ chain_err, uint32_t* __restrict__ sink, const WorkerArgs wk)
 {
-    lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
-                                              costs, chain_err, sink, nullptr);
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) {
+        if (is_worker(wk)) {
+            extern __shared__ int worker_lds[];
+            run_worker(wk, meta, labels, lat, logp, chain_err, costs, worker_lds, true);
+            return;
+        }
+    }
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_started(wk, order[blockIdx.x]);
+    const int u = lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
+                                                            costs, chain_err, sink, nullptr);
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, u);
 }
 
 // Multi-wavefront chains with the halo exchange.
@@ -1813,11 +2197,19 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
                         const float* __restrict__ emit_label,
                         const LatticeOut lat,
                         double* __restrict__ logp, float* __restrict__ costs,
-                        int* __restrict__ chain_err, uint32_t* __restrict__ sink)
+                        int* __restrict__ chain_err, uint32_t* __restrict__ sink, const WorkerArgs wk)
 {
     extern __shared__ double2 halo_lds[];                    // halo_lds_bytes(wavefronts of the workgroup)
-    lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
-                                              costs, chain_err, sink, halo_lds);
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) {
+        if (is_worker(wk)) {
+            run_worker(wk, meta, labels, lat, logp, chain_err, costs, reinterpret_cast<int*>(halo_lds), false);
+            return;
+        }
+    }
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_started(wk, order[blockIdx.x]);
+    const int u = lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
+                                                            costs, chain_err, sink, halo_lds);
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, u);
 }
 
 // Labels too long to leave room for a halo (more than 16 * 63 pairs): 64 pairs per wavefront
@@ -1829,7 +2221,7 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
                                 const float* __restrict__ emit_label,
                                 const LatticeOut lat,
                                 double* __restrict__ logp, float* __restrict__ costs,
-                                int* __restrict__ chain_err, uint32_t* __restrict__ sink)
+                                int* __restrict__ chain_err, uint32_t* __restrict__ sink, const WorkerArgs)
 {
     __shared__ double xch[2][16];
     lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
@@ -1919,33 +2311,6 @@ void ctc_backtrace_kernel(const Utt* __restrict__ meta, const unsigned char* __r
 //   sparse (wider):     the dense part of the row was written by the softmax launch; only the
 //          label columns and the blank column are rewritten (no A-bin histogram).
 // Dynamic LDS: 2 * L_max ints + 4 * (L_max + 1 + (dense ? A : 0)) floats.
-
-constexpr int kAhead = 4;             // 64-state pieces of a row requested together
-
-// The stored lattice of one utterance as the gradient kernels read it: the label states of frame t
-// are one row of alpha values, one of beta values, and the exponent rows that the two chains wrote
-// for the steps at which they reached that frame (exponent_row: alpha's step is t, beta's Tb-1-t).
-struct LatticeRow {
-    const uint32_t* a;
-    const int* ea;
-    const uint32_t* b;
-    const int* eb;
-};
-struct LatticeRows {
-    const uint32_t* a;
-    const int* ea;
-    const uint32_t* b;
-    const int* eb;
-    size_t pitch;
-    int Tb;
-    bool log_domain;
-    __device__ __forceinline__ LatticeRow at(int t) const
-    {
-        const size_t values = static_cast<size_t>(t) * pitch;
-        return {a + values, ea + static_cast<size_t>(exponent_row(t, log_domain)) * pitch,
-                b + values, eb + static_cast<size_t>(exponent_row(Tb - 1 - t, log_domain)) * pitch};
-    }
-};
 
 template <typename T, bool kSparse>
 __global__ __launch_bounds__(kRowThreads)
@@ -2149,13 +2514,15 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
                                 const LatticeOut lat,
                                 const double* __restrict__ logp, const int* __restrict__ chain_err,
                                 float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
-                                int rows_per_group)
+                                int rows_per_group, const int* __restrict__ only_marked)
 {
+    // After a lattice launch whose workers have written the gradient: only the utterances they left.
+    if (only_marked && only_marked[blockIdx.y] == 0) return;
     extern __shared__ int g_lds[];
     int* s_slot = g_lds;                         // [Lmax]  slot of each label position
     int* s_start = g_lds + Lmax;                 // [64]    first slot of each symbol's run
     int* s_count = s_start + 64;                 // [64]    length of the run (0: symbol not in the label)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, wave = tid >> 6;
     float* g_slot = reinterpret_cast<float*>(s_count + 64) + wave * (Lmax + 1);   // mass shares in slot order
     const int b = blockIdx.y, t0 = blockIdx.x * rows_per_group;
     const Utt m = meta[b];
@@ -2179,100 +2546,8 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         __syncthreads();
     }
-    const size_t pitch = static_cast<size_t>(lattice_pitch(L));
-    const double packed_inverse_p = runs ? logp[b] : 0.0;
-    const float inverse_p = static_cast<float>(packed_inverse_p);
-    const int inverse_p_exponent = __double2loint(packed_inverse_p);
-    const int tend = min(t0 + rows_per_group, Tt);
-    const bool log_domain = (m.flags & kUttLogDomain) != 0;  // decides where a row's exponents are (exponent_row)
-    const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
-                              lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
-                              pitch, m.Tb, log_domain};
-    // What a row needs from memory: the lattice words of its first kAhead * 64 label states
-    // (longer labels read the rest in line), its log-sum-exp and its activations.  A row's
-    // values are requested while the row before it is still being summed up out of LDS: by then
-    // the registers are free again (the shares are in LDS), so the overlap costs none.
-    struct RowData {
-        uint32_t a[kAhead], b[kAhead];
-        int ea[kAhead], eb[kAhead];
-        float l2, x0;
-    };
-    // Row addresses are kept as running pointers of this wavefront's rows (t_first, t_first + 4,
-    // ...): the product (t x B + b) x A is formed once, not per row.
-    const int t_first = t0 + wave;
-    const float* next_lse = lse + static_cast<size_t>(b) * Tt + t_first;
-    const size_t row_step = static_cast<size_t>(4) * B * A;
-    const T* next_x = x + (static_cast<size_t>(t_first) * B + b) * A;
-    T* grow = grads + (static_cast<size_t>(t_first) * B + b) * A;                     // of the row being written
-    // A lattice larger than the caches is read once and never again: such launches read the values
-    // with loads that leave no copy behind (kStreaming), which keeps the caches for the rest (the
-    // exponent rows among it: eight frames share one).
-    auto value_word = [&](const uint32_t* p) { return kStreaming ? __builtin_nontemporal_load(p) : *p; };
-    auto request = [&](int t, RowData& d) {
-        const LatticeRow row = rows_of.at(t);
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            if (u * 64 >= L) break;                      // (the same for every lane)
-            const int j = u * 64 + lane;
-            if (j < L) {
-                d.a[u] = value_word(row.a + j);
-                d.b[u] = value_word(row.b + j);
-                d.ea[u] = row.ea[j];
-                d.eb[u] = row.eb[j];
-            }
-        }
-        d.l2 = *next_lse;
-        d.x0 = (lane < A) ? load_elem(next_x, lane) : 0.0f;
-    };
-    auto advance_request = [&]() {
-        next_lse += 4;
-        next_x += row_step;
-    };
-    RowData cur = {};
-    if (runs && t_first < tend && t_first < m.Tb) request(t_first, cur);
-    for (int t = t_first; t < tend; t += 4, grow += row_step) {
-        if (t >= m.Tb || !runs) {
-            if (lane < A) store_elem(grow, lane, 0.0f);
-            continue;
-        }
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            if (u * 64 >= L) break;                      // (the same for every lane)
-            const int j = u * 64 + lane;
-            if (j < L) g_slot[s_slot[j]] = mass_share(cur.a[u], cur.ea[u], cur.b[u], cur.eb[u], inverse_p, inverse_p_exponent);
-        }
-        if (L > kAhead * 64) {
-            const LatticeRow row = rows_of.at(t);         // this row's states past the first kAhead * 64
-            for (int j = kAhead * 64 + lane; j < L; j += 64)
-                g_slot[s_slot[j]] = mass_share(value_word(row.a + j), row.ea[j], value_word(row.b + j), row.eb[j],
-                                               inverse_p, inverse_p_exponent);
-        }
-        const float l2 = cur.l2, x0 = cur.x0;
-        advance_request();
-        if (t + 4 < tend && t + 4 < m.Tb) request(t + 4, cur);
-        // LDS operations of one wavefront complete in program order; the fences only keep the
-        // compiler from moving them across.
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        // The shares now sit in slot order, the positions of a symbol next to each other: turn
-        // them into running sums (64 slots at a time, the total so far carried along), so that
-        // a symbol's occupancy is the difference of two entries and the blank's 1 minus the last.
-        float carried = 0.0f;
-        for (int base = 0; base < L; base += 64) {
-            const int slot = base + lane;
-            const float sum = wave_running_sum(slot < L ? g_slot[slot] : 0.0f) + carried;
-            if (slot < L) g_slot[slot] = sum;
-            carried = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sum), 63));
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (lane < A) {
-            const int first = s_start[lane], count = s_count[lane];
-            float o = 0.0f;
-            if (count > 0) o = g_slot[first + count - 1] - (first > 0 ? g_slot[first - 1] : 0.0f);
-            if (lane == blank) o = 1.0f - carried;       // the blank states share what is left of 1
-            store_elem(grow, lane, fast_exp2(fmaf(x0, kLog2e, -l2)) - o);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    }
+    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, Tt, B, A, blank, t0 + wave, 4,
+                                        min(t0 + rows_per_group, Tt), s_slot, s_start, s_count, g_slot);
 }
 
 template <typename F>
@@ -2333,7 +2608,9 @@ int launch_softmax(const Launch& p, void* stream)
     auto* emit_blank = reinterpret_cast<float*>(p.ws + p.lay.emit_blank);
     auto* emit_label = reinterpret_cast<float*>(p.ws + p.lay.emit_label);
     const SetupArgs sa{reinterpret_cast<int*>(p.ws + p.lay.links), p.costs,
-                       reinterpret_cast<int*>(p.ws + p.lay.chain_err), emit_label,
+                       reinterpret_cast<int*>(p.ws + p.lay.chain_err),
+                       reinterpret_cast<int*>(p.ws + p.lay.done), reinterpret_cast<int*>(p.ws + p.lay.where),
+                       reinterpret_cast<int*>(p.ws + p.lay.leftover), emit_label,
                        p.host_flag, p.host_flag_value, p.mode == Mode::kBest,
                        // few utterances: spread each one's grouping over several workgroups (its
                        // latency counts); many: one workgroup each keeps the chip busy already
@@ -2415,12 +2692,35 @@ int launch_lattice(const Launch& p, void* stream)
     const LatticeOut lat = lattice_blocks(p);
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
-    const dim3 grid(p.n_chains), block(64 * p.max_waves);
-    const size_t lds_bytes = (p.max_waves > 1 && !p.needs_barrier) ? halo_lds_bytes(p.max_waves) : 0;
+    size_t lds_bytes = (p.max_waves > 1 && !p.needs_barrier) ? halo_lds_bytes(p.max_waves) : 0;
+    // Workers (kTaskRows): as many workgroups per idle compute unit as make kWorkerWavesPerCu
+    // wavefronts, in rounds of n_cu workgroups whose first n_chains leave at once; their LDS holds
+    // the queue's table and a piece per wavefront.
+    int n_groups = p.n_chains;
+    WorkerArgs wk{};
+    if (p.n_tasks > 0) {
+        const size_t table = kXcds + 1 + 3 * static_cast<size_t>(p.n_task_entries) + 1, piece = 2 * static_cast<size_t>(p.max_label) + 129;
+        lds_bytes = std::min<size_t>(std::max(lds_bytes, (table + p.max_waves * piece) * 4), 64 << 10);
+        const int waves = static_cast<int>(std::min<size_t>(p.max_waves, (lds_bytes / 4 - table) / piece));
+        const int idle = p.n_cu - p.n_chains;
+        const int per_cu = std::max(1, kWorkerWavesPerCu / p.max_waves);
+        // no more workgroups than give every working wavefront a task
+        const int rounds = std::max(1, std::min(per_cu, (p.n_tasks + idle * waves - 1) / (idle * waves)));
+        n_groups = p.n_cu * rounds;
+        wk = WorkerArgs{p.x, p.grads, reinterpret_cast<const int*>(p.ws + p.lay.links),
+                        reinterpret_cast<const float*>(p.ws + p.lay.lse),
+                        reinterpret_cast<const int*>(p.ws + p.lay.tasks),
+                        reinterpret_cast<int*>(p.ws + p.lay.done), reinterpret_cast<int*>(p.ws + p.lay.where),
+                        reinterpret_cast<int*>(p.ws + p.lay.leftover),
+                        p.n_tasks, p.n_task_entries, p.n_chains, p.n_cu, rounds, waves,
+                        p.T, p.B, p.A, p.blank, p.max_label, static_cast<int>(p.dtype), static_cast<int>(lds_bytes / 4)
+        };
+    }
+    const dim3 grid(n_groups), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
     hipLaunchKernelGGL(KERNEL, grid, block, lds_bytes, s, meta, order, labels, emit_blank, emit_label,     \
-                       lat, logp, p.costs, chain_err, sink)
+                       lat, logp, p.costs, chain_err, sink, wk)
     // The emission layout is the launch's (emission_layout), and a template parameter of the kernels.
     const bool symbol_major = emission_layout(p.A) == kEmitSymbolMajor;
 #define CTC_LAUNCH_LATTICE_MODE(KERNEL, MODE)                                                       \
@@ -2484,7 +2784,7 @@ int launch_gradient(const Launch& p, void* stream)
     hipLaunchKernelGGL((ctc_gradient_narrow_kernel<TYPE, STREAMING>), grid, block, nlds, s,         \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,    \
                        links, lse, lat, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,           \
-                       Lmax, rows)
+                       Lmax, rows, p.n_tasks > 0 ? reinterpret_cast<const int*>(p.ws + p.lay.leftover) : nullptr)
         return checked_launch([&] {
             if (f32 && streaming) CTC_LAUNCH_NARROW(float, true);
             else if (f32) CTC_LAUNCH_NARROW(float, false);

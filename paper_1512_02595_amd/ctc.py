@@ -33,7 +33,7 @@ EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
            "ctc_workspace_size_device", "ctc_loss_and_grad_device", "ctc_loss_and_grad_device_static",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget",
-           "ctc_debug_staging_allocations")
+           "ctc_debug_staging_allocations", "ctc_debug_set_overlap")
 
 _lib = None
 
@@ -81,6 +81,8 @@ def load() -> ctypes.CDLL:
     lib.ctc_last_hip_error.argtypes = []
     lib.ctc_debug_set_poll_budget.restype = None
     lib.ctc_debug_set_poll_budget.argtypes = [ci]
+    lib.ctc_debug_set_overlap.restype = None
+    lib.ctc_debug_set_overlap.argtypes = [ci]
     lib.ctc_debug_staging_allocations.restype = ctypes.c_long
     lib.ctc_debug_staging_allocations.argtypes = []
     _lib = lib
@@ -234,3 +236,9 @@ def debug_set_poll_budget(polls: int) -> None:
 def debug_staging_allocations() -> int:
     """Pinned host allocations the library has made so far in this process."""
     return int(load().ctc_debug_staging_allocations())
+
+
+def debug_set_overlap(percent: int) -> None:
+    """Gradient rows inside the lattice launch where it leaves compute units idle: 0 off, 1..100 the
+    share of the launch within which an utterance's chains must end, negative the default."""
+    load().ctc_debug_set_overlap(int(percent))
