@@ -331,6 +331,26 @@ void ctc_debug_set_poll_budget(int polls);
  */
 void ctc_debug_set_overlap(int percent);
 
+/*
+ * Diagnostics, host only (no GPU is touched).  The recursions read their emissions several steps
+ * ahead and without bounds checks, up to three chunks past either end of an utterance's block;
+ * margins around the emission regions of the workspace are there to take those reads.  This
+ * function replays, on the host, every emission read that the chains of the given batch would
+ * make -- the very schedule and address arithmetic the kernels are built from -- against the
+ * workspace layout, and returns the number of reads outside their region (0 is the only acceptable
+ * answer), or -1 for arguments that ctc_workspace_size refuses.
+ *
+ *   max_label_length  negative: the layout of ctc_loss_and_grad (exact sizes); otherwise the layout
+ *                     of ctc_loss_and_grad_device for that bound
+ *   margin_floats     (host, may be NULL) receives the smallest distance, in floats, between a read
+ *                     and an end of its region
+ */
+long ctc_debug_replay_emission_fetches(int T, int B, int A,
+                                       const int32_t *label_lengths,
+                                       const int32_t *input_lengths,
+                                       int max_label_length,
+                                       long *margin_floats);
+
 /* Diagnostics: how many times the library has allocated pinned host memory so far in this
  * process (all devices).  1 after the first host-metadata call on one device, and still 1 after
  * any number of further calls that keep within 8 in flight and 256 KiB of metadata. */

@@ -774,6 +774,86 @@ long ctc_debug_staging_allocations(void)
     return n;
 }
 
+long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label_lengths, const int32_t* input_lengths,
+                                       int max_label_length, long* margin_floats)
+{
+    using namespace ctc;
+    if (!label_lengths || !input_lengths) return -1;
+    const bool bounds = max_label_length >= 0;
+    Layout lay;
+    const ctc_status_t st = bounds ? make_layout_bounds(T, B, A, max_label_length, CTC_DTYPE_F32, &lay)
+                                   : make_layout(T, B, A, label_lengths, input_lengths, CTC_DTYPE_F32, &lay);
+    if (st != CTC_STATUS_SUCCESS) return -1;
+    const bool symbol_major = emission_layout(A) == kEmitSymbolMajor;
+    // the regions as carved: slack, blocks, slack
+    const int64_t label_floats = lay.emit_floats + 2 * static_cast<int64_t>(kLabelSlack);
+    const int64_t blank_floats = lay.frames + 2 * static_cast<int64_t>(kBlankSlack);
+    long violations = 0;
+    int64_t margin = INT64_MAX;
+    auto touch = [&](int64_t off, int64_t size) {
+        if (off < 0 || off >= size) ++violations;
+        margin = std::min(margin, std::min(off, size - 1 - off));
+    };
+    int64_t e_off = 0, f_off = 0;
+    for (int b = 0; b < B; ++b) {
+        const int L = label_lengths[b], Tb = input_lengths[b];
+        // block offsets as the launcher (prepare) and the device-side planner (ctc_plan_kernel) set them
+        Utt m{};
+        m.Tb = Tb;
+        m.L = L;
+        m.e_direct = emission_layout(A);
+        if (bounds) {
+            m.f_off = b * T;
+            m.e_off = static_cast<int64_t>(b) * T * (symbol_major ? A : max_label_length);
+            m.e_pitch = symbol_major ? T : L;
+        } else {
+            m.f_off = static_cast<int32_t>(f_off);
+            m.e_off = e_off;
+            m.e_pitch = symbol_major ? Tb : L;
+            e_off += static_cast<int64_t>(Tb) * (symbol_major ? A : L);
+            f_off += Tb;
+        }
+        if (Tb < 1) continue;                       // its chains do not run
+        for (int backward = 0; backward < 2; ++backward) {
+            const int f0 = backward ? Tb - 1 : 0, fdir = backward ? -1 : 1;
+            // Lanes at the ends of every range a pointer depends on: first and last label position, first
+            // and last symbol; a lane without a label state, for either constant.
+            struct LaneKind { bool has_label; int symbol, li, constant; };
+            const LaneKind kinds[] = {{L > 0, 0, 0, 0}, {L > 0, A - 1, L - 1, 0}, {L > 0, 0, L - 1, 0}, {L > 0, A - 1, 0, 0},
+                                      {false, 0, 0, kZeroEmission}, {false, 0, 0, kLogZeroEmission}};
+            for (const LaneKind& k : kinds) {
+                if (!k.has_label && k.constant == 0) continue;          // (L == 0: no label lanes)
+                int64_t p = label_emission_offset(m, k.has_label, symbol_major, k.symbol, k.li, f0, k.constant);
+                const int64_t step = label_emission_step(m, k.has_label, symbol_major, fdir);
+                touch(p, label_floats);                                  // step 0
+                auto fetch = [&](int) {
+                    if (symbol_major) {
+                        touch(p + fetch_window_first(backward != 0), label_floats);
+                        touch(p + fetch_window_first(backward != 0) + kChunk - 1, label_floats);
+                        p += step * kChunk;
+                    } else {
+                        for (int i = 0; i < kChunk; ++i) {
+                            p += step;
+                            touch(p, label_floats);
+                        }
+                    }
+                };
+                auto nothing = [](int) {};
+                chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
+            }
+            for (int lane = 0; lane < kChunk; ++lane) {
+                const int64_t bp = blank_emission_offset(m, f0, fdir, lane);
+                touch(bp, blank_floats);                                  // step 0 (lane 0's is the one used)
+                auto fetch = [&](int s0) { touch(bp + static_cast<int64_t>(fdir) * s0, blank_floats); };
+                auto nothing = [](int) {};
+                chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
+            }
+        }
+    }
+    if (margin_floats) *margin_floats = margin == INT64_MAX ? -1 : static_cast<long>(margin);
+    return violations;
+}
+
 void ctc_debug_set_overlap(int percent)
 {
     ctc::g_overlap.store(percent < 0 ? ctc::kWorkerSharePercent : std::min(percent, 100), std::memory_order_relaxed);

@@ -273,6 +273,66 @@ constexpr int kOverFetchRows = 3 * kChunk;
 constexpr int kBlankSlack = kOverFetchRows + kChunk;                          // floats, each side
 constexpr int kLabelSlack = kOverFetchRows * (CTC_MAX_LABEL_LENGTH + 1);      // floats, each side
 
+// Constants that lanes without a label state read as their emission, at the start of the
+// label-emission region (inside its front slack): 20 floats of probability 0, then 20 of log 0.  Such
+// a lane points at entry 8 of its 20: a fetch reads the 8 floats before it or the 8 after it, the
+// first step the entry itself.
+constexpr int kEmissionConstantRun = 20;
+constexpr int kZeroEmission = 8, kLogZeroEmission = kEmissionConstantRun + 8, kEmissionConstants = 2 * kEmissionConstantRun;
+static_assert(kChunk <= 8 && kEmissionConstants <= kLabelSlack, "constants sit inside the front slack");
+
+// ---- where and when a chain reads its emissions -------------------------------------------------
+// Shared by the lattice kernels and by the host-side replay that checks every read against the
+// regions' bounds (ctc_debug_replay_emission_fetches): the kernels fetch ahead without bounds
+// checks, so what they may touch is defined here, once.  Offsets are in floats from the start of
+// the region (Layout::emit_label, Layout::emit_blank).
+
+// Pointer of a lane's label emissions before step 0: at the emission of its label state in frame
+// f0 (the chain's first frame), or at `constant` for a lane without a label state.  `symbol` is the
+// state's symbol (symbol-major blocks: a row per symbol), `li` its label position (gathered blocks).
+CTC_HOST_DEVICE inline int64_t label_emission_offset(const Utt& m, bool has_label, bool symbol_major, int symbol,
+                                                     int li, int f0, int constant)
+{
+    if (!has_label) return constant;
+    return kLabelSlack + m.e_off + (symbol_major ? static_cast<int64_t>(symbol) * m.e_pitch + f0
+                                                 : static_cast<int64_t>(f0) * m.e_pitch + li);
+}
+// The same pointer moves by this much per step (gathered blocks: one row; symbol-major: one float),
+// in the chain's direction fdir = +1 / -1; a lane without a label state stays where it is.
+CTC_HOST_DEVICE inline int64_t label_emission_step(const Utt& m, bool has_label, bool symbol_major, int fdir)
+{
+    return !has_label ? 0 : (symbol_major ? fdir : static_cast<int64_t>(fdir) * m.e_pitch);
+}
+// Pointer of a lane's blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
+CTC_HOST_DEVICE inline int64_t blank_emission_offset(const Utt& m, int f0, int fdir, int lane)
+{
+    return kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+}
+// One fetch out of a symbol-major block reads the kChunk floats next to the pointer p in the chain's
+// direction, p[first] .. p[first + kChunk - 1], and moves p on by kChunk steps.
+CTC_HOST_DEVICE constexpr int fetch_window_first(bool backward) { return backward ? -kChunk : 1; }
+
+// The order in which a chain requests (fetch) and consumes (run) the emissions of its steps
+// 1 .. Tb-1, kChunk steps at a time, in two register sets a and b; each callback gets the first
+// step of its chunk.  Step 0 is read directly before this.  The last requests reach up to
+// 3 * kChunk - 1 steps beyond the chain's end: what kOverFetchRows provides for.
+template <typename FetchA, typename FetchB, typename RunA, typename RunB, typename EndChunk>
+CTC_HOST_DEVICE inline void chain_schedule(int Tb, FetchA&& fetch_a, FetchB&& fetch_b, RunA&& run_a, RunB&& run_b,
+                                           EndChunk&& end_chunk)
+{
+    fetch_a(1);
+    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
+        fetch_b(s0 + kChunk);
+        run_a(s0);
+        end_chunk();
+        fetch_a(s0 + 2 * kChunk);
+        if (s0 + kChunk < Tb) {
+            run_b(s0 + kChunk);
+            end_chunk();
+        }
+    }
+}
+
 // Row pitch (8-byte words) of an utterance's lattice blocks: column 1 + i holds label state i.
 CTC_HOST_DEVICE inline int64_t lattice_pitch(int64_t L) { return L + 2; }
 

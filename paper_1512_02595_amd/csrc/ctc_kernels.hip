@@ -332,13 +332,8 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
 constexpr int kLinkSlotMask = 0x3FF, kLinkCountShift = 12;
 static_assert(CTC_MAX_LABEL_LENGTH <= kLinkSlotMask, "slot and count fields hold 10 bits");
 
-// Constants that lanes without a label state read as their emission, at the start of the
-// emission array (inside its slack): 20 floats of probability 0, then 20 of log 0.  Such a lane
-// points at entry 8 of its 20: a fetch reads the 8 floats before it or the 8 after it
-// (fetch_frames), the first step the entry itself.
-constexpr int kEmissionConstantRun = 20;
-constexpr int kZeroEmission = 8, kLogZeroEmission = kEmissionConstantRun + 8, kEmissionConstants = 2 * kEmissionConstantRun;
-static_assert(kChunk <= 8 && kEmissionConstants <= kLabelSlack, "constants sit inside the front slack");
+// (The constants that lanes without a label state read as their emission, kZeroEmission and
+// kLogZeroEmission, are laid out in the launcher's header, with the chains' fetch schedule.)
 
 struct SetupArgs {
     int* links;
@@ -764,8 +759,8 @@ static_assert(kChunk == 8, "fetch_frames loads two Float4");
 template <bool kBackward>
 __device__ __forceinline__ void fetch_frames(const float*& p, int advance, float (&el)[kChunk])
 {
-    const Float4 lo = *reinterpret_cast<const Float4*>(kBackward ? p - 8 : p + 1);
-    const Float4 hi = *reinterpret_cast<const Float4*>(kBackward ? p - 4 : p + 5);
+    const Float4 lo = *reinterpret_cast<const Float4*>(p + fetch_window_first(kBackward));
+    const Float4 hi = *reinterpret_cast<const Float4*>(p + fetch_window_first(kBackward) + 4);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         el[i] = kBackward ? hi.v[3 - i] : lo.v[i];
@@ -878,13 +873,11 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     // different numbers of loads under way, and the waits after the join would be the
     // cautious ones.)
     constexpr bool direct = kSymbolMajor;
-    const float* ep = !has_label ? emit_label + kLogZeroEmission
-                      : direct   ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(lab[li]) * m.e_pitch + f0
-                                 : emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch + li;
-    const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
-    const int eadvance = has_label ? fdir * kChunk : 0;
+    const float* ep = emit_label + label_emission_offset(m, has_label, direct, has_label ? lab[li] : 0, li, f0, kLogZeroEmission);
+    const int64_t estride = label_emission_step(m, has_label, false, fdir);
+    const int eadvance = static_cast<int>(label_emission_step(m, has_label, true, fdir)) * kChunk;
     // Blank emissions: lane i of a chunk's load takes the frame of step (chunk start + i % kChunk).
-    const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    const float* bp = emit_blank + blank_emission_offset(m, f0, fdir, lane);
     // Output: only the label state of each pair is kept (row pitch L+2 words, column = 1 + label
     // index, in both directions; value rows by frame, exponent rows by step: one per step in the
     // log domain); the gradient gets the blank's share as the complement.
@@ -1092,17 +1085,8 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
                 if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
         }
     };
-    fetch(el_a, eb_a, 1);
-    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
-        fetch(el_b, eb_b, s0 + kChunk);
-        run(el_a, eb_a, s0);
-        end_chunk();
-        fetch(el_a, eb_a, s0 + 2 * kChunk);
-        if (s0 + kChunk < Tb) {
-            run(el_b, eb_b, s0 + kChunk);
-            end_chunk();
-        }
-    }
+    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); }, [&](int s0) { fetch(el_b, eb_b, s0); },
+                   [&](int s0) { run(el_a, eb_a, s0); }, [&](int s0) { run(el_b, eb_b, s0); }, end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L-1.
@@ -1191,12 +1175,10 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     const int fdir = kBackward ? -1 : 1;
     // A lane without a label state reads a constant probability 0 and stays there.
     constexpr bool direct = kSymbolMajor;                // see run_chain_log
-    const float* ep = !has_label ? emit_label + kZeroEmission
-                      : direct   ? emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(lab[li]) * m.e_pitch + f0
-                                 : emit_label + kLabelSlack + m.e_off + static_cast<int64_t>(f0) * m.e_pitch + li;
-    const int64_t estride = has_label ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
-    const int eadvance = has_label ? fdir * kChunk : 0;
-    const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    const float* ep = emit_label + label_emission_offset(m, has_label, direct, has_label ? lab[li] : 0, li, f0, kZeroEmission);
+    const int64_t estride = label_emission_step(m, has_label, false, fdir);
+    const int eadvance = static_cast<int>(label_emission_step(m, has_label, true, fdir)) * kChunk;
+    const float* bp = emit_blank + blank_emission_offset(m, f0, fdir, lane);
     // Values by frame, exponents by chunk (exponent_row): the lane's frame is what it is until the
     // chunk ends.
     const bool stores = kMode == Mode::kGrad && active && has_label;
@@ -1379,17 +1361,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
                 if (s0 + i < Tb) advance(readlane(eb, i), el[i]);
         }
     };
-    fetch(el_a, eb_a, 1);
-    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
-        fetch(el_b, eb_b, s0 + kChunk);
-        run(el_a, eb_a, s0);
-        end_chunk();
-        fetch(el_a, eb_a, s0 + 2 * kChunk);
-        if (s0 + kChunk < Tb) {
-            run(el_b, eb_b, s0 + kChunk);
-            end_chunk();
-        }
-    }
+    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); }, [&](int s0) { fetch(el_b, eb_b, s0); },
+                   [&](int s0) { run(el_a, eb_a, s0); }, [&](int s0) { run(el_b, eb_b, s0); }, end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1), from the lane of pair L (exact, as is the
@@ -1469,14 +1442,14 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     const int f0 = kBackward ? (Tb - 1) : 0;
     const int fdir = kBackward ? -1 : 1;
     constexpr bool direct = kSymbolMajor;                // see run_chain_log
-    const float* const rows = emit_label + kLabelSlack + m.e_off + (direct ? f0 : static_cast<int64_t>(f0) * m.e_pitch);
     // A pair without a label state reads a constant probability 0 and stays there.
-    const float* epa = has_a ? rows + (direct ? static_cast<int64_t>(lab[lia]) * m.e_pitch : lia) : emit_label + kZeroEmission;
-    const float* epb = has_b ? rows + (direct ? static_cast<int64_t>(lab[lib]) * m.e_pitch : lib) : emit_label + kZeroEmission;
-    const int advance_a = has_a ? fdir * kChunk : 0, advance_b = has_b ? fdir * kChunk : 0;
-    const int64_t stride_a = has_a ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
-    const int64_t stride_b = has_b ? static_cast<int64_t>(fdir) * m.e_pitch : 0;
-    const float* bp = emit_blank + kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
+    const float* epa = emit_label + label_emission_offset(m, has_a, direct, has_a ? lab[lia] : 0, lia, f0, kZeroEmission);
+    const float* epb = emit_label + label_emission_offset(m, has_b, direct, has_b ? lab[lib] : 0, lib, f0, kZeroEmission);
+    const int advance_a = static_cast<int>(label_emission_step(m, has_a, true, fdir)) * kChunk;
+    const int advance_b = static_cast<int>(label_emission_step(m, has_b, true, fdir)) * kChunk;
+    const int64_t stride_a = label_emission_step(m, has_a, false, fdir);
+    const int64_t stride_b = label_emission_step(m, has_b, false, fdir);
+    const float* bp = emit_blank + blank_emission_offset(m, f0, fdir, lane);
     // Output: label state i sits in column 1 + i; the lane's two are columns 1 + min(lia, lib) and
     // the next one.  (has_a false: nothing of this lane is kept.)
     const bool stores = kMode == Mode::kGrad && active && has_a;
@@ -1681,17 +1654,8 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
                 if (s0 + i < Tb) advance(readlane(eb, i), ela[i], elb[i]);
         }
     };
-    fetch(ela_a, elb_a, eb_a, 1);
-    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
-        fetch(ela_b, elb_b, eb_b, s0 + kChunk);
-        run(ela_a, elb_a, eb_a, s0);
-        end_chunk();
-        fetch(ela_a, elb_a, eb_a, s0 + 2 * kChunk);
-        if (s0 + kChunk < Tb) {
-                run(ela_b, elb_b, eb_b, s0 + kChunk);
-            end_chunk();
-        }
-    }
+    chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, s0); }, [&](int s0) { fetch(ela_b, elb_b, eb_b, s0); },
+                   [&](int s0) { run(ela_a, elb_a, eb_a, s0); }, [&](int s0) { run(ela_b, elb_b, eb_b, s0); }, end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L - 1.

@@ -33,7 +33,7 @@ EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
            "ctc_workspace_size_device", "ctc_loss_and_grad_device", "ctc_loss_and_grad_device_static",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget",
-           "ctc_debug_staging_allocations", "ctc_debug_set_overlap")
+           "ctc_debug_staging_allocations", "ctc_debug_set_overlap", "ctc_debug_replay_emission_fetches")
 
 _lib = None
 
@@ -81,6 +81,8 @@ def load() -> ctypes.CDLL:
     lib.ctc_last_hip_error.argtypes = []
     lib.ctc_debug_set_poll_budget.restype = None
     lib.ctc_debug_set_poll_budget.argtypes = [ci]
+    lib.ctc_debug_replay_emission_fetches.restype = ctypes.c_long
+    lib.ctc_debug_replay_emission_fetches.argtypes = [ci, ci, ci, i32p, i32p, ci, ctypes.POINTER(ctypes.c_long)]
     lib.ctc_debug_set_overlap.restype = None
     lib.ctc_debug_set_overlap.argtypes = [ci]
     lib.ctc_debug_staging_allocations.restype = ctypes.c_long
@@ -242,3 +244,14 @@ def debug_set_overlap(percent: int) -> None:
     """Gradient rows inside the lattice launch where it leaves compute units idle: 0 off, 1..100 the
     share of the launch within which an utterance's chains must end, negative the default."""
     load().ctc_debug_set_overlap(int(percent))
+
+
+def debug_replay_emission_fetches(T, B, A, label_lengths, input_lengths, max_label_length=-1):
+    """(reads outside their region, smallest margin in floats) of the chains' emission fetch schedule,
+    replayed on the host against the workspace layout (host-metadata layout, or bounds layout)."""
+    _ll, llp = _i32(label_lengths)
+    _il, ilp = _i32(input_lengths)
+    margin = ctypes.c_long(0)
+    n = load().ctc_debug_replay_emission_fetches(int(T), int(B), int(A), llp, ilp, int(max_label_length),
+                                                 ctypes.byref(margin))
+    return int(n), int(margin.value)
