@@ -69,6 +69,7 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.order = off;  off += static_cast<size_t>(B) * 2 * sizeof(int32_t);
     l.labels = off; off += static_cast<size_t>(sumL) * sizeof(int32_t);
     l.tasks = off;  off += (static_cast<size_t>(B) * 6 + 1 + kXcds + 1) * sizeof(int32_t);
+    l.labels8 = off; off += (static_cast<size_t>(sumL) + 3) / 4 * 4;
     l.upload_bytes = off;
     off = align_up(off);
     l.links = off;  off = align_up(off + static_cast<size_t>(sumL) * sizeof(int32_t));
@@ -76,6 +77,9 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.sink = off;   off = align_up(off + 256);
     l.chain_err = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.done = off;   off = align_up(off + static_cast<size_t>(B) * kDoneStride * sizeof(int32_t));
+    l.domain = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
+    l.row_flags = off;
+    off = align_up(off + static_cast<size_t>(B) * ((T + kFlagFrames - 1) / kFlagFrames) * sizeof(int32_t));
     l.where = off;  off = align_up(off + static_cast<size_t>(B) * 2 * sizeof(int32_t));
     l.leftover = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.lse = off;    off = align_up(off + static_cast<size_t>(B) * T * sizeof(float));
@@ -288,6 +292,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     Utt* meta = reinterpret_cast<Utt*>(image + lay.meta);
     int32_t* order = reinterpret_cast<int32_t*>(image + lay.order);
     int32_t* labels = reinterpret_cast<int32_t*>(image + lay.labels);
+    uint8_t* labels8 = reinterpret_cast<uint8_t*>(image + lay.labels8);
 
     const bool symbol_major = emission_layout(c.A) == kEmitSymbolMajor;
     // Would the launch, planned for latency, put more than two wavefronts on every SIMD?
@@ -311,6 +316,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
             if (s < 0 || s >= c.A || s == c.blank) return CTC_STATUS_INVALID_VALUE;
             if (i > 0 && s == lab[i - 1]) ++repeats;
             labels[lab_off + i] = s;
+            labels8[lab_off + i] = static_cast<uint8_t>(s);          // (meaningful for alphabets up to 256 symbols)
         }
         // An alignment exists iff every symbol gets a frame and equal neighbours a blank between them.
         const bool runs = Tb > 0 && Tb >= L + repeats;
@@ -445,6 +451,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->n_tasks = n_tasks;
     out->n_task_entries = n_entries;
     out->n_cu = n_cu;
+    out->folded = c.A <= kDirectMaxA && c.B <= kNarrowMaxB && c.T < (1 << 29);
     out->lay = lay;
     return CTC_STATUS_SUCCESS;
 }
@@ -516,18 +523,23 @@ ctc_status_t run(const Call& c, float* kernel_ms)
         p.host_flag = slot->flag();
         p.host_flag_value = slot->generation;
         // The upload launch's own time is not reported separately: it is a few microseconds and
-        // overlaps the tail of whatever ran before on the stream.
-        if (!record(launch_setup(p, c.stream))) return CTC_STATUS_HIP_ERROR;
-        // The softmax launch, which follows, is the one that releases the image.  Should it fail to
-        // go out, nothing would ever release the slot while the upload kernel may still be reading
-        // it: wait for the stream (an error path) and leave the slot free.
-        if ((kernel_ms && !record(hipEventRecord(ev[0], s))) || !record(launch_softmax(p, c.stream))) {
+        // overlaps the tail of whatever ran before on the stream.  (Narrow alphabets have none: their
+        // softmax launch reads the image itself, and the lattice launch releases it.)
+        if (!p.folded && !record(launch_setup(p, c.stream))) return CTC_STATUS_HIP_ERROR;
+        // The image is released by the softmax launch, or by the lattice launch after it (narrow
+        // alphabets).  Should the releasing launch fail to go out, nothing would ever release the slot
+        // while a kernel may still be reading it: wait for the stream (an error path) and leave the
+        // slot free.
+        bool out = (!kernel_ms || record(hipEventRecord(ev[0], s))) && record(launch_softmax(p, c.stream)) &&
+                   (!kernel_ms || record(hipEventRecord(ev[1], s)));
+        if (out && p.folded)
+            out = record(launch_lattice(p, c.stream)) && (!kernel_ms || record(hipEventRecord(ev[2], s)));
+        if (!out) {
             (void)hipStreamSynchronize(s);
             return CTC_STATUS_HIP_ERROR;
         }
         slot->in_flight = true;
     }
-    if (kernel_ms && !record(hipEventRecord(ev[1], s))) return CTC_STATUS_HIP_ERROR;
 
     // Cost-only calls end with the lattice launch.
     // (Where the lattice launch carries the gradient rows itself, Launch::n_tasks, the gradient launch only
@@ -535,7 +547,7 @@ ctc_status_t run(const Call& c, float* kernel_ms)
     int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {
         launch_softmax, launch_lattice,
         c.mode == Mode::kGrad ? launch_gradient : (c.mode == Mode::kLoss ? nullptr : launch_backtrace)};
-    for (int i = 1; i < CTC_NUM_KERNELS; ++i) {
+    for (int i = p.folded ? 2 : 1; i < CTC_NUM_KERNELS; ++i) {
         if (stages[i] && !record(stages[i](p, c.stream))) return CTC_STATUS_HIP_ERROR;
         if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
     }
@@ -613,6 +625,7 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.n_tasks = 0;                     // the queue of an overlapped launch is prepared on the host
     p.n_task_entries = 0;
     p.n_cu = 0;
+    p.folded = false;
     p.lay = lay;
     int (*const stages[4])(const Launch&, void*) = {
         launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : nullptr};

@@ -41,6 +41,8 @@ static_assert(sizeof(Utt) == 64, "Utt is copied word by word and read with scala
 // the gathered emissions would be, and the rows themselves, transposed, are the emission block
 // (emission_layout).
 constexpr int kDirectMaxA = 64;
+constexpr int kNarrowMaxB = 128;      // utterances whose frame counts travel in the narrow softmax launch's arguments
+constexpr int kFlagFrames = 64;       // frames per word of Layout::row_flags = frames per workgroup of the narrow softmax launch
 
 #if defined(__HIPCC__)
 #define CTC_HOST_DEVICE __host__ __device__
@@ -343,11 +345,17 @@ struct Layout {
                           //              (0 forward, 1 backward), -1 for a workgroup without one (order_chains)
     size_t labels = 0;    // int32[sumL]
     size_t tasks = 0;     // int32[9 + 3 * 2B + 1]  the workers' tasks: die[9], prefix[2B + 1], info[2B], first[2B] (see kTaskRows)
+    size_t labels8 = 0;   // uint8[sumL]  the label strings once more, a byte per symbol (image only; narrow alphabets)
     size_t links = 0;     // int32[sumL]  grouping of the label positions by symbol (slot, count, first)
     size_t logp = 0;      // double[B]    log2 of the alignment mass
     size_t sink = 0;      // 256 bytes that lanes with nothing to store may scribble on
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
     size_t done = 0;      // int32[B * kDoneStride]  wavefronts of the utterance's chains that have ended (overlapped launches)
+    size_t domain = 0;    // int32[B]     nonzero: the utterance's chains ran in the log domain (published by the forward
+                          //              chain for the gradient, which must know where the exponent rows are)
+    size_t row_flags = 0; // int32[B * ceil(T / 64)]  narrow alphabets: per 64 frames of an utterance, nonzero if one of
+                          //              their emissions is too small for the linear domain (written by the softmax
+                          //              launch, one word per workgroup, so that nothing needs clearing beforehand)
     size_t where = 0;     // int32[2B]    1 + the die each chain's workgroup runs on
     size_t leftover = 0;  // int32[B]     utterances whose rows a worker had to leave to the gradient launch
     size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits
@@ -414,6 +422,9 @@ struct Launch {
     int n_tasks;
     int n_task_entries;
     int n_cu;                 // compute units of the device
+    // Narrow alphabets, host metadata: there is no upload launch; the softmax launch reads the pinned image
+    // itself and copies it into the workspace for the launches after it, and the lattice launch releases it.
+    bool folded;
     Layout lay;
 };
 

@@ -355,14 +355,23 @@ struct SetupArgs {
 // of the label, so that a label of 500 symbols costs 125 steps per lane instead of 1000.
 constexpr int kSetupLabelSlots = CTC_MAX_LABEL_LENGTH + 5;     // the label and a quarter's padding
 
+// `labels8`: the label strings as bytes (narrow alphabets, read out of the pinned host image: a
+// quarter of the traffic), to be written out as ints to `labels_out` by the utterance's first part;
+// nullptr: `labels` holds them as ints.
 __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* __restrict__ labels,
-                                           const SetupArgs sa, int* s_lab, const int part, const int parts)
+                                           const SetupArgs sa, int* s_lab, const int part, const int parts,
+                                           const unsigned char* __restrict__ labels8 = nullptr,
+                                           int* __restrict__ labels_out = nullptr)
 {
     const int tid = threadIdx.x;
     const int* lab = labels + m.lab_off;
     const int quarter_length = (m.L + 3) / 4;
     // padding: a symbol that is neither smaller than nor equal to any real one
-    for (int j = tid; j < 4 * quarter_length; j += kRowThreads) s_lab[j] = (j < m.L) ? lab[j] : 0x7FFFFFFF;
+    for (int j = tid; j < 4 * quarter_length; j += kRowThreads) {
+        const int c = (j >= m.L) ? 0x7FFFFFFF : (labels8 ? static_cast<int>(labels8[m.lab_off + j]) : lab[j]);
+        s_lab[j] = c;
+        if (labels_out && part == 0 && j < m.L) labels_out[m.lab_off + j] = c;
+    }
     __syncthreads();
     const int quarter = tid & 3;
     const int* const mine = s_lab + quarter * quarter_length;
@@ -647,6 +656,145 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
         }
     }
     raise_log_domain(meta, b, small);
+}
+
+// The narrowest alphabets (at most kDirectMaxA symbols), host-resident metadata: the first launch of
+// the call.  There is no upload launch before it: every workgroup reads its utterance's record out
+// of the pinned host image itself (one PCIe round trip, which the upload launch cost as well, but
+// no launch boundary after it), and the workgroups of the setup role, besides their own work, copy
+// the image into the workspace for the launches that follow.  Nothing in this launch writes where
+// another of its workgroups reads: instead of raising a flag in the utterance's record, a workgroup
+// that meets an emission too small for the linear domain says so in a word of its own
+// (row_flags: one per kFlagFrames frames of an utterance, written by every workgroup that has rows),
+// which the chains gather when they start.
+// A workgroup takes 64 frames of one utterance, four lanes per frame, so that it has several
+// kilobytes under way; the normalised rows are the emission block, stored symbol-major.
+// grid (ceil(T / 64) + parts, B); dynamic LDS 64 * A floats.
+struct NarrowImage {
+    const int* words;         // the pinned image: meta, order, labels, tasks as they lie in the workspace, then the labels as bytes
+    int labels_first, labels_end;   // the label strings' place in it (4-byte words): not copied, the setup role writes them
+    int count;                // words to copy (up to the byte labels)
+    size_t labels8_offset;    // of the byte labels (bytes)
+    int* labels_out;          // the workspace's label strings
+};
+// What the workgroups with rows need to know of an utterance travels with the kernel's arguments
+// (hundreds of small reads out of host memory at once were measured to take longer than the upload
+// launch they replace): its frames, with kRowsRun set if its chains run, and the frames of all
+// utterances before it.  An utterance's emission block starts A times that many floats into the
+// region and has a pitch of its frames.
+constexpr int kRowsRun = 1 << 30, kRowsGradientLater = 1 << 29;     // (flags of the record that ride along)
+struct NarrowRows {
+    int frames[kNarrowMaxB];
+    int frames_before[kNarrowMaxB];
+    int label_length[kNarrowMaxB];       // and, for the setup role, the label's length and the symbols before it
+    int labels_before[kNarrowMaxB];
+};
+
+template <typename T>
+__global__ __launch_bounds__(kRowThreads)
+void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image, int* __restrict__ workspace_words,
+                               float* __restrict__ lse, float* __restrict__ emit_blank,
+                               float* __restrict__ emit_label, int* __restrict__ row_flags,
+                               const SetupArgs sa, const NarrowRows rows_of, int Tt, int B, int A, int blank)
+{
+    constexpr int kRows = kFlagFrames, kPerRow = kRowThreads / kRows;
+    static_assert(kPerRow == 4, "a quad per frame");
+    extern __shared__ float lp[];                          // [kRows][A]
+    __shared__ int s_lab[kSetupLabelSlots];
+    __shared__ int s_small;
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int row_blocks = static_cast<int>(gridDim.x) - sa.parts;
+    if (static_cast<int>(blockIdx.x) >= row_blocks) {
+        // (what the setup role uses of the utterance's record: no read of the record out of host memory,
+        // so that the label's bytes are the first and only thing this workgroup waits for from there)
+        Utt m{};
+        m.Tb = rows_of.frames[b] & (kRowsGradientLater - 1);
+        m.flags = ((rows_of.frames[b] & kRowsRun) ? kUttRuns : 0) |
+                  ((rows_of.frames[b] & kRowsGradientLater) ? kUttGradientLater : 0);
+        m.L = rows_of.label_length[b];
+        m.lab_off = rows_of.labels_before[b];
+        const int part = static_cast<int>(blockIdx.x) - row_blocks;
+        // this workgroup's share of the image
+        const int groups = B * sa.parts, group = b * sa.parts + part;
+        const int share = (image.count + groups - 1) / groups;
+        for (int i = group * share + tid; i < min((group + 1) * share, image.count); i += kRowThreads)
+            if (i < image.labels_first || i >= image.labels_end) workspace_words[i] = image.words[i];
+        setup_role(m, b, nullptr, sa, s_lab, part, sa.parts,
+                   reinterpret_cast<const unsigned char*>(image.words) + image.labels8_offset, image.labels_out);
+        return;
+    }
+    // (the fields of the utterance's record that the rows need)
+    struct { int Tb, flags, f_off, e_pitch; int64_t e_off; } m;
+    m.Tb = rows_of.frames[b] & (kRowsGradientLater - 1);
+    m.flags = (rows_of.frames[b] & kRowsRun) ? kUttRuns : 0;
+    m.f_off = rows_of.frames_before[b];
+    m.e_off = static_cast<int64_t>(m.f_off) * A;
+    m.e_pitch = m.Tb;
+    const int t0 = blockIdx.x * kRows;
+    if (t0 >= m.Tb) return;
+    if (tid == 0) s_small = 0;
+    const int r = tid / kPerRow, q = tid % kPerRow, t = t0 + r;
+    float* lrow = lp + r * A;
+    if (t < m.Tb) {
+        const T* row = x + (static_cast<size_t>(t) * B + b) * A;
+        float mx = -__builtin_inff();
+        // eight reads in flight per thread: a row costs a few memory latencies, not A / kPerRow
+        for (int k0 = q; k0 < A; k0 += 8 * kPerRow) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + u * kPerRow;
+                v[u] = (k < A) ? load_elem(row, k) : -__builtin_inff();
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + u * kPerRow;
+                if (k < A) lrow[k] = v[u];
+                mx = fmaxf(mx, v[u]);
+            }
+        }
+        mx = quad_max(mx) * kLog2e;
+        float sum = 0.0f;
+        for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
+        sum = quad_sum(sum);
+        const float l2 = mx + fast_log2(sum);
+        bool unused = false;       // (what counts is which of the coded emissions get stored below)
+        for (int k = q; k < A; k += kPerRow) lrow[k] = encode_emission(fmaf(lrow[k], kLog2e, -l2), unused, sa.plain_logs);
+        if (q == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
+    }
+    if (!(m.flags & kUttRuns)) return;
+    __syncthreads();
+    const int rows = min(kRows, m.Tb - t0);
+    bool small = false;
+    if (tid < rows) {
+        const float e = lp[tid * A + blank];
+        emit_blank[kBlankSlack + m.f_off + t0 + tid] = e;
+        small = !sa.plain_logs && e < 0.0f;
+    }
+    // The emission block: a symbol's frames side by side, e_pitch floats per symbol (fetch_frames).
+    // A wavefront writes up to 64 frames of one symbol at a time.
+    float* out = emit_label + kLabelSlack + m.e_off + t0;
+    const int rr = tid & 63;
+    if (rr < rows)
+        for (int a = tid >> 6; a < A; a += kRowThreads / 64) {
+            const float e = lp[rr * A + a];
+            out[static_cast<size_t>(a) * m.e_pitch + rr] = e;
+            small = small || (!sa.plain_logs && e < 0.0f);
+        }
+    if (small) s_small = 1;
+    __syncthreads();
+    if (tid == 0) row_flags[static_cast<size_t>(b) * row_blocks + blockIdx.x] = s_small;
+}
+
+// Has the narrow softmax launch met an emission below the linear domain's range in one of the
+// utterance's frames?  Asked by a whole wavefront; the same answer in every lane.
+__device__ __forceinline__ bool rows_flagged(const int* __restrict__ row_flags, int b, int blocks_per_utterance, int Tb)
+{
+    if (!row_flags) return false;
+    const int lane = threadIdx.x & 63, n = (Tb + kFlagFrames - 1) / kFlagFrames;
+    bool any = false;
+    for (int i = lane; i < n; i += 64) any = any || row_flags[static_cast<size_t>(b) * blocks_per_utterance + i] != 0;
+    return __ballot(any) != 0;
 }
 
 // ---- lattice storage -------------------------------------------------------------------------
@@ -1702,26 +1850,102 @@ struct LatticeOut {
     int* beta_exponents;
 };
 
-// Returns the utterance whose chain this wavefront has run to its end, -1 if it ran none.
+// ---- gradient rows inside the lattice launch (kTaskRows in the launcher's header) ----------------
+// What the workgroups after the chains' get besides the chains' arguments.
+struct WorkerArgs {
+    const void* x;            // activations and gradient tensor, of type `dtype`
+    void* grads;
+    const int* links;
+    const float* lse;
+    const int* tasks;         // the list of tasks: die[kXcds + 1], prefix[2B + 1], info[2B], first[2B]
+    int* done;                // per utterance: wavefronts of its chains that have ended
+    int* where;               // per chain: 1 + the die its workgroup runs on
+    int* leftover;            // per utterance: set if a worker had to leave its rows to the gradient launch
+    int n_tasks;              // 0: the launch has no workers
+    int n_entries;
+    int n_chains;
+    int n_cu;
+    int rounds;               // the launch has rounds x n_cu workgroups; the first n_chains of every round do not work
+    int worker_waves;         // wavefronts of a working workgroup that have a piece of LDS to work in
+    int T, B, A, blank, Lmax;
+    int dtype;
+    int lds_ints;             // ints of dynamic LDS of the launch's workgroups
+    // (used by the chains as well)
+    const int* row_flags;     // narrow softmax launch's words (rows_flagged), or nullptr: the records' flags say it all
+    int flag_blocks;          // ... per utterance
+    int* domain;              // per utterance: did its chains run in the log domain (published by the forward chain)
+    int* host_flag;           // pinned host word that receives host_flag_value: the image may be reused (or nullptr)
+    int host_flag_value;
+};
+
+// The die (XCD) this wavefront runs on: each has an L2 of its own.
+__device__ __forceinline__ int this_xcd() { return static_cast<int>(__builtin_amdgcn_s_getreg(63508) & 15u); }   // XCC_ID, 32 bits
+
+// How a chain hands its lattice to the workers without a device-wide cache write-back (which,
+// with the matching invalidation on the workers' side, was measured to lengthen the running chains
+// by half): the L2 of a die is the point at which all its compute units agree, a chain's stores are
+// complete once that L2 has them, and workgroups are dealt to the dies in turn, so that the workers
+// of a die can be given the utterances whose chains ran there.  A chain's first wavefront publishes
+// the die it finds itself on; a worker that finds itself on another die than both chains of an
+// utterance does not touch it and marks the utterance for the gradient launch that follows.
+__device__ __forceinline__ void chain_started(const WorkerArgs& wk, int chain)
+{
+    if (wk.n_tasks > 0 && threadIdx.x == 0)
+        __hip_atomic_store(&wk.where[chain], this_xcd() + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// A chain's wavefront has ended.  Once all its stores have completed (the L2 has them) it counts
+// itself in; the last wavefront of the chain's workgroup to do so moves the utterance's counter,
+// which therefore reaches 2 when both chains have ended.
+__device__ __forceinline__ void chain_ended(const WorkerArgs& wk, int u, int waves, void* lds)
+{
+    if (wk.n_tasks == 0 || u < 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // (waits for the stores; no cache operation)
+    __builtin_amdgcn_s_waitcnt(0);
+    bool last = true;
+    if (lds) {
+        int before = 0;
+        if ((threadIdx.x & 63) == 0)
+            before = __hip_atomic_fetch_add(&static_cast<HaloHeader*>(lds)->finished, 1, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_WORKGROUP);
+        last = __builtin_amdgcn_readfirstlane(before) == waves - 1;
+    }
+    if (last && (threadIdx.x & 63) == 0)
+        __hip_atomic_fetch_add(&wk.done[u * kDoneStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+
+// What a wavefront of a lattice workgroup has done: the utterance whose chain it ran to its end
+// (-1: none) and the number of wavefronts of that chain.
+struct ChainRun {
+    int u, waves;
+};
+
 template <Sync kSync, Mode kMode, bool kSymbolMajor>
-__device__ __forceinline__ int lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
+__device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
                                              const float* __restrict__ emit_blank,
                                              const float* __restrict__ emit_label,
                                              const LatticeOut lat,
                                              double* __restrict__ logp, float* __restrict__ costs,
                                              int* __restrict__ chain_err, uint32_t* __restrict__ sink,
-                                             void* lds)
+                                             void* lds, const WorkerArgs& wk)
 {
+    // The first workgroup of the launch tells the host that the pinned image of the call is free
+    // again (calls whose softmax launch read the image itself: this launch follows it).
+    if (blockIdx.x == 0 && threadIdx.x == 0 && wk.host_flag)
+        __hip_atomic_store(wk.host_flag, wk.host_flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     const int chain = order[blockIdx.x];           // utterance * 2 + direction
-    if (chain < 0) return -1;           // device-planned batches launch a workgroup per utterance and direction, running or not
+    if (chain < 0) return {-1, 0};      // device-planned batches launch a workgroup per utterance and direction, running or not
     const int u = chain >> 1;
     const bool forward = kMode != Mode::kGrad || (chain & 1) == 0;
     const Utt m = meta[u];
     // Which recursion: the barrier kernel and the maximum recursion have the log domain only;
     // otherwise the flag that the softmax launch may have raised decides.  A linear-domain chain
     // gives one pair or two to a lane as the launcher planned it (two_pairs_per_lane).
-    const bool in_log_domain = kSync == Sync::kBarrier || kMode == Mode::kBest || (m.flags & kUttLogDomain) != 0;
+    const bool in_log_domain = kSync == Sync::kBarrier || kMode == Mode::kBest || (m.flags & kUttLogDomain) != 0 ||
+                               rows_flagged(wk.row_flags, u, wk.flag_blocks, m.Tb);
+    // (for the gradient, which must know where this utterance's exponent rows are)
+    if (kMode == Mode::kGrad && forward && threadIdx.x == 0) wk.domain[u] = in_log_domain ? 1 : 0;
     const bool two_pairs = kSync == Sync::kHalo && !in_log_domain && (m.flags & kUttTwoPairs) != 0;
     const int waves = two_pairs ? m.waves2 : m.waves;
     const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves;
@@ -1742,14 +1966,14 @@ __device__ __forceinline__ int lattice_body(const Utt* __restrict__ meta, const 
             hl->gave_up = 0;
         }
         __syncthreads();
-        if (idle) return -1;
+        if (idle) return {-1, 0};
     } else if (kSync == Sync::kBarrier) {
         if (idle) {
             // Nothing to compute, but keep meeting the barriers of the working wavefronts:
             // one per recursion step, plus the forward chain's final exchange.
             const int barriers = (m.Tb - 1) + (forward ? 1 : 0);
             for (int i = 0; i < barriers; ++i) __syncthreads();
-            return -1;
+            return {-1, 0};
         }
     }
     if constexpr (kSync != Sync::kBarrier && kMode != Mode::kBest) {
@@ -1760,21 +1984,21 @@ __device__ __forceinline__ int lattice_body(const Utt* __restrict__ meta, const 
                 else
                     run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
             }
-            return u;
+            return {u, waves};
         }
         if (!in_log_domain) {
             if (forward)
                 run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
             else
                 run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
-            return u;
+            return {u, waves};
         }
     }
     if (forward)
         run_chain_log<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
     else
         run_chain_log<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
-    return u;
+    return {u, waves};
 }
 
 // ---- gradient rows of narrow alphabets (shared by the gradient kernel and the lattice launch's workers) ----
@@ -1813,6 +2037,7 @@ template <typename T, bool kStreaming, bool kCoherent>
 __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T* __restrict__ grads, const Utt m,
                                                      const int b, const LatticeOut lat,
                                                      const float* __restrict__ lse, const double* __restrict__ logp,
+                                                     const bool log_domain,   // decides where a row's exponents are (exponent_row)
                                                      const int Tt, const int B, const int A, const int blank,
                                                      const int t_first, const int t_step, const int tend,
                                                      const int* s_slot, const int* s_start, const int* s_count,
@@ -1825,7 +2050,6 @@ __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T*
     const double packed_inverse_p = runs ? lattice_load<kCoherent>(&logp[b]) : 0.0;
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
-    const bool log_domain = (m.flags & kUttLogDomain) != 0;  // decides where a row's exponents are (exponent_row)
     const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
                               lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
                               pitch, m.Tb, log_domain};
@@ -1918,54 +2142,6 @@ __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T*
     }
 }
 
-// ---- gradient rows inside the lattice launch (kTaskRows in the launcher's header) ----------------
-// What the workgroups after the chains' get besides the chains' arguments.
-struct WorkerArgs {
-    const void* x;            // activations and gradient tensor, of type `dtype`
-    void* grads;
-    const int* links;
-    const float* lse;
-    const int* tasks;         // the list of tasks: die[kXcds + 1], prefix[2B + 1], info[2B], first[2B]
-    int* done;                // per utterance: wavefronts of its chains that have ended
-    int* where;               // per chain: 1 + the die its workgroup runs on
-    int* leftover;            // per utterance: set if a worker had to leave its rows to the gradient launch
-    int n_tasks;              // 0: the launch has no workers
-    int n_entries;
-    int n_chains;
-    int n_cu;
-    int rounds;               // the launch has rounds x n_cu workgroups; the first n_chains of every round do not work
-    int worker_waves;         // wavefronts of a working workgroup that have a piece of LDS to work in
-    int T, B, A, blank, Lmax;
-    int dtype;
-    int lds_ints;             // ints of dynamic LDS of the launch's workgroups
-};
-
-// The die (XCD) this wavefront runs on: each has an L2 of its own.
-__device__ __forceinline__ int this_xcd() { return static_cast<int>(__builtin_amdgcn_s_getreg(63508) & 15u); }   // XCC_ID, 32 bits
-
-// How a chain hands its lattice to the workers without a device-wide cache write-back (which,
-// with the matching invalidation on the workers' side, was measured to lengthen the running chains
-// by half): the L2 of a die is the point at which all its compute units agree, a chain's stores are
-// complete once that L2 has them, and workgroups are dealt to the dies in turn, so that the workers
-// of a die can be given the utterances whose chains ran there.  A chain's first wavefront publishes
-// the die it finds itself on; a worker that finds itself on another die than both chains of an
-// utterance does not touch it and marks the utterance for the gradient launch that follows.
-__device__ __forceinline__ void chain_started(const WorkerArgs& wk, int chain)
-{
-    if (wk.n_tasks > 0 && threadIdx.x == 0)
-        __hip_atomic_store(&wk.where[chain], this_xcd() + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// A chain's wavefront has ended: once all its stores have completed (the L2 has them), the
-// utterance's counter moves.
-__device__ __forceinline__ void chain_ended(const WorkerArgs& wk, int u)
-{
-    if (wk.n_tasks == 0 || u < 0) return;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // (waits for the stores; no cache operation)
-    __builtin_amdgcn_s_waitcnt(0);
-    if ((threadIdx.x & 63) == 0)
-        __hip_atomic_fetch_add(&wk.done[u * kDoneStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // A workgroup after the chains'.  Its wavefronts work on their own: the tasks are dealt out in
 // turn over all working wavefronts of the launch (wavefront w takes tasks w, w + W, w + 2W, ...:
 // no shared counter, whose traffic was measured to slow the chains severalfold), so that the
@@ -1977,8 +2153,7 @@ template <typename T>
 __device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* __restrict__ meta,
                                                 const int* __restrict__ labels, const LatticeOut lat,
                                                 const double* __restrict__ logp, const int* __restrict__ chain_err,
-                                                float* __restrict__ costs, int* lds, const int lds_ints,
-                                                const bool one_wave_chains)
+                                                float* __restrict__ costs, int* lds, const int lds_ints)
 {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int E = wk.n_entries, Lmax = wk.Lmax;
@@ -2058,9 +2233,7 @@ __device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* 
                     if (lane == 0) wk.leftover[b] = 1;
                     continue;
                 }
-                // both chains of the utterance, every wavefront of them (as lattice_body counts them)
-                const bool two_pairs = !one_wave_chains && (m.flags & (kUttLogDomain | kUttTwoPairs)) == kUttTwoPairs;
-                const int expected = 2 * (two_pairs ? m.waves2 : m.waves);
+                const int expected = 2;          // both chains of the utterance (chain_ended)
                 // (one lane asks; a sleep of some hundred nanoseconds between two questions)
                 int budget = kWorkerPollBudget;
                 auto ended_now = [&]() {
@@ -2102,8 +2275,9 @@ __device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* 
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
         }
-        narrow_gradient_rows<T, false, true>(x, grads, m, b, lat, wk.lse, logp, wk.T, wk.B, wk.A, wk.blank, t0, 1, tend,
-                                       s_slot, s_start, s_count, g_slot);
+        const bool log_domain = runs && t0 < m.Tb && lattice_load<true>(&wk.domain[b]) != 0;
+        narrow_gradient_rows<T, false, true>(x, grads, m, b, lat, wk.lse, logp, log_domain, wk.T, wk.B, wk.A, wk.blank, t0, 1,
+                                       tend, s_slot, s_start, s_count, g_slot);
     }
 }
 
@@ -2117,13 +2291,13 @@ __device__ __forceinline__ bool is_worker(const WorkerArgs& wk)
 __device__ __forceinline__ void run_worker(const WorkerArgs& wk, const Utt* __restrict__ meta,
                                            const int* __restrict__ labels, const LatticeOut lat,
                                            const double* __restrict__ logp, const int* __restrict__ chain_err,
-                                           float* __restrict__ costs, int* lds, bool one_wave_chains)
+                                           float* __restrict__ costs, int* lds)
 {
     if (static_cast<int>(blockIdx.x % static_cast<unsigned>(wk.n_cu)) < wk.n_chains) return;
     if (wk.dtype == CTC_DTYPE_F32)
-        gradient_worker<float>(wk, meta, labels, lat, logp, chain_err, costs, lds, wk.lds_ints, one_wave_chains);
+        gradient_worker<float>(wk, meta, labels, lat, logp, chain_err, costs, lds, wk.lds_ints);
     else
-        gradient_worker<bf16_t>(wk, meta, labels, lat, logp, chain_err, costs, lds, wk.lds_ints, one_wave_chains);
+        gradient_worker<bf16_t>(wk, meta, labels, lat, logp, chain_err, costs, lds, wk.lds_ints);
 }
 
 // grid = one workgroup per entry of `order` (utterance * 2 + direction: 0 forward, 1 backward; only
@@ -2143,14 +2317,14 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) {
         if (is_worker(wk)) {
             extern __shared__ int worker_lds[];
-            run_worker(wk, meta, labels, lat, logp, chain_err, costs, worker_lds, true);
+            run_worker(wk, meta, labels, lat, logp, chain_err, costs, worker_lds);
             return;
         }
     }
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_started(wk, order[blockIdx.x]);
-    const int u = lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
-                                                            costs, chain_err, sink, nullptr);
-    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, u);
+    const ChainRun ran = lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat,
+                                                                   logp, costs, chain_err, sink, nullptr, wk);
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, ran.u, ran.waves, nullptr);
 }
 
 // Multi-wavefront chains with the halo exchange.
@@ -2166,14 +2340,14 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
     extern __shared__ double2 halo_lds[];                    // halo_lds_bytes(wavefronts of the workgroup)
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) {
         if (is_worker(wk)) {
-            run_worker(wk, meta, labels, lat, logp, chain_err, costs, reinterpret_cast<int*>(halo_lds), false);
+            run_worker(wk, meta, labels, lat, logp, chain_err, costs, reinterpret_cast<int*>(halo_lds));
             return;
         }
     }
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_started(wk, order[blockIdx.x]);
-    const int u = lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
-                                                            costs, chain_err, sink, halo_lds);
-    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, u);
+    const ChainRun ran = lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat,
+                                                                   logp, costs, chain_err, sink, halo_lds, wk);
+    if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, ran.u, ran.waves, halo_lds);
 }
 
 // Labels too long to leave room for a halo (more than 16 * 63 pairs): 64 pairs per wavefront
@@ -2185,11 +2359,11 @@ void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restr
                                 const float* __restrict__ emit_label,
                                 const LatticeOut lat,
                                 double* __restrict__ logp, float* __restrict__ costs,
-                                int* __restrict__ chain_err, uint32_t* __restrict__ sink, const WorkerArgs)
+                                int* __restrict__ chain_err, uint32_t* __restrict__ sink, const WorkerArgs wk)
 {
     __shared__ double xch[2][16];
     lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
-                                               costs, chain_err, sink, &xch[0][0]);
+                                               costs, chain_err, sink, &xch[0][0], wk);
 }
 
 // ---- after a forward-only chain -------------------------------------------------------------
@@ -2285,7 +2459,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
                               const double* __restrict__ logp, const int* __restrict__ chain_err,
                               float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
                               int rows_per_group, const float* __restrict__ emit_blank,
-                              const float* __restrict__ emit_label)
+                              const float* __restrict__ emit_label, const int* __restrict__ domain)
 {
     extern __shared__ int g_lds[];
     int* s_lab = g_lds;
@@ -2310,7 +2484,7 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
-    const bool log_domain = (m.flags & kUttLogDomain) != 0;  // decides where a row's exponents are (exponent_row)
+    const bool log_domain = runs && domain[b] != 0;         // decides where a row's exponents are (exponent_row)
     const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
                               lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
                               pitch, m.Tb, log_domain};
@@ -2478,7 +2652,8 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
                                 const LatticeOut lat,
                                 const double* __restrict__ logp, const int* __restrict__ chain_err,
                                 float* __restrict__ costs, int Tt, int B, int A, int blank, int Lmax,
-                                int rows_per_group, const int* __restrict__ only_marked)
+                                int rows_per_group, const int* __restrict__ only_marked,
+                                const int* __restrict__ domain)
 {
     // After a lattice launch whose workers have written the gradient: only the utterances they left.
     if (only_marked && only_marked[blockIdx.y] == 0) return;
@@ -2510,7 +2685,7 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         __syncthreads();
     }
-    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, Tt, B, A, blank, t0 + wave, 4,
+    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, runs && domain[b] != 0, Tt, B, A, blank, t0 + wave, 4,
                                         min(t0 + rows_per_group, Tt), s_slot, s_start, s_count, g_slot);
 }
 
@@ -2545,7 +2720,7 @@ static LatticeOut lattice_blocks(const Launch& p)
 
 int launch_setup(const Launch& p, void* stream)
 {
-    const int words = static_cast<int>(p.lay.upload_bytes / 4);
+    const int words = static_cast<int>(p.lay.labels8 / 4);      // (the byte labels after that are for the narrow softmax launch)
     return checked_launch([&] {
         hipLaunchKernelGGL(ctc_upload_kernel, dim3((words + kRowThreads - 1) / kRowThreads), dim3(kRowThreads),
                            0, static_cast<hipStream_t>(stream), static_cast<const int*>(p.host_image),
@@ -2575,7 +2750,7 @@ int launch_softmax(const Launch& p, void* stream)
                        reinterpret_cast<int*>(p.ws + p.lay.chain_err),
                        reinterpret_cast<int*>(p.ws + p.lay.done), reinterpret_cast<int*>(p.ws + p.lay.where),
                        reinterpret_cast<int*>(p.ws + p.lay.leftover), emit_label,
-                       p.host_flag, p.host_flag_value, p.mode == Mode::kBest,
+                       p.folded ? nullptr : p.host_flag, p.host_flag_value, p.mode == Mode::kBest,
                        // few utterances: spread each one's grouping over several workgroups (its
                        // latency counts); many: one workgroup each keeps the chip busy already
                        p.B >= 256 ? 1 : std::max(1, (p.max_label + 63) / 64)};
@@ -2583,7 +2758,32 @@ int launch_softmax(const Launch& p, void* stream)
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;
     return checked_launch([&] {
-        if (p.A <= kDirectMaxA) {
+        if (p.A <= kDirectMaxA && p.folded) {
+            // the smallest alphabets, host metadata: the launch reads the pinned image itself
+            const dim3 grid((p.T + kFlagFrames - 1) / kFlagFrames + sa.parts, p.B);
+            const size_t lds = static_cast<size_t>(kFlagFrames) * p.A * sizeof(float);
+            const NarrowImage image{static_cast<const int*>(p.host_image), static_cast<int>(p.lay.labels / 4),
+                                    static_cast<int>(p.lay.tasks / 4), static_cast<int>(p.lay.labels8 / 4), p.lay.labels8,
+                                    reinterpret_cast<int*>(p.ws + p.lay.labels)};
+            auto* row_flags = reinterpret_cast<int*>(p.ws + p.lay.row_flags);
+            NarrowRows rows_of;
+            const Utt* records = static_cast<const Utt*>(p.host_image);      // (the host reads its own image)
+            for (int b = 0; b < p.B; ++b) {
+                rows_of.frames[b] = records[b].Tb | ((records[b].flags & kUttRuns) ? kRowsRun : 0) |
+                                    ((records[b].flags & kUttGradientLater) ? kRowsGradientLater : 0);
+                rows_of.frames_before[b] = records[b].f_off;
+                rows_of.label_length[b] = records[b].L;
+                rows_of.labels_before[b] = records[b].lab_off;
+            }
+            if (f32)
+                hipLaunchKernelGGL(ctc_softmax_narrow_kernel<float>, grid, block, lds, s, static_cast<const float*>(p.x),
+                                   image, reinterpret_cast<int*>(p.ws), lse, emit_blank, emit_label, row_flags, sa,
+                                   rows_of, p.T, p.B, p.A, p.blank);
+            else
+                hipLaunchKernelGGL(ctc_softmax_narrow_kernel<bf16_t>, grid, block, lds, s, static_cast<const bf16_t*>(p.x),
+                                   image, reinterpret_cast<int*>(p.ws), lse, emit_blank, emit_label, row_flags, sa,
+                                   rows_of, p.T, p.B, p.A, p.blank);
+        } else if (p.A <= kDirectMaxA) {
             // the smallest alphabets: 64 frames per workgroup, four lanes per frame, so that a
             // workgroup has several kilobytes under way
             const dim3 grid((p.T + 63) / 64 + sa.parts, p.B);
@@ -2646,7 +2846,8 @@ int launch_softmax(const Launch& p, void* stream)
 
 int launch_lattice(const Launch& p, void* stream)
 {
-    if (p.n_run == 0) return 0;
+    // (a call whose softmax launch read the pinned image itself needs this launch for the release, chains or not)
+    if (p.n_run == 0 && !(p.folded && p.host_flag)) return 0;
     auto* meta = reinterpret_cast<const Utt*>(p.ws + p.lay.meta);
     auto* order = reinterpret_cast<const int*>(p.ws + p.lay.order);
     const int* labels = p.labels;
@@ -2657,11 +2858,16 @@ int launch_lattice(const Launch& p, void* stream)
     auto* logp = reinterpret_cast<double*>(p.ws + p.lay.logp);
     auto* chain_err = reinterpret_cast<int*>(p.ws + p.lay.chain_err);
     size_t lds_bytes = (p.max_waves > 1 && !p.needs_barrier) ? halo_lds_bytes(p.max_waves) : 0;
+    int n_groups = std::max(p.n_chains, 1);
+    WorkerArgs wk{};
+    wk.row_flags = p.folded ? reinterpret_cast<const int*>(p.ws + p.lay.row_flags) : nullptr;
+    wk.flag_blocks = (p.T + kFlagFrames - 1) / kFlagFrames;
+    wk.domain = reinterpret_cast<int*>(p.ws + p.lay.domain);
+    wk.host_flag = p.folded ? p.host_flag : nullptr;
+    wk.host_flag_value = p.host_flag_value;
     // Workers (kTaskRows): as many workgroups per idle compute unit as make kWorkerWavesPerCu
     // wavefronts, in rounds of n_cu workgroups whose first n_chains leave at once; their LDS holds
-    // the queue's table and a piece per wavefront.
-    int n_groups = p.n_chains;
-    WorkerArgs wk{};
+    // the list's table and a piece per wavefront.
     if (p.n_tasks > 0) {
         const size_t table = kXcds + 1 + 3 * static_cast<size_t>(p.n_task_entries) + 1, piece = 2 * static_cast<size_t>(p.max_label) + 129;
         lds_bytes = std::min<size_t>(std::max(lds_bytes, (table + p.max_waves * piece) * 4), 64 << 10);
@@ -2671,14 +2877,23 @@ int launch_lattice(const Launch& p, void* stream)
         // no more workgroups than give every working wavefront a task
         const int rounds = std::max(1, std::min(per_cu, (p.n_tasks + idle * waves - 1) / (idle * waves)));
         n_groups = p.n_cu * rounds;
-        wk = WorkerArgs{p.x, p.grads, reinterpret_cast<const int*>(p.ws + p.lay.links),
-                        reinterpret_cast<const float*>(p.ws + p.lay.lse),
-                        reinterpret_cast<const int*>(p.ws + p.lay.tasks),
-                        reinterpret_cast<int*>(p.ws + p.lay.done), reinterpret_cast<int*>(p.ws + p.lay.where),
-                        reinterpret_cast<int*>(p.ws + p.lay.leftover),
-                        p.n_tasks, p.n_task_entries, p.n_chains, p.n_cu, rounds, waves,
-                        p.T, p.B, p.A, p.blank, p.max_label, static_cast<int>(p.dtype), static_cast<int>(lds_bytes / 4)
-        };
+        wk.x = p.x;
+        wk.grads = p.grads;
+        wk.links = reinterpret_cast<const int*>(p.ws + p.lay.links);
+        wk.lse = reinterpret_cast<const float*>(p.ws + p.lay.lse);
+        wk.tasks = reinterpret_cast<const int*>(p.ws + p.lay.tasks);
+        wk.done = reinterpret_cast<int*>(p.ws + p.lay.done);
+        wk.where = reinterpret_cast<int*>(p.ws + p.lay.where);
+        wk.leftover = reinterpret_cast<int*>(p.ws + p.lay.leftover);
+        wk.n_tasks = p.n_tasks;
+        wk.n_entries = p.n_task_entries;
+        wk.n_chains = p.n_chains;
+        wk.n_cu = p.n_cu;
+        wk.rounds = rounds;
+        wk.worker_waves = waves;
+        wk.T = p.T; wk.B = p.B; wk.A = p.A; wk.blank = p.blank; wk.Lmax = p.max_label;
+        wk.dtype = static_cast<int>(p.dtype);
+        wk.lds_ints = static_cast<int>(lds_bytes / 4);
     }
     const dim3 grid(n_groups), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
@@ -2748,7 +2963,8 @@ int launch_gradient(const Launch& p, void* stream)
     hipLaunchKernelGGL((ctc_gradient_narrow_kernel<TYPE, STREAMING>), grid, block, nlds, s,         \
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,    \
                        links, lse, lat, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank,           \
-                       Lmax, rows, p.n_tasks > 0 ? reinterpret_cast<const int*>(p.ws + p.lay.leftover) : nullptr)
+                       Lmax, rows, p.n_tasks > 0 ? reinterpret_cast<const int*>(p.ws + p.lay.leftover) : nullptr,   \
+                       reinterpret_cast<const int*>(p.ws + p.lay.domain))
         return checked_launch([&] {
             if (f32 && streaming) CTC_LAUNCH_NARROW(float, true);
             else if (f32) CTC_LAUNCH_NARROW(float, false);
@@ -2762,7 +2978,8 @@ int launch_gradient(const Launch& p, void* stream)
                        static_cast<const TYPE*>(p.x), static_cast<TYPE*>(p.grads), meta, labels,     \
                        links, lse, lat, logp, chain_err, p.costs, p.T, p.B, p.A, p.blank, Lmax, rows,               \
                        reinterpret_cast<const float*>(p.ws + p.lay.emit_blank),                                       \
-                       reinterpret_cast<const float*>(p.ws + p.lay.emit_label))
+                       reinterpret_cast<const float*>(p.ws + p.lay.emit_label),                                       \
+                       reinterpret_cast<const int*>(p.ws + p.lay.domain))
     return checked_launch([&] {
         if (f32 && sparse) CTC_LAUNCH_GRADIENT(float, true);
         else if (f32) CTC_LAUNCH_GRADIENT(float, false);
