@@ -135,7 +135,7 @@ def main():
                     help="grad: cost + gradient (headline); loss: cost only; align: most probable alignment")
     ap.add_argument("--metadata", choices=("host", "device"), default="host",
                     help="device: ctc_loss_and_grad_device (lengths and labels resident on the GPU, workspace "
-                         "sized by bounds); no per-kernel times, so no roofline object")
+                         "sized by bounds)")
     ap.add_argument("--graph", action="store_true",
                     help="with --metadata device: record each minibatch's call into a HIP graph and time replays")
     ap.add_argument("--buffers", type=int, default=4, help="distinct minibatches rotated through")
@@ -209,10 +209,10 @@ def main():
 
             def step(d, stream, kernel_ms=None):
                 graphs[id(d)].replay()
+            args.profile_steps = 0                 # (a replay has no events inside it)
         else:
             def step(d, stream, kernel_ms=None):
-                d.run(stream, want_grad=want_grad)
-        args.profile_steps = 0
+                d.run(stream, want_grad=want_grad, kernel_ms=kernel_ms)
     else:
         if args.graph:
             sys.exit("bench.py: --graph needs --metadata device (the host-metadata call reads host memory)")

@@ -218,6 +218,24 @@ ctc_status_t ctc_loss_and_grad_device(const void *activations,
                                       void *workspace, size_t workspace_bytes,
                                       hipStream_t stream);
 
+/* ctc_loss_and_grad_device with per-launch device times, as ctc_profile_kernels (it waits for the
+ * stream, so it cannot be captured): kernel_ms (host) [CTC_NUM_KERNELS] = softmax, lattice, gradient;
+ * where a planning launch precedes the softmax launch (alphabets wider than 64 symbols, more than
+ * 512 utterances) it is not timed separately. */
+ctc_status_t ctc_profile_kernels_device(const void *activations,
+                                        const int32_t *labels,
+                                        const int32_t *label_lengths,
+                                        const int32_t *input_lengths,
+                                        int max_label_length,
+                                        int T, int B, int A, int blank,
+                                        ctc_dtype_t dtype,
+                                        float *costs,
+                                        void *grads,
+                                        int32_t *status_out,
+                                        void *workspace, size_t workspace_bytes,
+                                        hipStream_t stream,
+                                        float *kernel_ms);
+
 /*
  * ctc_loss_and_grad_device without a workspace argument, for callers that cannot allocate device
  * memory or have it allocated for them: code recorded into a HIP graph, tight serving loops,

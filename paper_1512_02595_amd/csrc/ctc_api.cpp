@@ -80,6 +80,7 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.domain = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.row_flags = off;
     off = align_up(off + static_cast<size_t>(B) * ((T + kFlagFrames - 1) / kFlagFrames) * sizeof(int32_t));
+    l.status = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.where = off;  off = align_up(off + static_cast<size_t>(B) * 2 * sizeof(int32_t));
     l.leftover = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.lse = off;    off = align_up(off + static_cast<size_t>(B) * T * sizeof(float));
@@ -93,6 +94,25 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     *lay = l;
 }
 }  // namespace
+
+const PlanTable& plan_table(int max_label, bool crowded, bool symbol_major)
+{
+    struct Entry { int max_label; bool crowded, symbol_major; PlanTable table; };
+    static std::mutex mutex;
+    static std::vector<Entry*> entries;
+    std::lock_guard<std::mutex> lock(mutex);
+    for (const Entry* e : entries)
+        if (e->max_label >= max_label && e->crowded == crowded && e->symbol_major == symbol_major) return e->table;
+    Entry* e = new Entry{max_label, crowded, symbol_major, {}};
+    for (int L = 0; L <= max_label; ++L) {
+        const WavePlan one = plan_waves(L, crowded), two = plan_waves2(L, crowded);
+        e->table.one[L] = static_cast<uint8_t>((one.waves - 1) | ((one.halo / 8) << 4) |
+                                               (two_pairs_per_lane(L, crowded, symbol_major) ? 128 : 0));
+        e->table.two[L] = static_cast<uint8_t>((two.waves - 1) | ((two.halo / 4) << 4));
+    }
+    entries.push_back(e);
+    return e->table;
+}
 
 ctc_status_t make_layout(int T, int B, int A, const int32_t* label_lengths,
                          const int32_t* input_lengths, ctc_dtype_t dtype, Layout* lay)
@@ -573,7 +593,7 @@ ctc_status_t run(const Call& c, float* kernel_ms)
 ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* label_lengths,
                         const int32_t* input_lengths, int max_label, int T, int B, int A, int blank,
                         ctc_dtype_t dtype, float* costs, void* grads, int32_t* status, void* ws,
-                        size_t ws_bytes, void* stream)
+                        size_t ws_bytes, void* stream, float* kernel_ms = nullptr)
 {
     if (!x || !label_lengths || !input_lengths || !costs || !status || !ws) return CTC_STATUS_INVALID_VALUE;
     if (max_label > 0 && !labels) return CTC_STATUS_INVALID_VALUE;
@@ -625,12 +645,35 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.n_tasks = 0;                     // the queue of an overlapped launch is prepared on the host
     p.n_task_entries = 0;
     p.n_cu = 0;
-    p.folded = false;
+    // Narrow alphabets: the softmax launch builds the records itself (no planning launch before it); every
+    // utterance's setup workgroup weighs all B utterances for the run order, which is worth it up to here.
+    p.folded = A <= kDirectMaxA && B <= kDeviceFoldMaxB && max_label > 0;
     p.lay = lay;
-    int (*const stages[4])(const Launch&, void*) = {
-        launch_plan, launch_softmax, launch_lattice, grads ? launch_gradient : nullptr};
-    for (auto stage : stages)
-        if (stage && !record(stage(p, stream))) return CTC_STATUS_HIP_ERROR;
+    // Per-launch device times for measurements (ctc_profile_kernels_device): events around the launches as in run().
+    Events events;
+    hipEvent_t* const ev = events.ev;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kernel_ms && !events.create()) return CTC_STATUS_HIP_ERROR;
+    if (!p.folded && !record(launch_plan(p, stream))) return CTC_STATUS_HIP_ERROR;
+    int (*const stages[CTC_NUM_KERNELS])(const Launch&, void*) = {launch_softmax, launch_lattice,
+                                                                   grads ? launch_gradient : nullptr};
+    if (kernel_ms && !record(hipEventRecord(ev[0], s))) return CTC_STATUS_HIP_ERROR;
+    for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
+        if (stages[i] && !record(stages[i](p, stream))) return CTC_STATUS_HIP_ERROR;
+        if (kernel_ms && !record(hipEventRecord(ev[i + 1], s))) return CTC_STATUS_HIP_ERROR;
+    }
+    if (kernel_ms) {
+        if (!record(hipEventRecord(ev[CTC_NUM_KERNELS + 1], s))) return CTC_STATUS_HIP_ERROR;
+        if (!record(hipEventRecord(ev[CTC_NUM_KERNELS + 2], s))) return CTC_STATUS_HIP_ERROR;
+        if (!record(hipStreamSynchronize(s))) return CTC_STATUS_HIP_ERROR;
+        float empty = 0.0f;
+        if (!record(hipEventElapsedTime(&empty, ev[CTC_NUM_KERNELS + 1], ev[CTC_NUM_KERNELS + 2])))
+            return CTC_STATUS_HIP_ERROR;
+        for (int i = 0; i < CTC_NUM_KERNELS; ++i) {
+            if (!record(hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]))) return CTC_STATUS_HIP_ERROR;
+            kernel_ms[i] = stages[i] ? std::max(kernel_ms[i] - empty, 0.0f) : 0.0f;
+        }
+    }
     return CTC_STATUS_SUCCESS;
 }
 
@@ -660,6 +703,18 @@ void* static_workspace()
 }  // namespace ctc
 
 extern "C" {
+
+ctc_status_t ctc_profile_kernels_device(const void* activations, const int32_t* labels,
+                                        const int32_t* label_lengths, const int32_t* input_lengths,
+                                        int max_label_length, int T, int B, int A, int blank,
+                                        ctc_dtype_t dtype, float* costs, void* grads, int32_t* status_out,
+                                        void* workspace, size_t workspace_bytes, hipStream_t stream,
+                                        float* kernel_ms)
+{
+    if (!kernel_ms) return CTC_STATUS_INVALID_VALUE;
+    return ctc::run_device(activations, labels, label_lengths, input_lengths, max_label_length, T, B, A,
+                           blank, dtype, costs, grads, status_out, workspace, workspace_bytes, stream, kernel_ms);
+}
 
 ctc_status_t ctc_loss_and_grad_device_static(const void* activations, const int32_t* labels,
                                              const int32_t* label_lengths, const int32_t* input_lengths,

@@ -41,6 +41,7 @@ static_assert(sizeof(Utt) == 64, "Utt is copied word by word and read with scala
 // the gathered emissions would be, and the rows themselves, transposed, are the emission block
 // (emission_layout).
 constexpr int kDirectMaxA = 64;
+constexpr int kDeviceFoldMaxB = 512;  // device-resident metadata: utterances up to which the narrow softmax launch builds the records
 constexpr int kNarrowMaxB = 128;      // utterances whose frame counts travel in the narrow softmax launch's arguments
 constexpr int kFlagFrames = 64;       // frames per word of Layout::row_flags = frames per workgroup of the narrow softmax launch
 
@@ -104,7 +105,11 @@ CTC_HOST_DEVICE inline WavePlan plan_waves2(int label_length, bool crowded = fal
     if (lanes <= 64) return {1, 0, false};
     WavePlan best{16, 4, false};
     float best_cost = 1e30f;
-    for (int w = 2; w <= 16; ++w) {
+    // Fewest wavefronts with a halo of 4: w * 60 + 4 >= lanes.  The halo reaches its cap of 16 within
+    // three more wavefronts (lanes / 48 against lanes / 60, lanes <= 512), and beyond that a further
+    // wavefront only costs: no need to look further (the device-side planners run this per utterance).
+    const int w_first = (lanes - 4 + 59) / 60 > 2 ? (lanes - 4 + 59) / 60 : 2;
+    for (int w = w_first; w <= 16 && w <= w_first + 3; ++w) {
         // w * (64 - halo) + halo >= lanes
         int halo = (64 * w - lanes) / (w - 1);
         if (halo > 16) halo = 16;
@@ -136,6 +141,22 @@ CTC_HOST_DEVICE inline bool two_pairs_per_lane(int label_length, bool crowded, b
     const WavePlan one = plan_waves(label_length, crowded);
     return crowded || one.barrier || one.waves > 4 || (symbol_major && one.halo < 2 * kChunkSteps);
 }
+
+// The plans of every label length, packed: what a launch that builds its utterance records on the
+// GPU carries in its arguments instead of evaluating plan_waves per utterance there.
+//   one[L]: bits 0..3 wavefronts - 1, bits 4..6 halo / 8 (plan_waves), bit 7 two_pairs_per_lane
+//   two[L]: bits 0..3 wavefronts - 1, bits 4..6 halo / 4 (plan_waves2)
+struct PlanTable {
+    uint8_t one[CTC_MAX_LABEL_LENGTH + 1];
+    uint8_t two[CTC_MAX_LABEL_LENGTH + 1];
+    CTC_HOST_DEVICE int waves1(int L) const { return (one[L] & 15) + 1; }
+    CTC_HOST_DEVICE int halo1(int L) const { return ((one[L] >> 4) & 7) * 8; }
+    CTC_HOST_DEVICE bool two_pairs(int L) const { return (one[L] & 128) != 0; }
+    CTC_HOST_DEVICE int waves2(int L) const { return (two[L] & 15) + 1; }
+    CTC_HOST_DEVICE int halo2(int L) const { return (two[L] >> 4) * 4; }
+};
+// For labels up to max_label (kept per distinct request: a training run asks for one or two).
+const PlanTable& plan_table(int max_label, bool crowded, bool symbol_major);
 
 // How a launch's label emissions are laid out (Utt::e_direct).
 //   kEmitGathered:    [frame][label position], L floats per frame (alphabets above kDirectMaxA)
@@ -356,6 +377,8 @@ struct Layout {
     size_t row_flags = 0; // int32[B * ceil(T / 64)]  narrow alphabets: per 64 frames of an utterance, nonzero if one of
                           //              their emissions is too small for the linear domain (written by the softmax
                           //              launch, one word per workgroup, so that nothing needs clearing beforehand)
+    size_t status = 0;    // int32[B]     device-resident metadata, records built by the narrow softmax launch: nonzero
+                          //              if the utterance's lengths or labels are invalid
     size_t where = 0;     // int32[2B]    1 + the die each chain's workgroup runs on
     size_t leftover = 0;  // int32[B]     utterances whose rows a worker had to leave to the gradient launch
     size_t lse = 0;       // float[B*T]   row-wise log2-sum-exp2 of the scaled logits

@@ -689,13 +689,110 @@ struct NarrowRows {
     int label_length[kNarrowMaxB];       // and, for the setup role, the label's length and the symbols before it
     int labels_before[kNarrowMaxB];
 };
+// Either that (host-resident metadata) or the wavefront plans by label length (device-resident
+// metadata: see NarrowDevice), in the same 2 KB of kernel arguments.
+union NarrowArgs {
+    NarrowRows rows;
+    PlanTable plans;
+};
+
+// Device-resident metadata (ctc_loss_and_grad_device): there is no image and there are no records
+// yet.  The workgroups with rows derive what they need from the lengths themselves (blocks are laid
+// out by the caller's bounds: see ctc_plan_kernel); the first setup workgroup of an utterance builds
+// its record, as ctc_plan_kernel does for wider alphabets in a launch of its own, and finds the
+// utterance's place in the run order by counting the utterances that weigh more (all utterances
+// take part, those without an alignment too: their chains' workgroups leave at once).
+struct NarrowDevice {
+    const int* labels;            // [B][max_label]; nullptr: the metadata is the host's (NarrowImage, NarrowRows)
+    const int* label_lengths;
+    const int* input_lengths;
+    Utt* meta;                    // records to build
+    int* order;
+    int* status_words;            // [B] nonzero: the utterance's lengths or labels are invalid
+    int max_label, poll_budget, dirs;
+    bool crowded, log_domain;
+};
+
+// Weight of an utterance in the run order: its frames times the wavefronts of its chains.
+__device__ __forceinline__ long long chain_weight(const PlanTable& plans, int L, int Tb, int Tt, int max_label,
+                                                  bool log_domain)
+{
+    if (L < 0 || L > max_label || Tb < 0 || Tb > Tt) return 0;
+    const bool two = !log_domain && Tb <= kLinearMaxFrames && plans.two_pairs(L);
+    return static_cast<long long>(Tb) * (two ? plans.waves2(L) : plans.waves1(L));
+}
+
+// By the whole workgroup; `s_lab` holds scratch ints.  Returns the record (the same in every thread).
+__device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTable& plans, int b, int Tt, int B, int A,
+                                            int blank)
+{
+    __shared__ int s_repeats, s_bad, s_rank;
+    const int tid = threadIdx.x;
+    const int L_in = dv.label_lengths[b], Tb_in = dv.input_lengths[b];
+    const bool bad_length = L_in < 0 || L_in > dv.max_label || Tb_in < 0 || Tb_in > Tt;
+    const int L = bad_length ? 0 : L_in;
+    if (tid == 0) {
+        s_repeats = 0;
+        s_bad = 0;
+        s_rank = 0;
+    }
+    __syncthreads();
+    const int* lab = dv.labels + static_cast<size_t>(b) * dv.max_label;
+    int repeats = 0, bad = 0;
+    for (int j = tid; j < L; j += kRowThreads) {
+        const int c = lab[j];
+        bad |= (c < 0 || c >= A || c == blank) ? 1 : 0;
+        repeats += (j > 0 && c == lab[j - 1]) ? 1 : 0;
+    }
+    if (repeats) atomicAdd(&s_repeats, repeats);
+    if (bad) s_bad = 1;
+    // the utterances that come before this one in the run order: heavier, or as heavy and earlier
+    const long long mine = chain_weight(plans, L_in, Tb_in, Tt, dv.max_label, dv.log_domain);
+    int before = 0;
+    for (int j = tid; j < B; j += kRowThreads) {
+        const long long w = chain_weight(plans, dv.label_lengths[j], dv.input_lengths[j], Tt, dv.max_label, dv.log_domain);
+        before += (w > mine || (w == mine && j < b)) ? 1 : 0;
+    }
+    if (before) atomicAdd(&s_rank, before);
+    __syncthreads();
+    const bool invalid = bad_length || s_bad != 0;
+    const int Tb = invalid ? 0 : Tb_in;
+    const bool runs = !invalid && Tb > 0 && Tb >= L + s_repeats;
+    const int Lp = invalid ? 0 : L;
+    Utt m;
+    m.Tb = Tb;
+    m.L = Lp;
+    m.lab_off = b * dv.max_label;
+    m.flags = (runs ? kUttRuns : 0) | (invalid ? kUttInvalid : 0) |
+              ((dv.log_domain || Tb > kLinearMaxFrames) ? kUttLogDomain : 0) |
+              (!invalid && plans.two_pairs(L) ? kUttTwoPairs : 0);
+    m.f_off = b * Tt;
+    m.waves = plans.waves1(Lp);
+    m.halo = plans.halo1(Lp);
+    m.waves2 = plans.waves2(Lp);
+    m.halo2 = plans.halo2(Lp);
+    m.poll_budget = dv.poll_budget;
+    m.e_direct = emission_layout(A);
+    m.e_pitch = m.e_direct == kEmitSymbolMajor ? Tt : m.L;
+    m.e_off = static_cast<int64_t>(b) * Tt * (m.e_direct ? A : dv.max_label);
+    m.ab_off = static_cast<int64_t>(b) * Tt * lattice_pitch(dv.max_label);
+    if (tid == 0) {
+        dv.meta[b] = m;
+        dv.status_words[b] = invalid ? 1 : 0;
+        // heaviest first, in blocks of kChainBlock utterances: a block's forward chains, then its backward chains
+        const int rank = s_rank, first = rank - rank % kChainBlock, in_block = min(kChainBlock, B - first);
+        for (int d = 0; d < dv.dirs; ++d) dv.order[first * dv.dirs + d * in_block + rank % kChainBlock] = 2 * b + d;
+    }
+    return m;
+}
 
 template <typename T>
 __global__ __launch_bounds__(kRowThreads)
 void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image, int* __restrict__ workspace_words,
                                float* __restrict__ lse, float* __restrict__ emit_blank,
                                float* __restrict__ emit_label, int* __restrict__ row_flags,
-                               const SetupArgs sa, const NarrowRows rows_of, int Tt, int B, int A, int blank)
+                               const SetupArgs sa, const NarrowArgs args, const NarrowDevice dv,
+                               int Tt, int B, int A, int blank)
 {
     constexpr int kRows = kFlagFrames, kPerRow = kRowThreads / kRows;
     static_assert(kPerRow == 4, "a quad per frame");
@@ -704,15 +801,30 @@ void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image,
     __shared__ int s_small;
     const int b = blockIdx.y, tid = threadIdx.x;
     const int row_blocks = static_cast<int>(gridDim.x) - sa.parts;
+    if (static_cast<int>(blockIdx.x) >= row_blocks && dv.labels) {
+        // device-resident metadata: the first part builds the record, the others need the label only
+        const int part = static_cast<int>(blockIdx.x) - row_blocks;
+        Utt m{};
+        if (part == 0) {
+            m = build_record(dv, args.plans, b, Tt, B, A, blank);
+        } else {
+            const int L = dv.label_lengths[b], Tb = dv.input_lengths[b];
+            const bool bad_length = L < 0 || L > dv.max_label || Tb < 0 || Tb > Tt;
+            m.L = bad_length ? 0 : L;
+            m.lab_off = b * dv.max_label;
+        }
+        setup_role(m, b, dv.labels, sa, s_lab, part, sa.parts);
+        return;
+    }
     if (static_cast<int>(blockIdx.x) >= row_blocks) {
         // (what the setup role uses of the utterance's record: no read of the record out of host memory,
         // so that the label's bytes are the first and only thing this workgroup waits for from there)
         Utt m{};
-        m.Tb = rows_of.frames[b] & (kRowsGradientLater - 1);
-        m.flags = ((rows_of.frames[b] & kRowsRun) ? kUttRuns : 0) |
-                  ((rows_of.frames[b] & kRowsGradientLater) ? kUttGradientLater : 0);
-        m.L = rows_of.label_length[b];
-        m.lab_off = rows_of.labels_before[b];
+        m.Tb = args.rows.frames[b] & (kRowsGradientLater - 1);
+        m.flags = ((args.rows.frames[b] & kRowsRun) ? kUttRuns : 0) |
+                  ((args.rows.frames[b] & kRowsGradientLater) ? kUttGradientLater : 0);
+        m.L = args.rows.label_length[b];
+        m.lab_off = args.rows.labels_before[b];
         const int part = static_cast<int>(blockIdx.x) - row_blocks;
         // this workgroup's share of the image
         const int groups = B * sa.parts, group = b * sa.parts + part;
@@ -725,11 +837,21 @@ void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image,
     }
     // (the fields of the utterance's record that the rows need)
     struct { int Tb, flags, f_off, e_pitch; int64_t e_off; } m;
-    m.Tb = rows_of.frames[b] & (kRowsGradientLater - 1);
-    m.flags = (rows_of.frames[b] & kRowsRun) ? kUttRuns : 0;
-    m.f_off = rows_of.frames_before[b];
+    if (dv.labels) {
+        // (whether an alignment exists is not known here: the rows of every utterance with frames are prepared)
+        const int L = dv.label_lengths[b], Tb = dv.input_lengths[b];
+        const bool bad_length = L < 0 || L > dv.max_label || Tb < 0 || Tb > Tt;
+        m.Tb = bad_length ? 0 : Tb;
+        m.flags = kUttRuns;
+        m.f_off = b * Tt;
+        m.e_pitch = Tt;
+    } else {
+        m.Tb = args.rows.frames[b] & (kRowsGradientLater - 1);
+        m.flags = (args.rows.frames[b] & kRowsRun) ? kUttRuns : 0;
+        m.f_off = args.rows.frames_before[b];
+        m.e_pitch = m.Tb;
+    }
     m.e_off = static_cast<int64_t>(m.f_off) * A;
-    m.e_pitch = m.Tb;
     const int t0 = blockIdx.x * kRows;
     if (t0 >= m.Tb) return;
     if (tid == 0) s_small = 0;
@@ -1876,6 +1998,9 @@ struct WorkerArgs {
     int* domain;              // per utterance: did its chains run in the log domain (published by the forward chain)
     int* host_flag;           // pinned host word that receives host_flag_value: the image may be reused (or nullptr)
     int host_flag_value;
+    const int* status_words;  // device-resident metadata built by the narrow softmax launch: per utterance, nonzero if
+    int* status_out;          // invalid; gathered into the caller's status word by this launch (or nullptr)
+    int status_count;
 };
 
 // The die (XCD) this wavefront runs on: each has an L2 of its own.
@@ -1934,11 +2059,19 @@ __device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, c
     // again (calls whose softmax launch read the image itself: this launch follows it).
     if (blockIdx.x == 0 && threadIdx.x == 0 && wk.host_flag)
         __hip_atomic_store(wk.host_flag, wk.host_flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    // ... and gathers the per-utterance verdicts of a softmax launch that built the records itself.
+    if (blockIdx.x == 0 && threadIdx.x < 64 && wk.status_out) {
+        bool bad = false;
+        for (int i = threadIdx.x; i < wk.status_count; i += 64) bad = bad || wk.status_words[i] != 0;
+        const bool any = __ballot(bad) != 0;
+        if (threadIdx.x == 0) *wk.status_out = any ? CTC_STATUS_INVALID_VALUE : CTC_STATUS_SUCCESS;
+    }
     const int chain = order[blockIdx.x];           // utterance * 2 + direction
     if (chain < 0) return {-1, 0};      // device-planned batches launch a workgroup per utterance and direction, running or not
     const int u = chain >> 1;
     const bool forward = kMode != Mode::kGrad || (chain & 1) == 0;
     const Utt m = meta[u];
+    if (!(m.flags & kUttRuns)) return {-1, 0};     // (a run order built on the device lists every utterance)
     // Which recursion: the barrier kernel and the maximum recursion have the log domain only;
     // otherwise the flag that the softmax launch may have raised decides.  A linear-domain chain
     // gives one pair or two to a lane as the launcher planned it (two_pairs_per_lane).
@@ -2766,9 +2899,16 @@ int launch_softmax(const Launch& p, void* stream)
                                     static_cast<int>(p.lay.tasks / 4), static_cast<int>(p.lay.labels8 / 4), p.lay.labels8,
                                     reinterpret_cast<int*>(p.ws + p.lay.labels)};
             auto* row_flags = reinterpret_cast<int*>(p.ws + p.lay.row_flags);
-            NarrowRows rows_of;
+            NarrowArgs args;
+            NarrowRows& rows_of = args.rows;
+            NarrowDevice dv{};
+            if (p.dev_label_lengths) args.plans = plan_table(p.max_label, p.crowded, emission_layout(p.A) == kEmitSymbolMajor);
+            if (p.dev_label_lengths)
+                dv = NarrowDevice{p.labels, p.dev_label_lengths, p.dev_input_lengths, meta, reinterpret_cast<int*>(p.ws + p.lay.order),
+                                  reinterpret_cast<int*>(p.ws + p.lay.status), p.max_label, p.poll_budget,
+                                  p.mode == Mode::kGrad ? 2 : 1, p.crowded, p.needs_barrier};
             const Utt* records = static_cast<const Utt*>(p.host_image);      // (the host reads its own image)
-            for (int b = 0; b < p.B; ++b) {
+            for (int b = 0; records && b < p.B; ++b) {
                 rows_of.frames[b] = records[b].Tb | ((records[b].flags & kUttRuns) ? kRowsRun : 0) |
                                     ((records[b].flags & kUttGradientLater) ? kRowsGradientLater : 0);
                 rows_of.frames_before[b] = records[b].f_off;
@@ -2778,11 +2918,11 @@ int launch_softmax(const Launch& p, void* stream)
             if (f32)
                 hipLaunchKernelGGL(ctc_softmax_narrow_kernel<float>, grid, block, lds, s, static_cast<const float*>(p.x),
                                    image, reinterpret_cast<int*>(p.ws), lse, emit_blank, emit_label, row_flags, sa,
-                                   rows_of, p.T, p.B, p.A, p.blank);
+                                   args, dv, p.T, p.B, p.A, p.blank);
             else
                 hipLaunchKernelGGL(ctc_softmax_narrow_kernel<bf16_t>, grid, block, lds, s, static_cast<const bf16_t*>(p.x),
                                    image, reinterpret_cast<int*>(p.ws), lse, emit_blank, emit_label, row_flags, sa,
-                                   rows_of, p.T, p.B, p.A, p.blank);
+                                   args, dv, p.T, p.B, p.A, p.blank);
         } else if (p.A <= kDirectMaxA) {
             // the smallest alphabets: 64 frames per workgroup, four lanes per frame, so that a
             // workgroup has several kilobytes under way
@@ -2865,6 +3005,11 @@ int launch_lattice(const Launch& p, void* stream)
     wk.domain = reinterpret_cast<int*>(p.ws + p.lay.domain);
     wk.host_flag = p.folded ? p.host_flag : nullptr;
     wk.host_flag_value = p.host_flag_value;
+    if (p.folded && p.dev_status) {
+        wk.status_words = reinterpret_cast<const int*>(p.ws + p.lay.status);
+        wk.status_out = p.dev_status;
+        wk.status_count = p.B;
+    }
     // Workers (kTaskRows): as many workgroups per idle compute unit as make kWorkerWavesPerCu
     // wavefronts, in rounds of n_cu workgroups whose first n_chains leave at once; their LDS holds
     // the list's table and a piece per wavefront.

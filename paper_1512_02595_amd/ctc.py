@@ -32,6 +32,7 @@ KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
            "ctc_workspace_size_device", "ctc_loss_and_grad_device", "ctc_loss_and_grad_device_static",
+           "ctc_profile_kernels_device",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget",
            "ctc_debug_staging_allocations", "ctc_debug_set_overlap", "ctc_debug_replay_emission_fetches")
 
@@ -71,6 +72,9 @@ def load() -> ctypes.CDLL:
     lib.ctc_loss_and_grad_device.restype = st
     lib.ctc_loss_and_grad_device.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp,
                                              ctypes.c_size_t, vp]
+    lib.ctc_profile_kernels_device.restype = st
+    lib.ctc_profile_kernels_device.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp,
+                                               ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_float)]
     lib.ctc_loss_and_grad_device_static.restype = st
     lib.ctc_loss_and_grad_device_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp]
     lib.ctc_kernel_name.restype = ctypes.c_char_p
@@ -200,8 +204,17 @@ def workspace_size_device(T, B, A, max_label_length, dtype=DTYPE_F32) -> int:
 
 def loss_and_grad_device_status(activations_ptr, labels_ptr, label_lengths_ptr, input_lengths_ptr,
                                 max_label_length, T, B, A, blank, dtype, costs_ptr, grads_ptr,
-                                status_ptr, workspace_ptr, workspace_bytes, stream=0) -> int:
-    """Raw ctc_loss_and_grad_device: every array argument is a device address."""
+                                status_ptr, workspace_ptr, workspace_bytes, stream=0, kernel_ms=None) -> int:
+    """Raw ctc_loss_and_grad_device: every array argument is a device address.  With `kernel_ms` (float32
+    numpy array of NUM_KERNELS) the profiling entry point is used and the array is filled."""
+    if kernel_ms is not None:
+        assert kernel_ms.dtype == np.float32 and kernel_ms.size >= NUM_KERNELS
+        return int(load().ctc_profile_kernels_device(
+            ctypes.c_void_p(activations_ptr), ctypes.c_void_p(labels_ptr), ctypes.c_void_p(label_lengths_ptr),
+            ctypes.c_void_p(input_lengths_ptr), int(max_label_length), int(T), int(B), int(A), int(blank),
+            int(dtype), ctypes.c_void_p(costs_ptr), ctypes.c_void_p(grads_ptr), ctypes.c_void_p(status_ptr),
+            ctypes.c_void_p(workspace_ptr), ctypes.c_size_t(workspace_bytes), ctypes.c_void_p(stream),
+            kernel_ms.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
     return int(load().ctc_loss_and_grad_device(
         ctypes.c_void_p(activations_ptr), ctypes.c_void_p(labels_ptr), ctypes.c_void_p(label_lengths_ptr),
         ctypes.c_void_p(input_lengths_ptr), int(max_label_length), int(T), int(B), int(A), int(blank),

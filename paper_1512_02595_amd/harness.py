@@ -142,13 +142,13 @@ class DeviceMetaBatch:
         self.costs.fill_(float("nan"))
         self.status.fill_(-1)
 
-    def run(self, stream=None, want_grad=True):
+    def run(self, stream=None, want_grad=True, kernel_ms=None):
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         ctc.loss_and_grad_device(self.x.data_ptr(), self.labels.data_ptr(), self.label_lengths.data_ptr(),
                                  self.input_lengths.data_ptr(), self.max_label, self.T, self.B, self.A,
                                  self.blank, self.dtype, self.costs.data_ptr(),
                                  self.grads.data_ptr() if want_grad else None, self.status.data_ptr(),
-                                 self.ws_ptr, self.ws_bytes, s)
+                                 self.ws_ptr, self.ws_bytes, s, kernel_ms)
 
     def results(self):
         """(status int, costs float32 [B], grads float32 [T,B,A]) on the host, after synchronising."""

@@ -119,3 +119,26 @@ def test_emission_margins_cover_the_prefetch(plans):
     _, c = plans
     assert c["label_slack"] >= (3 * c["chunk"] - 1) * 1024
     assert c["blank_slack"] >= 3 * c["chunk"] - 1 + c["chunk"] - 1
+
+
+def test_the_two_pair_plan_is_the_cheapest_over_all_wavefront_counts(plans):
+    """plan_waves2 only looks at four wavefront counts from the smallest feasible one (the planners run on the
+    GPU per utterance); here its choice is compared with a search over all counts 2 .. 16 with the same cost
+    model (restated: clocks per step and per hand-over as the header gives them)."""
+    _, c = plans
+    for crowded, L, waves, halo, barrier, _two in c["two_pairs"]:
+        lanes = (L + 2) // 2
+        if lanes <= 64:
+            assert (waves, halo) == (1, 0)
+            continue
+        best, best_cost = None, float("inf")
+        for w in range(2, 17):
+            h = min((64 * w - lanes) // (w - 1), 16)
+            h -= h % 4
+            if h < 4:
+                continue
+            per_simd = (w + 3) // 4
+            cost = w * (110.0 + 300.0 / h) if crowded else (150.0 if per_simd == 1 else per_simd * 110.0) + 300.0 / h + 4.0 * w
+            if cost < best_cost - 1e-9:
+                best, best_cost = (w, h), cost
+        assert (waves, halo) == best, (crowded, L, (waves, halo), best)
