@@ -906,14 +906,14 @@ long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label
                         }
                     }
                 };
-                auto nothing = [](int) {};
+                auto nothing = [](int, bool) {};
                 chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
             }
             for (int lane = 0; lane < kChunk; ++lane) {
                 const int64_t bp = blank_emission_offset(m, f0, fdir, lane);
                 touch(bp, blank_floats);                                  // step 0 (lane 0's is the one used)
                 auto fetch = [&](int s0) { touch(bp + static_cast<int64_t>(fdir) * s0, blank_floats); };
-                auto nothing = [](int) {};
+                auto nothing = [](int, bool) {};
                 chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
             }
         }

@@ -344,13 +344,26 @@ CTC_HOST_DEVICE inline void chain_schedule(int Tb, FetchA&& fetch_a, FetchB&& fe
                                            EndChunk&& end_chunk)
 {
     fetch_a(1);
-    for (int s0 = 1; s0 < Tb; s0 += 2 * kChunk) {
+    int s0 = 1;
+    // Two whole chunks per round, with no branch on the step number inside: the compiler's count of the
+    // memory operations in flight stays exact there, and a wavefront waits for the emissions it is
+    // about to use only, not for the stores of the chunk before.
+    for (; s0 + 2 * kChunk <= Tb; s0 += 2 * kChunk) {
         fetch_b(s0 + kChunk);
-        run_a(s0);
+        run_a(s0, true);
+        end_chunk();
+        fetch_a(s0 + 2 * kChunk);
+        run_b(s0 + kChunk, true);
+        end_chunk();
+    }
+    // the last, short round (run_x(s0, false) checks every step against the end)
+    if (s0 < Tb) {
+        fetch_b(s0 + kChunk);
+        run_a(s0, false);
         end_chunk();
         fetch_a(s0 + 2 * kChunk);
         if (s0 + kChunk < Tb) {
-            run_b(s0 + kChunk);
+            run_b(s0 + kChunk, false);
             end_chunk();
         }
     }

@@ -1344,9 +1344,9 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     // inside the instruction cache that two compute units share.
     // Whole chunks run without looking at the step number; only the last, short chunk of a
     // chain checks every step against the end.
-    auto run = [&](const float (&el)[kChunk], const float eb_coded, int s0) {
+    auto run = [&](const float (&el)[kChunk], const float eb_coded, int s0, bool whole) {
         const float eb = kCoded ? emission_log2(eb_coded) : eb_coded;
-        if (s0 + kChunk <= Tb) {
+        if (whole) {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i) advance(s0 + i, readlane(eb, i), el[i]);
         } else {
@@ -1355,8 +1355,10 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
                 if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
         }
     };
-    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); }, [&](int s0) { fetch(el_b, eb_b, s0); },
-                   [&](int s0) { run(el_a, eb_a, s0); }, [&](int s0) { run(el_b, eb_b, s0); }, end_chunk);
+    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0) { fetch(el_b, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0, bool whole) { run(el_a, eb_a, s0, whole); }, [&](int s0, bool whole) { run(el_b, eb_b, s0, whole); },
+                   end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L-1.
@@ -1621,8 +1623,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
             el[i] = *ep;
         }
     };
-    auto run = [&](const float (&el)[kChunk], const float eb, int s0) {
-        if (s0 + kChunk <= Tb) {
+    auto run = [&](const float (&el)[kChunk], const float eb, int s0, bool whole) {
+        if (whole) {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i) advance(readlane(eb, i), el[i]);
         } else {
@@ -1631,8 +1633,10 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
                 if (s0 + i < Tb) advance(readlane(eb, i), el[i]);
         }
     };
-    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); }, [&](int s0) { fetch(el_b, eb_b, s0); },
-                   [&](int s0) { run(el_a, eb_a, s0); }, [&](int s0) { run(el_b, eb_b, s0); }, end_chunk);
+    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0) { fetch(el_b, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0, bool whole) { run(el_a, eb_a, s0, whole); }, [&](int s0, bool whole) { run(el_b, eb_b, s0, whole); },
+                   end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1), from the lane of pair L (exact, as is the
@@ -1849,10 +1853,10 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         skip_a_scale = skip_a ? scale : 0.0;
     };
 
-    auto store = [&]() {
+    auto store = [&](double label_a, double label_b) {
         if (kMode == Mode::kGrad) {
-            const uint32_t a = static_cast<uint32_t>(__double2hiint(kBackward ? ia_label : va_label));
-            const uint32_t b = static_cast<uint32_t>(__double2hiint(kBackward ? ib_label : vb_label));
+            const uint32_t a = static_cast<uint32_t>(__double2hiint(label_a));
+            const uint32_t b = static_cast<uint32_t>(__double2hiint(label_b));
             // (one 8-byte word: b's value in the upper half when a's column comes first)
             lattice_store(reinterpret_cast<unsigned long long*>(op),
                           kBackward ? (static_cast<unsigned long long>(a) << 32) | b : (static_cast<unsigned long long>(b) << 32) | a);
@@ -1865,13 +1869,13 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             lattice_store(reinterpret_cast<unsigned long long*>(xp),
                           (static_cast<unsigned long long>(static_cast<unsigned>(frame)) << 32) | static_cast<unsigned>(frame));
     };
-    auto finish_step = [&](float eb, float ela, float elb) {
+    auto first_step = [&](float eb, float ela, float elb) {
         const double ebd = static_cast<double>(eb);
         va_blank = ia_blank * ebd;
         va_label = ia_label * static_cast<double>(ela);
         vb_blank = ib_blank * ebd;
         vb_label = ib_label * static_cast<double>(elb);
-        store();
+        store(kBackward ? ia_label : va_label, kBackward ? ib_label : vb_label);
     };
     auto end_chunk = [&]() {
         if (--until_hand_over == 0) {
@@ -1882,13 +1886,46 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         xp += xstride;                                   // the next chunk's exponent row
         store_frame();
     };
+    // One step.  A lone wavefront on its SIMD issues an instruction every 2 ns, but one that reads the
+    // result of the instruction before it only after 4 ns, and of the one before that after 3 (measured
+    // on gfx950 with chains of dependent v_fma_f64).  The step is therefore written so that no
+    // instruction needs a result younger than two instructions, and the order of the statements is
+    // the order of issue (pin): the sums that do not need the neighbour's value come first, while the
+    // two DPP moves are on their way, and the two pairs' products alternate.
+    //   label' = (label + blank + skip * previous label) * emission, as fma(previous, skip, label + blank)
+    auto pin = []() { __builtin_amdgcn_sched_barrier(0); };
     auto advance = [&](float eb, float ela, float elb) {
+#pragma clang fp contract(off)                           // (a product stays a product: fusing it into the next step's sum would tie the steps together)
         const double prev = from_lane_below(vb_label);
-        ia_blank = __builtin_fma(prev, scale, va_blank);
-        ia_label = va_label + __builtin_fma(prev, skip_a_scale, va_blank);
+        pin();
+        const double ub = vb_blank + vb_label;
+        pin();
+        const double ua = va_blank + va_label;
+        pin();
         ib_blank = vb_blank + va_label;
-        ib_label = vb_label + __builtin_fma(va_label, skip_b_one, vb_blank);
-        finish_step(eb, ela, elb);
+        pin();
+        const double ela_d = static_cast<double>(ela);
+        pin();
+        ib_label = __builtin_fma(va_label, skip_b_one, ub);
+        pin();
+        ia_label = __builtin_fma(prev, skip_a_scale, ua);
+        pin();
+        ia_blank = __builtin_fma(prev, scale, va_blank);
+        pin();
+        const double elb_d = static_cast<double>(elb);
+        pin();
+        const double eb_d = static_cast<double>(eb);
+        pin();
+        va_label = ia_label * ela_d;
+        pin();
+        vb_label = ib_label * elb_d;
+        pin();
+        va_blank = ia_blank * eb_d;
+        pin();
+        vb_blank = ib_blank * eb_d;
+        pin();
+        store(kBackward ? ia_label : va_label, kBackward ? ib_label : vb_label);
+        pin();
     };
     auto readlane = [](float v, int l) {
         return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
@@ -1896,7 +1933,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
 
     // step 0
     store_frame();                                       // exponent row 0: step 0 and the first chunk
-    finish_step(readlane(*bp, 0), *epa, *epb);
+    first_step(readlane(*bp, 0), *epa, *epb);
 
     float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk], eb_a, eb_b;
     auto fetch = [&](float (&ela)[kChunk], float (&elb)[kChunk], float& eb, int s0) {
@@ -1914,8 +1951,8 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             elb[i] = *epb;
         }
     };
-    auto run = [&](const float (&ela)[kChunk], const float (&elb)[kChunk], const float eb, int s0) {
-        if (s0 + kChunk <= Tb) {
+    auto run = [&](const float (&ela)[kChunk], const float (&elb)[kChunk], const float eb, int s0, bool whole) {
+        if (whole) {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i) advance(readlane(eb, i), ela[i], elb[i]);
         } else {
@@ -1924,8 +1961,10 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
                 if (s0 + i < Tb) advance(readlane(eb, i), ela[i], elb[i]);
         }
     };
-    chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, s0); }, [&](int s0) { fetch(ela_b, elb_b, eb_b, s0); },
-                   [&](int s0) { run(ela_a, elb_a, eb_a, s0); }, [&](int s0) { run(ela_b, elb_b, eb_b, s0); }, end_chunk);
+    chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0) { fetch(ela_b, elb_b, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0, bool whole) { run(ela_a, elb_a, eb_a, s0, whole); },
+                   [&](int s0, bool whole) { run(ela_b, elb_b, eb_b, s0, whole); }, end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L - 1.
