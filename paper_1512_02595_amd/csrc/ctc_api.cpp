@@ -86,6 +86,8 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.lse = off;    off = align_up(off + static_cast<size_t>(B) * T * sizeof(float));
     l.emit_blank = off;
     off = align_up(off + (static_cast<size_t>(frames) + 2 * kBlankSlack) * sizeof(float));
+    l.emit_blank64 = off;
+    off = align_up(off + (static_cast<size_t>(frames) + 2 * kBlankSlack) * sizeof(double));
     l.emit_label = off;
     off = align_up(off + (static_cast<size_t>(emit) + 2 * kLabelSlack) * sizeof(float));
     l.alpha = off;  off = align_up(off + static_cast<size_t>(ab) * sizeof(double));
@@ -913,6 +915,16 @@ long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label
                 const int64_t bp = blank_emission_offset(m, f0, fdir, lane);
                 touch(bp, blank_floats);                                  // step 0 (lane 0's is the one used)
                 auto fetch = [&](int s0) { touch(bp + static_cast<int64_t>(fdir) * s0, blank_floats); };
+                auto nothing = [](int, bool) {};
+                chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
+            }
+            {
+                // the scalar windows of the linear-domain chains (the block of doubles has the same extent)
+                touch(blank64_window(m, f0, fdir, 0) + (fdir > 0 ? 0 : kChunk - 1), blank_floats);     // step 0
+                auto fetch = [&](int s0) {
+                    touch(blank64_window(m, f0, fdir, s0), blank_floats);
+                    touch(blank64_window(m, f0, fdir, s0) + kChunk - 1, blank_floats);
+                };
                 auto nothing = [](int, bool) {};
                 chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
             }

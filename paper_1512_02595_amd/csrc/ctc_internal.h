@@ -331,6 +331,14 @@ CTC_HOST_DEVICE inline int64_t blank_emission_offset(const Utt& m, int f0, int f
 {
     return kBlankSlack + m.f_off + f0 + fdir * (lane & (kChunk - 1));
 }
+// The linear-domain chains take the blank's probability as an fp64 scalar, a chunk's kChunk frames in one
+// scalar load out of a block of doubles (Layout::emit_blank64, same slack in doubles): the window of the
+// chunk that starts at step s0 is w[0] .. w[kChunk - 1] from this offset, in frame order (a backward chain
+// uses it last to first).
+CTC_HOST_DEVICE inline int64_t blank64_window(const Utt& m, int f0, int fdir, int s0)
+{
+    return kBlankSlack + m.f_off + f0 + (fdir > 0 ? s0 : -s0 - (kChunk - 1));
+}
 // One fetch out of a symbol-major block reads the kChunk floats next to the pointer p in the chain's
 // direction, p[first] .. p[first + kChunk - 1], and moves p on by kChunk steps.
 CTC_HOST_DEVICE constexpr int fetch_window_first(bool backward) { return backward ? -kChunk : 1; }
@@ -398,6 +406,8 @@ struct Layout {
     size_t emit_blank = 0; // float[slack + sum Tb + slack]  emission of blank per frame: the probability y, or
                            // log2 y (negative) where y < 2^kLinearMinLog2 (plain log2 y in launches for
                            // the most probable alignment)
+    size_t emit_blank64 = 0; // double[slack + sum Tb + slack]  the blank's probability once more, for the scalar loads of
+                             // the linear-domain chains (blank64_window)
     size_t emit_label = 0; // float[slack + sum Tb*L + slack]  emission of each label position, same coding
                            // (sum Tb*A for small alphabets: emission_layout); the front slack starts with
                            // the constants that lanes without a label state read: probability 0 and log 0

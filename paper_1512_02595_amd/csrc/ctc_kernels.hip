@@ -344,6 +344,7 @@ struct SetupArgs {
     int* leftover;        // per utterance: rows left to the gradient launch
     float* log0;          // kEmissionConstants floats that lattice lanes without a label state read as their
                           // emission: probability 0 (linear-domain chains) and log 0 (log-domain chains)
+    double* emit_blank64; // the blank's probability per frame as fp64 (Layout::emit_blank64)
     int* host_flag;       // pinned host word: receives flag_value once the upload has been consumed
     int flag_value;
     bool plain_logs;      // emissions are stored as log2 probabilities throughout (most probable alignment)
@@ -480,7 +481,11 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
             store_elem(grow, k, fast_exp2(fmaf(load_elem(row, k), kLog2e, -l2)));
     bool small = false;
     if (threadIdx.x == 0)
-        emit_blank[kBlankSlack + m.f_off + t] = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
+    {
+        const float e = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
+        emit_blank[kBlankSlack + m.f_off + t] = e;
+        sa.emit_blank64[kBlankSlack + m.f_off + t] = static_cast<double>(emission_probability(e));
+    }
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = threadIdx.x; j < m.L; j += kRowThreads)
@@ -556,7 +561,11 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
     }
     bool small = false;
     if (tid == 0)
-        emit_blank[kBlankSlack + m.f_off + t] = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
+    {
+        const float e = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
+        emit_blank[kBlankSlack + m.f_off + t] = e;
+        sa.emit_blank64[kBlankSlack + m.f_off + t] = static_cast<double>(emission_probability(e));
+    }
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = tid; j < m.L; j += kRowThreads)
@@ -629,6 +638,7 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
     if (tid < rows) {
         const float e = lp[tid * A + blank];
         emit_blank[kBlankSlack + m.f_off + t0 + tid] = e;
+        sa.emit_blank64[kBlankSlack + m.f_off + t0 + tid] = static_cast<double>(emission_probability(e));
         small = !sa.plain_logs && e < 0.0f;
     }
     if (m.e_direct == kEmitSymbolMajor) {
@@ -891,6 +901,7 @@ void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image,
     if (tid < rows) {
         const float e = lp[tid * A + blank];
         emit_blank[kBlankSlack + m.f_off + t0 + tid] = e;
+        sa.emit_blank64[kBlankSlack + m.f_off + t0 + tid] = static_cast<double>(emission_probability(e));
         small = !sa.plain_logs && e < 0.0f;
     }
     // The emission block: a symbol's frames side by side, e_pitch floats per symbol (fetch_frames).
@@ -1009,6 +1020,15 @@ __device__ __forceinline__ double shift_up(double v, int& into_lo, int& into_hi)
     into_lo = __builtin_amdgcn_update_dpp(into_lo, __double2loint(v), 0x138, 0xf, 0xf, false);
     into_hi = __builtin_amdgcn_update_dpp(into_hi, __double2hiint(v), 0x138, 0xf, 0xf, false);
     return __hiloint2double(into_hi, into_lo);
+}
+
+// max(window of the lane below, mine) in one instruction, the DPP shift as an operand of the maximum.
+// Lane 0 has no lane below: the instruction then leaves its register alone, and `window` starts out as
+// the lanes' own values.  (s_nop 1: a DPP operand must be two wait states old.)
+__device__ __forceinline__ int window_max_step(int window, int mine)
+{
+    asm("s_nop 1\n\tv_max_i32_dpp %0, %0, %1 wave_shr:1 row_mask:0xf bank_mask:0xf" : "+v"(window) : "v"(mine));
+    return window;
 }
 
 constexpr int kHaloEntries = 64;      // 16-byte entries of one wavefront boundary's exchange buffer (2 x 32)
@@ -1424,6 +1444,7 @@ constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real 
 template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
                                                  const float* __restrict__ emit_blank,
+                                                 const double* __restrict__ emit_blank64,
                                                  const float* __restrict__ emit_label,
                                                  uint32_t* __restrict__ out, int* __restrict__ out_exponents,
                                                  double* __restrict__ logp,
@@ -1450,7 +1471,11 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     const float* ep = emit_label + label_emission_offset(m, has_label, direct, has_label ? lab[li] : 0, li, f0, kZeroEmission);
     const int64_t estride = label_emission_step(m, has_label, false, fdir);
     const int eadvance = static_cast<int>(label_emission_step(m, has_label, true, fdir)) * kChunk;
-    const float* bp = emit_blank + blank_emission_offset(m, f0, fdir, lane);
+    // The blank's probability is the same for all lanes: an fp64 scalar, a chunk's frames in one load.
+    (void)emit_blank;
+    const double* const bq = emit_blank64;
+    auto blank_window = [&](int s0) { return bq + blank64_window(m, f0, fdir, s0); };
+    auto blank_of = [&](const double* w, int i) { return w[kBackward ? kChunk - 1 - i : i]; };
     // Values by frame, exponents by chunk (exponent_row): the lane's frame is what it is until the
     // chunk ends.
     const bool stores = kMode == Mode::kGrad && active && has_label;
@@ -1554,7 +1579,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         const int mine = (top > 0.0) ? frame + __builtin_amdgcn_frexp_exp(top) : kNoExponent;
         int window = mine;
 #pragma unroll
-        for (int k = 0; k < kChunk; ++k) window = max(mine, shift_up_int(window));
+        for (int k = 0; k < kChunk; ++k) window = window_max_step(window, mine);
         const int rise = frame - window;
         v_blank = __builtin_amdgcn_ldexp(v_blank, rise);
         v_label = __builtin_amdgcn_ldexp(v_label, rise);
@@ -1566,12 +1591,6 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         skip_scale = skip_ok ? scale : 0.0;
     };
 
-    auto finish_step = [&](float eb, float el) {
-        v_blank = i_blank * static_cast<double>(eb);
-        v_label = i_label * static_cast<double>(el);
-        if (kMode == Mode::kGrad) lattice_store(op, static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label)));
-        op += ostride;
-    };
     auto end_chunk = [&]() {
         if (kSync == Sync::kHalo) {
             if (--until_hand_over == 0) {
@@ -1584,23 +1603,42 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         xp += xstride;
         if (kMode == Mode::kGrad) lattice_store(xp, frame);
     };
-    auto advance = [&](float eb, float el) {
-        // The blank state sums its own value and the label of the pair before; the label state
-        // its own value, the old blank and, where the skip is allowed, that label too.
+    // One step.  The blank state sums its own value and the label of the pair before; the label state
+    // its own value, the old blank and, where the skip is allowed, that label too:
+    //   label' = fma(previous label, skip, label + blank) * emission.
+    // A lone wavefront on its SIMD issues an instruction every 2 ns, but one that reads the result of
+    // the instruction before it only after 4 ns, and of the one before that after 3 (measured on gfx950
+    // with chains of dependent v_fma_f64).  So the statements are in the order of issue (pin keeps the
+    // compiler from moving them), and none needs a result younger than two instructions: the sum and
+    // the conversions fill the time the two DPP moves take, the address the time of the multiply-adds.
+    auto pin = []() { __builtin_amdgcn_sched_barrier(0); };
+    auto advance = [&](double eb_d, float el) {
+#pragma clang fp contract(off)                           // (a product stays a product: fused into the next step's sum it would tie the steps together)
         const double prev = from_prev_pair(v_label);
+        pin();
+        const double u = v_blank + v_label;
+        pin();
+        const double el_d = static_cast<double>(el);
+        pin();
+        i_label = __builtin_fma(prev, skip_scale, u);
+        pin();
         i_blank = __builtin_fma(prev, scale, v_blank);
-        i_label = v_label + __builtin_fma(prev, skip_scale, v_blank);
-        finish_step(eb, el);
-    };
-    auto readlane = [](float v, int l) {
-        return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
+        pin();
+        uint32_t* const here = op;
+        op += ostride;
+        pin();
+        v_label = i_label * el_d;
+        pin();
+        v_blank = i_blank * eb_d;
+        pin();
+        if (kMode == Mode::kGrad) lattice_store(here, static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label)));
+        pin();
     };
 
     // step 0
     {
-        const float ebv = *bp;
         const float el = *ep;
-        v_blank = i_blank * static_cast<double>(readlane(ebv, 0));
+        v_blank = i_blank * blank_of(blank_window(0), 0);
         v_label = i_label * static_cast<double>(el);
         if (kMode == Mode::kGrad) {
             lattice_store(op, static_cast<uint32_t>(__double2hiint(kBackward ? i_label : v_label)));
@@ -1610,9 +1648,15 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     }
 
     // Emissions of steps 1..: two register sets, one in use, one being filled (as run_chain_log).
-    float el_a[kChunk], el_b[kChunk], eb_a, eb_b;
-    auto fetch = [&](float (&el)[kChunk], float& eb, int s0) {
-        eb = bp[fdir * s0];
+    float el_a[kChunk], el_b[kChunk];
+    double eb_a[kChunk] = {}, eb_b[kChunk] = {};
+    // (Scalar loads return in any order, so a wavefront can only wait for all of them: the set in use is
+    // waited for before the other set's load goes out, while that wait is still free.)
+    auto fetch = [&](float (&el)[kChunk], double (&eb)[kChunk], const double (&in_use)[kChunk], int s0) {
+        asm volatile("" : : "s"(in_use[0]), "s"(in_use[kChunk - 1]));
+        const double* const w = blank_window(s0);
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) eb[i] = blank_of(w, i);
         if (direct) {
             fetch_frames<kBackward>(ep, eadvance, el);
             return;
@@ -1623,18 +1667,18 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
             el[i] = *ep;
         }
     };
-    auto run = [&](const float (&el)[kChunk], const float eb, int s0, bool whole) {
+    auto run = [&](const float (&el)[kChunk], const double (&eb)[kChunk], int s0, bool whole) {
         if (whole) {
 #pragma unroll
-            for (int i = 0; i < kChunk; ++i) advance(readlane(eb, i), el[i]);
+            for (int i = 0; i < kChunk; ++i) advance(eb[i], el[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i)
-                if (s0 + i < Tb) advance(readlane(eb, i), el[i]);
+                if (s0 + i < Tb) advance(eb[i], el[i]);
         }
     };
-    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
-                   [&](int s0) { fetch(el_b, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0) { fetch(el_b, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
                    [&](int s0, bool whole) { run(el_a, eb_a, s0, whole); }, [&](int s0, bool whole) { run(el_b, eb_b, s0, whole); },
                    end_chunk);
 
@@ -1691,6 +1735,7 @@ struct alignas(4) ExponentPair { int lo, hi; };
 template <bool kBackward, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, const int* __restrict__ labels,
                                                   const float* __restrict__ emit_blank,
+                                                  const double* __restrict__ emit_blank64,
                                                   const float* __restrict__ emit_label,
                                                   uint32_t* __restrict__ out, int* __restrict__ out_exponents,
                                                   double* __restrict__ logp,
@@ -1723,7 +1768,10 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     const int advance_b = static_cast<int>(label_emission_step(m, has_b, true, fdir)) * kChunk;
     const int64_t stride_a = label_emission_step(m, has_a, false, fdir);
     const int64_t stride_b = label_emission_step(m, has_b, false, fdir);
-    const float* bp = emit_blank + blank_emission_offset(m, f0, fdir, lane);
+    (void)emit_blank;                                    // the blank's probability: fp64 scalars (see run_chain_linear)
+    const double* const bq = emit_blank64;
+    auto blank_window = [&](int s0) { return bq + blank64_window(m, f0, fdir, s0); };
+    auto blank_of = [&](const double* w, int i) { return w[kBackward ? kChunk - 1 - i : i]; };
     // Output: label state i sits in column 1 + i; the lane's two are columns 1 + min(lia, lib) and
     // the next one.  (has_a false: nothing of this lane is kept.)
     const bool stores = kMode == Mode::kGrad && active && has_a;
@@ -1841,7 +1889,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         const int mine = (top > 0.0) ? frame + __builtin_amdgcn_frexp_exp(top) : kNoExponent;
         int window = mine;
 #pragma unroll
-        for (int k = 0; k < kChunk / 2; ++k) window = max(mine, shift_up_int(window));
+        for (int k = 0; k < kChunk / 2; ++k) window = window_max_step(window, mine);
         const int rise = frame - window;
         va_blank = __builtin_amdgcn_ldexp(va_blank, rise);
         va_label = __builtin_amdgcn_ldexp(va_label, rise);
@@ -1869,8 +1917,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             lattice_store(reinterpret_cast<unsigned long long*>(xp),
                           (static_cast<unsigned long long>(static_cast<unsigned>(frame)) << 32) | static_cast<unsigned>(frame));
     };
-    auto first_step = [&](float eb, float ela, float elb) {
-        const double ebd = static_cast<double>(eb);
+    auto first_step = [&](double ebd, float ela, float elb) {
         va_blank = ia_blank * ebd;
         va_label = ia_label * static_cast<double>(ela);
         vb_blank = ib_blank * ebd;
@@ -1894,7 +1941,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     // two DPP moves are on their way, and the two pairs' products alternate.
     //   label' = (label + blank + skip * previous label) * emission, as fma(previous, skip, label + blank)
     auto pin = []() { __builtin_amdgcn_sched_barrier(0); };
-    auto advance = [&](float eb, float ela, float elb) {
+    auto advance = [&](double eb_d, float ela, float elb) {
 #pragma clang fp contract(off)                           // (a product stays a product: fusing it into the next step's sum would tie the steps together)
         const double prev = from_lane_below(vb_label);
         pin();
@@ -1914,8 +1961,6 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         pin();
         const double elb_d = static_cast<double>(elb);
         pin();
-        const double eb_d = static_cast<double>(eb);
-        pin();
         va_label = ia_label * ela_d;
         pin();
         vb_label = ib_label * elb_d;
@@ -1927,17 +1972,18 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         store(kBackward ? ia_label : va_label, kBackward ? ib_label : vb_label);
         pin();
     };
-    auto readlane = [](float v, int l) {
-        return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
-    };
 
     // step 0
     store_frame();                                       // exponent row 0: step 0 and the first chunk
-    first_step(readlane(*bp, 0), *epa, *epb);
+    first_step(blank_of(blank_window(0), 0), *epa, *epb);
 
-    float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk], eb_a, eb_b;
-    auto fetch = [&](float (&ela)[kChunk], float (&elb)[kChunk], float& eb, int s0) {
-        eb = bp[fdir * s0];
+    float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk];
+    double eb_a[kChunk] = {}, eb_b[kChunk] = {};
+    auto fetch = [&](float (&ela)[kChunk], float (&elb)[kChunk], double (&eb)[kChunk], const double (&in_use)[kChunk], int s0) {
+        asm volatile("" : : "s"(in_use[0]), "s"(in_use[kChunk - 1]));     // (see run_chain_linear)
+        const double* const w = blank_window(s0);
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) eb[i] = blank_of(w, i);
         if (direct) {
             fetch_frames<kBackward>(epa, advance_a, ela);
             fetch_frames<kBackward>(epb, advance_b, elb);
@@ -1951,18 +1997,18 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             elb[i] = *epb;
         }
     };
-    auto run = [&](const float (&ela)[kChunk], const float (&elb)[kChunk], const float eb, int s0, bool whole) {
+    auto run = [&](const float (&ela)[kChunk], const float (&elb)[kChunk], const double (&eb)[kChunk], int s0, bool whole) {
         if (whole) {
 #pragma unroll
-            for (int i = 0; i < kChunk; ++i) advance(readlane(eb, i), ela[i], elb[i]);
+            for (int i = 0; i < kChunk; ++i) advance(eb[i], ela[i], elb[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i)
-                if (s0 + i < Tb) advance(readlane(eb, i), ela[i], elb[i]);
+                if (s0 + i < Tb) advance(eb[i], ela[i], elb[i]);
         }
     };
-    chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
-                   [&](int s0) { fetch(ela_b, elb_b, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+    chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                   [&](int s0) { fetch(ela_b, elb_b, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
                    [&](int s0, bool whole) { run(ela_a, elb_a, eb_a, s0, whole); },
                    [&](int s0, bool whole) { run(ela_b, elb_b, eb_b, s0, whole); }, end_chunk);
 
@@ -2087,7 +2133,7 @@ struct ChainRun {
 template <Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, const int* __restrict__ order,
                                              const int* __restrict__ labels,
-                                             const float* __restrict__ emit_blank,
+                                             const float* __restrict__ emit_blank, const double* __restrict__ emit_blank64,
                                              const float* __restrict__ emit_label,
                                              const LatticeOut lat,
                                              double* __restrict__ logp, float* __restrict__ costs,
@@ -2152,17 +2198,17 @@ __device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, c
         if (two_pairs) {
             if constexpr (kSync == Sync::kHalo) {
                 if (forward)
-                    run_chain_linear2<false, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
+                    run_chain_linear2<false, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_blank64, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
                 else
-                    run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
+                    run_chain_linear2<true, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_blank64, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
             }
             return {u, waves};
         }
         if (!in_log_domain) {
             if (forward)
-                run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
+                run_chain_linear<false, kSync, kMode, kSymbolMajor>(m, u, labels, emit_blank, emit_blank64, emit_label, lat.alpha, lat.alpha_exponents, logp, costs, chain_err, sink, lds);
             else
-                run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
+                run_chain_linear<true, kSync, Mode::kGrad, kSymbolMajor>(m, u, labels, emit_blank, emit_blank64, emit_label, lat.beta, lat.beta_exponents, logp, costs, chain_err, sink, lds);
             return {u, waves};
         }
     }
@@ -2481,6 +2527,7 @@ template <Mode kMode, bool kSymbolMajor>
 __global__ __launch_bounds__(64)
 void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__ order,
                            const int* __restrict__ labels, const float* __restrict__ emit_blank,
+                           const double* __restrict__ emit_blank64,
                            const float* __restrict__ emit_label,
                            const LatticeOut lat,
                            double* __restrict__ logp, float* __restrict__ costs,
@@ -2494,7 +2541,7 @@ void ctc_lattice_kernel_w1(const Utt* __restrict__ meta, const int* __restrict__
         }
     }
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_started(wk, order[blockIdx.x]);
-    const ChainRun ran = lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat,
+    const ChainRun ran = lattice_body<Sync::kNone, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_blank64, emit_label, lat,
                                                                    logp, costs, chain_err, sink, nullptr, wk);
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, ran.u, ran.waves, nullptr);
 }
@@ -2504,6 +2551,7 @@ template <Mode kMode, bool kSymbolMajor>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ order,
                         const int* __restrict__ labels, const float* __restrict__ emit_blank,
+                        const double* __restrict__ emit_blank64,
                         const float* __restrict__ emit_label,
                         const LatticeOut lat,
                         double* __restrict__ logp, float* __restrict__ costs,
@@ -2517,7 +2565,7 @@ void ctc_lattice_kernel(const Utt* __restrict__ meta, const int* __restrict__ or
         }
     }
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_started(wk, order[blockIdx.x]);
-    const ChainRun ran = lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat,
+    const ChainRun ran = lattice_body<Sync::kHalo, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_blank64, emit_label, lat,
                                                                    logp, costs, chain_err, sink, halo_lds, wk);
     if constexpr (kMode == Mode::kGrad && kSymbolMajor) chain_ended(wk, ran.u, ran.waves, halo_lds);
 }
@@ -2528,13 +2576,14 @@ template <Mode kMode, bool kSymbolMajor>
 __global__ __launch_bounds__(1024)
 void ctc_lattice_kernel_barrier(const Utt* __restrict__ meta, const int* __restrict__ order,
                                 const int* __restrict__ labels, const float* __restrict__ emit_blank,
+                                const double* __restrict__ emit_blank64,
                                 const float* __restrict__ emit_label,
                                 const LatticeOut lat,
                                 double* __restrict__ logp, float* __restrict__ costs,
                                 int* __restrict__ chain_err, uint32_t* __restrict__ sink, const WorkerArgs wk)
 {
     __shared__ double xch[2][16];
-    lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_label, lat, logp,
+    lattice_body<Sync::kBarrier, kMode, kSymbolMajor>(meta, order, labels, emit_blank, emit_blank64, emit_label, lat, logp,
                                                costs, chain_err, sink, &xch[0][0], wk);
 }
 
@@ -2922,6 +2971,7 @@ int launch_softmax(const Launch& p, void* stream)
                        reinterpret_cast<int*>(p.ws + p.lay.chain_err),
                        reinterpret_cast<int*>(p.ws + p.lay.done), reinterpret_cast<int*>(p.ws + p.lay.where),
                        reinterpret_cast<int*>(p.ws + p.lay.leftover), emit_label,
+                       reinterpret_cast<double*>(p.ws + p.lay.emit_blank64),
                        p.folded ? nullptr : p.host_flag, p.host_flag_value, p.mode == Mode::kBest,
                        // few utterances: spread each one's grouping over several workgroups (its
                        // latency counts); many: one workgroup each keeps the chip busy already
@@ -3082,7 +3132,8 @@ int launch_lattice(const Launch& p, void* stream)
     const dim3 grid(n_groups), block(64 * p.max_waves);
     auto s = static_cast<hipStream_t>(stream);
 #define CTC_LAUNCH_LATTICE(KERNEL)                                                                 \
-    hipLaunchKernelGGL(KERNEL, grid, block, lds_bytes, s, meta, order, labels, emit_blank, emit_label,     \
+    hipLaunchKernelGGL(KERNEL, grid, block, lds_bytes, s, meta, order, labels, emit_blank,                 \
+                       reinterpret_cast<const double*>(p.ws + p.lay.emit_blank64), emit_label,            \
                        lat, logp, p.costs, chain_err, sink, wk)
     // The emission layout is the launch's (emission_layout), and a template parameter of the kernels.
     const bool symbol_major = emission_layout(p.A) == kEmitSymbolMajor;
