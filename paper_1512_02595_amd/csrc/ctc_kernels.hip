@@ -1440,6 +1440,21 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
 // Storage (Mode::kGrad): the label state's value and its frame at every step, in one word
 // (pack_state).  The gradient kernels do not know which kind of chain wrote the lattice.
 constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real one, far from int32's ends
+// A renewal is put off while it is not needed (a third of a chunk's instructions are the renewal's): every
+// pair of the wavefront has mass, lies within [2^kEasyLow, 2^kEasyHigh] of its frame, and at the last
+// renewal no frame lay more than kSmoothFrames below the frame of the lane below it.  Then one more chunk
+// takes a value down to 2^(kEasyLow - 800) at worst, and up to 3^kChunk times the largest of the nine-pair
+// window in this lane's frame, 2^(kEasyHigh + kChunk * kSmoothFrames + 13): both far inside fp64.  The
+// frames, the scale factors and the exponent rows simply stay what they are.
+constexpr int kEasyLow = -200, kEasyHigh = 100;
+constexpr int kSmoothFrames = 60;
+// The test, on the high dword of the largest value of a lane (biased exponent in bits 20..30): one
+// subtraction and one unsigned compare; zero, denormals, infinities and NaN fail it.
+__device__ __forceinline__ bool outside_easy_range(double top)
+{
+    const unsigned hi = static_cast<unsigned>(__double2hiint(top));
+    return hi - (static_cast<unsigned>(1023 + kEasyLow) << 20) >= (static_cast<unsigned>(kEasyHigh - kEasyLow + 1) << 20);
+}
 
 template <bool kBackward, Sync kSync, Mode kMode, bool kSymbolMajor>
 __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const int* __restrict__ labels,
@@ -1570,6 +1585,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     // leaves lane 0 what it had).
     int prev_lo = 0, prev_hi = 0;
     auto from_prev_pair = [&](double mine) { return shift_up(mine, prev_lo, prev_hi); };
+    const unsigned long long counted = __ballot(j >= 0 && j <= L);   // the lanes with a pair of the label (the others hold zeros)
+    unsigned long long rough = ~0ull;                    // lanes whose frame lies far below that of the lane below (kSmoothFrames)
     auto shift_up_int = [](int v) { return __builtin_amdgcn_update_dpp(kNoExponent, v, 0x138, 0xf, 0xf, false); };
 
     // New frames after a chunk.  (A pair whose window holds no mass yet gets kNoExponent: its
@@ -1586,19 +1603,28 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         frame = window;
         // 2^1023 is the largest factor there is; a pair that far below its neighbour has been
         // rounded away already.
-        const int below = min(max(shift_up_int(window) - window, -1100), 1023);
+        const int down = shift_up_int(window) - window;
+        const int below = min(max(down, -1100), 1023);
         scale = __builtin_amdgcn_ldexp(1.0, below);
         skip_scale = skip_ok ? scale : 0.0;
+        rough = __ballot(down > kSmoothFrames) & counted;
+    };
+    auto renewal_due = [&]() {
+        return ((__ballot(outside_easy_range(fmax(v_blank, v_label))) & counted) | rough) != 0;
     };
 
     auto end_chunk = [&]() {
+        bool handed = false;
         if (kSync == Sync::kHalo) {
             if (--until_hand_over == 0) {
-                hand_over();
+                hand_over();                             // (the halo lanes come back with other frames)
                 until_hand_over = chunks_per_hand_over;
+                handed = true;
             }
         }
-        renew_frames();
+        // (Only chains of one wavefront put renewals off: the wavefronts of a longer chain keep in step
+        // best when all of them do the same work per chunk; measured 5 % slower otherwise.)
+        if (kSync != Sync::kNone || handed || renewal_due()) renew_frames();
         // the next chunk's exponent row
         xp += xstride;
         if (kMode == Mode::kGrad) lattice_store(xp, frame);
