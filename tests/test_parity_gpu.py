@@ -151,6 +151,43 @@ def test_steep_fronts_just_inside_the_linear_domain():
     check(batch)
 
 
+def test_renewals_put_off_in_single_wavefront_chains():
+    """Batches whose labels all fit one wavefront run the chain that renews its lanes' exponents only
+    when needed.  Long quiet stretches (most renewals skipped), steep fronts (every chunk shrinks the
+    values by hundreds of binary orders), peaky rows (neighbouring lanes far apart) and stretches of
+    likely and of nearly impossible label symbols in turn (values that grow again after shrinking)."""
+    check(wl.make_random(91, T=1200, B=6, A=29, max_label=60, min_input=1000, sigma=2.0, feasible_only=True))
+    rng = np.random.default_rng(92)
+    T, B, A = 600, 5, 4
+    lab_len = np.array([63, 40, 12, 1, 55])
+    labs = [rng.integers(1, A, size=n) for n in lab_len]
+    x = rng.standard_normal((T, B, A)).astype(np.float32)
+    x[:, :, 0] += 62.0                                   # every label emission near 2^-90
+    check(wl.CTCBatch(name="steep1", T=T, B=B, A=A, blank=0, logits=x,
+                      flat_labels=np.concatenate(labs).astype(np.int32), label_lengths=lab_len.astype(np.int32),
+                      input_lengths=np.array([600, 580, 300, 64, 590], dtype=np.int32)))
+    x = rng.standard_normal((T, B, A)).astype(np.float32)
+    for t0 in range(0, T, 50):                           # 25 frames of likely symbols, 25 of symbols near 2^-85
+        x[t0:t0 + 25, :, 0] -= 8.0
+        x[t0 + 25:t0 + 50, :, 0] += 58.0
+    check(wl.CTCBatch(name="swing1", T=T, B=B, A=A, blank=0, logits=x,
+                      flat_labels=np.concatenate(labs).astype(np.int32), label_lengths=lab_len.astype(np.int32),
+                      input_lengths=np.array([600, 580, 300, 64, 590], dtype=np.int32)))
+    T, B, A = 400, 6, 29
+    lab_len = rng.integers(20, 64, size=B)
+    labs = [rng.integers(1, A, size=n) for n in lab_len]
+    x = rng.standard_normal((T, B, A)).astype(np.float32) * 2.0
+    for b in range(B):                                   # (as in the peaky case above)
+        pos = np.sort(rng.choice(T, size=lab_len[b], replace=False))
+        x[:, b, 0] += 20.0
+        for i, t in enumerate(pos):
+            x[t, b, 0] -= 20.0
+            x[t, b, labs[b][i]] += 25.0
+    check(wl.CTCBatch(name="peaky1", T=T, B=B, A=A, blank=0, logits=x,
+                      flat_labels=np.concatenate(labs).astype(np.int32), label_lengths=lab_len.astype(np.int32),
+                      input_lengths=rng.integers(380, T + 1, size=B).astype(np.int32)))
+
+
 def test_single_symbol_alphabet_long_repeats():
     """Every label position repeats its predecessor: each needs a blank in between."""
     check(wl.make_random(79, T=500, B=3, A=2, max_label=240, min_input=490, blank=0, sigma=3.0,
