@@ -26,7 +26,7 @@
 // (run_chain_log): base-2 logarithms in fp64 (v_exp_f32 / v_log_f32 are base 2, so no scaling
 // multiplies; only the bounded differences that enter them are narrowed to fp32), log(0) a
 // large finite negative number, which keeps every operation NaN-free.
-// Either way the lattice is stored as (value, exponent) words, see pack_state.
+// Either way the lattice is stored as value words and exponent rows, see "lattice storage".
 
 #include <hip/hip_runtime.h>
 
@@ -1112,9 +1112,10 @@ __device__ __forceinline__ Wave* halo_wave(void* lds, int wave)
 // the gradient, which takes the blank's occupancy as 1 minus that of all label states
 // (sum_s alpha_t(s) beta_t(s) = p at every frame).
 //
-// A lone wavefront per SIMD issues one instruction every four clocks whatever its kind, so
-// the step is written for instruction count: pointers advance by adds, the blank emissions of
-// a chunk arrive in one load and are read by lane, lanes without a pair write to a sink.
+// A lone wavefront on its SIMD issues an instruction about every five clocks whatever its kind
+// (a vector memory instruction counts for three), so the step is written for instruction count:
+// pointers advance by adds, lanes without a pair write to a sink, whole chunks run without a look
+// at the step number.
 //
 // Labels of more than 63 symbols span several wavefronts.  Exchanging a value at every step
 // costs more than a third of the step, so with Sync::kHalo each wavefront recomputes, in its
@@ -1437,8 +1438,8 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
 // away.  The value shifted in from the pair below is brought into this lane's frame by `scale`
 // = 2^(frame below - frame here), constant between renewals and folded into the multiply-adds.
 //
-// Storage (Mode::kGrad): the label state's value and its frame at every step, in one word
-// (pack_state).  The gradient kernels do not know which kind of chain wrote the lattice.
+// Storage (Mode::kGrad): the label state's value word at every step, its frame once per chunk
+// (see "lattice storage").
 constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real one, far from int32's ends
 // A renewal is put off while it is not needed (a third of a chunk's instructions are the renewal's): every
 // pair of the wavefront has mass, lies within [2^kEasyLow, 2^kEasyHigh] of its frame, and at the last
