@@ -910,6 +910,9 @@ long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label
                 };
                 auto nothing = [](int, bool) {};
                 chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
+                // the same pointer walk on the schedule with three register sets (run_chain_linear)
+                p = label_emission_offset(m, k.has_label, symbol_major, k.symbol, k.li, f0, k.constant);
+                chain_schedule3(Tb, fetch, fetch, fetch, nothing, nothing, nothing, [] {});
             }
             for (int lane = 0; lane < kChunk; ++lane) {
                 const int64_t bp = blank_emission_offset(m, f0, fdir, lane);
@@ -927,6 +930,7 @@ long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label
                 };
                 auto nothing = [](int, bool) {};
                 chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
+                chain_schedule3(Tb, fetch, fetch, fetch, nothing, nothing, nothing, [] {});
             }
         }
     }

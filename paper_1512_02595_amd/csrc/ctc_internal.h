@@ -288,7 +288,9 @@ constexpr int kMaxDeviceMetaB = 4096;   // utterances the device-side planner ra
 
 // The lattice kernel reads emissions ahead of the recursion without bounds checks.  It
 // fetches kChunk steps at a time and, at the start of a pass that begins at step s0 <= Tb-1,
-// has requested steps up to s0 + 3*kChunk - 1: at most 3*kChunk - 1 rows past either end of
+// has requested steps up to s0 + 3*kChunk - 1 (two register sets, chain_schedule; with three sets,
+// chain_schedule3, requests run up to 5 chunks ahead but a round's later ones only go out while a
+// chunk of the chain is still to come, which bounds them the same): at most 3*kChunk - 1 rows past either end of
 // an utterance's block (past the end going forward, before the start going backward).  These
 // margins keep such reads inside the workspace; the values read there are never used.
 constexpr int kChunk = kChunkSteps;   // steps whose emissions are fetched together (plan_waves: halo % 8 == 0)
@@ -373,6 +375,44 @@ CTC_HOST_DEVICE inline void chain_schedule(int Tb, FetchA&& fetch_a, FetchB&& fe
         if (s0 + kChunk < Tb) {
             run_b(s0 + kChunk, false);
             end_chunk();
+        }
+    }
+}
+
+// The same with three register sets a, b, c: a chunk's emissions are requested two chunks before they are
+// used (a request out of the die's L2 takes longer than the 300 ns of a chunk).  The last requests reach up
+// to 3 * kChunk - 1 steps beyond the chain's end, as with two sets.
+template <typename FetchA, typename FetchB, typename FetchC, typename RunA, typename RunB, typename RunC, typename EndChunk>
+CTC_HOST_DEVICE inline void chain_schedule3(int Tb, FetchA&& fetch_a, FetchB&& fetch_b, FetchC&& fetch_c, RunA&& run_a,
+                                            RunB&& run_b, RunC&& run_c, EndChunk&& end_chunk)
+{
+    fetch_a(1);
+    fetch_b(1 + kChunk);
+    int s0 = 1;
+    for (; s0 + 3 * kChunk <= Tb; s0 += 3 * kChunk) {       // three whole chunks per round (see chain_schedule)
+        fetch_c(s0 + 2 * kChunk);
+        run_a(s0, true);
+        end_chunk();
+        fetch_a(s0 + 3 * kChunk);
+        run_b(s0 + kChunk, true);
+        end_chunk();
+        fetch_b(s0 + 4 * kChunk);
+        run_c(s0 + 2 * kChunk, true);
+        end_chunk();
+    }
+    if (s0 < Tb) {
+        fetch_c(s0 + 2 * kChunk);
+        run_a(s0, false);
+        end_chunk();
+        if (s0 + kChunk < Tb) {
+            fetch_a(s0 + 3 * kChunk);
+            run_b(s0 + kChunk, false);
+            end_chunk();
+            if (s0 + 2 * kChunk < Tb) {
+                fetch_b(s0 + 4 * kChunk);
+                run_c(s0 + 2 * kChunk, false);
+                end_chunk();
+            }
         }
     }
 }

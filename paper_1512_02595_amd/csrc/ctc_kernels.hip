@@ -1675,8 +1675,10 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     }
 
     // Emissions of steps 1..: two register sets, one in use, one being filled (as run_chain_log).
-    float el_a[kChunk], el_b[kChunk];
-    double eb_a[kChunk] = {}, eb_b[kChunk] = {};
+    // Three register sets: a chunk's emissions are requested two chunks before their use (with two sets,
+    // one chunk ahead, a seventh of a single-wavefront chain's time went into waiting for them).
+    float el_a[kChunk], el_b[kChunk], el_c[kChunk];
+    double eb_a[kChunk] = {}, eb_b[kChunk] = {}, eb_c[kChunk] = {};
     // (Scalar loads return in any order, so a wavefront can only wait for all of them: the set in use is
     // waited for before the other set's load goes out, while that wait is still free.)
     auto fetch = [&](float (&el)[kChunk], double (&eb)[kChunk], const double (&in_use)[kChunk], int s0) {
@@ -1704,10 +1706,11 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
                 if (s0 + i < Tb) advance(eb[i], el[i]);
         }
     };
-    chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
-                   [&](int s0) { fetch(el_b, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
-                   [&](int s0, bool whole) { run(el_a, eb_a, s0, whole); }, [&](int s0, bool whole) { run(el_b, eb_b, s0, whole); },
-                   end_chunk);
+    chain_schedule3(Tb, [&](int s0) { fetch(el_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0) { fetch(el_b, eb_b, eb_c, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0) { fetch(el_c, eb_c, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0, bool whole) { run(el_a, eb_a, s0, whole); }, [&](int s0, bool whole) { run(el_b, eb_b, s0, whole); },
+                    [&](int s0, bool whole) { run(el_c, eb_c, s0, whole); }, end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1), from the lane of pair L (exact, as is the
@@ -2034,6 +2037,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
                 if (s0 + i < Tb) advance(eb[i], ela[i], elb[i]);
         }
     };
+    // (Two register sets: a third, as in run_chain_linear, gains 2 % here and costs the long chains as much.)
     chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
                    [&](int s0) { fetch(ela_b, elb_b, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
                    [&](int s0, bool whole) { run(ela_a, elb_a, eb_a, s0, whole); },
