@@ -644,12 +644,22 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.dev_input_lengths = input_lengths;
     p.dev_status = status;
     p.poll_budget = g_poll_budget.load(std::memory_order_relaxed);
-    p.n_tasks = 0;                     // the queue of an overlapped launch is prepared on the host
+    p.n_tasks = 0;
     p.n_task_entries = 0;
     p.n_cu = 0;
     // Narrow alphabets: the softmax launch builds the records itself (no planning launch before it); every
     // utterance's setup workgroup weighs all B utterances for the run order, which is worth it up to here.
     p.folded = A <= kDirectMaxA && B <= kDeviceFoldMaxB && max_label > 0;
+    // Gradient rows inside the lattice launch, under the conditions of prepare(); the task list is built on the GPU.
+    const int n_cu = compute_units(), share_percent = g_overlap.load(std::memory_order_relaxed);
+    p.n_cu = n_cu;
+    if (p.folded && grads && share_percent > 0 && !p.needs_barrier && 2 * B <= kMaxTaskEntries && n_cu % kXcds == 0 &&
+        p.n_chains + n_cu / 4 <= n_cu) {
+        p.device_tasks = true;
+        p.share_percent = share_percent;
+        p.n_tasks = B * ((T + kTaskRows - 1) / kTaskRows);
+        p.n_task_entries = 2 * B;
+    }
     p.lay = lay;
     // Per-launch device times for measurements (ctc_profile_kernels_device): events around the launches as in run().
     Events events;

@@ -511,6 +511,10 @@ struct Launch {
     // Narrow alphabets, host metadata: there is no upload launch; the softmax launch reads the pinned image
     // itself and copies it into the workspace for the launches after it, and the lattice launch releases it.
     bool folded;
+    // Device-resident metadata with workers: the softmax launch builds their task list (build_task_table) from the
+    // lengths on the GPU; n_tasks and n_task_entries are then upper bounds, the list itself says how many there are.
+    bool device_tasks = false;
+    int share_percent = 0;    // (kWorkerSharePercent, or what ctc_debug_set_overlap asked for)
     Layout lay;
 };
 

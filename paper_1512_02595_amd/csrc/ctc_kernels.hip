@@ -721,22 +721,161 @@ struct NarrowDevice {
     int* status_words;            // [B] nonzero: the utterance's lengths or labels are invalid
     int max_label, poll_budget, dirs;
     bool crowded, log_domain;
+    int* tasks;                   // the lattice launch's workers' task list, to be built here (nullptr: no workers)
+    int share_percent;            // utterances whose chains end later than this share of the longest go to the gradient launch
+    int n_cu;                     // compute units of the device (a multiple of kChainBlock, or 0: keep the plain order)
 };
 
+// Wavefronts of an utterance's chains (0: its lengths are out of range).
+__device__ __forceinline__ int chain_waves(const PlanTable& plans, int L, int Tb, int Tt, int max_label, bool log_domain)
+{
+    if (L < 0 || L > max_label || Tb < 0 || Tb > Tt) return 0;
+    const bool two = !log_domain && Tb <= kLinearMaxFrames && plans.two_pairs(L);
+    return two ? plans.waves2(L) : plans.waves1(L);
+}
 // Weight of an utterance in the run order: its frames times the wavefronts of its chains.
 __device__ __forceinline__ long long chain_weight(const PlanTable& plans, int L, int Tb, int Tt, int max_label,
                                                   bool log_domain)
 {
-    if (L < 0 || L > max_label || Tb < 0 || Tb > Tt) return 0;
-    const bool two = !log_domain && Tb <= kLinearMaxFrames && plans.two_pairs(L);
-    return static_cast<long long>(Tb) * (two ? plans.waves2(L) : plans.waves1(L));
+    return static_cast<long long>(Tb) * chain_waves(plans, L, Tb, Tt, max_label, log_domain);
+}
+// When an utterance's chains end, in the unit the launcher orders by (prepare: chains that exchange
+// between wavefronts take a little longer per frame); 0 for an utterance without frames or with bad lengths.
+__device__ __forceinline__ int chain_end_estimate(const PlanTable& plans, int L, int Tb, int Tt, int max_label, bool log_domain)
+{
+    const int waves = chain_waves(plans, L, Tb, Tt, max_label, log_domain);
+    return waves == 0 ? 0 : Tb * (waves > 1 ? 5 : 4);
+}
+__device__ __forceinline__ bool ends_late(int ends, int last_end, int share_percent)
+{
+    return static_cast<long long>(ends) * 100 > static_cast<long long>(last_end) * share_percent;
+}
+
+// The workers' task list (see gradient_worker and the launcher's prepare, whose list this reproduces from the
+// device-resident lengths), by one workgroup.  An utterance's place in the run order is its rank by weight
+// over all B utterances (build_record), its chains' die that rank mod kXcds (the order's blocks of kChainBlock
+// keep both chains of an utterance on one die; in a last, partial block they may not be, and a worker that
+// finds them elsewhere leaves the utterance to the gradient launch).  Whether an alignment exists is not
+// looked at: the workers take that from the records.  B <= kMaxTaskEntries / 2.
+__device__ __forceinline__ void build_task_table(const NarrowDevice& dv, const PlanTable& plans, int Tt, int B)
+{
+    constexpr int kMax = kMaxTaskEntries / 2;
+    static_assert(kRowThreads == 2 * kMax, "two threads per utterance");
+    __shared__ long long s_weight[kMax];
+    __shared__ int s_frames[kMax], s_ends[kMax], s_rank[kMax], s_wait[kMax], s_pad[kMax], s_at[kMax], s_sum[kMax];
+    __shared__ int s_last_end, s_entries[kXcds][2], s_tasks[kXcds][2];      // per die: [padding rows, waiting rows]
+    __shared__ int s_entries_before[kXcds + 1], s_tasks_before[kXcds + 1];
+    const int tid = threadIdx.x, blocks = (Tt + kTaskRows - 1) / kTaskRows;
+    // Four threads per utterance j (two beyond 64 utterances), each comparing it with a quarter (half) of the
+    // others in one unrolled pass, so that its LDS reads travel together; entries beyond B are neutral.
+    const int span = B <= kMax / 2 ? kMax / 2 : kMax, share = span / (kRowThreads / span);
+    const int j = tid & (span - 1), k_first = (tid / span) * share, k_end = k_first + share;
+    if (tid == 0) s_last_end = 0;
+    if (tid < kXcds * 2) {
+        s_entries[tid >> 1][tid & 1] = 0;
+        s_tasks[tid >> 1][tid & 1] = 0;
+    }
+    if (tid < B) {
+        const int L = dv.label_lengths[tid], Tb = dv.input_lengths[tid];
+        s_weight[tid] = chain_weight(plans, L, Tb, Tt, dv.max_label, dv.log_domain);
+        s_ends[tid] = chain_end_estimate(plans, L, Tb, Tt, dv.max_label, dv.log_domain);
+        s_frames[tid] = Tb;
+        s_rank[tid] = 0;
+        s_at[tid] = 0;
+        s_sum[tid] = 0;
+    } else if (tid < kMax) {
+        s_weight[tid] = -1;                             // (lighter than any utterance)
+        s_ends[tid] = 0;
+        s_rank[tid] = 0;
+        s_wait[tid] = 0;
+    }
+    __syncthreads();
+    if (tid < B && s_ends[tid] > 0) atomicMax(&s_last_end, s_ends[tid]);
+    if (j < B) {
+        const long long mine = s_weight[j];
+        int before = 0;
+#pragma unroll 16
+        for (int k = k_first; k < k_end; ++k) before += (s_weight[k] > mine || (s_weight[k] == mine && k < j)) ? 1 : 0;
+        if (before) atomicAdd(&s_rank[j], before);
+    }
+    __syncthreads();
+    if (tid < B) {
+        const int data = s_ends[tid] > 0 ? (s_frames[tid] + kTaskRows - 1) / kTaskRows : 0;
+        s_pad[tid] = blocks - data;
+        s_wait[tid] = ends_late(s_ends[tid], s_last_end, dv.share_percent) ? 0 : data;
+        if (s_pad[tid] > 0) {
+            atomicAdd(&s_entries[tid % kXcds][0], 1);
+            atomicAdd(&s_tasks[tid % kXcds][0], s_pad[tid]);
+        }
+        if (s_wait[tid] > 0) {
+            atomicAdd(&s_entries[s_rank[tid] % kXcds][1], 1);
+            atomicAdd(&s_tasks[s_rank[tid] % kXcds][1], s_wait[tid]);
+        }
+    }
+    __syncthreads();
+    // a waiting entry's place in its die's section: the die's utterances that end earlier (ties: in the run order)
+    if (j < B && s_wait[j] > 0) {
+        const int die = s_rank[j] % kXcds, ends = s_ends[j], rank = s_rank[j];
+        int at = 0, sum = 0;
+#pragma unroll 16
+        for (int k = k_first; k < k_end; ++k) {
+            const int wait_k = s_wait[k], rank_k = s_rank[k], ends_k = s_ends[k];
+            const bool earlier = wait_k > 0 && rank_k % kXcds == die && (ends_k < ends || (ends_k == ends && rank_k < rank));
+            at += earlier ? 1 : 0;
+            sum += earlier ? wait_k : 0;
+        }
+        if (at) {
+            atomicAdd(&s_at[j], at);
+            atomicAdd(&s_sum[j], sum);
+        }
+    }
+    if (tid <= kXcds) {
+        int entries = 0, tasks = 0;
+        for (int d = 0; d < tid; ++d) {
+            entries += s_entries[d][0] + s_entries[d][1];
+            tasks += s_tasks[d][0] + s_tasks[d][1];
+        }
+        s_entries_before[tid] = entries;
+        s_tasks_before[tid] = tasks;
+    }
+    __syncthreads();
+    int* const task_die = dv.tasks;                     // [kXcds + 1]
+    int* const task_prefix = task_die + kXcds + 1;      // [2B + 1]
+    int* const task_info = task_prefix + 2 * B + 1;     // [2B]
+    int* const task_first = task_info + 2 * B;          // [2B]
+    if (tid < B) {
+        if (s_pad[tid] > 0) {
+            // the die's padding rows come first, by utterance number
+            const int die = tid % kXcds;
+            int at = 0, sum = 0;
+            for (int k = die; k < tid; k += kXcds)
+                if (s_pad[k] > 0) {
+                    ++at;
+                    sum += s_pad[k];
+                }
+            const int e = s_entries_before[die] + at;
+            task_prefix[e] = s_tasks_before[die] + sum;
+            task_info[e] = tid | (kTaskRowsLog2 << kTaskRowsShift);
+            task_first[e] = blocks - s_pad[tid];
+        }
+        if (s_wait[tid] > 0) {
+            // then its utterances as their chains end
+            const int die = s_rank[tid] % kXcds;
+            const int e = s_entries_before[die] + s_entries[die][0] + s_at[tid];
+            task_prefix[e] = s_tasks_before[die] + s_tasks[die][0] + s_sum[tid];
+            task_info[e] = tid | kTaskWaits | (kTaskRowsLog2 << kTaskRowsShift);
+            task_first[e] = 0;
+        }
+    }
+    if (tid <= kXcds) task_die[tid] = s_entries_before[tid];
+    if (tid == 0) task_prefix[s_entries_before[kXcds]] = s_tasks_before[kXcds];
 }
 
 // By the whole workgroup; `s_lab` holds scratch ints.  Returns the record (the same in every thread).
 __device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTable& plans, int b, int Tt, int B, int A,
                                             int blank)
 {
-    __shared__ int s_repeats, s_bad, s_rank;
+    __shared__ int s_repeats, s_bad, s_rank, s_last_end;
     const int tid = threadIdx.x;
     const int L_in = dv.label_lengths[b], Tb_in = dv.input_lengths[b];
     const bool bad_length = L_in < 0 || L_in > dv.max_label || Tb_in < 0 || Tb_in > Tt;
@@ -745,6 +884,7 @@ __device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTa
         s_repeats = 0;
         s_bad = 0;
         s_rank = 0;
+        s_last_end = 0;
     }
     __syncthreads();
     const int* lab = dv.labels + static_cast<size_t>(b) * dv.max_label;
@@ -758,13 +898,19 @@ __device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTa
     if (bad) s_bad = 1;
     // the utterances that come before this one in the run order: heavier, or as heavy and earlier
     const long long mine = chain_weight(plans, L_in, Tb_in, Tt, dv.max_label, dv.log_domain);
-    int before = 0;
+    int before = 0, last_end = 0;
     for (int j = tid; j < B; j += kRowThreads) {
-        const long long w = chain_weight(plans, dv.label_lengths[j], dv.input_lengths[j], Tt, dv.max_label, dv.log_domain);
+        const int Lj = dv.label_lengths[j], Tj = dv.input_lengths[j];
+        const long long w = chain_weight(plans, Lj, Tj, Tt, dv.max_label, dv.log_domain);
         before += (w > mine || (w == mine && j < b)) ? 1 : 0;
+        if (dv.tasks) last_end = max(last_end, chain_end_estimate(plans, Lj, Tj, Tt, dv.max_label, dv.log_domain));
     }
     if (before) atomicAdd(&s_rank, before);
+    if (last_end) atomicMax(&s_last_end, last_end);
     __syncthreads();
+    // (workers in the lattice launch: the utterances that end last are the gradient launch's, as in prepare)
+    const bool later = dv.tasks && ends_late(chain_end_estimate(plans, L_in, Tb_in, Tt, dv.max_label, dv.log_domain),
+                                             s_last_end, dv.share_percent);
     const bool invalid = bad_length || s_bad != 0;
     const int Tb = invalid ? 0 : Tb_in;
     const bool runs = !invalid && Tb > 0 && Tb >= L + s_repeats;
@@ -775,7 +921,7 @@ __device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTa
     m.lab_off = b * dv.max_label;
     m.flags = (runs ? kUttRuns : 0) | (invalid ? kUttInvalid : 0) |
               ((dv.log_domain || Tb > kLinearMaxFrames) ? kUttLogDomain : 0) |
-              (!invalid && plans.two_pairs(L) ? kUttTwoPairs : 0);
+              (!invalid && plans.two_pairs(L) ? kUttTwoPairs : 0) | (later ? kUttGradientLater : 0);
     m.f_off = b * Tt;
     m.waves = plans.waves1(Lp);
     m.halo = plans.halo1(Lp);
@@ -790,7 +936,16 @@ __device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTa
         dv.meta[b] = m;
         dv.status_words[b] = invalid ? 1 : 0;
         // heaviest first, in blocks of kChainBlock utterances: a block's forward chains, then its backward chains
-        const int rank = s_rank, first = rank - rank % kChainBlock, in_block = min(kChainBlock, B - first);
+        // Launches of more chains than compute units: workgroup i shares its compute unit with workgroups
+        // i +- n_cu, so every other round of n_cu chains runs lightest first, and a compute unit's chains
+        // add up to about the same (the host's order_chains goes by the SIMDs' loads; this is its first-order part).
+        int rank = s_rank;
+        const int per_round = dv.n_cu / dv.dirs;
+        if (per_round >= kChainBlock && B * dv.dirs > dv.n_cu && ((rank / per_round) & 1)) {
+            const int round_first = rank - rank % per_round, in_round = min(per_round, B - round_first);
+            rank = round_first + (in_round - 1 - rank % per_round);
+        }
+        const int first = rank - rank % kChainBlock, in_block = min(kChainBlock, B - first);
         for (int d = 0; d < dv.dirs; ++d) dv.order[first * dv.dirs + d * in_block + rank % kChainBlock] = 2 * b + d;
     }
     return m;
@@ -810,7 +965,13 @@ void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image,
     __shared__ int s_lab[kSetupLabelSlots];
     __shared__ int s_small;
     const int b = blockIdx.y, tid = threadIdx.x;
-    const int row_blocks = static_cast<int>(gridDim.x) - sa.parts;
+    // (device-resident metadata with workers in the lattice launch: one more column, whose first workgroup
+    // builds their task list)
+    const int row_blocks = static_cast<int>(gridDim.x) - sa.parts - (dv.tasks ? 1 : 0);
+    if (dv.tasks && blockIdx.x == gridDim.x - 1) {
+        if (b == 0) build_task_table(dv, args.plans, Tt, B);
+        return;
+    }
     if (static_cast<int>(blockIdx.x) >= row_blocks && dv.labels) {
         // device-resident metadata: the first part builds the record, the others need the label only
         const int part = static_cast<int>(blockIdx.x) - row_blocks;
@@ -2405,7 +2566,7 @@ __device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* 
                                                 float* __restrict__ costs, int* lds, const int lds_ints)
 {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int E = wk.n_entries, Lmax = wk.Lmax;
+    const int E = wk.n_entries >= 0 ? wk.n_entries : min(max(wk.tasks[kXcds], 0), 2 * wk.B), Lmax = wk.Lmax;
     int* const s_die = lds;                       // [kXcds + 1]
     int* const s_prefix = s_die + kXcds + 1;      // [E + 1]
     int* const s_info = s_prefix + E + 1;         // [E]
@@ -3013,7 +3174,7 @@ int launch_softmax(const Launch& p, void* stream)
     return checked_launch([&] {
         if (p.A <= kDirectMaxA && p.folded) {
             // the smallest alphabets, host metadata: the launch reads the pinned image itself
-            const dim3 grid((p.T + kFlagFrames - 1) / kFlagFrames + sa.parts, p.B);
+            const dim3 grid((p.T + kFlagFrames - 1) / kFlagFrames + sa.parts + (p.device_tasks ? 1 : 0), p.B);
             const size_t lds = static_cast<size_t>(kFlagFrames) * p.A * sizeof(float);
             const NarrowImage image{static_cast<const int*>(p.host_image), static_cast<int>(p.lay.labels / 4),
                                     static_cast<int>(p.lay.tasks / 4), static_cast<int>(p.lay.labels8 / 4), p.lay.labels8,
@@ -3026,7 +3187,9 @@ int launch_softmax(const Launch& p, void* stream)
             if (p.dev_label_lengths)
                 dv = NarrowDevice{p.labels, p.dev_label_lengths, p.dev_input_lengths, meta, reinterpret_cast<int*>(p.ws + p.lay.order),
                                   reinterpret_cast<int*>(p.ws + p.lay.status), p.max_label, p.poll_budget,
-                                  p.mode == Mode::kGrad ? 2 : 1, p.crowded, p.needs_barrier};
+                                  p.mode == Mode::kGrad ? 2 : 1, p.crowded, p.needs_barrier,
+                                  p.device_tasks ? reinterpret_cast<int*>(p.ws + p.lay.tasks) : nullptr, p.share_percent,
+                                  p.n_cu % kChainBlock == 0 ? p.n_cu : 0};
             const Utt* records = static_cast<const Utt*>(p.host_image);      // (the host reads its own image)
             for (int b = 0; records && b < p.B; ++b) {
                 rows_of.frames[b] = records[b].Tb | ((records[b].flags & kUttRuns) ? kRowsRun : 0) |
@@ -3151,7 +3314,7 @@ int launch_lattice(const Launch& p, void* stream)
         wk.where = reinterpret_cast<int*>(p.ws + p.lay.where);
         wk.leftover = reinterpret_cast<int*>(p.ws + p.lay.leftover);
         wk.n_tasks = p.n_tasks;
-        wk.n_entries = p.n_task_entries;
+        wk.n_entries = p.device_tasks ? -1 : p.n_task_entries;      // (-1: the list's first block says how many)
         wk.n_chains = p.n_chains;
         wk.n_cu = p.n_cu;
         wk.rounds = rounds;
