@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--overlap", type=int, default=-1,
                     help="0: write the whole gradient in a launch of its own even where the lattice launch has idle "
                          "compute units; 1..100: ctc_debug_set_overlap; default: the library's setting")
+    ap.add_argument("--sequential-chains", action="store_true",
+                    help="measurement of the paper's order: the forward recursion's launch, then the backward one's "
+                         "(ctc_debug_set_sequential_chains); the JSON line says so and is no headline figure")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (reference for HBM counters)")
     args = ap.parse_args()
@@ -177,6 +180,8 @@ def main():
     ctc.load()
     if args.overlap >= 0:
         ctc.debug_set_overlap(args.overlap)
+    if args.sequential_chains:
+        ctc.debug_set_sequential_chains(True)
     dtype = ctc.DTYPE_F32 if args.dtype == "f32" else ctc.DTYPE_BF16
     elem = 4 if dtype == ctc.DTYPE_F32 else 2
 
@@ -321,7 +326,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "config[%d] %s: B=%d A=%d T=%d, %d rotating minibatches"
                    % (args.config, batches[0].name, B, batches[0].A, batches[0].T, len(batches)),
-                   "mode": args.mode, "metadata": args.metadata, "graph": bool(args.graph)},
+                   "mode": args.mode, "metadata": args.metadata, "graph": bool(args.graph),
+                   "sequential_chains": bool(args.sequential_chains)},
         "activation_frames_per_s": round(frames / (ms_per_step * 1e-3), 1),
         "hbm_roofline_frac_end_to_end": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
         "compulsory_bytes": int(compulsory),

@@ -350,6 +350,15 @@ void ctc_debug_set_poll_budget(int polls);
 void ctc_debug_set_overlap(int percent);
 
 /*
+ * Diagnostics, for one measurement: the order of the paper's own GPU design (CTC appendix: the forward
+ * pass, then the backward pass) against this library's, which runs the two recursions side by side.
+ * Nonzero `on`: host-metadata gradient calls made afterwards, process-wide, run the forward chains in
+ * one launch and the backward chains in a second one after it (and no gradient rows inside those
+ * launches); 0 restores the default.  Results are bitwise the same.
+ */
+void ctc_debug_set_sequential_chains(int on);
+
+/*
  * Diagnostics, host only (no GPU is touched).  The recursions read their emissions several steps
  * ahead and without bounds checks, up to three chunks past either end of an utterance's block;
  * margins around the emission regions of the workspace are there to take those reads.  This

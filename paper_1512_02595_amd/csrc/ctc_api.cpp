@@ -29,6 +29,7 @@ std::atomic<int> g_poll_budget{kDefaultPollBudget};
 // percentage of the launch's expected duration up to which an utterance's chains must end for its rows
 // to be written by the launch's workers (the rest are written by the gradient launch that follows).
 std::atomic<int> g_overlap{kWorkerSharePercent};
+std::atomic<int> g_sequential_chains{0};
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -402,7 +403,8 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     int32_t* const task_info = task_prefix + 2 * c.B + 1;                        // [2B]
     int32_t* const task_first = task_info + 2 * c.B;                             // [2B]
     int n_entries = 0, n_tasks = 0;
-    const int share_percent = g_overlap.load(std::memory_order_relaxed);
+    const bool sequential_chains = c.mode == Mode::kGrad && g_sequential_chains.load(std::memory_order_relaxed) != 0;
+    const int share_percent = sequential_chains ? 0 : g_overlap.load(std::memory_order_relaxed);
     if (share_percent > 0 && c.mode == Mode::kGrad && c.A <= kDirectMaxA && !needs_barrier &&
         n_run > 0 && 2 * c.B <= kMaxTaskEntries && n_cu % kXcds == 0 && n_run * dirs + n_cu / 4 <= n_cu) {
         // The die of an utterance's chains: workgroup i runs on die i mod kXcds (order_chains puts an
@@ -470,6 +472,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
     out->dev_status = nullptr;
     out->poll_budget = g_poll_budget.load(std::memory_order_relaxed);
     out->crowded = crowded;
+    out->sequential_chains = sequential_chains;
     out->n_tasks = n_tasks;
     out->n_task_entries = n_entries;
     out->n_cu = n_cu;
@@ -951,6 +954,11 @@ long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label
 void ctc_debug_set_overlap(int percent)
 {
     ctc::g_overlap.store(percent < 0 ? ctc::kWorkerSharePercent : std::min(percent, 100), std::memory_order_relaxed);
+}
+
+extern "C" void ctc_debug_set_sequential_chains(int on)
+{
+    ctc::g_sequential_chains.store(on ? 1 : 0, std::memory_order_relaxed);
 }
 
 void ctc_debug_set_poll_budget(int polls)

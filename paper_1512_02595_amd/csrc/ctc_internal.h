@@ -513,6 +513,7 @@ struct Launch {
     bool folded;
     // Device-resident metadata with workers: the softmax launch builds their task list (build_task_table) from the
     // lengths on the GPU; n_tasks and n_task_entries are then upper bounds, the list itself says how many there are.
+    bool sequential_chains = false;   // measurements: forward and backward chains in two launches, one after the other
     bool device_tasks = false;
     int share_percent = 0;    // (kWorkerSharePercent, or what ctc_debug_set_overlap asked for)
     Layout lay;

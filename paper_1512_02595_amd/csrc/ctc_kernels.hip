@@ -2278,6 +2278,7 @@ struct WorkerArgs {
     const int* status_words;  // device-resident metadata built by the narrow softmax launch: per utterance, nonzero if
     int* status_out;          // invalid; gathered into the caller's status word by this launch (or nullptr)
     int status_count;
+    int skip_directions;      // bit 0: leave the forward chains out, bit 1: the backward chains (measurements only)
 };
 
 // The die (XCD) this wavefront runs on: each has an L2 of its own.
@@ -2345,6 +2346,8 @@ __device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, c
     }
     const int chain = order[blockIdx.x];           // utterance * 2 + direction
     if (chain < 0) return {-1, 0};      // device-planned batches launch a workgroup per utterance and direction, running or not
+    // (measurements of the recursions one after the other: a launch that leaves one direction out)
+    if (kMode == Mode::kGrad && ((wk.skip_directions >> (chain & 1)) & 1)) return {-1, 0};
     const int u = chain >> 1;
     const bool forward = kMode != Mode::kGrad || (chain & 1) == 0;
     const Utt m = meta[u];
@@ -3343,9 +3346,13 @@ int launch_lattice(const Launch& p, void* stream)
         else CTC_LAUNCH_LATTICE_MODE(KERNEL, Mode::kGrad);                                         \
     } while (0)
     return checked_launch([&] {
-        if (p.max_waves == 1) CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel_w1);
-        else if (!p.needs_barrier) CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel);
-        else CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel_barrier);
+        // (measurements: the two recursions one after the other, forward chains first, as two launches)
+        for (int pass = 0; pass < (p.sequential_chains ? 2 : 1); ++pass) {
+            wk.skip_directions = p.sequential_chains ? (pass == 0 ? 2 : 1) : 0;
+            if (p.max_waves == 1) CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel_w1);
+            else if (!p.needs_barrier) CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel);
+            else CTC_LAUNCH_LATTICE_KERNEL(ctc_lattice_kernel_barrier);
+        }
     });
 #undef CTC_LAUNCH_LATTICE_KERNEL
 #undef CTC_LAUNCH_LATTICE_MODE

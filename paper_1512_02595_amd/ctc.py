@@ -32,7 +32,7 @@ KERNEL_BACKTRACE = 3          # name index of the third launch of best_path
 EXPORTS = ("ctc_workspace_size", "ctc_loss_and_grad", "ctc_profile_kernels",
            "ctc_best_path", "ctc_profile_best_path",
            "ctc_workspace_size_device", "ctc_loss_and_grad_device", "ctc_loss_and_grad_device_static",
-           "ctc_profile_kernels_device",
+           "ctc_profile_kernels_device", "ctc_debug_set_sequential_chains",
            "ctc_kernel_name", "ctc_status_string", "ctc_last_hip_error", "ctc_debug_set_poll_budget",
            "ctc_debug_staging_allocations", "ctc_debug_set_overlap", "ctc_debug_replay_emission_fetches")
 
@@ -89,6 +89,8 @@ def load() -> ctypes.CDLL:
     lib.ctc_debug_replay_emission_fetches.argtypes = [ci, ci, ci, i32p, i32p, ci, ctypes.POINTER(ctypes.c_long)]
     lib.ctc_debug_set_overlap.restype = None
     lib.ctc_debug_set_overlap.argtypes = [ci]
+    lib.ctc_debug_set_sequential_chains.restype = None
+    lib.ctc_debug_set_sequential_chains.argtypes = [ci]
     lib.ctc_debug_staging_allocations.restype = ctypes.c_long
     lib.ctc_debug_staging_allocations.argtypes = []
     _lib = lib
@@ -251,6 +253,11 @@ def debug_set_poll_budget(polls: int) -> None:
 def debug_staging_allocations() -> int:
     """Pinned host allocations the library has made so far in this process."""
     return int(load().ctc_debug_staging_allocations())
+
+
+def debug_set_sequential_chains(on: bool) -> None:
+    """Measurements: forward and backward recursions in two launches, one after the other."""
+    load().ctc_debug_set_sequential_chains(1 if on else 0)
 
 
 def debug_set_overlap(percent: int) -> None:

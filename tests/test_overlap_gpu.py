@@ -67,3 +67,27 @@ def test_repeated_calls_on_one_workspace():
         d.run()
         c, g = d.results()
         assert np.array_equal(c, rc, equal_nan=True) and np.array_equal(g, rg), i
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: wl.make_config(0),
+    lambda: wl.make_config(1),
+    lambda: wl.make_config(3, B=8),                                                             # several wavefronts per chain
+    lambda: wl.make_random(81, T=120, B=6, A=7, max_label=40, min_input=90, sigma=60.0, feasible_only=True),  # log domain
+    lambda: wl.make_random(7, T=60, B=12, A=80, max_label=20, min_input=30),                    # frame-major emissions
+])
+def test_recursions_one_after_the_other_give_the_same_results(maker):
+    """The measurement switch that runs the forward chains' launch before the backward chains' (the order
+    of the paper's GPU design, CTC appendix) changes when things run, not what they compute."""
+    batch = maker()
+    print(f"sequential case {batch.name} seed={batch.seed} T={batch.T} B={batch.B} A={batch.A}", flush=True)
+    ref_c, ref_g = run_with(batch, ctc.DTYPE_F32, 0)
+    ctc.debug_set_sequential_chains(True)
+    try:
+        db = harness.DeviceBatch(batch, ctc.DTYPE_F32)
+        db.run()
+        c, g = db.results()
+    finally:
+        ctc.debug_set_sequential_chains(False)
+    assert np.array_equal(c, ref_c, equal_nan=True)
+    assert np.array_equal(g, ref_g)
