@@ -75,7 +75,7 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     off = align_up(off);
     l.links = off;  off = align_up(off + static_cast<size_t>(sumL) * sizeof(int32_t));
     l.logp = off;   off = align_up(off + static_cast<size_t>(B) * sizeof(double));
-    l.sink = off;   off = align_up(off + 256);
+    l.sink = off;   off = align_up(off + static_cast<size_t>(B) * 2 * kSinkWaves * kSinkBytes);
     l.chain_err = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.done = off;   off = align_up(off + static_cast<size_t>(B) * kDoneStride * sizeof(int32_t));
     l.domain = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));

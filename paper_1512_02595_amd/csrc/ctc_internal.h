@@ -169,6 +169,10 @@ const PlanTable& plan_table(int max_label, bool crowded, bool symbol_major);
 constexpr int kEmitGathered = 0, kEmitSymbolMajor = 1;
 CTC_HOST_DEVICE inline int emission_layout(int A) { return A <= kDirectMaxA ? kEmitSymbolMajor : kEmitGathered; }
 
+// The sink of a lattice launch: for each of its up to 2 B chain workgroups, kSinkBytes for each of the
+// up to kSinkWaves wavefronts.
+constexpr int kSinkWaves = 16, kSinkBytes = 64;
+
 constexpr int kUttRuns = 1;
 constexpr int kUttInvalid = 2;
 // Set by the softmax launch when some emission of the utterance is too improbable for the
@@ -430,7 +434,7 @@ struct Layout {
     size_t labels8 = 0;   // uint8[sumL]  the label strings once more, a byte per symbol (image only; narrow alphabets)
     size_t links = 0;     // int32[sumL]  grouping of the label positions by symbol (slot, count, first)
     size_t logp = 0;      // double[B]    log2 of the alignment mass
-    size_t sink = 0;      // 256 bytes that lanes with nothing to store may scribble on
+    size_t sink = 0;      // what lanes with nothing to store scribble on: kSinkBytes per wavefront of a lattice launch
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
     size_t done = 0;      // int32[B * kDoneStride]  wavefronts of the utterance's chains that have ended (overlapped launches)
     size_t domain = 0;    // int32[B]     nonzero: the utterance's chains ran in the log domain (published by the forward

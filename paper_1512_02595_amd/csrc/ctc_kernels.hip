@@ -2344,6 +2344,12 @@ __device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, c
         const bool any = __ballot(bad) != 0;
         if (threadIdx.x == 0) *wk.status_out = any ? CTC_STATUS_INVALID_VALUE : CTC_STATUS_SUCCESS;
     }
+    // Lanes with nothing to store write to a sink: 64 bytes of it per wavefront of the launch.  (One
+    // address for the whole launch was what a crowded launch waited for: every store instruction of
+    // every chain carried a write to it, and they all met in one channel of each die's L2.  512
+    // utterances of 20 symbols and 740 frames: 59 -> 40 us.  Writing to an unused column of the
+    // chain's own rows instead was slower than either in launches that are not crowded.)
+    sink += (static_cast<size_t>(blockIdx.x) * kSinkWaves + (threadIdx.x >> 6)) * (kSinkBytes / sizeof(uint32_t));
     const int chain = order[blockIdx.x];           // utterance * 2 + direction
     if (chain < 0) return {-1, 0};      // device-planned batches launch a workgroup per utterance and direction, running or not
     // (measurements of the recursions one after the other: a launch that leaves one direction out)
