@@ -72,3 +72,38 @@ def test_calls_enqueued_behind_a_long_kernel_never_wait():
         dbs[i % 4].run()
     torch.cuda.synchronize()
     assert ctc.debug_staging_allocations() - before == grown
+
+
+def test_two_threads_on_two_streams():
+    """Calls from several threads are serialised while they prepare and enqueue, and share the pinned slots;
+    with a stream, a workspace and output buffers of its own each thread gets the results it gets alone."""
+    import threading
+    batches = [wl.make_config(1, B=16), wl.make_random(320, T=120, B=24, A=29, max_label=50, min_input=60, sigma=2.0)]
+    refs = []
+    for b in batches:
+        d = harness.DeviceBatch(b)
+        d.run()
+        refs.append(d.results())
+    dbs = [harness.DeviceBatch(b) for b in batches]
+    streams = [torch.cuda.Stream() for _ in batches]
+    torch.cuda.synchronize()
+    failures = []
+
+    def work(i):
+        try:
+            for _ in range(25):
+                dbs[i].run(streams[i].cuda_stream)
+            streams[i].synchronize()
+        except Exception as e:                              # (surfaces in the main thread below)
+            failures.append((i, repr(e)))
+
+    print("  two threads, 25 calls each", flush=True)
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(60)
+    assert not any(t.is_alive() for t in threads) and not failures, failures
+    for d, (rc, rg) in zip(dbs, refs):
+        c, g = d.results()
+        assert np.array_equal(c, rc, equal_nan=True) and np.array_equal(g, rg)
