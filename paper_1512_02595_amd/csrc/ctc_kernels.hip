@@ -2452,7 +2452,10 @@ struct LatticeRows {
 // symbol k (alphabets of at most 64 symbols).  s_slot, s_start, s_count: the grouping of the label's
 // positions as ctc_gradient_narrow_kernel describes it, in LDS; g_slot: L + 1 floats of LDS of this
 // wavefront's own.
-template <typename T, bool kStreaming, bool kCoherent>
+// `stage` is called once, after the first row's values have been requested and before anything is read
+// out of s_slot, s_start and s_count: a caller that still has to fill them does it there, so that its
+// loads and the first row's are under way together.
+template <typename T, bool kStreaming, bool kCoherent, typename Stage>
 __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T* __restrict__ grads, const Utt m,
                                                      const int b, const LatticeOut lat,
                                                      const float* __restrict__ lse, const double* __restrict__ logp,
@@ -2460,7 +2463,7 @@ __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T*
                                                      const int Tt, const int B, const int A, const int blank,
                                                      const int t_first, const int t_step, const int tend,
                                                      const int* s_slot, const int* s_start, const int* s_count,
-                                                     float* g_slot)
+                                                     float* g_slot, Stage&& stage)
 {
     const int lane = threadIdx.x & 63;
     const bool runs = (m.flags & kUttRuns) != 0;
@@ -2516,6 +2519,7 @@ __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T*
     };
     RowData cur = {};
     if (runs && t_first < tend && t_first < m.Tb) request(t_first, cur);
+    stage();
     for (int t = t_first; t < tend; t += t_step, grow += row_step) {
         if (t >= m.Tb || !runs) {
             if (lane < A) store_elem(grow, lane, 0.0f);
@@ -2696,7 +2700,7 @@ __device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* 
         }
         const bool log_domain = runs && t0 < m.Tb && lattice_load<true>(&wk.domain[b]) != 0;
         narrow_gradient_rows<T, false, true>(x, grads, m, b, lat, wk.lse, logp, log_domain, wk.T, wk.B, wk.A, wk.blank, t0, 1,
-                                       tend, s_slot, s_start, s_count, g_slot);
+                                       tend, s_slot, s_start, s_count, g_slot, [] {});
     }
 }
 
@@ -3077,6 +3081,10 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
                                 int rows_per_group, const int* __restrict__ only_marked,
                                 const int* __restrict__ domain)
 {
+    // (what the rows need of the utterance is asked for in one go: each of these is a trip to memory)
+    const Utt m = meta[blockIdx.y];
+    const int in_log_domain = domain[blockIdx.y];
+    const int chain_gave_up = chain_err[blockIdx.y];
     // After a lattice launch whose workers have written the gradient: only the utterances they left.
     if (only_marked && only_marked[blockIdx.y] == 0) return;
     extern __shared__ int g_lds[];
@@ -3086,11 +3094,12 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const int tid = threadIdx.x, wave = tid >> 6;
     float* g_slot = reinterpret_cast<float*>(s_count + 64) + wave * (Lmax + 1);   // mass shares in slot order
     const int b = blockIdx.y, t0 = blockIdx.x * rows_per_group;
-    const Utt m = meta[b];
-    if (t0 == 0 && tid == 0 && chain_err[b] != 0) costs[b] = __uint_as_float(0x7FC00000u);
+    if (t0 == 0 && tid == 0 && chain_gave_up != 0) costs[b] = __uint_as_float(0x7FC00000u);
     const bool runs = (m.flags & kUttRuns) != 0;
     const int L = m.L;
-    if (runs && t0 < m.Tb) {
+    // The grouping of the label's positions, staged while the first rows' lattice values are on their way.
+    auto stage = [&]() {
+        if (!(runs && t0 < m.Tb)) return;               // (the same for the whole workgroup)
         if (tid < 64) {
             s_start[tid] = 0;
             s_count[tid] = 0;
@@ -3098,17 +3107,17 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         __syncthreads();
         for (int j = tid; j < L; j += kRowThreads) {
             const int link = links[m.lab_off + j];
+            const int c = labels[m.lab_off + j];         // (asked for with the link, not after it)
             s_slot[j] = link & kLinkSlotMask;
             if (link < 0) {
-                const int c = labels[m.lab_off + j];
                 s_start[c] = link & kLinkSlotMask;
                 s_count[c] = (link >> kLinkCountShift) & kLinkSlotMask;
             }
         }
         __syncthreads();
-    }
-    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, runs && domain[b] != 0, Tt, B, A, blank, t0 + wave, 4,
-                                        min(t0 + rows_per_group, Tt), s_slot, s_start, s_count, g_slot);
+    };
+    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, runs && in_log_domain != 0, Tt, B, A, blank, t0 + wave, 4,
+                                        min(t0 + rows_per_group, Tt), s_slot, s_start, s_count, g_slot, stage);
 }
 
 template <typename F>
