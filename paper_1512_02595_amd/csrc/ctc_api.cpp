@@ -78,7 +78,7 @@ void carve(int T, int B, int64_t sumL, int64_t emit, int64_t frames, int64_t ab,
     l.sink = off;   off = align_up(off + static_cast<size_t>(B) * 2 * kSinkWaves * kSinkBytes);
     l.chain_err = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
     l.done = off;   off = align_up(off + static_cast<size_t>(B) * kDoneStride * sizeof(int32_t));
-    l.domain = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
+    l.domain = off; off = align_up(off + static_cast<size_t>(B) * 2 * sizeof(int32_t));
     l.row_flags = off;
     off = align_up(off + static_cast<size_t>(B) * ((T + kFlagFrames - 1) / kFlagFrames) * sizeof(int32_t));
     l.status = off; off = align_up(off + static_cast<size_t>(B) * sizeof(int32_t));
@@ -348,7 +348,7 @@ ctc_status_t prepare(const Call& c, const Layout& lay, Launch* out, char* image)
         m.L = L;
         m.lab_off = static_cast<int32_t>(lab_off);
         m.flags = (runs ? kUttRuns : 0) | (two_pairs_per_lane(L, crowded, symbol_major) ? kUttTwoPairs : 0) |
-                  (Tb > kLinearMaxFrames ? kUttLogDomain : 0);
+                  ((Tb > kLinearMaxFrames || tight_fit(Tb, L, repeats)) ? kUttLogDomain : 0);
         m.f_off = static_cast<int32_t>(f_off);
         const WavePlan wp = plan_waves(L, crowded);
         m.waves = wp.waves;

@@ -189,6 +189,18 @@ constexpr float kLinearMinLog2 = -100.0f;
 // Utterances of more frames than this run the log domain whatever their emissions: the lanes'
 // exponents, which fall by up to 100 per frame, must stay clear of kNoExponent and of int32's end.
 constexpr int kLinearMaxFrames = 1 << 21;
+// Utterances with fewer than this many frames to spare (frames - symbols - repeated neighbours) run the log
+// domain too.  Where hardly a frame is to spare the alignments run along the front of the lattice, and the
+// states behind the front, whose mass can no longer reach the end, may outweigh it by more than the lanes'
+// frames of the linear domain hold (lane_frame in the kernels: 2^950 within ten state pairs); with this
+// many frames to spare every state that near the front can still reach the end.  Measured before the rule:
+// 138 frames, 91 symbols, 47 repeats, emissions down to 2^-95: the front 2^1900 below its neighbours, the
+// linear domain's cost +inf.
+constexpr int kTightFrames = 16;
+CTC_HOST_DEVICE inline bool tight_fit(int frames, int label_length, int repeats)
+{
+    return frames - label_length - repeats < kTightFrames;
+}
 // Lattice wavefronts of one launch beyond which chains are planned for total work: two per SIMD
 // of the 256 compute units.
 constexpr int kCrowdedWaves = 2 * 4 * 256;
@@ -437,8 +449,8 @@ struct Layout {
     size_t sink = 0;      // what lanes with nothing to store scribble on: kSinkBytes per wavefront of a lattice launch
     size_t chain_err = 0; // int32[B]     set when a lattice wavefront gave up waiting for its neighbour
     size_t done = 0;      // int32[B * kDoneStride]  wavefronts of the utterance's chains that have ended (overlapped launches)
-    size_t domain = 0;    // int32[B]     nonzero: the utterance's chains ran in the log domain (published by the forward
-                          //              chain for the gradient, which must know where the exponent rows are)
+    size_t domain = 0;    // int32[2 B]   per utterance and direction, nonzero: that chain ran in the log domain (published by
+                          //              the chain for the gradient, which must know where its exponent rows are)
     size_t row_flags = 0; // int32[B * ceil(T / 64)]  narrow alphabets: per 64 frames of an utterance, nonzero if one of
                           //              their emissions is too small for the linear domain (written by the softmax
                           //              launch, one word per workgroup, so that nothing needs clearing beforehand)

@@ -42,6 +42,14 @@ constexpr int kRowThreads = 256;
 
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 __device__ __forceinline__ float fast_log2(float v) { return __builtin_amdgcn_logf(v); }
+// log2 of a softmax output from the logit, the row's largest logit and log2 of the row's sum of
+// 2^((x - max) log2 e).  The difference comes first: formed as x log2 e - (max log2 e + log2 sum) the
+// result would carry the rounding of the offset, 6e-8 of its size, and a row of logits of size 100 whose
+// winner has probability 1 - 1e-6 would give that winner an emission wrong by 1e-5, frame after frame.
+__device__ __forceinline__ float log2_softmax(float x, float row_max, float log2_sum)
+{
+    return fmaf(x - row_max, kLog2e, -log2_sum);
+}
 
 // ---- element access for the two activation types -------------------------------------
 
@@ -280,7 +288,7 @@ void ctc_plan_kernel(const int* __restrict__ labels, const int* __restrict__ lab
         m.L = bad ? 0 : L;
         m.lab_off = b * max_label;
         m.flags = (runs ? kUttRuns : 0) | (bad ? kUttInvalid : 0) |
-                  ((log_domain || Tb > kLinearMaxFrames) ? kUttLogDomain : 0) |
+                  ((log_domain || Tb > kLinearMaxFrames || tight_fit(Tb, L, rep)) ? kUttLogDomain : 0) |
                   (!bad && two_pairs_per_lane(L, crowded, emission_layout(A) == kEmitSymbolMajor) ? kUttTwoPairs : 0);
         m.f_off = b * Tt;
         m.waves = wp.waves;
@@ -428,7 +436,21 @@ __device__ __forceinline__ float encode_emission(float lp, bool& small, bool pla
     small = true;
     return lp;
 }
-__device__ __forceinline__ float emission_log2(float v) { return v > 0.0f ? fast_log2(v) : v; }
+// log2 of a coded emission in two floats whose sum it is: the binary exponent of a stored probability
+// and the logarithm of its mantissa.  (As one float the logarithm of 2^-40 would be good to 4e-6 only,
+// frame after frame; a chain of 400 steps then misses the gradient's bound.)
+struct Log2Parts { float whole, part; };
+__device__ __forceinline__ Log2Parts emission_log2_parts(float v)
+{
+    if (v > 0.0f)
+        return {static_cast<float>(__builtin_amdgcn_frexp_expf(v)), fast_log2(__builtin_amdgcn_frexp_mantf(v))};
+    return {v, 0.0f};
+}
+__device__ __forceinline__ double emission_log2(float v)
+{
+    const Log2Parts p = emission_log2_parts(v);
+    return static_cast<double>(p.whole) + static_cast<double>(p.part);
+}
 __device__ __forceinline__ float emission_probability(float v) { return fmaxf(v, 0.0f); }
 __device__ __forceinline__ void raise_log_domain(Utt* meta, int b, bool small)
 {
@@ -468,28 +490,31 @@ void ctc_softmax_kernel(const T* __restrict__ x, T* __restrict__ grads,
 
     float mx = -__builtin_inff();
     for (int k = threadIdx.x; k < A; k += kRowThreads) mx = fmaxf(mx, load_elem(row, k));
-    mx = block_max(mx, red) * kLog2e;
+    mx = block_max(mx, red);
     float s = 0.0f;
     for (int k = threadIdx.x; k < A; k += kRowThreads)
-        s += fast_exp2(fmaf(load_elem(row, k), kLog2e, -mx));
+        s += fast_exp2((load_elem(row, k) - mx) * kLog2e);
     s = block_sum(s, red + 4);
-    const float l2 = mx + fast_log2(s);
+    // log2 y_k = (x_k - max) log2 e - log2 sum: the difference first, so that the error is relative to
+    // log2 y_k itself and not to the row's offset (see log2_softmax)
+    const float ls = fast_log2(s);
+    const float l2 = fmaf(mx, kLog2e, ls);
     if (threadIdx.x == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
 
     if (grads)
         for (int k = threadIdx.x; k < A; k += kRowThreads)
-            store_elem(grow, k, fast_exp2(fmaf(load_elem(row, k), kLog2e, -l2)));
+            store_elem(grow, k, fast_exp2(log2_softmax(load_elem(row, k), mx, ls)));
     bool small = false;
     if (threadIdx.x == 0)
     {
-        const float e = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
+        const float e = encode_emission(log2_softmax(load_elem(row, blank), mx, ls), small, sa.plain_logs);
         emit_blank[kBlankSlack + m.f_off + t] = e;
         sa.emit_blank64[kBlankSlack + m.f_off + t] = static_cast<double>(emission_probability(e));
     }
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = threadIdx.x; j < m.L; j += kRowThreads)
-        erow[j] = encode_emission(fmaf(load_elem(row, lab[j]), kLog2e, -l2), small, sa.plain_logs);
+        erow[j] = encode_emission(log2_softmax(load_elem(row, lab[j]), mx, ls), small, sa.plain_logs);
     raise_log_domain(meta, b, small);
 }
 
@@ -536,17 +561,18 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
             for (int e = 0; e < N; ++e) mx = fmaxf(mx, v[i][e]);
         }
     }
-    mx = block_max(mx, red) * kLog2e;
+    mx = block_max(mx, red);
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < kVecs; ++i) {
         if (tid + i * kRowThreads < nvec) {
 #pragma unroll
-            for (int e = 0; e < N; ++e) sum += fast_exp2(fmaf(v[i][e], kLog2e, -mx));
+            for (int e = 0; e < N; ++e) sum += fast_exp2((v[i][e] - mx) * kLog2e);
         }
     }
     sum = block_sum(sum, red + 4);
-    const float l2 = mx + fast_log2(sum);
+    const float ls = fast_log2(sum);
+    const float l2 = fmaf(mx, kLog2e, ls);
     if (tid == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
 
 #pragma unroll
@@ -555,21 +581,21 @@ void ctc_softmax_wide_kernel(const T* __restrict__ x, T* __restrict__ grads,
         if (grads && idx < nvec) {
             float y[N];
 #pragma unroll
-            for (int e = 0; e < N; ++e) y[e] = fast_exp2(fmaf(v[i][e], kLog2e, -l2));
+            for (int e = 0; e < N; ++e) y[e] = fast_exp2(log2_softmax(v[i][e], mx, ls));
             Vec<T>::store(grow + static_cast<size_t>(idx) * N, y);
         }
     }
     bool small = false;
     if (tid == 0)
     {
-        const float e = encode_emission(fmaf(load_elem(row, blank), kLog2e, -l2), small, sa.plain_logs);
+        const float e = encode_emission(log2_softmax(load_elem(row, blank), mx, ls), small, sa.plain_logs);
         emit_blank[kBlankSlack + m.f_off + t] = e;
         sa.emit_blank64[kBlankSlack + m.f_off + t] = static_cast<double>(emission_probability(e));
     }
     float* erow = emit_label + kLabelSlack + m.e_off + static_cast<size_t>(t) * m.L;
     const int* lab = labels + m.lab_off;
     for (int j = tid; j < m.L; j += kRowThreads)
-        erow[j] = encode_emission(fmaf(load_elem(row, lab[j]), kLog2e, -l2), small, sa.plain_logs);
+        erow[j] = encode_emission(log2_softmax(load_elem(row, lab[j]), mx, ls), small, sa.plain_logs);
     raise_log_domain(meta, b, small);
 }
 
@@ -621,14 +647,14 @@ void ctc_softmax_rows_kernel(const T* __restrict__ x, Utt* __restrict__ meta,
             }
         }
         mx = (kPerRow == 4) ? quad_max(mx) : (kPerRow == 16) ? row16_max(mx) : wave_max(mx);
-        mx *= kLog2e;
         float sum = 0.0f;
-        for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
+        for (int k = q; k < A; k += kPerRow) sum += fast_exp2((lrow[k] - mx) * kLog2e);
         sum = (kPerRow == 4) ? quad_sum(sum) : (kPerRow == 16) ? row16_sum(sum) : wave_sum(sum);
-        const float l2 = mx + fast_log2(sum);
+        const float ls = fast_log2(sum);
+        const float l2 = fmaf(mx, kLog2e, ls);
         // (coded as emissions; `unused` because what counts is which of them get stored below)
         bool unused = false;
-        for (int k = q; k < A; k += kPerRow) lrow[k] = encode_emission(fmaf(lrow[k], kLog2e, -l2), unused, sa.plain_logs);
+        for (int k = q; k < A; k += kPerRow) lrow[k] = encode_emission(log2_softmax(lrow[k], mx, ls), unused, sa.plain_logs);
         if (q == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
     }
     if (!(m.flags & kUttRuns)) return;
@@ -920,7 +946,7 @@ __device__ __forceinline__ Utt build_record(const NarrowDevice& dv, const PlanTa
     m.L = Lp;
     m.lab_off = b * dv.max_label;
     m.flags = (runs ? kUttRuns : 0) | (invalid ? kUttInvalid : 0) |
-              ((dv.log_domain || Tb > kLinearMaxFrames) ? kUttLogDomain : 0) |
+              ((dv.log_domain || Tb > kLinearMaxFrames || tight_fit(Tb, L, s_repeats)) ? kUttLogDomain : 0) |
               (!invalid && plans.two_pairs(L) ? kUttTwoPairs : 0) | (later ? kUttGradientLater : 0);
     m.f_off = b * Tt;
     m.waves = plans.waves1(Lp);
@@ -1046,13 +1072,14 @@ void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image,
                 mx = fmaxf(mx, v[u]);
             }
         }
-        mx = quad_max(mx) * kLog2e;
+        mx = quad_max(mx);
         float sum = 0.0f;
-        for (int k = q; k < A; k += kPerRow) sum += fast_exp2(fmaf(lrow[k], kLog2e, -mx));
+        for (int k = q; k < A; k += kPerRow) sum += fast_exp2((lrow[k] - mx) * kLog2e);
         sum = quad_sum(sum);
-        const float l2 = mx + fast_log2(sum);
+        const float ls = fast_log2(sum);
+        const float l2 = fmaf(mx, kLog2e, ls);
         bool unused = false;       // (what counts is which of the coded emissions get stored below)
-        for (int k = q; k < A; k += kPerRow) lrow[k] = encode_emission(fmaf(lrow[k], kLog2e, -l2), unused, sa.plain_logs);
+        for (int k = q; k < A; k += kPerRow) lrow[k] = encode_emission(log2_softmax(lrow[k], mx, ls), unused, sa.plain_logs);
         if (q == 0) lse[static_cast<size_t>(b) * Tt + t] = l2;
     }
     if (!(m.flags & kUttRuns)) return;
@@ -1149,19 +1176,20 @@ __device__ __forceinline__ double pack_log2(double w)          // the same as on
     return __hiloint2double(static_cast<int>(value), exponent);
 }
 // alpha * beta * (1 / p) from the stored parts.  (The missing low dword of a value is a relative
-// 2^-20 at most.)  Either of alpha and beta may lie a thousand binary orders below the top of its
-// own frame while their product is a share of order one, so the exponent that the three add up to
-// is spread over both factors before they are multiplied.  m_a, m_b < 2^(kChunk + 2) in their
-// frames, hence 2^1000 of either cannot overflow; a share that needed more is of values that
-// had been rounded away in their frames.
+// 2^-20 at most.)  Either of alpha and beta may lie a thousand binary orders below or above the unit
+// of its own frame (lane_frame) while their product is a share of order one, so the factors are
+// balanced before they are multiplied.
 __device__ __forceinline__ float mass_share(uint32_t a_value, int a_exponent, uint32_t b_value, int b_exponent,
                                             float inverse_p_mantissa, int inverse_p_exponent)
 {
-    const int e = min(a_exponent + b_exponent + inverse_p_exponent, 2000);
-    const int half = e >> 1;
+    // alpha's word is brought to [1, 2) by its own exponent field, and everything else goes to beta: the
+    // product is a share, at most 1, so beta's factor stays in range wherever alpha is not 0; next to an
+    // alpha that is the number 0 it is capped, so that the product is 0 and not 0 times infinity.
+    const int to_one = 1023 - static_cast<int>(a_value >> 20);
+    const int rest = a_exponent + b_exponent + inverse_p_exponent - to_one;
     const double a = __hiloint2double(static_cast<int>(a_value), 0);
     const double b = __hiloint2double(static_cast<int>(b_value), 0);
-    return static_cast<float>(__builtin_amdgcn_ldexp(a, half) * __builtin_amdgcn_ldexp(b, e - half)) *
+    return static_cast<float>(__builtin_amdgcn_ldexp(a, to_one) * fmin(__builtin_amdgcn_ldexp(b, rest), 0x1p200)) *
            inverse_p_mantissa;
 }
 
@@ -1449,9 +1477,9 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
         return r;
     };
 
-    auto finish_step = [&](float eb, float el) {
-        v_blank = i_blank + static_cast<double>(eb);
-        v_label = i_label + static_cast<double>(kCoded ? emission_log2(el) : el);
+    auto finish_step = [&](double eb, float el) {
+        v_blank = i_blank + eb;
+        v_label = i_label + (kCoded ? emission_log2(el) : static_cast<double>(el));
         if (kMode == Mode::kBest) {
             *op = static_cast<unsigned char>(choice);
         } else if (kMode == Mode::kLoss) {
@@ -1471,7 +1499,7 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
             }
         }
     };
-    auto advance = [&](int step, float eb, float el) {
+    auto advance = [&](int step, double eb, float el) {
         const double prev = from_prev_pair(v_label, step - 1);
         if (kMode == Mode::kBest) {
             const double via_skip = prev + skip_penalty;
@@ -1499,10 +1527,9 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
 
     // step 0: every lane starts from the exact state of its pair, halo lanes included
     {
-        const float ebv = kCoded ? emission_log2(*bp) : *bp;
-        const float el = kCoded ? emission_log2(*ep) : *ep;
-        v_blank = i_blank + static_cast<double>(readlane(ebv, 0));
-        v_label = i_label + static_cast<double>(el);
+        const Log2Parts ebv = kCoded ? emission_log2_parts(*bp) : Log2Parts{*bp, 0.0f};
+        v_blank = i_blank + static_cast<double>(readlane(ebv.whole, 0)) + static_cast<double>(readlane(ebv.part, 0));
+        v_label = i_label + (kCoded ? emission_log2(*ep) : static_cast<double>(*ep));
         // (the predecessor choices of frame 0 are never looked at: nothing is written for it)
         if (kMode == Mode::kGrad) store_state(kBackward ? i_label : v_label);
         op += ostride;
@@ -1527,14 +1554,18 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
     // Whole chunks run without looking at the step number; only the last, short chunk of a
     // chain checks every step against the end.
     auto run = [&](const float (&el)[kChunk], const float eb_coded, int s0, bool whole) {
-        const float eb = kCoded ? emission_log2(eb_coded) : eb_coded;
+        const Log2Parts eb = kCoded ? emission_log2_parts(eb_coded) : Log2Parts{eb_coded, 0.0f};
+        auto blank_of_step = [&](int i) {
+            const double whole_part = static_cast<double>(readlane(eb.whole, i));
+            return kCoded ? whole_part + static_cast<double>(readlane(eb.part, i)) : whole_part;
+        };
         if (whole) {
 #pragma unroll
-            for (int i = 0; i < kChunk; ++i) advance(s0 + i, readlane(eb, i), el[i]);
+            for (int i = 0; i < kChunk; ++i) advance(s0 + i, blank_of_step(i), el[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < kChunk; ++i)
-                if (s0 + i < Tb) advance(s0 + i, readlane(eb, i), el[i]);
+                if (s0 + i < Tb) advance(s0 + i, blank_of_step(i), el[i]);
         }
     };
     chain_schedule(Tb, [&](int s0) { fetch(el_a, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
@@ -1602,6 +1633,29 @@ __device__ __forceinline__ void run_chain_log(const Utt m, const int u, const in
 // Storage (Mode::kGrad): the label state's value word at every step, its frame once per chunk
 // (see "lattice storage").
 constexpr int kNoExponent = -(1 << 28);   // exponent of zero: below every real one, far from int32's ends
+// A lane's new frame is the largest exponent of its window (its own pairs and those that can reach it
+// before the next renewal), so that nothing arriving overflows -- but no more than kFrameSlack above
+// its own largest value where the window's top lies further up than that, down to kFrameDrop below the
+// window's top.  With the window's top as the frame of every lane, a pair whose neighbours below carry
+// 2^1000 times its mass was rounded away: wrong when those neighbours' mass can no longer reach the
+// end of the label and the small pair is all there is (an utterance with exactly as many frames as its
+// label needs, logits spread over 40 nats: cost off by 0.03, gradient by 0.03).  Now a pair keeps
+// 2^-kFrameSlack of its frame, 2^-(kFrameSlack + 800) after a chunk of the smallest emissions the
+// linear domain admits, as long as the window's top is within 2^(kFrameSlack + kFrameDrop) of it; what
+// arrives from the window is at most 2^(kFrameDrop + 9) in the lane's frame, and two neighbouring
+// frames differ by at most kFrameSlack + kFrameDrop, which the factor between them (scale) can hold.
+// A pair further below its window than that has neighbours with 2^950 times its mass that can still
+// reach the end (utterances with fewer than kTightFrames frames to spare, where they could not, run in
+// the log domain from the start: tight_fit), each of their extra moves costing an emission of 2^-100 at
+// worst: what is rounded away then is below 2^-50 of the whole.
+constexpr int kFrameSlack = 150, kFrameDrop = 800;
+// (A lane without mass, whose own largest exponent is kNoExponent, sits kFrameDrop below the top: the
+// first mass to reach it may come from a lane whose own frame lies that low, and must not be rounded
+// away on arrival.)
+__device__ __forceinline__ int lane_frame(int window_top, int own_top)
+{
+    return window_top - min(max(window_top - own_top - kFrameSlack, 0), kFrameDrop);
+}
 // A renewal is put off while it is not needed (a third of a chunk's instructions are the renewal's): every
 // pair of the wavefront has mass, lies within [2^kEasyLow, 2^kEasyHigh] of its frame, and at the last
 // renewal no frame lay more than kSmoothFrames below the frame of the lane below it.  Then one more chunk
@@ -1759,6 +1813,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
         int window = mine;
 #pragma unroll
         for (int k = 0; k < kChunk; ++k) window = window_max_step(window, mine);
+        window = lane_frame(window, mine);
         const int rise = frame - window;
         v_blank = __builtin_amdgcn_ldexp(v_blank, rise);
         v_label = __builtin_amdgcn_ldexp(v_label, rise);
@@ -1842,9 +1897,13 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     double eb_a[kChunk] = {}, eb_b[kChunk] = {}, eb_c[kChunk] = {};
     // (Scalar loads return in any order, so a wavefront can only wait for all of them: the set in use is
     // waited for before the other set's load goes out, while that wait is still free.)
+    // The label emissions of the chunk at s0 go into `el`, two chunks ahead of their use; the blank's
+    // scalars into `eb`, the set of the chunk that runs next, for the chunk before s0, so that only two of
+    // the three scalar sets are in use at any time (48 scalar registers for them were more than the kernel
+    // has: the compiler parked a set in vector lanes and fetched it back, 32 moves per round).
     auto fetch = [&](float (&el)[kChunk], double (&eb)[kChunk], const double (&in_use)[kChunk], int s0) {
         asm volatile("" : : "s"(in_use[0]), "s"(in_use[kChunk - 1]));
-        const double* const w = blank_window(s0);
+        const double* const w = blank_window(max(s0 - kChunk, 1));
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) eb[i] = blank_of(w, i);
         if (direct) {
@@ -1867,9 +1926,9 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
                 if (s0 + i < Tb) advance(eb[i], el[i]);
         }
     };
-    chain_schedule3(Tb, [&](int s0) { fetch(el_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
-                    [&](int s0) { fetch(el_b, eb_b, eb_c, s0); __builtin_amdgcn_sched_barrier(0); },
-                    [&](int s0) { fetch(el_c, eb_c, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
+    chain_schedule3(Tb, [&](int s0) { fetch(el_a, eb_c, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0) { fetch(el_b, eb_a, eb_c, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0) { fetch(el_c, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
                     [&](int s0, bool whole) { run(el_a, eb_a, s0, whole); }, [&](int s0, bool whole) { run(el_b, eb_b, s0, whole); },
                     [&](int s0, bool whole) { run(el_c, eb_c, s0, whole); }, end_chunk);
 
@@ -1882,8 +1941,8 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
             const double p = v_blank + from_below;
             const double mantissa = __builtin_amdgcn_frexp_mant(p);
             const int exponent = frame + __builtin_amdgcn_frexp_exp(p);
-            const double l2 = static_cast<double>(exponent) +
-                              static_cast<double>(fast_log2(static_cast<float>(mantissa)));
+            // (in double: once per chain, and a cost near zero, p near 1, would keep few of a float logarithm's bits)
+            const double l2 = static_cast<double>(exponent) + ::log2(mantissa);
             lattice_store(&logp[u], (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0);     // 1 / p
             const float cost = (p > 0.0) ? static_cast<float>(-l2 * kLn2) : __builtin_inff();
             if (kSync == Sync::kHalo && kMode == Mode::kLoss) hl->cost = cost;
@@ -2081,6 +2140,7 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
         int window = mine;
 #pragma unroll
         for (int k = 0; k < kChunk / 2; ++k) window = window_max_step(window, mine);
+        window = lane_frame(window, mine);
         const int rise = frame - window;
         va_blank = __builtin_amdgcn_ldexp(va_blank, rise);
         va_label = __builtin_amdgcn_ldexp(va_label, rise);
@@ -2212,8 +2272,8 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
             const double p = (ja == L) ? va_blank + from_below : vb_blank + va_label;
             const double mantissa = __builtin_amdgcn_frexp_mant(p);         // [0.5, 1)
             const int exponent = frame + __builtin_amdgcn_frexp_exp(p);
-            const double l2 = static_cast<double>(exponent) +
-                              static_cast<double>(fast_log2(static_cast<float>(mantissa)));
+            // (in double: once per chain, and a cost near zero, p near 1, would keep few of a float logarithm's bits)
+            const double l2 = static_cast<double>(exponent) + ::log2(mantissa);
             lattice_store(&logp[u], (p > 0.0) ? pack_state(1.0 / mantissa, -exponent) : 0.0);     // 1 / p
             const float cost = (p > 0.0) ? static_cast<float>(-l2 * kLn2) : __builtin_inff();
             if (kMode == Mode::kLoss) hl->cost = cost;
@@ -2363,8 +2423,8 @@ __device__ __forceinline__ ChainRun lattice_body(const Utt* __restrict__ meta, c
     // gives one pair or two to a lane as the launcher planned it (two_pairs_per_lane).
     const bool in_log_domain = kSync == Sync::kBarrier || kMode == Mode::kBest || (m.flags & kUttLogDomain) != 0 ||
                                rows_flagged(wk.row_flags, u, wk.flag_blocks, m.Tb);
-    // (for the gradient, which must know where this utterance's exponent rows are)
-    if (kMode == Mode::kGrad && forward && threadIdx.x == 0) wk.domain[u] = in_log_domain ? 1 : 0;
+    // (for the gradient, which must know where each chain's exponent rows are: a word per direction)
+    if (kMode == Mode::kGrad && threadIdx.x == 0) wk.domain[2 * u + (forward ? 0 : 1)] = in_log_domain ? 1 : 0;
     const bool two_pairs = kSync == Sync::kHalo && !in_log_domain && (m.flags & kUttTwoPairs) != 0;
     const int waves = two_pairs ? m.waves2 : m.waves;
     const bool idle = static_cast<int>(threadIdx.x >> 6) >= waves;
@@ -2439,14 +2499,21 @@ struct LatticeRows {
     const int* eb;
     size_t pitch;
     int Tb;
-    bool log_domain;
+    int log_domains;          // bit 0: the forward chain ran in the log domain, bit 1: the backward chain (chain_domains)
     __device__ __forceinline__ LatticeRow at(int t) const
     {
         const size_t values = static_cast<size_t>(t) * pitch;
-        return {a + values, ea + static_cast<size_t>(exponent_row(t, log_domain)) * pitch,
-                b + values, eb + static_cast<size_t>(exponent_row(Tb - 1 - t, log_domain)) * pitch};
+        return {a + values, ea + static_cast<size_t>(exponent_row(t, (log_domains & 1) != 0)) * pitch,
+                b + values, eb + static_cast<size_t>(exponent_row(Tb - 1 - t, (log_domains & 2) != 0)) * pitch};
     }
 };
+// The domains of an utterance's two chains as its chains published them (a word per direction:
+// either chain may have gone over to the log domain on its own, see lattice_body).
+template <bool kCoherent>
+__device__ __forceinline__ int chain_domains(const int* __restrict__ domain, int b)
+{
+    return (lattice_load<kCoherent>(&domain[2 * b]) != 0 ? 1 : 0) | (lattice_load<kCoherent>(&domain[2 * b + 1]) != 0 ? 2 : 0);
+}
 
 // The rows t_first, t_first + t_step, ... (below tend) of utterance b, by one wavefront: lane k is
 // symbol k (alphabets of at most 64 symbols).  s_slot, s_start, s_count: the grouping of the label's
@@ -2459,7 +2526,7 @@ template <typename T, bool kStreaming, bool kCoherent, typename Stage>
 __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T* __restrict__ grads, const Utt m,
                                                      const int b, const LatticeOut lat,
                                                      const float* __restrict__ lse, const double* __restrict__ logp,
-                                                     const bool log_domain,   // decides where a row's exponents are (exponent_row)
+                                                     const int log_domains,   // decides where a row's exponents are (LatticeRows)
                                                      const int Tt, const int B, const int A, const int blank,
                                                      const int t_first, const int t_step, const int tend,
                                                      const int* s_slot, const int* s_start, const int* s_count,
@@ -2474,7 +2541,7 @@ __device__ __forceinline__ void narrow_gradient_rows(const T* __restrict__ x, T*
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
                               lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
-                              pitch, m.Tb, log_domain};
+                              pitch, m.Tb, log_domains};
     // What a row needs from memory: the lattice words of its first kAhead * 64 label states
     // (longer labels read the rest in line), its log-sum-exp and its activations.  A row's
     // values are requested while the row before it is still being summed up out of LDS: by then
@@ -2698,8 +2765,8 @@ __device__ __forceinline__ void gradient_worker(const WorkerArgs wk, const Utt* 
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
         }
-        const bool log_domain = runs && t0 < m.Tb && lattice_load<true>(&wk.domain[b]) != 0;
-        narrow_gradient_rows<T, false, true>(x, grads, m, b, lat, wk.lse, logp, log_domain, wk.T, wk.B, wk.A, wk.blank, t0, 1,
+        const int log_domains = (runs && t0 < m.Tb) ? chain_domains<true>(wk.domain, b) : 0;
+        narrow_gradient_rows<T, false, true>(x, grads, m, b, lat, wk.lse, logp, log_domains, wk.T, wk.B, wk.A, wk.blank, t0, 1,
                                        tend, s_slot, s_start, s_count, g_slot, [] {});
     }
 }
@@ -2910,10 +2977,10 @@ void ctc_gradient_rows_kernel(const T* __restrict__ x, T* __restrict__ grads,
     const float inverse_p = static_cast<float>(packed_inverse_p);
     const int inverse_p_exponent = __double2loint(packed_inverse_p);
     const int tend = min(t0 + rows_per_group, Tt);
-    const bool log_domain = runs && domain[b] != 0;         // decides where a row's exponents are (exponent_row)
+    const int log_domains = runs ? chain_domains<false>(domain, b) : 0;     // decides where a row's exponents are (LatticeRows)
     const LatticeRows rows_of{lat.alpha + m.ab_off + 1, lat.alpha_exponents + m.ab_off + 1,     // label state i sits
                               lat.beta + m.ab_off + 1, lat.beta_exponents + m.ab_off + 1,       // in column 1 + i
-                              pitch, m.Tb, log_domain};
+                              pitch, m.Tb, log_domains};
 
     // What a row needs from memory, requested in one go before any of it is used, so that a
     // row costs one memory latency: the lattice values of the first kAhead * 64 label states
@@ -3083,7 +3150,7 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
 {
     // (what the rows need of the utterance is asked for in one go: each of these is a trip to memory)
     const Utt m = meta[blockIdx.y];
-    const int in_log_domain = domain[blockIdx.y];
+    const int log_domains = chain_domains<false>(domain, blockIdx.y);
     const int chain_gave_up = chain_err[blockIdx.y];
     // After a lattice launch whose workers have written the gradient: only the utterances they left.
     if (only_marked && only_marked[blockIdx.y] == 0) return;
@@ -3116,7 +3183,7 @@ void ctc_gradient_narrow_kernel(const T* __restrict__ x, T* __restrict__ grads,
         }
         __syncthreads();
     };
-    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, runs && in_log_domain != 0, Tt, B, A, blank, t0 + wave, 4,
+    narrow_gradient_rows<T, kStreaming, false>(x, grads, m, b, lat, lse, logp, runs ? log_domains : 0, Tt, B, A, blank, t0 + wave, 4,
                                         min(t0 + rows_per_group, Tt), s_slot, s_start, s_count, g_slot, stage);
 }
 

@@ -405,3 +405,17 @@ def test_many_random_shapes():
         db.run_loss()
         loss_only, _ = db.results()
         assert np.array_equal(loss_only, costs)
+
+
+def test_hardly_a_frame_to_spare_and_widely_spread_logits():
+    """Utterances with exactly as many frames as their labels need, under logits spread over tens of nats:
+    the one alignment left runs along the front of the lattice, a thousand and more binary orders below
+    the states behind it, whose mass can no longer reach the end.  Such utterances run in the log domain
+    (fewer than 16 frames to spare), and the linear domain keeps a pair within 2^-150 of its lane's frame
+    where its neighbours are up to 2^950 heavier."""
+    # (seed 9117: an utterance of 408 frames, 399 symbols, 9 repeats; one of 396 frames with 50 to spare)
+    check(wl.make_random(9117, T=417, B=19, A=29, blank=23, max_label=409, min_input=387, sigma=6.0, feasible_only=True))
+    # (seed 9406: 138 frames, 91 symbols, 47 repeats, emissions down to 2^-95: the front 2^1900 below its neighbours)
+    check(wl.make_random(9406, T=150, B=158, A=3, blank=1, max_label=128, min_input=120, sigma=20.0, feasible_only=True))
+    # (one symbol only: 445 frames for 223 symbols and 222 repeats)
+    check(wl.make_random(9192, T=452, B=31, A=2, blank=1, max_label=450, min_input=433, sigma=6.0, feasible_only=True))
