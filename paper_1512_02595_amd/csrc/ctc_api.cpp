@@ -942,7 +942,8 @@ long ctc_debug_replay_emission_fetches(int T, int B, int A, const int32_t* label
                 };
                 auto nothing = [](int, bool) {};
                 chain_schedule(Tb, fetch, fetch, nothing, nothing, [] {});
-                chain_schedule3(Tb, fetch, fetch, fetch, nothing, nothing, nothing, [] {});
+                auto fetch3 = [&](int s0) { fetch(blank64_chunk_with(s0)); };
+                chain_schedule3(Tb, fetch3, fetch3, fetch3, nothing, nothing, nothing, [] {});
             }
         }
     }

@@ -433,6 +433,10 @@ CTC_HOST_DEVICE inline void chain_schedule3(int Tb, FetchA&& fetch_a, FetchB&& f
     }
 }
 
+// With three register sets the blank's scalar window (blank64_window) goes out one chunk ahead only, together
+// with the label emissions of the chunk after it: the chunk whose window accompanies the request for s0.
+CTC_HOST_DEVICE inline int blank64_chunk_with(int s0) { return s0 - kChunkSteps > 1 ? s0 - kChunkSteps : 1; }
+
 // Row pitch (8-byte words) of an utterance's lattice blocks: column 1 + i holds label state i.
 CTC_HOST_DEVICE inline int64_t lattice_pitch(int64_t L) { return L + 2; }
 

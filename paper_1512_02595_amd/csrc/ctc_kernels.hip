@@ -1903,7 +1903,7 @@ __device__ __forceinline__ void run_chain_linear(const Utt m, const int u, const
     // has: the compiler parked a set in vector lanes and fetched it back, 32 moves per round).
     auto fetch = [&](float (&el)[kChunk], double (&eb)[kChunk], const double (&in_use)[kChunk], int s0) {
         asm volatile("" : : "s"(in_use[0]), "s"(in_use[kChunk - 1]));
-        const double* const w = blank_window(max(s0 - kChunk, 1));
+        const double* const w = blank_window(blank64_chunk_with(s0));
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) eb[i] = blank_of(w, i);
         if (direct) {
