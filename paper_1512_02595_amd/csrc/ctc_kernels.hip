@@ -2228,11 +2228,12 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
     store_frame();                                       // exponent row 0: step 0 and the first chunk
     first_step(blank_of(blank_window(0), 0), *epa, *epb);
 
-    float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk];
-    double eb_a[kChunk] = {}, eb_b[kChunk] = {};
+    float ela_a[kChunk], elb_a[kChunk], ela_b[kChunk], elb_b[kChunk], ela_c[kChunk], elb_c[kChunk];
+    double eb_a[kChunk] = {}, eb_b[kChunk] = {}, eb_c[kChunk] = {};
+    // (label emissions two chunks ahead, the blank's scalars one: see run_chain_linear)
     auto fetch = [&](float (&ela)[kChunk], float (&elb)[kChunk], double (&eb)[kChunk], const double (&in_use)[kChunk], int s0) {
         asm volatile("" : : "s"(in_use[0]), "s"(in_use[kChunk - 1]));     // (see run_chain_linear)
-        const double* const w = blank_window(s0);
+        const double* const w = blank_window(blank64_chunk_with(s0));
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) eb[i] = blank_of(w, i);
         if (direct) {
@@ -2258,11 +2259,12 @@ __device__ __forceinline__ void run_chain_linear2(const Utt m, const int u, cons
                 if (s0 + i < Tb) advance(eb[i], ela[i], elb[i]);
         }
     };
-    // (Two register sets: a third, as in run_chain_linear, gains 2 % here and costs the long chains as much.)
-    chain_schedule(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_a, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
-                   [&](int s0) { fetch(ela_b, elb_b, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
-                   [&](int s0, bool whole) { run(ela_a, elb_a, eb_a, s0, whole); },
-                   [&](int s0, bool whole) { run(ela_b, elb_b, eb_b, s0, whole); }, end_chunk);
+    chain_schedule3(Tb, [&](int s0) { fetch(ela_a, elb_a, eb_c, eb_b, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0) { fetch(ela_b, elb_b, eb_a, eb_c, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0) { fetch(ela_c, elb_c, eb_b, eb_a, s0); __builtin_amdgcn_sched_barrier(0); },
+                    [&](int s0, bool whole) { run(ela_a, elb_a, eb_a, s0, whole); },
+                    [&](int s0, bool whole) { run(ela_b, elb_b, eb_b, s0, whole); },
+                    [&](int s0, bool whole) { run(ela_c, elb_c, eb_c, s0, whole); }, end_chunk);
 
     if (!kBackward) {
         // p = alpha_{T-1}(2L) + alpha_{T-1}(2L-1): the blank of pair L and the label of pair L - 1.
