@@ -419,3 +419,18 @@ def test_hardly_a_frame_to_spare_and_widely_spread_logits():
     check(wl.make_random(9406, T=150, B=158, A=3, blank=1, max_label=128, min_input=120, sigma=20.0, feasible_only=True))
     # (one symbol only: 445 frames for 223 symbols and 222 repeats)
     check(wl.make_random(9192, T=452, B=31, A=2, blank=1, max_label=450, min_input=433, sigma=6.0, feasible_only=True))
+
+
+@pytest.mark.parametrize("A,blank", [(29, 0), (130, 129), (256, 255), (257, 256), (700, 3)])
+def test_metadata_upload_launch_with_byte_and_word_labels(A, blank):
+    """Minibatches of more than 128 utterances (and every alphabet above 64 symbols) send their metadata in a
+    launch of its own, which builds the label words from the labels' bytes where a symbol fits one (alphabets of
+    at most 256 symbols) and copies the words otherwise: both sides of that limit, with the largest symbol id
+    in use as a label or as the blank."""
+    batch = wl.make_random(7300 + A, T=70, B=150, A=A, blank=blank, max_label=40, min_input=30, sigma=2.0)
+    top = A - 1 if blank != A - 1 else A - 2                    # the largest symbol a label may hold
+    labels = batch.flat_labels.copy()
+    labels[::7] = top
+    batch = wl.CTCBatch(batch.name, batch.T, batch.B, batch.A, batch.blank, batch.logits, labels,
+                        batch.label_lengths, batch.input_lengths, seed=batch.seed)
+    check(batch)
