@@ -52,7 +52,8 @@ def both_paths(batch, dtype=ctc.DTYPE_F32, max_label=None, same_kernels=True):
         # a different recursion kernel: the same numbers up to rounding
         assert np.array_equal(np.isfinite(costs), np.isfinite(ref_costs))
         ok = np.isfinite(ref_costs)
-        assert np.abs(costs[ok] - ref_costs[ok]).max() <= 1e-5 * max(np.abs(ref_costs[ok]).max(), 1e-2)
+        if ok.any():                                             # (a batch may hold no utterance with an alignment)
+            assert np.abs(costs[ok] - ref_costs[ok]).max() <= 1e-5 * max(np.abs(ref_costs[ok]).max(), 1e-2)
         assert np.abs(grads - ref_grads).max() <= 2e-5
     return dm, costs, grads
 
