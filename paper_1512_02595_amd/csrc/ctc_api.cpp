@@ -625,9 +625,12 @@ ctc_status_t run_device(const void* x, const int32_t* labels, const int32_t* lab
     p.n_chains = B * (grads ? 2 : 1);
     p.max_waves = 1;
     const bool symbol_major = emission_layout(A) == kEmitSymbolMajor;
-    p.crowded = static_cast<int64_t>(B) * (two_pairs_per_lane(max_label, false, symbol_major) ? plan_waves2(max_label).waves
-                                                                                : plan_waves(max_label).waves) *
-                    (grads ? 2 : 1) > 2 * kCrowdedWaves;
+    // Would the launch, planned for latency, put more than two wavefronts on every SIMD (prepare's question)?  The
+    // labels' lengths are on the GPU; the answer here is for lengths spread evenly up to the bound.
+    int64_t waves_up_to_bound = 0;
+    for (int L = 0; L <= max_label; ++L)
+        waves_up_to_bound += two_pairs_per_lane(L, false, symbol_major) ? plan_waves2(L).waves : plan_waves(L).waves;
+    p.crowded = static_cast<int64_t>(B) * (grads ? 2 : 1) * waves_up_to_bound > static_cast<int64_t>(kCrowdedWaves) * (max_label + 1);
     for (int L = 0; L <= max_label; ++L)
         p.max_waves = std::max(p.max_waves, std::max(plan_waves(L, p.crowded).waves, plan_waves2(L, p.crowded).waves));
     p.max_frames = T;

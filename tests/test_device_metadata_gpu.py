@@ -86,6 +86,13 @@ def test_bounds_far_above_the_actual_labels():
     both_paths(wl.make_random(32, T=150, B=5, A=6, max_label=100, min_input=120, feasible_only=True), max_label=900)
 
 
+def test_launch_of_more_chains_than_the_chip_runs_side_by_side():
+    """The 512-utterance sweep at full size: from the bounds alone the call takes the launch for a crowded one
+    (lengths spread evenly up to the bound would put more than two wavefronts on every SIMD) and plans its chains
+    for total work, as the host-metadata call does from the actual lengths."""
+    both_paths(wl.make_config(4), same_kernels=False)
+
+
 def test_bf16_and_cost_only():
     batch = wl.make_config(4, B=32)
     both_paths(batch, ctc.DTYPE_BF16)
