@@ -375,10 +375,12 @@ constexpr int kSetupLabelSlots = CTC_MAX_LABEL_LENGTH + 5;     // the label and 
 // `labels8`: the label strings as bytes (narrow alphabets, read out of the pinned host image: a
 // quarter of the traffic), to be written out as ints to `labels_out` by the utterance's first part;
 // nullptr: `labels` holds them as ints.
+__device__ __forceinline__ void setup_words(const Utt m, const int b, const SetupArgs sa);
+// (`with_words`: the utterance's first part also writes its setup_words)
 __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* __restrict__ labels,
                                            const SetupArgs sa, int* s_lab, const int part, const int parts,
                                            const unsigned char* __restrict__ labels8 = nullptr,
-                                           int* __restrict__ labels_out = nullptr)
+                                           int* __restrict__ labels_out = nullptr, const bool with_words = true)
 {
     const int tid = threadIdx.x;
     const int* lab = labels + m.lab_off;
@@ -410,8 +412,14 @@ __device__ __forceinline__ void setup_role(const Utt m, const int b, const int* 
             sa.links[m.lab_off + j] = (below + before) | (count << kLinkCountShift) |
                                       (before == 0 ? static_cast<int>(0x80000000u) : 0);
     }
-    if (part != 0) return;
-    if (tid == 0) {
+    if (part == 0 && with_words) setup_words(m, b, sa);
+}
+
+// The per-utterance words that every call starts from, the constants of the emission array, and the costs
+// of utterances without a lattice.  By one workgroup per utterance.
+__device__ __forceinline__ void setup_words(const Utt m, const int b, const SetupArgs sa)
+{
+    if (threadIdx.x == 0) {
         sa.chain_err[b] = 0;
         sa.done[b * kDoneStride] = 0;
         sa.where[2 * b] = 0;
@@ -1007,18 +1015,20 @@ void ctc_softmax_narrow_kernel(const T* __restrict__ x, const NarrowImage image,
         return;
     }
     if (static_cast<int>(blockIdx.x) >= row_blocks && dv.labels) {
-        // device-resident metadata: the first part builds the record, the others need the label only
+        // device-resident metadata: the first of these workgroups builds the record (and writes what depends on
+        // it), the others group the label's positions, for which they need the label only: side by side, so that
+        // the launch lasts as long as the longer of the two, not their sum
         const int part = static_cast<int>(blockIdx.x) - row_blocks;
-        Utt m{};
         if (part == 0) {
-            m = build_record(dv, args.plans, b, Tt, B, A, blank);
-        } else {
-            const int L = dv.label_lengths[b], Tb = dv.input_lengths[b];
-            const bool bad_length = L < 0 || L > dv.max_label || Tb < 0 || Tb > Tt;
-            m.L = bad_length ? 0 : L;
-            m.lab_off = b * dv.max_label;
+            setup_words(build_record(dv, args.plans, b, Tt, B, A, blank), b, sa);
+            return;
         }
-        setup_role(m, b, dv.labels, sa, s_lab, part, sa.parts);
+        Utt m{};
+        const int L = dv.label_lengths[b], Tb = dv.input_lengths[b];
+        const bool bad_length = L < 0 || L > dv.max_label || Tb < 0 || Tb > Tt;
+        m.L = bad_length ? 0 : L;
+        m.lab_off = b * dv.max_label;
+        setup_role(m, b, dv.labels, sa, s_lab, part - 1, sa.parts - 1, nullptr, nullptr, false);
         return;
     }
     if (static_cast<int>(blockIdx.x) >= row_blocks) {
@@ -3265,7 +3275,9 @@ int launch_softmax(const Launch& p, void* stream)
                        p.folded ? nullptr : p.host_flag, p.host_flag_value, p.mode == Mode::kBest,
                        // few utterances: spread each one's grouping over several workgroups (its
                        // latency counts); many: one workgroup each keeps the chip busy already
-                       p.B >= 256 ? 1 : std::max(1, (p.max_label + 63) / 64)};
+                       (p.B >= 256 ? 1 : std::max(1, (p.max_label + 63) / 64)) +
+                           // (device-resident metadata, narrow alphabets: one more, which builds the utterance's record)
+                           (p.folded && p.dev_label_lengths ? 1 : 0)};
     const dim3 block(kRowThreads);
     auto s = static_cast<hipStream_t>(stream);
     const bool f32 = p.dtype == CTC_DTYPE_F32;
